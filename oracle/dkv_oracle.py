@@ -1,0 +1,233 @@
+"""CPU oracle for DynamicKV's prefill-time KV compression (arxiv 2412.14838).
+
+TEST INFRASTRUCTURE ONLY.  This is the plain, slow reference the HIP kernels are
+checked against.  It shares no code with the HIP path and nothing in the
+product may import it; only the tests, the smoke check and the benchmark's
+cpu_baseline leg call it.
+
+The method is a heuristic, so the oracle takes the steps of Algorithm 1
+("DynamicKV in Prefill Phase") in the paper's order, one sequence at a time
+(prefill is per sample, Section 4.3 Q1), in float64.  Pooled scores are rounded
+once to float32 (step O5) so that every later, integer-valued decision is a pure
+function of float32 values - the precision the kernels take those decisions in.
+
+Notation (paper -> here): L layers; H -> Hq query heads / Hkv KV heads,
+G = Hq // Hkv; d_k -> d; S sequence length; ws -> w; prefix length S' = S - w;
+(wt - ws) -> mean_budget; B^l = (wt - ws) * r_max -> layer_max;
+B = (wt - ws) * L -> global budget; m -> interval.
+
+Readings where the paper is silent or garbled (each one is a decision shared
+with the kernels and listed in the design notes):
+  * softmax scale 1/sqrt(d) (Eq. 1; the algorithm listing omits it);
+  * causal mask inside the window: window query i sits at position S - w + i;
+  * window rows are summed (row_scale = 1; 1/w gives the listing's mean);
+  * GQA: the G query heads of a KV head are summed before pooling;
+  * pooling = max, kernel P, stride 1, same length, taken over the prefix only;
+  * ties in every top-k go to the lower (flat) index;
+  * flat index -> layer by integer division with Hkv * S' (the listing's
+    divisor is garbled);
+  * the normalisation of the counts cancels in t / max, and both int() steps
+    are exact integer floors;
+  * truncation never grows a layer: n_i <- min(n_i, Z'_i).
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# Eq. 1-2 / Algorithm 1 "A^l_h <- softmax(...).mean(dim=-2).pooling(dim=-1)"
+# --------------------------------------------------------------------------
+def window_logits(q_win: np.ndarray, k: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
+    """O1+O2: x[g, i, s] = scale * <q_win[g, i], k[g // G, s]>, causally masked.
+
+    q_win [Hq, w, d], k [Hkv, S, d] -> x [Hq, w, S] float64 (Eq. 1 numerator).
+    """
+    q = np.asarray(q_win, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    Hq, w, d = q.shape
+    Hkv, S, _ = kk.shape
+    assert Hq % Hkv == 0 and S >= w
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    x = np.empty((Hq, w, S), dtype=np.float64)
+    for g in range(Hq):
+        x[g] = scale * (q[g] @ kk[g // G].T)
+    # window query i is the token at position S - w + i and sees keys s <= S - w + i
+    pos = np.arange(S)[None, :]
+    own = (S - w + np.arange(w))[:, None]
+    x[:, pos > own] = -np.inf
+    return x
+
+
+def softmax_rows(x: np.ndarray) -> np.ndarray:
+    """O3: softmax over the key axis (Eq. 1)."""
+    m = x.max(axis=-1, keepdims=True)
+    e = np.exp(x - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def window_sum(p: np.ndarray, Hkv: int, row_scale: float = 1.0) -> np.ndarray:
+    """O4: a[h, s] = row_scale * sum over the G heads of KV head h and the w window rows."""
+    Hq, w, S = p.shape
+    G = Hq // Hkv
+    return row_scale * p.reshape(Hkv, G * w, S).sum(axis=1)
+
+
+def max_pool_prefix(a: np.ndarray, w: int, P: int) -> np.ndarray:
+    """O5: A[h, s] = max_{|j - s| <= (P-1)/2, 0 <= j < S'} a[h, j] for s in [0, S'), as float32 (Eq. 2)."""
+    assert P % 2 == 1 and P >= 1
+    Hkv, S = a.shape
+    Sp = S - w
+    half = (P - 1) // 2
+    pre = a[:, :Sp]
+    out = np.empty((Hkv, Sp), dtype=np.float64)
+    for s in range(Sp):
+        lo, hi = max(0, s - half), min(Sp - 1, s + half)
+        out[:, s] = pre[:, lo:hi + 1].max(axis=1)
+    return out.astype(np.float32)
+
+
+def score_window(q_win: np.ndarray, k: np.ndarray, P: int, scale: Optional[float] = None,
+                 row_scale: float = 1.0) -> np.ndarray:
+    """Steps O1-O5 for one layer of one sequence -> A^l [Hkv, S'] float32."""
+    Hq, w, _ = q_win.shape
+    Hkv = k.shape[0]
+    p = softmax_rows(window_logits(q_win, k, scale))
+    a = window_sum(p, Hkv, row_scale)
+    return max_pool_prefix(a, w, P)
+
+
+# --------------------------------------------------------------------------
+# Eq. 3 / Algorithm 1 "indices <- A^l.topk(B^l, dim=-1).indices"
+# --------------------------------------------------------------------------
+def select_topk(A: np.ndarray, layer_max: int) -> np.ndarray:
+    """O6: per KV head the k = min(B^l, S') best prefix positions, (score desc, index asc).
+
+    A [Hkv, S'] float32 -> idx [Hkv, k] int32.
+    """
+    A = np.asarray(A, dtype=np.float32)
+    Hkv, Sp = A.shape
+    kk = min(layer_max, Sp)
+    idx = np.empty((Hkv, kk), dtype=np.int32)
+    for h in range(Hkv):
+        order = np.argsort(-A[h].astype(np.float64), kind="stable")
+        idx[h] = order[:kk]
+    return idx
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1 "K^b_l <- cat(K^s[:, :-ws].gather(indices), K^s[:, -ws:])"
+# --------------------------------------------------------------------------
+def gather_kv(k: np.ndarray, v: np.ndarray, idx: np.ndarray, w: int) -> Tuple[np.ndarray, np.ndarray]:
+    """O7: buffer rows = selected prefix rows (in idx order) followed by the w window rows."""
+    Hkv, S, d = k.shape
+    n = idx.shape[1]
+    kb = np.empty((Hkv, n + w, d), dtype=k.dtype)
+    vb = np.empty((Hkv, n + w, d), dtype=v.dtype)
+    for h in range(Hkv):
+        kb[h, :n] = k[h, idx[h]]
+        kb[h, n:] = k[h, S - w:]
+        vb[h, :n] = v[h, idx[h]]
+        vb[h, n:] = v[h, S - w:]
+    return kb, vb
+
+
+# --------------------------------------------------------------------------
+# Eq. 4-6 / Algorithm 1 "Update_Buffer_Length"
+# --------------------------------------------------------------------------
+def layer_hit_counts(A_list: Sequence[np.ndarray], mean_budget: int) -> np.ndarray:
+    """Phi(TopK(A, (wt - ws) * H * l)) of Eq. 4: hits of the global top-k per layer.
+
+    A_list: l arrays [Hkv, S'] float32 (layers processed so far).  The flat
+    order is (layer, head, position); ties go to the lower flat index.
+    """
+    l = len(A_list)
+    Hkv, Sp = A_list[0].shape
+    flat = np.concatenate([np.asarray(a, dtype=np.float32).reshape(-1) for a in A_list])
+    kg = min(mean_budget * Hkv * l, flat.size)
+    order = np.argsort(-flat.astype(np.float64), kind="stable")[:kg]
+    per_layer = Hkv * Sp
+    cnt = np.zeros(l, dtype=np.int64)
+    if per_layer > 0:
+        np.add.at(cnt, order // per_layer, 1)
+    return cnt
+
+
+def budgets_from_counts(cnt: np.ndarray, layer_max: int, mean_budget: int, L: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 5-6: Z_i = floor(B^l * cnt_i / max cnt), Z'_i = floor(Z_i * B / sum Z), B = (wt - ws) * L.
+
+    Exact integer arithmetic (python ints).  All-zero counts give all-zero budgets.
+    """
+    c = [int(x) for x in cnt]
+    cmax = max(c) if c else 0
+    if cmax == 0:
+        z = [0] * len(c)
+        return np.array(z, dtype=np.int64), np.array(z, dtype=np.int64)
+    Z = [(layer_max * t) // cmax for t in c]
+    total = sum(Z)
+    B = mean_budget * L
+    Zp = [(z * B) // total for z in Z]
+    return np.array(Z, dtype=np.int64), np.array(Zp, dtype=np.int64)
+
+
+def update_buffer_length(A_list: Sequence[np.ndarray], layer_max: int, mean_budget: int, L: int
+                         ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """O8: (cnt, Z, Z') after the layers in A_list have been processed."""
+    cnt = layer_hit_counts(A_list, mean_budget)
+    Z, Zp = budgets_from_counts(cnt, layer_max, mean_budget, L)
+    return cnt, Z, Zp
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1, the whole prefill loop for one sequence
+# --------------------------------------------------------------------------
+class Compressed:
+    """Result of compress(): per-layer scores, ordered indices, counts and budgets."""
+
+    def __init__(self):
+        self.A: List[np.ndarray] = []          # A^b: pooled scores [Hkv, S'] float32 per layer
+        self.idx: List[np.ndarray] = []        # ordered retained candidates [Hkv, k] per layer
+        self.n: List[int] = []                 # retained prefix rows per head, per layer
+        self.kb: List[np.ndarray] = []         # K^b_l  [Hkv, k + w, d]
+        self.vb: List[np.ndarray] = []
+        self.budgets: List[Tuple[int, np.ndarray, np.ndarray, np.ndarray]] = []  # (l, cnt, Z, Z')
+
+    def cache(self, layer: int, w: int) -> Tuple[np.ndarray, np.ndarray]:
+        """K^c_l, V^c_l: the first n_l buffer rows followed by the window rows."""
+        n = self.n[layer]
+        kb, vb = self.kb[layer], self.vb[layer]
+        return (np.concatenate([kb[:, :n], kb[:, kb.shape[1] - w:]], axis=1),
+                np.concatenate([vb[:, :n], vb[:, vb.shape[1] - w:]], axis=1))
+
+
+def compress(layers, L: int, w: int, P: int, layer_max: int, mean_budget: int, interval: int,
+             scale: Optional[float] = None, row_scale: float = 1.0, keep_buffers: bool = True,
+             scores_override: Optional[Sequence[np.ndarray]] = None) -> Compressed:
+    """Algorithm 1 for one sequence.
+
+    layers: iterable yielding (q_win [Hq, w, d], k [Hkv, S, d], v [Hkv, S, d]) per layer.
+    scores_override: if given, A^l is taken from it instead of being computed
+    (used to check selection and budgets in isolation on a fixed float32 input).
+    """
+    out = Compressed()
+    for l, (q_win, k, v) in enumerate(layers, start=1):
+        A = (np.asarray(scores_override[l - 1], dtype=np.float32) if scores_override is not None
+             else score_window(q_win, k, P, scale, row_scale))
+        out.A.append(A)
+        idx = select_topk(A, layer_max)
+        out.idx.append(idx)
+        out.n.append(idx.shape[1])
+        if keep_buffers:
+            kb, vb = gather_kv(k, v, idx, w)
+            out.kb.append(kb)
+            out.vb.append(vb)
+        if l % interval == 0:
+            cnt, Z, Zp = update_buffer_length(out.A, layer_max, mean_budget, L)
+            out.budgets.append((l, cnt, Z, Zp))
+            for i in range(l):
+                out.n[i] = min(out.n[i], int(Zp[i]))
+    return out

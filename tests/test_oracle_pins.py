@@ -1,0 +1,340 @@
+"""Pins for the CPU oracle: closed forms, invariants, library special cases, brute force.
+
+The paper prints no worked numeric example of Algorithm 1, so each oracle step
+is pinned to something other than itself: the mathematics of Eq. 1-6, library
+routines on the special cases that reduce to them, hand-worked budget rows
+(tests/golden/budget_examples.txt) and pure-Python brute force on tiny inputs.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dkv_oracle as O
+from paper_2412_14838_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---------------------------------------------------------------- O1-O4 (Eq. 1)
+def test_unpooled_scores_sum_to_number_of_rows():
+    """Every softmax row sums to 1 over all S keys => sum_s a[h, s] = G * w (Eq. 1)."""
+    Hq, Hkv, w, d, S = 6, 2, 5, 16, 97
+    q, k = _rand((Hq, w, d), 1), _rand((Hkv, S, d), 2)
+    p = O.softmax_rows(O.window_logits(q, k))
+    assert np.allclose(p.sum(axis=-1), 1.0, atol=1e-12)
+    a = O.window_sum(p, Hkv)
+    assert np.allclose(a.sum(axis=-1), (Hq // Hkv) * w, atol=1e-10)
+    assert np.allclose(O.window_sum(p, Hkv, row_scale=1.0 / w).sum(axis=-1), Hq // Hkv, atol=1e-10)
+
+
+def test_single_row_reduces_to_library_softmax():
+    """w = 1, G = 1: the only window row sees all keys; score = softmax(q K^T / sqrt(d)) (Eq. 1)."""
+    d, S = 32, 200
+    q, k = _rand((1, 1, d), 3), _rand((1, S, d), 4)
+    a = O.window_sum(O.softmax_rows(O.window_logits(q, k)), 1)
+    ref = torch.softmax(torch.from_numpy(q[0]) @ torch.from_numpy(k[0]).T / math.sqrt(d), dim=-1).numpy()
+    assert np.allclose(a[0], ref[0], rtol=1e-12, atol=1e-15)
+    # P = 1 pooling is the identity on the prefix
+    A = O.score_window(q, k, P=1)
+    assert np.array_equal(A[0], ref[0, :S - 1].astype(np.float32))
+
+
+def test_zero_queries_closed_form_proves_causal_mask():
+    """Q = 0: window row i is uniform over its S - w + i + 1 visible keys, so every prefix
+    score is G * sum_i 1 / (S - w + i + 1); without the causal mask it would be G * w / S."""
+    Hq, Hkv, w, d, S = 4, 2, 8, 8, 50
+    q, k = np.zeros((Hq, w, d)), _rand((Hkv, S, d), 5)
+    a = O.window_sum(O.softmax_rows(O.window_logits(q, k)), Hkv)
+    G = Hq // Hkv
+    expect = G * sum(Fraction(1, S - w + i + 1) for i in range(w))
+    assert np.allclose(a[:, :S - w], float(expect), rtol=1e-13)
+    assert abs(float(expect) - G * w / S) > 1e-3
+    # inside the window, column S - w + j is visible to rows i >= j only
+    for j in range(w):
+        col = G * sum(Fraction(1, S - w + i + 1) for i in range(j, w))
+        assert np.allclose(a[:, S - w + j], float(col), rtol=1e-13)
+
+
+def test_scale_is_one_over_sqrt_d_and_sign_is_right():
+    """Hand example (Eq. 1): d = 4, one row q = (2,0,0,0), keys (1,..), (0,..), (-1,..):
+    logits 2/2, 0, -2/2 => softmax = e^{1}, e^{0}, e^{-1} normalised."""
+    q = np.array([[[2.0, 0, 0, 0]]])
+    k = np.array([[[1.0, 0, 0, 0], [0, 0, 0, 0], [-1.0, 0, 0, 0]]])
+    p = O.softmax_rows(O.window_logits(q, k))[0, 0]
+    e = np.array([math.e, 1.0, 1.0 / math.e])
+    assert np.allclose(p, e / e.sum(), rtol=1e-14)
+    # explicit scale overrides the default
+    p2 = O.softmax_rows(O.window_logits(q, k, scale=1.0))[0, 0]
+    e2 = np.array([math.e ** 2, 1.0, math.e ** -2])
+    assert np.allclose(p2, e2 / e2.sum(), rtol=1e-14)
+
+
+def test_brute_force_scores_tiny():
+    """Pure-Python loops over every (head, row, key) with math.exp, masked by position."""
+    Hq, Hkv, w, d, S, P = 4, 2, 3, 5, 17, 3
+    G = Hq // Hkv
+    q, k = _rand((Hq, w, d), 6), _rand((Hkv, S, d), 7)
+    a = [[0.0] * S for _ in range(Hkv)]
+    for g in range(Hq):
+        for i in range(w):
+            last = S - w + i
+            logits = [sum(q[g, i, t] * k[g // G, s, t] for t in range(d)) / math.sqrt(d) for s in range(last + 1)]
+            mx = max(logits)
+            den = sum(math.exp(x - mx) for x in logits)
+            for s in range(last + 1):
+                a[g // G][s] += math.exp(logits[s] - mx) / den
+    Sp = S - w
+    pooled = [[max(a[h][max(0, s - 1):min(Sp - 1, s + 1) + 1]) for s in range(Sp)] for h in range(Hkv)]
+    A = O.score_window(q, k, P)
+    assert A.dtype == np.float32 and A.shape == (Hkv, Sp)
+    assert np.allclose(A, np.array(pooled), rtol=1e-6)
+
+
+def test_gqa_is_the_sum_of_its_query_heads():
+    """Linearity of the group reduction: G = 4 scores = sum of four G = 1 runs on the same K."""
+    G, w, d, S = 4, 4, 16, 64
+    q, k = _rand((G, w, d), 8), _rand((1, S, d), 9)
+    full = O.window_sum(O.softmax_rows(O.window_logits(q, k)), 1)
+    parts = sum(O.window_sum(O.softmax_rows(O.window_logits(q[g:g + 1], k)), 1) for g in range(G))
+    assert np.allclose(full, parts, rtol=1e-13)
+    # heads of different KV groups do not mix
+    k2 = _rand((2, S, d), 10)
+    both = O.window_sum(O.softmax_rows(O.window_logits(q, k2)), 2)
+    only0 = O.window_sum(O.softmax_rows(O.window_logits(q[:2], k2[:1])), 1)
+    assert np.allclose(both[0], only0[0], rtol=1e-13)
+
+
+# ---------------------------------------------------------------- O5 (Eq. 2)
+def test_pool_matches_library_max_pool_on_prefix():
+    Hkv, S, w = 3, 101, 9
+    a = np.abs(_rand((Hkv, S), 11))
+    for P in (1, 3, 7, 13):
+        got = O.max_pool_prefix(a, w, P)
+        pre = torch.from_numpy(a[:, :S - w]).unsqueeze(0)
+        ref = torch.nn.functional.max_pool1d(pre, kernel_size=P, stride=1, padding=(P - 1) // 2)[0].numpy()
+        assert np.array_equal(got, ref.astype(np.float32))
+
+
+def test_pool_spike_and_window_isolation():
+    """A single spike spreads to exactly P positions (clipped at the ends); a large value in
+    the first window column must not leak into the last prefix positions."""
+    S, w, P = 40, 8, 7
+    Sp = S - w
+    for spike in (0, 2, 15, Sp - 1):
+        a = np.zeros((1, S))
+        a[0, spike] = 5.0
+        a[0, Sp] = 99.0              # first window column
+        A = O.max_pool_prefix(a, w, P)[0]
+        lo, hi = max(0, spike - 3), min(Sp - 1, spike + 3)
+        expect = np.zeros(Sp, dtype=np.float32)
+        expect[lo:hi + 1] = 5.0
+        assert np.array_equal(A, expect)
+
+
+# ---------------------------------------------------------------- O6 (Eq. 3)
+def test_select_brute_force_and_ties():
+    rng = np.random.default_rng(12)
+    for trial in range(20):
+        Sp = int(rng.integers(1, 60))
+        # few distinct values => many exact ties
+        A = rng.integers(0, 5, size=(2, Sp)).astype(np.float32) / 4
+        kmax = int(rng.integers(1, 70))
+        got = O.select_topk(A, kmax)
+        for h in range(2):
+            brute = sorted(range(Sp), key=lambda s: (-float(A[h, s]), s))[:min(kmax, Sp)]
+            assert got[h].tolist() == brute
+    assert O.select_topk(np.ones((1, 10), dtype=np.float32), 4)[0].tolist() == [0, 1, 2, 3]
+    # the selected values agree with the library's top-k values
+    A = np.abs(_rand((3, 500), 13)).astype(np.float32)
+    got = O.select_topk(A, 37)
+    ref = torch.topk(torch.from_numpy(A), 37, dim=-1).values.numpy()
+    assert np.array_equal(np.take_along_axis(A, got, axis=1), ref)
+
+
+# ---------------------------------------------------------------- O7
+def test_gather_rows_are_copies():
+    Hkv, S, d, w = 2, 30, 4, 5
+    k, v = _rand((Hkv, S, d), 14).astype(np.float32), _rand((Hkv, S, d), 15).astype(np.float32)
+    idx = np.array([[7, 0, 24, 3], [1, 2, 23, 11]], dtype=np.int32)
+    kb, vb = O.gather_kv(k, v, idx, w)
+    assert kb.shape == (Hkv, 4 + w, d)
+    for h in range(Hkv):
+        for j, s in enumerate(idx[h]):
+            assert np.array_equal(kb[h, j], k[h, s]) and np.array_equal(vb[h, j], v[h, s])
+        assert np.array_equal(kb[h, 4:], k[h, S - w:]) and np.array_equal(vb[h, 4:], v[h, S - w:])
+
+
+# ---------------------------------------------------------------- O8 (Eq. 4-6)
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "budget_examples.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [[int(x) for x in p.split()] for p in line.split("|")]
+            rows.append(parts)
+    return rows
+
+
+def test_budget_formulas_against_hand_worked_rows():
+    rows = _golden_rows()
+    assert len(rows) >= 6
+    for (layer_max, mean_budget, L), cnt, Z, Zp in rows:
+        gotZ, gotZp = O.budgets_from_counts(np.array(cnt), layer_max, mean_budget, L)
+        assert gotZ.tolist() == Z and gotZp.tolist() == Zp
+
+
+def test_budget_normalisation_cancels_in_exact_arithmetic():
+    """The listing divides the counts by l and normalises them to (0, 1) before t / max(norm);
+    in exact rational arithmetic any positive rescaling cancels (Eq. 5), and r = sum(Z)/B."""
+    rng = np.random.default_rng(16)
+    for _ in range(50):
+        l = int(rng.integers(1, 9))
+        L = l + int(rng.integers(0, 4))
+        cnt = rng.integers(0, 5000, size=l)
+        cnt[int(rng.integers(0, l))] += 1
+        layer_max, mean_budget = int(rng.integers(1, 3000)), int(rng.integers(1, 700))
+        norm = [Fraction(int(c), l) / Fraction(int(cnt.sum()), l) for c in cnt]
+        Z = [math.floor(layer_max * t / max(norm)) for t in norm]
+        r = Fraction(sum(Z), mean_budget * L)
+        Zp = [math.floor(z / r) for z in Z]
+        gotZ, gotZp = O.budgets_from_counts(cnt, layer_max, mean_budget, L)
+        assert gotZ.tolist() == Z and gotZp.tolist() == Zp
+        B = mean_budget * L
+        assert B - l < sum(Zp) <= B
+    z, zp = O.budgets_from_counts(np.zeros(3, dtype=np.int64), 10, 5, 3)
+    assert z.tolist() == [0, 0, 0] and zp.tolist() == [0, 0, 0]
+
+
+def test_layer_hit_counts_brute_force_and_ties():
+    rng = np.random.default_rng(17)
+    for _ in range(10):
+        l, Hkv, Sp = int(rng.integers(1, 5)), 2, int(rng.integers(3, 40))
+        A_list = [(rng.integers(0, 6, size=(Hkv, Sp)) / 5).astype(np.float32) for _ in range(l)]
+        mean_budget = int(rng.integers(1, Sp + 5))
+        cnt = O.layer_hit_counts(A_list, mean_budget)
+        flat = [(-float(A_list[i][h, s]), (i * Hkv + h) * Sp + s) for i in range(l) for h in range(Hkv) for s in range(Sp)]
+        kg = min(mean_budget * Hkv * l, len(flat))
+        brute = [0] * l
+        for _, fi in sorted(flat)[:kg]:
+            brute[fi // (Hkv * Sp)] += 1
+        assert cnt.tolist() == brute and int(cnt.sum()) == kg
+    # bit-equal scores everywhere: the earlier layers win the ties
+    same = [np.ones((2, 10), dtype=np.float32) for _ in range(3)]
+    assert O.layer_hit_counts(same, 4).tolist() == [20, 4, 0]
+    # all mass in one layer
+    A_list = [np.zeros((2, 10), dtype=np.float32), np.ones((2, 10), dtype=np.float32)]
+    assert O.layer_hit_counts(A_list, 5).tolist() == [0, 20]
+
+
+def test_flat_counts_give_the_fixed_budget_pattern():
+    """Equal hit counts => Z' = floor(mean_budget * L / l); at l = L that is the fixed per-layer budget."""
+    for l, L in ((4, 4), (2, 4), (8, 32)):
+        _, Zp = O.budgets_from_counts(np.full(l, 77), 512, 128, L)
+        assert Zp.tolist() == [(512 * 128 * L) // (512 * l)] * l
+
+
+# ---------------------------------------------------------------- Algorithm 1 as a whole
+def _layers(cfg, seq=0):
+    cu = cfg.cu_seqlens
+    for l in range(cfg.L):
+        d = W.make_layer(cfg, l)
+        yield d["q_win"][seq], d["k"][:, cu[seq]:cu[seq + 1]], d["v"][:, cu[seq]:cu[seq + 1]]
+
+
+@pytest.mark.parametrize("normalize", [False, True])
+def test_driver_invariants_on_tiny(normalize):
+    cfg = W.standard_configs()["tiny"].with_(plant_normalize=normalize)
+    S, w = cfg.seqlens[0], cfg.w
+    r = O.compress(_layers(cfg), cfg.L, w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval)
+    B = cfg.global_budget
+    prev = [cfg.layer_max] * cfg.L
+    for (l, cnt, Z, Zp) in r.budgets:
+        assert l % cfg.interval == 0 and len(cnt) == l
+        assert int(cnt.sum()) == min(cfg.mean_budget * cfg.Hkv * l, l * cfg.Hkv * (S - w))
+        assert int(Z.max()) == cfg.layer_max and B - l < int(Zp.sum()) <= B
+    for i in range(cfg.L):
+        assert 0 <= r.n[i] <= cfg.layer_max and r.n[i] <= prev[i]
+        assert r.n[i] == min(cfg.layer_max, int(r.budgets[-1][3][i]), *(int(b[3][i]) for b in r.budgets if b[0] > i))
+        kc, vc = r.cache(i, w)
+        assert kc.shape == (cfg.Hkv, r.n[i] + w, cfg.d)
+        assert sum(r.n) <= B
+    if normalize:
+        # calibrated planting: every planted key is among the layer's candidates, ranked first, all tied
+        for l in range(cfg.L):
+            pos = W.planted_positions(cfg, l, 0)
+            for h in range(cfg.Hkv):
+                # pooling spreads every planted spike over P tied neighbours
+                top = r.idx[l][h][:cfg.P * len(pos)]
+                assert len(np.unique(r.A[l][h][pos])) == 1
+                if cfg.P * len(pos) <= r.idx[l].shape[1]:
+                    assert np.isin(pos, top).all()
+                else:   # more tied plateau positions than candidates: all candidates carry the planted score
+                    assert (r.A[l][h][r.idx[l][h]] == r.A[l][h][pos[0]]).all()
+
+
+def test_scores_override_isolates_selection():
+    cfg = W.standard_configs()["tiny"]
+    r = O.compress(_layers(cfg), cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval)
+    r2 = O.compress(_layers(cfg), cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval,
+                    scores_override=r.A, keep_buffers=False)
+    assert r.n == r2.n and all(np.array_equal(a, b) for a, b in zip(r.idx, r2.idx))
+
+
+# ---------------------------------------------------------------- planted mistakes must be caught
+def test_pins_catch_planted_mistakes(monkeypatch):
+    """Plant plausible mistakes in the oracle (on the CPU) and check that a pin fails."""
+    def fails(fn):
+        try:
+            fn()
+        except AssertionError:
+            return True
+        return False
+
+    orig_logits = O.window_logits
+
+    def no_mask(q, k, scale=None):
+        q64, k64 = np.asarray(q, np.float64), np.asarray(k, np.float64)
+        G = q64.shape[0] // k64.shape[0]
+        sc = 1.0 / np.sqrt(q64.shape[-1]) if scale is None else scale
+        return np.stack([sc * (q64[g] @ k64[g // G].T) for g in range(q64.shape[0])])
+
+    monkeypatch.setattr(O, "window_logits", no_mask)
+    assert fails(test_zero_queries_closed_form_proves_causal_mask)
+    assert fails(test_brute_force_scores_tiny)
+    monkeypatch.setattr(O, "window_logits", lambda q, k, scale=None: orig_logits(q, k, 1.0 if scale is None else scale))
+    assert fails(test_scale_is_one_over_sqrt_d_and_sign_is_right)
+    monkeypatch.setattr(O, "window_logits", lambda q, k, scale=None: -orig_logits(q, k, scale))
+    assert fails(test_brute_force_scores_tiny)
+    monkeypatch.setattr(O, "window_logits", orig_logits)
+
+    orig_pool = O.max_pool_prefix
+    monkeypatch.setattr(O, "max_pool_prefix", lambda a, w, P: orig_pool(a, 0, P)[:, :a.shape[1] - w])
+    assert fails(test_pool_spike_and_window_isolation)
+    monkeypatch.setattr(O, "max_pool_prefix", orig_pool)
+
+    orig_sel = O.select_topk
+    monkeypatch.setattr(O, "select_topk", lambda A, m: np.stack(
+        [np.argsort(-A[h], kind="stable")[::-1][:min(m, A.shape[1])][::-1] for h in range(A.shape[0])]).astype(np.int32))
+    assert fails(test_select_brute_force_and_ties)
+    monkeypatch.setattr(O, "select_topk", orig_sel)
+
+    orig_b = O.budgets_from_counts
+
+    def rounded(cnt, layer_max, mean_budget, L):
+        c = np.asarray(cnt, dtype=np.float64)
+        Z = np.round(layer_max * c / c.max())
+        return Z.astype(np.int64), np.round(Z * mean_budget * L / Z.sum()).astype(np.int64)
+
+    monkeypatch.setattr(O, "budgets_from_counts", rounded)
+    assert fails(test_budget_formulas_against_hand_worked_rows)
+    monkeypatch.setattr(O, "budgets_from_counts", orig_b)
