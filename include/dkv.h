@@ -1,0 +1,150 @@
+/*
+ * dkv.h - C ABI of the DynamicKV prefill-time KV-cache compression path for AMD MI355X (gfx950).
+ *
+ * The four stage calls follow the problem statement of the paper (arxiv 2412.14838), Algorithm 1
+ * "DynamicKV in Prefill Phase": per layer, score the cached keys against the last ws queries
+ * (Eq. 1-2), keep the top B^l positions per KV head (Eq. 3), copy their K/V rows next to the window
+ * rows, and every m layers shrink all layers processed so far to the global budget (Section 4.2,
+ * Eq. 4-6, function Update_Buffer_Length).
+ *
+ * Conventions
+ *   - plain C; every stage call returns an int status (DKV_OK or a negative DKV_ERR_*); nothing throws.
+ *   - every pointer is a DEVICE pointer unless the parameter comment says "host"; the descriptor is host.
+ *   - the caller owns every buffer; the library allocates no device memory, keeps no state between
+ *     calls except what it writes into the caller's workspace, and never synchronises the stream.
+ *   - all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - arguments are validated on the host before anything is launched; on a negative status nothing
+ *     was enqueued.
+ *   - sequences are packed along the token axis: sequence s owns tokens [cu_seqlens[s], cu_seqlens[s+1]);
+ *     its length S_s must be >= window for its scores to be meaningful; a sequence with S_s <= window
+ *     has no candidate positions (count 0) and only its existing window rows are copied.
+ *   - "prefix" of a sequence = its first S' = S - window positions: the candidates for retention.
+ */
+#ifndef DKV_H
+#define DKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DKV_VERSION 1
+
+enum { DKV_F32 = 0, DKV_BF16 = 1 };
+
+enum {
+  DKV_OK = 0,
+  DKV_ERR_INVALID_ARG = -1, /* null pointer, inconsistent descriptor, misaligned pointer or stride   */
+  DKV_ERR_UNSUPPORTED = -2, /* head_dim / dtype / size outside what the kernels are built for        */
+  DKV_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than dkv_workspace_bytes()   */
+  DKV_ERR_LAUNCH = -4       /* the HIP runtime refused a launch (hipGetLastError)                    */
+};
+
+/* Limits of this build (checked by every call). */
+#define DKV_MAX_LAYER_MAX 4096 /* B^l                                        */
+#define DKV_MAX_POOL 63        /* pooling kernel size                        */
+#define DKV_MAX_ROWS 256       /* G * window: score rows per KV head         */
+#define DKV_MAX_SEQS 4096
+#define DKV_MAX_LAYERS 512
+
+/* Problem descriptor (host memory, read during the call only). Symbols as in Algorithm 1. */
+typedef struct dkv_desc {
+  int32_t n_layers;     /* L                                                                         */
+  int32_t n_q_heads;    /* query heads Hq                                                            */
+  int32_t n_kv_heads;   /* KV heads Hkv; Hq % Hkv == 0, G = Hq / Hkv query heads share one KV head   */
+  int32_t head_dim;     /* d_k: 64 or 128                                                            */
+  int32_t window;       /* ws: observation window = last ws tokens, always retained; >= 1            */
+  int32_t pool_kernel;  /* P: size of the 1-D max pooling of Eq. 2 (odd, stride 1, same length)      */
+  int32_t layer_max;    /* B^l = (wt - ws) * r_max: per-layer maximum budget per KV head             */
+  int32_t mean_budget;  /* wt - ws: mean retained prefix rows per layer per KV head                  */
+  int32_t interval;     /* m: layers between two progressive updates                                 */
+  int32_t dtype;        /* DKV_F32 or DKV_BF16: element type of q_win, k, v and the gathered copies  */
+  int32_t n_seqs;       /* sequences in this launch (ragged lengths allowed)                         */
+  int32_t total_tokens; /* T = cu_seqlens[n_seqs]                                                    */
+  int32_t max_seq_len;  /* an upper bound on every sequence length (sizes grids and the workspace)   */
+  float softmax_scale;  /* 0 => 1/sqrt(d_k) (Eq. 1)                                                  */
+  float row_scale;      /* 0 => 1: scores are SUMS over the window rows; 1/ws gives the listing's mean */
+} dkv_desc;
+
+/* Library version (DKV_VERSION it was built with). Host only. */
+int dkv_version(void);
+
+/* Static text for a status code. Host only. */
+const char* dkv_status_string(int status);
+
+/* Bytes of device workspace the stage calls need for this descriptor (0 if the descriptor is invalid).
+ * Host only, launches nothing. The workspace must be 256-byte aligned. */
+size_t dkv_workspace_bytes(const dkv_desc* desc);
+
+/* Zero the workspace's counters. Call once after allocating the workspace (and again after any call
+ * that was aborted mid-flight); the stage calls leave the workspace ready for the next call. */
+int dkv_workspace_init(const dkv_desc* desc, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Observation-window scoring of ONE layer (Eq. 1-2; Algorithm 1, the softmax(...).mean(dim=-2).pooling(dim=-1) line).
+ * For every sequence and KV head h and prefix position s:
+ *     x[g,i,t]  = softmax_scale * <q_win[g,i,:], k[h,t,:]>   for the G query heads g of h, window rows i,
+ *                 masked causally (window row i is the token at position S - ws + i);
+ *     p[g,i,:]  = softmax over all S keys;
+ *     a[h,t]    = row_scale * sum_g sum_i p[g,i,t];
+ *     A[h,s]    = max over t in [s - (P-1)/2, s + (P-1)/2] intersected with [0, S') of a[h,t].
+ * q_win      [n_seqs][Hq][ws][d], contiguous.
+ * k          element (seq s, token t, head h, j) at k[(cu_seqlens[s] + t) * k_stride_token + h * k_stride_head + j];
+ *            strides in elements, rows 16-byte aligned.
+ * scores_out fp32; A[h,s] of sequence q is written to scores_out[h * scores_stride_head + cu_seqlens[q] + s]
+ *            for s < S'; the window slots [S', S) of each sequence receive -inf. Candidate scores are >= 0.
+ * Accumulation is fp32 (bf16 products are exact in fp32). Two kernels are enqueued (row statistics, then scores).
+ */
+int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                     int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                     int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-layer, per-KV-head top-k (Eq. 3; Algorithm 1, the A^l.topk(B^l).indices line) for layer index `layer`.
+ * For every (sequence, KV head): the k = min(layer_max, S') prefix positions with the largest scores,
+ * ORDERED by (score descending, position ascending) - ties go to the lower position - so that a later
+ * truncation to the first n entries is again a top-n set.
+ * scores     as written by dkv_score_window for this layer.
+ * idx_out    int32 [n_seqs][Hkv][layer_max], sequence-local positions; entries >= k are set to -1.
+ * counts     int32 [n_seqs][L]; counts[q][layer] = k is written.
+ */
+int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,
+                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* stream);
+
+/*
+ * Progressive cache update after `layers_done` layers (Section 4.2, Eq. 4-6; Update_Buffer_Length and the
+ * truncation loop of Algorithm 1). Per sequence: the kg = min(mean_budget * Hkv * l, l * Hkv * S') largest
+ * entries of the scores of layers [0, l) (ties to the lower (layer, head, position)) are counted per layer
+ * (cnt_i), then Z_i = floor(layer_max * cnt_i / max cnt), Z'_i = floor(Z_i * mean_budget * L / sum Z)
+ * (exact integers), and counts[q][i] <- min(counts[q][i], Z'_i) for i < l.
+ * layers_done  l: a positive multiple of desc->interval, <= L.
+ * scores_all   fp32 [L][Hkv][total_tokens] contiguous (layer i at scores_all + i * Hkv * total_tokens).
+ * counts       int32 [n_seqs][L], updated in place for layers < l.
+ * budgets_out  int32 [n_seqs][L]: Z' for layers < l (others untouched). May be NULL.
+ * hits_out     int32 [n_seqs][L]: cnt for layers < l. May be NULL.
+ */
+int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
+                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/*
+ * Compaction of the retained K/V rows of layer index `layer` (Algorithm 1, the two cat(gather(...), window) lines).
+ * For every (sequence q, KV head h) the output block holds ws + layer_max row slots:
+ *     slots [0, ws)              the window rows (positions S - ws .. S - 1, in position order),
+ *     slots [ws, ws + count)     the rows at idx[q][h][0 .. count), in that order (count = counts[q][layer]).
+ * The window comes first so that truncating a layer to n rows is the prefix [0, ws + n) of its block: the
+ * compressed cache is a view of this buffer (attention is invariant to the order of cached rows).
+ * k, v       same addressing as k of dkv_score_window (v uses the same strides).
+ * k_out,v_out element (q, h, slot, j) at out[q * out_stride_seq + h * out_stride_head + slot * d + j] (elements).
+ * Slots >= ws + count are left untouched. Entries of idx outside [0, S') are skipped.
+ */
+int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void* v, int64_t stride_token,
+                  int64_t stride_head, const int32_t* cu_seqlens, const int32_t* idx, const int32_t* counts,
+                  void* k_out, void* v_out, int64_t out_stride_seq, int64_t out_stride_head, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DKV_H */

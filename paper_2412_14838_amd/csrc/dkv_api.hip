@@ -1,0 +1,164 @@
+// C ABI entry points of libdkv.so: host-side validation, then the stage launchers.
+// The operations are those of Algorithm 1 of the paper (DynamicKV in Prefill Phase); see include/dkv.h.
+#include <math.h>
+#include "dkv_internal.h"
+
+namespace dkv {
+
+int validate_desc(const dkv_desc* d) {
+  if (d == nullptr) return DKV_ERR_INVALID_ARG;
+  if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->window < 1 || d->n_seqs < 1) return DKV_ERR_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads != 0) return DKV_ERR_INVALID_ARG;
+  if (d->pool_kernel < 1 || d->pool_kernel % 2 == 0) return DKV_ERR_INVALID_ARG;
+  if (d->layer_max < 1 || d->mean_budget < 1 || d->interval < 1) return DKV_ERR_INVALID_ARG;
+  if (d->total_tokens < 0 || d->max_seq_len < 0 || d->max_seq_len > d->total_tokens) return DKV_ERR_INVALID_ARG;
+  if (!(d->softmax_scale >= 0.0f) || !(d->row_scale >= 0.0f)) return DKV_ERR_INVALID_ARG;
+  if (d->dtype != DKV_F32 && d->dtype != DKV_BF16) return DKV_ERR_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 128) return DKV_ERR_UNSUPPORTED;
+  if (d->layer_max > DKV_MAX_LAYER_MAX || d->pool_kernel > DKV_MAX_POOL) return DKV_ERR_UNSUPPORTED;
+  if ((d->n_q_heads / d->n_kv_heads) * (int64_t)d->window > DKV_MAX_ROWS) return DKV_ERR_UNSUPPORTED;
+  if (d->n_seqs > DKV_MAX_SEQS || d->n_layers > DKV_MAX_LAYERS) return DKV_ERR_UNSUPPORTED;
+  // 64-bit budget arithmetic must not overflow: layer_max * (L * Hkv * S') and Z * B
+  if ((int64_t)d->n_layers * d->n_kv_heads * (int64_t)d->max_seq_len > (int64_t)1 << 31) return DKV_ERR_UNSUPPORTED;
+  return DKV_OK;
+}
+
+Params make_params(const dkv_desc& d) {
+  Params p{};
+  p.L = d.n_layers; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads;
+  p.d = d.head_dim; p.w = d.window; p.P = d.pool_kernel; p.half = (d.pool_kernel - 1) / 2;
+  p.layer_max = d.layer_max; p.mean_budget = d.mean_budget; p.interval = d.interval;
+  p.n_seqs = d.n_seqs; p.total_tokens = d.total_tokens; p.max_seq_len = d.max_seq_len;
+  p.rows = p.G * p.w; p.rows_pad = (p.rows + 63) / 64 * 64;
+  p.scale = d.softmax_scale > 0.0f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
+  p.row_scale = d.row_scale > 0.0f ? d.row_scale : 1.0f;
+  return p;
+}
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+static int check_workspace(const dkv_desc& d, const void* ws, size_t bytes, WorkspaceLayout& wl) {
+  wl = workspace_layout(d);
+  if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255) != 0 || bytes < wl.total) return DKV_ERR_WORKSPACE;
+  return DKV_OK;
+}
+
+static int check_kv_strides(const dkv_desc& d, int64_t stride_token, int64_t stride_head) {
+  const int64_t elt = d.dtype == DKV_BF16 ? 2 : 4;
+  if (stride_token < d.head_dim || stride_head < d.head_dim) return DKV_ERR_INVALID_ARG;
+  if ((stride_token * elt) % 16 != 0 || (stride_head * elt) % 16 != 0) return DKV_ERR_INVALID_ARG;
+  return DKV_OK;
+}
+
+}  // namespace dkv
+
+using namespace dkv;
+
+extern "C" {
+
+int dkv_version(void) { return DKV_VERSION; }
+
+const char* dkv_status_string(int status) {
+  switch (status) {
+    case DKV_OK: return "ok";
+    case DKV_ERR_INVALID_ARG: return "invalid argument";
+    case DKV_ERR_UNSUPPORTED: return "unsupported head_dim, dtype or size";
+    case DKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DKV_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t dkv_workspace_bytes(const dkv_desc* desc) {
+  if (validate_desc(desc) != DKV_OK) return 0;
+  return workspace_layout(*desc).total;
+}
+
+int dkv_workspace_init(const dkv_desc* desc, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  // the two ticket arrays (adjacent) are the only regions a call expects to find zeroed
+  const hipError_t e = launch_fill_zero(static_cast<char*>(workspace) + wl.counters, wl.lse - wl.counters,
+                                        static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                     int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                     int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!q_win || !k || !cu_seqlens || !scores_out) return DKV_ERR_INVALID_ARG;
+  if (!aligned16(q_win) || !aligned16(k)) return DKV_ERR_INVALID_ARG;
+  st = check_kv_strides(*desc, k_stride_token, k_stride_head);
+  if (st != DKV_OK) return st;
+  if (scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  if (desc->total_tokens == 0) return DKV_OK;
+  const Params p = make_params(*desc);
+  hipError_t e;
+  if (score_mfma_supported(p, desc->dtype)) {
+    e = launch_score_mfma(p, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+                          static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  } else {
+    e = launch_score_generic(p, desc->dtype, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  }
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,
+                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!scores || !cu_seqlens || !idx_out || !counts) return DKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= desc->n_layers) return DKV_ERR_INVALID_ARG;
+  if (scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_select(p, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
+                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!scores_all || !cu_seqlens || !counts) return DKV_ERR_INVALID_ARG;
+  if (layers_done < 1 || layers_done > desc->n_layers || layers_done % desc->interval != 0) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_rebalance(p, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out,
+                                        static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void* v, int64_t stride_token,
+                  int64_t stride_head, const int32_t* cu_seqlens, const int32_t* idx, const int32_t* counts,
+                  void* k_out, void* v_out, int64_t out_stride_seq, int64_t out_stride_head, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!k || !v || !cu_seqlens || !idx || !counts || !k_out || !v_out) return DKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= desc->n_layers) return DKV_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return DKV_ERR_INVALID_ARG;
+  st = check_kv_strides(*desc, stride_token, stride_head);
+  if (st != DKV_OK) return st;
+  const int64_t elt = desc->dtype == DKV_BF16 ? 2 : 4;
+  const int64_t block = (int64_t)(desc->window + desc->layer_max) * desc->head_dim;
+  if (out_stride_head < block || out_stride_seq < out_stride_head * desc->n_kv_heads) return DKV_ERR_INVALID_ARG;
+  if ((out_stride_head * elt) % 16 != 0 || (out_stride_seq * elt) % 16 != 0) return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_gather(p, (int)elt, layer, k, v, stride_token, stride_head, cu_seqlens, idx, counts,
+                                     k_out, v_out, out_stride_seq, out_stride_head, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+}  // extern "C"

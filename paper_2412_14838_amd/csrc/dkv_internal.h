@@ -1,0 +1,124 @@
+// Internal declarations shared by the translation units of libdkv.so (host side + device helpers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dkv.h"
+
+namespace dkv {
+
+// ----------------------------------------------------------------------------------------------
+// Tiling constants
+// ----------------------------------------------------------------------------------------------
+constexpr int kGenericKeys = 256;      // keys per workgroup in the generic (VALU) score kernels
+constexpr int kMfmaKeysStats = 256;    // keys per workgroup, MFMA row-statistics kernel
+constexpr int kMfmaKeysEmit = 256;     // keys computed per workgroup, MFMA score kernel (outputs = this - (P-1))
+constexpr int kRadixBins = 2048;       // 11-bit digits; 3 passes cover bits 31..21, 20..10, 9..0
+constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the rebalance histogram kernels
+
+// ----------------------------------------------------------------------------------------------
+// Workspace layout (byte offsets, all 256-byte aligned)
+// ----------------------------------------------------------------------------------------------
+struct WorkspaceLayout {
+  size_t counters;     // int32 [n_seqs][Hkv]            arrival tickets of the statistics kernel
+  size_t edge_counters;// int32 [chunks_max + 1][Hkv]    arrival tickets per chunk boundary (score kernel)
+  size_t lse;          // float [n_seqs][Hkv][rows_pad]  per-row log-sum-exp
+  size_t partials;     // float2 [chunks_max][Hkv][rows_pad]
+  size_t edges;        // float [chunks_max + 1][Hkv][128] raw sums next to each chunk boundary
+  size_t hist;         // int32 [3][n_seqs][L][kRadixBins]
+  size_t state;        // int32 [n_seqs][8]              radix-select state of the rebalance
+  size_t total;
+  int rows_pad;        // G*w rounded up to 64
+  int chunks_max;      // upper bound on statistics chunks over all sequences
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+inline int min_stats_keys() { return kGenericKeys < kMfmaKeysStats ? kGenericKeys : kMfmaKeysStats; }
+
+inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
+  WorkspaceLayout w{};
+  const int rows = (d.n_q_heads / d.n_kv_heads) * d.window;
+  w.rows_pad = (rows + 63) / 64 * 64;
+  w.chunks_max = d.total_tokens / min_stats_keys() + d.n_seqs;
+  size_t off = 0;
+  w.counters = off; off += align256(size_t(d.n_seqs) * d.n_kv_heads * sizeof(int32_t));
+  w.edge_counters = off; off += align256(size_t(w.chunks_max + 1) * d.n_kv_heads * sizeof(int32_t));
+  w.lse = off;      off += align256(size_t(d.n_seqs) * d.n_kv_heads * w.rows_pad * sizeof(float));
+  w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
+  w.edges = off;    off += align256(size_t(w.chunks_max + 1) * d.n_kv_heads * 128 * sizeof(float));
+  w.hist = off;     off += align256(size_t(3) * d.n_seqs * d.n_layers * kRadixBins * sizeof(int32_t));
+  w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+
+// Host-side descriptor validation shared by every entry point. Returns DKV_OK or a negative status.
+int validate_desc(const dkv_desc* d);
+
+// Resolved launch parameters handed to the kernels by value.
+struct Params {
+  int L, Hq, Hkv, G, d, w, P, half;   // half = (P-1)/2
+  int layer_max, mean_budget, interval;
+  int n_seqs, total_tokens, max_seq_len;
+  int rows;        // G*w
+  int rows_pad;
+  float scale;     // softmax scale
+  float row_scale;
+};
+
+Params make_params(const dkv_desc& d);
+
+// Stage launchers (defined next to their kernels). Each returns hipGetLastError() of its launches.
+hipError_t launch_score_generic(const Params& p, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
+                                int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
+                                char* ws, const WorkspaceLayout& wl, hipStream_t st);
+bool score_mfma_supported(const Params& p, int dtype);
+hipError_t launch_score_mfma(const Params& p, const void* q_win, const void* k, int64_t k_stride_token,
+                             int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
+                             char* ws, const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,
+                         const int32_t* cu, int32_t* idx_out, int32_t* counts, hipStream_t st);
+hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
+                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
+                            const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_gather(const Params& p, int elt_bytes, int layer, const void* k, const void* v, int64_t stride_token,
+                         int64_t stride_head, const int32_t* cu, const int32_t* idx, const int32_t* counts, void* k_out,
+                         void* v_out, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st);
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
+
+// ----------------------------------------------------------------------------------------------
+// Device helpers
+// ----------------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+// Maps a linear chunk index to (sequence, chunk within the sequence) when every sequence is cut into
+// chunks of `chunk` items and `window_off` is subtracted from each length first (0: all S keys,
+// w: the S' prefix positions). Returns false for indices past the last chunk (grids are sized by an
+// upper bound). A sequence whose item count is 0 owns no chunk.
+__device__ inline bool find_chunk(const int32_t* __restrict__ cu, int n_seqs, int chunk, int window_off, int b,
+                                  int& seq, int& c, int& seq_begin, int& seq_len) {
+  int begin = cu[0];
+  for (int s = 0; s < n_seqs; ++s) {
+    const int end = cu[s + 1];
+    const int len = end - begin;
+    int items = len - window_off;
+    items = items > 0 ? items : 0;
+    const int n = (items + chunk - 1) / chunk;
+    if (b < n) {
+      seq = s; c = b; seq_begin = begin; seq_len = len;
+      return true;
+    }
+    b -= n;
+    begin = end;
+  }
+  return false;
+}
+
+__device__ inline int chunks_of(int len, int window_off, int chunk) {
+  int items = len - window_off;
+  items = items > 0 ? items : 0;
+  return (items + chunk - 1) / chunk;
+}
+#endif
+
+}  // namespace dkv

@@ -1,0 +1,79 @@
+// Compaction of retained K/V rows (Algorithm 1, the two cat(K[:, :-ws].gather(indices), K[:, -ws:]) lines).
+// Pure streaming copy: every row slot is moved as 16-byte lane transfers, K and V in the same pass.
+#include "dkv_internal.h"
+
+namespace dkv {
+
+// One workgroup copies ROWS = 256 / LANES row slots of one (sequence, KV head); LANES lanes x 16 bytes = one row.
+// grid = (ceil((w + layer_max) / ROWS), Hkv, n_seqs).
+template <int LANES>
+__global__ __launch_bounds__(256) void gather_kernel(int w, int layer_max, int L, int layer, int row_bytes,
+                                                     const char* __restrict__ k, const char* __restrict__ v,
+                                                     int64_t stride_token_b, int64_t stride_head_b,
+                                                     const int32_t* __restrict__ cu, const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ counts, char* __restrict__ k_out,
+                                                     char* __restrict__ v_out, int64_t out_stride_seq_b,
+                                                     int64_t out_stride_head_b) {
+  constexpr int ROWS = 256 / LANES;
+  const int seq = blockIdx.z, head = blockIdx.y;
+  const int slot = blockIdx.x * ROWS + threadIdx.x / LANES;
+  const int lane = threadIdx.x % LANES;
+  if (slot >= w + layer_max || lane * 16 >= row_bytes) return;
+  const int begin = cu[seq];
+  const int S = cu[seq + 1] - begin;
+  const int prefix = S > w ? S - w : 0;
+  int src;
+  if (slot < w) {
+    src = S - w + slot;                 // window row; absent when the sequence is shorter than the window
+    if (src < 0) return;
+  } else {
+    const int j = slot - w;
+    int count = counts[seq * L + layer];
+    count = count < layer_max ? count : layer_max;
+    if (j >= count) return;
+    src = idx[((int64_t)seq * gridDim.y + head) * layer_max + j];
+    if (src < 0 || src >= prefix) return;
+  }
+  const int64_t in_off = (int64_t)(begin + src) * stride_token_b + (int64_t)head * stride_head_b + lane * 16;
+  const int64_t out_off = (int64_t)seq * out_stride_seq_b + (int64_t)head * out_stride_head_b +
+                          (int64_t)slot * row_bytes + lane * 16;
+  const uint4 kk = *reinterpret_cast<const uint4*>(k + in_off);
+  const uint4 vv = *reinterpret_cast<const uint4*>(v + in_off);
+  *reinterpret_cast<uint4*>(k_out + out_off) = kk;
+  *reinterpret_cast<uint4*>(v_out + out_off) = vv;
+}
+
+hipError_t launch_gather(const Params& p, int elt_bytes, int layer, const void* k, const void* v, int64_t stride_token,
+                         int64_t stride_head, const int32_t* cu, const int32_t* idx, const int32_t* counts, void* k_out,
+                         void* v_out, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st) {
+  const int row_bytes = p.d * elt_bytes;          // 128, 256 or 512
+  const int lanes = row_bytes / 16;               // 8, 16 or 32
+  const int slots = p.w + p.layer_max;
+  auto launch = [&](auto kernel, int LANES) {
+    const int rows = 256 / LANES;
+    dim3 grid((slots + rows - 1) / rows, p.Hkv, p.n_seqs);
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, layer, row_bytes,
+                       static_cast<const char*>(k), static_cast<const char*>(v), stride_token * elt_bytes,
+                       stride_head * elt_bytes, cu, idx, counts, static_cast<char*>(k_out), static_cast<char*>(v_out),
+                       out_stride_seq * elt_bytes, out_stride_head * elt_bytes);
+  };
+  if (lanes <= 8) launch(gather_kernel<8>, 8);
+  else if (lanes <= 16) launch(gather_kernel<16>, 16);
+  else launch(gather_kernel<32>, 32);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t n_words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
+  const size_t n_words = bytes / 4;
+  if (n_words == 0) return hipSuccess;
+  size_t blocks = (n_words + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint32_t*>(ptr), n_words);
+  return hipGetLastError();
+}
+
+}  // namespace dkv

@@ -1,0 +1,153 @@
+"""Thin ctypes binding over libdkv.so (argument marshalling only; every step runs in the HIP kernels).
+
+The functions carry the names of the C ABI (include/dkv.h).  torch is used for device memory and streams
+only: tensors are passed as raw device pointers, the current torch stream as the hipStream_t.
+There is no CPU fallback: a missing library or a failing call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdkv.so")
+
+DKV_F32, DKV_BF16 = 0, 1
+DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_workspace_init", "dkv_score_window",
+           "dkv_select_topk", "dkv_rebalance", "dkv_gather_kv")
+
+
+class dkv_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_q_heads", "n_kv_heads", "head_dim", "window", "pool_kernel",
+                                         "layer_max", "mean_budget", "interval", "dtype", "n_seqs", "total_tokens",
+                                         "max_seq_len")] + [("softmax_scale", C.c_float), ("row_scale", C.c_float)]
+
+
+class DkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.dkv_status_string(status).decode() if _lib is not None else "?"
+        super().__init__("%s: %s (%d)" % (where, msg, status))
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libdkv.so (built by paper_2412_14838_amd.build). Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError("libdkv.so not built: run `python -m paper_2412_14838_amd.build` (%s)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    D = C.POINTER(dkv_desc)
+    lib.dkv_version.restype = C.c_int
+    lib.dkv_version.argtypes = []
+    lib.dkv_status_string.restype = C.c_char_p
+    lib.dkv_status_string.argtypes = [C.c_int]
+    lib.dkv_workspace_bytes.restype = SZ
+    lib.dkv_workspace_bytes.argtypes = [D]
+    lib.dkv_workspace_init.restype = C.c_int
+    lib.dkv_workspace_init.argtypes = [D, P, SZ, P]
+    lib.dkv_score_window.restype = C.c_int
+    lib.dkv_score_window.argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
+    lib.dkv_select_topk.restype = C.c_int
+    lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P]
+    lib.dkv_rebalance.restype = C.c_int
+    lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
+    lib.dkv_gather_kv.restype = C.c_int
+    lib.dkv_gather_kv.argtypes = [D, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, P]
+    _lib = lib
+    return lib
+
+
+def make_desc(*, n_layers, n_q_heads, n_kv_heads, head_dim, window, pool_kernel, layer_max, mean_budget, interval,
+              dtype, n_seqs, total_tokens, max_seq_len, softmax_scale=0.0, row_scale=0.0) -> dkv_desc:
+    return dkv_desc(n_layers, n_q_heads, n_kv_heads, head_dim, window, pool_kernel, layer_max, mean_budget, interval,
+                    dtype, n_seqs, total_tokens, max_seq_len, softmax_scale, row_scale)
+
+
+def desc_from_workload(cfg, **override) -> dkv_desc:
+    kw = dict(n_layers=cfg.L, n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.d, window=cfg.w, pool_kernel=cfg.P,
+              layer_max=cfg.layer_max, mean_budget=cfg.mean_budget, interval=cfg.interval,
+              dtype=DKV_BF16 if cfg.dtype == "bf16" else DKV_F32, n_seqs=cfg.n_seqs, total_tokens=cfg.total_tokens,
+              max_seq_len=max(cfg.seqlens))
+    kw.update(override)
+    return make_desc(**kw)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != DKV_OK:
+        raise DkvError(status, where)
+
+
+def dkv_version() -> int:
+    return load().dkv_version()
+
+
+def dkv_status_string(status: int) -> str:
+    return load().dkv_status_string(status).decode()
+
+
+def dkv_workspace_bytes(desc: dkv_desc) -> int:
+    return int(load().dkv_workspace_bytes(C.byref(desc)))
+
+
+def dkv_workspace_init(desc, workspace, stream=None) -> None:
+    _check(load().dkv_workspace_init(C.byref(desc), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "dkv_workspace_init")
+
+
+def dkv_score_window(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+                     workspace, stream=None) -> None:
+    _check(load().dkv_score_window(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head, _ptr(cu_seqlens),
+                                   _ptr(scores_out), scores_stride_head, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_score_window")
+
+
+def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts, stream=None) -> None:
+    _check(load().dkv_select_topk(C.byref(desc), layer, _ptr(scores), scores_stride_head, _ptr(cu_seqlens),
+                                  _ptr(idx_out), _ptr(counts), _stream(stream)), "dkv_select_topk")
+
+
+def dkv_rebalance(desc, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out, workspace,
+                  stream=None) -> None:
+    _check(load().dkv_rebalance(C.byref(desc), layers_done, _ptr(scores_all), _ptr(cu_seqlens), _ptr(counts),
+                                _ptr(budgets_out), _ptr(hits_out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_rebalance")
+
+
+def dkv_gather_kv(desc, layer, k, v, stride_token, stride_head, cu_seqlens, idx, counts, k_out, v_out, out_stride_seq,
+                  out_stride_head, stream=None) -> None:
+    _check(load().dkv_gather_kv(C.byref(desc), layer, _ptr(k), _ptr(v), stride_token, stride_head, _ptr(cu_seqlens),
+                                _ptr(idx), _ptr(counts), _ptr(k_out), _ptr(v_out), out_stride_seq, out_stride_head,
+                                _stream(stream)), "dkv_gather_kv")
+
+
+def alloc_workspace(desc, device="cuda"):
+    """Allocate (torch) and initialise the workspace the stage calls need."""
+    import torch
+    n = dkv_workspace_bytes(desc)
+    if n == 0:
+        raise DkvError(DKV_ERR_INVALID_ARG, "dkv_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    dkv_workspace_init(desc, ws)
+    return ws

@@ -1,0 +1,82 @@
+"""Driver of Algorithm 1's layer loop over the C ABI: owns the device buffers, issues the stage calls.
+
+No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (all torch device tensors):
+    scores   fp32  [L][Hkv][T]                 A^b, pooled scores of every processed layer
+    idx      int32 [L][n_seqs][Hkv][layer_max] ordered candidates of every layer
+    counts   int32 [n_seqs][L]                 retained prefix rows per KV head
+    budgets  int32 [n_seqs][L]                 Z' of the latest update;  hits: cnt of the latest update
+    kb, vb   [L][n_seqs][Hkv][w + layer_max][d] compressed cache: window rows first, then retained rows;
+             layer i of sequence q holds w + counts[q][i] valid rows per head.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import dkv
+
+
+class Compressor:
+    def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None):
+        self.cfg = cfg
+        self.device = device
+        self.desc = dkv.desc_from_workload(cfg, **(desc_override or {}))
+        self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        L, Hkv, T, d = cfg.L, cfg.Hkv, cfg.total_tokens, cfg.d
+        self.slots = cfg.w + cfg.layer_max
+        self.cu = torch.tensor(cfg.cu_seqlens, dtype=torch.int32, device=device)
+        self.scores = torch.zeros((L, Hkv, T), dtype=torch.float32, device=device)
+        self.idx = torch.full((L, cfg.n_seqs, Hkv, cfg.layer_max), -1, dtype=torch.int32, device=device)
+        self.counts = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
+        self.budgets = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
+        self.hits = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
+        self.keep_cache = keep_cache
+        if keep_cache:
+            self.kb = torch.zeros((L, cfg.n_seqs, Hkv, self.slots, d), dtype=self.tdtype, device=device)
+            self.vb = torch.zeros_like(self.kb)
+        self.ws = dkv.alloc_workspace(self.desc, device)
+
+    # one layer of Algorithm 1's loop: score, select, gather, and the update every `interval` layers
+    def score(self, layer, q_win, k, stride_token=None, stride_head=None, stream=None):
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_score_window(self.desc, q_win, k, st, sh, self.cu, self.scores[layer], self.cfg.total_tokens, self.ws,
+                             stream)
+
+    def select(self, layer, stream=None):
+        dkv.dkv_select_topk(self.desc, layer, self.scores[layer], self.cfg.total_tokens, self.cu, self.idx[layer],
+                            self.counts, stream)
+
+    def gather(self, layer, k, v, stride_token=None, stride_head=None, stream=None):
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_gather_kv(self.desc, layer, k, v, st, sh, self.cu, self.idx[layer], self.counts, self.kb[layer],
+                          self.vb[layer], self.cfg.Hkv * self.slots * d, self.slots * d, stream)
+
+    def rebalance(self, layers_done, stream=None):
+        dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
+                          stream)
+
+    def step(self, layer, q_win, k, v, **strides):
+        self.score(layer, q_win, k, **strides)
+        self.select(layer)
+        if self.keep_cache:
+            self.gather(layer, k, v, **strides)
+        if (layer + 1) % self.cfg.interval == 0:
+            self.rebalance(layer + 1)
+
+    def run(self, layers):
+        """layers: sequence of (q_win, k, v) device tensors, one per layer."""
+        for l, (q, k, v) in enumerate(layers):
+            self.step(l, q, k, v)
+
+
+def to_device(cfg, layer_data, device="cuda"):
+    """Upload one make_layer() result in the workload's storage type (values are exactly representable)."""
+    tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    out = {}
+    for name in ("q_win", "k", "v"):
+        if name in layer_data:
+            out[name] = torch.from_numpy(layer_data[name]).to(device=device, dtype=tdtype).contiguous()
+    return out

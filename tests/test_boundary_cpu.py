@@ -1,0 +1,119 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/dkv.h declares, sizes its
+workspace and rejects bad arguments before anything is launched (no GPU needed, no compute calls)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2412_14838_amd import dkv
+from paper_2412_14838_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return dkv.load()
+
+
+def _good(**kw):
+    base = dict(n_layers=4, n_q_heads=4, n_kv_heads=2, head_dim=64, window=16, pool_kernel=7, layer_max=256,
+                mean_budget=128, interval=2, dtype=dkv.DKV_F32, n_seqs=1, total_tokens=1024, max_seq_len=1024)
+    base.update(kw)
+    return dkv.make_desc(**base)
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "dkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(dkv_[a-z_]+)\s*\(", text))
+    assert declared == set(dkv.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.dkv_version() == 1
+    assert dkv.dkv_status_string(0) == "ok" and "workspace" in dkv.dkv_status_string(dkv.DKV_ERR_WORKSPACE)
+
+
+def test_descriptor_struct_matches_header():
+    text = open(os.path.join(ROOT, "include", "dkv.h")).read()
+    body = re.search(r"typedef struct dkv_desc \{(.*?)\} dkv_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(int32_t|float)\s+(\w+);", body)
+    assert [n for _, n in fields] == [n for n, _ in dkv.dkv_desc._fields_]
+    assert C.sizeof(dkv.dkv_desc) == 4 * len(fields)
+
+
+def test_workspace_bytes(lib):
+    for cfg in W.standard_configs().values():
+        n = dkv.dkv_workspace_bytes(dkv.desc_from_workload(cfg))
+        assert n > 0 and n % 256 == 0 and n < 1 << 30
+    assert dkv.dkv_workspace_bytes(_good(n_q_heads=5)) == 0
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(n_q_heads=5), dkv.DKV_ERR_INVALID_ARG),           # Hq % Hkv
+    (dict(pool_kernel=4), dkv.DKV_ERR_INVALID_ARG),         # even pooling kernel
+    (dict(pool_kernel=0), dkv.DKV_ERR_INVALID_ARG),
+    (dict(window=0), dkv.DKV_ERR_INVALID_ARG),
+    (dict(layer_max=0), dkv.DKV_ERR_INVALID_ARG),
+    (dict(interval=0), dkv.DKV_ERR_INVALID_ARG),
+    (dict(max_seq_len=2048), dkv.DKV_ERR_INVALID_ARG),      # longer than total
+    (dict(softmax_scale=-1.0), dkv.DKV_ERR_INVALID_ARG),
+    (dict(head_dim=80), dkv.DKV_ERR_UNSUPPORTED),
+    (dict(dtype=7), dkv.DKV_ERR_UNSUPPORTED),
+    (dict(layer_max=1 << 20), dkv.DKV_ERR_UNSUPPORTED),
+    (dict(pool_kernel=129), dkv.DKV_ERR_UNSUPPORTED),
+    (dict(n_q_heads=64, n_kv_heads=2, window=32), dkv.DKV_ERR_UNSUPPORTED),   # G * w > 256 rows
+])
+def test_bad_descriptors_are_rejected(lib, bad, status):
+    d = _good(**bad)
+    fake = C.c_void_p(0x1000)
+    assert lib.dkv_workspace_init(C.byref(d), fake, 1 << 30, None) == status
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 64 * 1024, fake, fake, 1024, fake, 1 << 30, None) == status
+    assert lib.dkv_select_topk(C.byref(d), 0, fake, 1024, fake, fake, fake, None) == status
+    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 1 << 30, None) == status
+    assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64,
+                             272 * 64, None) == status
+
+
+def test_bad_call_arguments_are_rejected(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    odd = C.c_void_p(0x1004)
+    inv, wsp = dkv.DKV_ERR_INVALID_ARG, dkv.DKV_ERR_WORKSPACE
+    # null pointers
+    assert lib.dkv_score_window(C.byref(d), None, fake, 64, 65536, fake, fake, 1024, fake, need, None) == inv
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, None, fake, 1024, fake, need, None) == inv
+    assert lib.dkv_select_topk(C.byref(d), 0, None, 1024, fake, fake, fake, None) == inv
+    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, None, None, None, fake, need, None) == inv
+    assert lib.dkv_gather_kv(C.byref(d), 0, fake, None, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64, 272 * 64,
+                             None) == inv
+    assert lib.dkv_workspace_bytes(None) == 0
+    # misaligned pointers / strides
+    assert lib.dkv_score_window(C.byref(d), fake, odd, 64, 65536, fake, fake, 1024, fake, need, None) == inv
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 65, 65536, fake, fake, 1024, fake, need, None) == inv
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 32, 65536, fake, fake, 1024, fake, need, None) == inv
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1000, fake, need, None) == inv
+    # workspace missing, too small or misaligned
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, None, need, None) == wsp
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, fake, need - 1, None) == wsp
+    assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, C.c_void_p(0x1010), need, None) == wsp
+    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 16, None) == wsp
+    # layer / layers_done out of range or not a multiple of the interval
+    assert lib.dkv_select_topk(C.byref(d), 4, fake, 1024, fake, fake, fake, None) == inv
+    assert lib.dkv_select_topk(C.byref(d), -1, fake, 1024, fake, fake, fake, None) == inv
+    for bad_l in (0, 1, 3, 6):
+        assert lib.dkv_rebalance(C.byref(d), bad_l, fake, fake, fake, None, None, fake, need, None) == inv
+    # output block too small for window + layer_max rows
+    assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 100 * 64, 100 * 64,
+                             None) == inv
+    assert lib.dkv_gather_kv(C.byref(d), 9, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64, 272 * 64,
+                             None) == inv
+
+
+def test_binding_raises_on_error():
+    d = _good(pool_kernel=2)
+    with pytest.raises(dkv.DkvError):
+        dkv._check(dkv.load().dkv_select_topk(C.byref(d), 0, None, 0, None, None, None, None), "dkv_select_topk")

@@ -1,0 +1,283 @@
+"""GPU parity tests, stage by stage, through the C ABI against the CPU oracle.
+
+Every stage is fed the SAME input on both sides: scores are compared within the stated tolerance, and the
+integer-valued stages (selection, budgets, gathered rows) run the oracle on the GPU's own fp32 scores, so they
+are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dkv_oracle as O
+from paper_2412_14838_amd import workloads as W
+from paper_2412_14838_amd.pipeline import Compressor, to_device
+
+pytestmark = pytest.mark.gpu
+
+SCORE_RTOL = 2e-3      # pooled scores, relative (fp32 accumulation on the GPU, float64 in the oracle)
+
+
+def small_cfg(name="small_bf16", **kw):
+    base = dict(name=name, L=4, Hq=8, Hkv=2, d=128, seqlens=(1500,), dtype="bf16", w=32, P=7, mean_budget=64,
+                layer_max=160, interval=2, seed=77, plant="loguniform", plant_lo=4, plant_hi=40, gain=3.0,
+                plant_normalize=True)
+    base.update(kw)
+    return W.Workload(**base)
+
+
+CASES = {
+    "tiny": W.standard_configs()["tiny"],
+    "tiny_norm": W.standard_configs()["tiny"].with_(plant_normalize=True),
+    "small_bf16": small_cfg(),
+    "small_bf16_gqa7": small_cfg("gqa7", Hq=14, Hkv=2, seqlens=(1111,)),
+    "small_bf16_d64": small_cfg("d64", d=64, seqlens=(700,)),
+    "ragged_f32": small_cfg("ragged_f32", dtype="f32", d=64, Hq=4, Hkv=2, w=16, seqlens=(300, 17, 16, 1000, 259), L=2,
+                            interval=2, layer_max=100, mean_budget=30),
+    "ragged_bf16": small_cfg("ragged_bf16", seqlens=(700, 33, 32, 2049, 517), L=2, interval=1),
+    "pool1": small_cfg("pool1", P=1, seqlens=(600,)),
+    "pool15": small_cfg("pool15", P=15, seqlens=(900,)),
+}
+
+
+def oracle_scores(cfg, data):
+    """List over sequences of A [Hkv, S'] float32."""
+    cu = cfg.cu_seqlens
+    return [O.score_window(data["q_win"][s], data["k"][:, cu[s]:cu[s + 1]], cfg.P) for s in range(cfg.n_seqs)]
+
+
+def assert_scores_close(cfg, got, ref_list):
+    cu = cfg.cu_seqlens
+    for s in range(cfg.n_seqs):
+        n = cfg.seqlens[s] - cfg.w
+        assert np.isneginf(got[:, cu[s] + max(n, 0):cu[s + 1]]).all() or n <= 0
+        if n <= 0:
+            continue
+        g = got[:, cu[s]:cu[s] + n]
+        r = ref_list[s]
+        assert np.isfinite(g).all()
+        rel = np.abs(g - r) / np.maximum(np.abs(r), 1e-30)
+        assert rel.max() <= SCORE_RTOL, (s, rel.max())
+        assert np.isneginf(got[:, cu[s] + n:cu[s + 1]]).all()     # guard over the window slots
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_score_window_matches_oracle(dkv, case):
+    cfg = CASES[case]
+    comp = Compressor(cfg, keep_cache=False)
+    for layer in range(min(cfg.L, 2)):
+        data = W.make_layer(cfg, layer, with_v=False)
+        dev = to_device(cfg, data)
+        comp.score(layer, dev["q_win"], dev["k"])
+        torch.cuda.synchronize()
+        assert_scores_close(cfg, comp.scores[layer].cpu().numpy(), oracle_scores(cfg, data))
+
+
+def test_score_window_token_major_strides_and_determinism(dkv):
+    """K laid out [T][Hkv][d] (token-major) gives bit-identical scores to the head-major layout, run after run."""
+    cfg = CASES["small_bf16"]
+    data = W.make_layer(cfg, 0, with_v=False)
+    dev = to_device(cfg, data)
+    comp = Compressor(cfg, keep_cache=False)
+    comp.score(0, dev["q_win"], dev["k"])
+    a = comp.scores[0].clone()
+    k_tm = dev["k"].permute(1, 0, 2).contiguous()
+    comp.score(1, dev["q_win"], k_tm, stride_token=cfg.Hkv * cfg.d, stride_head=cfg.d)
+    comp.score(2, dev["q_win"], dev["k"])
+    torch.cuda.synchronize()
+    assert torch.equal(a, comp.scores[1]) and torch.equal(a, comp.scores[2])
+
+
+def test_score_scale_overrides(dkv):
+    cfg = CASES["tiny"]
+    data = W.make_layer(cfg, 0, with_v=False)
+    dev = to_device(cfg, data)
+    comp = Compressor(cfg, keep_cache=False, desc_override=dict(softmax_scale=0.25, row_scale=1.0 / cfg.w))
+    comp.score(0, dev["q_win"], dev["k"])
+    torch.cuda.synchronize()
+    ref = O.score_window(data["q_win"][0], data["k"], cfg.P, scale=0.25, row_scale=1.0 / cfg.w)
+    assert_scores_close(cfg, comp.scores[0].cpu().numpy(), [ref])
+
+
+def _tie_heavy_scores(cfg, seed):
+    rng = np.random.default_rng(seed)
+    T = cfg.total_tokens
+    kinds = [rng.integers(0, 6, size=(cfg.Hkv, T)).astype(np.float32) / 8,          # few distinct values
+             np.abs(rng.standard_normal((cfg.Hkv, T))).astype(np.float32),           # all distinct
+             np.full((cfg.Hkv, T), 0.125, dtype=np.float32),                         # one value
+             np.zeros((cfg.Hkv, T), dtype=np.float32)]
+    kinds.append(np.maximum.reduce([np.roll(kinds[1], r, axis=1) for r in range(-3, 4)]))  # pooled plateaus
+    sub = np.abs(rng.standard_normal((cfg.Hkv, T))).astype(np.float32) * np.float32(1e-41)   # subnormals
+    kinds.append(sub)
+    return kinds
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged_bf16", "small_bf16"])
+def test_select_topk_bit_exact(dkv, case):
+    cfg = CASES[case]
+    comp = Compressor(cfg, keep_cache=False)
+    cu = cfg.cu_seqlens
+    for n, A in enumerate(_tie_heavy_scores(cfg, 5)):
+        layer = n % cfg.L
+        comp.scores[layer].copy_(torch.from_numpy(A))
+        comp.idx[layer].fill_(-7)
+        comp.select(layer)
+        torch.cuda.synchronize()
+        idx = comp.idx[layer].cpu().numpy()
+        counts = comp.counts.cpu().numpy()
+        for s in range(cfg.n_seqs):
+            pre = cfg.seqlens[s] - cfg.w
+            ref = O.select_topk(A[:, cu[s]:cu[s] + pre], cfg.layer_max)
+            k = ref.shape[1]
+            assert counts[s, layer] == k == min(cfg.layer_max, pre)
+            assert np.array_equal(idx[s][:, :k], ref)
+            assert (idx[s][:, k:] == -1).all()
+
+
+def test_select_topk_large_k_and_long_rows(dkv):
+    """Maximum layer_max, a 40000-position row, k > S' and k == S'."""
+    cfg = small_cfg("long", Hq=2, Hkv=2, seqlens=(40000, 4096 + 32, 3000), layer_max=4096, mean_budget=512, L=1,
+                    interval=1)
+    comp = Compressor(cfg, keep_cache=False)
+    cu = cfg.cu_seqlens
+    A = np.abs(np.random.default_rng(3).standard_normal((cfg.Hkv, cfg.total_tokens))).astype(np.float32)
+    n5 = (cfg.total_tokens - 1) // 5
+    A[:, 0:5 * n5:5] = A[:, 1:5 * n5 + 1:5]                 # exact ties between neighbours
+    comp.scores[0].copy_(torch.from_numpy(A))
+    comp.select(0)
+    torch.cuda.synchronize()
+    idx = comp.idx[0].cpu().numpy()
+    for s in range(cfg.n_seqs):
+        pre = cfg.seqlens[s] - cfg.w
+        ref = O.select_topk(A[:, cu[s]:cu[s] + pre], cfg.layer_max)
+        assert np.array_equal(idx[s][:, :ref.shape[1]], ref)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged_f32", "small_bf16_d64"])
+def test_gather_kv_bit_exact(dkv, case):
+    cfg = CASES[case]
+    comp = Compressor(cfg)
+    data = W.make_layer(cfg, 0)
+    dev = to_device(cfg, data)
+    comp.score(0, dev["q_win"], dev["k"])
+    comp.select(0)
+    comp.kb.fill_(-5.0)
+    comp.vb.fill_(-5.0)
+    comp.gather(0, dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    kb, vb = comp.kb[0].float().cpu().numpy(), comp.vb[0].float().cpu().numpy()
+    idx, counts = comp.idx[0].cpu().numpy(), comp.counts.cpu().numpy()
+    cu, w = cfg.cu_seqlens, cfg.w
+    for s in range(cfg.n_seqs):
+        n = counts[s, 0]
+        k_s, v_s = data["k"][:, cu[s]:cu[s + 1]], data["v"][:, cu[s]:cu[s + 1]]
+        ref_k, ref_v = O.gather_kv(k_s, v_s, idx[s][:, :n], w)      # paper order: selected rows, then window
+        assert np.array_equal(kb[s][:, w:w + n], ref_k[:, :n]) and np.array_equal(kb[s][:, :w], ref_k[:, n:])
+        assert np.array_equal(vb[s][:, w:w + n], ref_v[:, :n]) and np.array_equal(vb[s][:, :w], ref_v[:, n:])
+        assert (kb[s][:, w + n:] == -5.0).all() and (vb[s][:, w + n:] == -5.0).all()   # untouched slots
+
+
+def test_gather_kv_token_major(dkv):
+    cfg = CASES["small_bf16"]
+    comp = Compressor(cfg)
+    data = W.make_layer(cfg, 0)
+    dev = to_device(cfg, data)
+    comp.score(0, dev["q_win"], dev["k"])
+    comp.select(0)
+    comp.gather(0, dev["k"], dev["v"])
+    a_k, a_v = comp.kb[0].clone(), comp.vb[0].clone()
+    k_tm, v_tm = dev["k"].permute(1, 0, 2).contiguous(), dev["v"].permute(1, 0, 2).contiguous()
+    torch.cuda.synchronize()
+    comp.counts[0, 1] = int(comp.counts[0, 0])
+    comp.idx[1].copy_(comp.idx[0])
+    comp.gather(1, k_tm, v_tm, stride_token=cfg.Hkv * cfg.d, stride_head=cfg.d)
+    torch.cuda.synchronize()
+    assert torch.equal(a_k, comp.kb[1]) and torch.equal(a_v, comp.vb[1])
+
+
+def _oracle_on_gpu_scores(cfg, scores):
+    """Run the oracle's selection and budget steps on the GPU's own fp32 scores, per sequence."""
+    cu = cfg.cu_seqlens
+    out = []
+    for s in range(cfg.n_seqs):
+        pre = cfg.seqlens[s] - cfg.w
+        A = [scores[l][:, cu[s]:cu[s] + pre] for l in range(cfg.L)]
+        out.append(O.compress([(None, None, None)] * cfg.L, cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget,
+                              cfg.interval, scores_override=A, keep_buffers=False))
+    return out
+
+
+@pytest.mark.parametrize("case", ["tiny", "tiny_norm", "small_bf16", "ragged_bf16", "ragged_f32"])
+def test_pipeline_selection_and_budgets_bit_exact(dkv, case):
+    """Whole loop on the GPU; the oracle repeats selection + updates on the GPU's scores: everything integer
+    (ordered indices, per-update hit counts and budgets, final counts) must agree bit for bit."""
+    cfg = CASES[case]
+    comp = Compressor(cfg)
+    snapshots = {}
+    for l in range(cfg.L):
+        dev = to_device(cfg, W.make_layer(cfg, l))
+        comp.step(l, dev["q_win"], dev["k"], dev["v"])
+        if (l + 1) % cfg.interval == 0:
+            torch.cuda.synchronize()
+            snapshots[l + 1] = (comp.hits.cpu().numpy().copy(), comp.budgets.cpu().numpy().copy())
+    torch.cuda.synchronize()
+    scores = comp.scores.cpu().numpy()
+    ref = _oracle_on_gpu_scores(cfg, scores)
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    for s in range(cfg.n_seqs):
+        r = ref[s]
+        for l in range(cfg.L):
+            k = r.idx[l].shape[1]
+            assert np.array_equal(idx[l, s][:, :k], r.idx[l])
+        for (l, cnt, Z, Zp) in r.budgets:
+            hits, budgets = snapshots[l]
+            assert np.array_equal(hits[s, :l], cnt) and np.array_equal(budgets[s, :l], np.minimum(Zp, 2**31 - 1))
+        assert counts[s].tolist() == r.n
+
+
+def test_rebalance_skewed_and_tied_scores(dkv):
+    """Synthetic score tensors that stress the global selection: all mass in one layer, bit-equal scores in
+    every layer (ties resolved toward earlier layers), and a two-level mix."""
+    cfg = small_cfg("reb", L=4, interval=4, Hq=2, Hkv=2, seqlens=(900, 500), layer_max=128, mean_budget=40)
+    cu = cfg.cu_seqlens
+    rng = np.random.default_rng(9)
+    T = cfg.total_tokens
+    variants = []
+    a = np.zeros((cfg.L, cfg.Hkv, T), dtype=np.float32); a[2] = 1.0
+    variants.append(a)
+    variants.append(np.full((cfg.L, cfg.Hkv, T), 0.5, dtype=np.float32))
+    variants.append((rng.integers(0, 3, size=(cfg.L, cfg.Hkv, T)) / 2).astype(np.float32))
+    variants.append(np.abs(rng.standard_normal((cfg.L, cfg.Hkv, T))).astype(np.float32) * np.array([1, 3, 0.2, 1], dtype=np.float32)[:, None, None])
+    for A in variants:
+        comp = Compressor(cfg, keep_cache=False)
+        comp.scores.copy_(torch.from_numpy(A))
+        for l in range(cfg.L):
+            comp.select(l)
+        comp.rebalance(cfg.L)
+        torch.cuda.synchronize()
+        hits, budgets, counts = comp.hits.cpu().numpy(), comp.budgets.cpu().numpy(), comp.counts.cpu().numpy()
+        for s in range(cfg.n_seqs):
+            pre = cfg.seqlens[s] - cfg.w
+            A_list = [A[l][:, cu[s]:cu[s] + pre] for l in range(cfg.L)]
+            cnt, Z, Zp = O.update_buffer_length(A_list, cfg.layer_max, cfg.mean_budget, cfg.L)
+            assert np.array_equal(hits[s], cnt) and np.array_equal(budgets[s], Zp)
+            assert counts[s].tolist() == [min(min(cfg.layer_max, pre), int(z)) for z in Zp]
+
+
+def test_sequence_not_longer_than_window(dkv):
+    """S == w: no candidates, count 0, only the window rows are copied; S < w is tolerated (no access out of bounds)."""
+    cfg = small_cfg("short", seqlens=(32, 200, 20), L=1, interval=1, layer_max=64, mean_budget=16)
+    comp = Compressor(cfg)
+    data = W.make_layer(cfg.with_(plant_lo=1, plant_hi=1), 0)
+    dev = to_device(cfg, data)
+    comp.kb.fill_(-5.0)
+    comp.step(0, dev["q_win"], dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    counts = comp.counts.cpu().numpy()
+    assert counts[0, 0] == 0 and counts[2, 0] == 0 and 0 < counts[1, 0] <= 64
+    kb = comp.kb[0].float().cpu().numpy()
+    cu = cfg.cu_seqlens
+    assert np.array_equal(kb[0][:, :32], data["k"][:, cu[0]:cu[1]])
+    assert (kb[0][:, 32:] == -5.0).all()
+    # 20 tokens < window 32: the existing rows land in the last 20 window slots
+    assert (kb[2][:, :12] == -5.0).all() and (kb[2][:, 32:] == -5.0).all()
+    assert np.array_equal(kb[2][:, 12:32], data["k"][:, cu[2]:cu[3]])
