@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the DynamicKV prefill-compression hot path on one MI355X.
+
+A step = one pass of Algorithm 1's layer loop over one synthetic batch: for every layer score (two kernels),
+select, gather, and the progressive update every `interval` layers.  All inputs are resident in HBM before
+the timed region.  Prints ONE JSON line: context tokens compressed per second, the roofline of the dominant
+kernel (timed live with events on the launch stream) and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import concurrent.futures as cf
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def _cpu_baseline(cfg, host_layers, n_layers):
+    """The oracle as it stands on the first `n_layers` layers (one progressive update included)."""
+    from oracle import dkv_oracle as O
+    cu = cfg.cu_seqlens
+    t0 = time.perf_counter()
+    for s in range(cfg.n_seqs):
+        layers = [(d["q_win"][s], d["k"][:, cu[s]:cu[s + 1]], d["v"][:, cu[s]:cu[s + 1]]) for d in host_layers[:n_layers]]
+        O.compress(layers, cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    tokens_per_s = cfg.total_tokens / (dt * cfg.L / n_layers)
+    return {"value": tokens_per_s, "unit": "context tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of %d layers of the same workload (scoring, selection, gather, one progressive update), "
+                      "%.1f s of CPU time, scaled by L/%d" % (n_layers, cfg.L, dt, n_layers)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mistral_7b_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures ONE GPU (the path has no cross-GPU step); run with --gpus 1")
+
+    import torch
+    from paper_2412_14838_amd import dkv, workloads as W
+    from paper_2412_14838_amd.pipeline import Compressor, to_device
+
+    dkv.load()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cfg = W.standard_configs()[args.workload]
+    workers = min(16, len(os.sched_getaffinity(0)))
+    dev, host_sample = [], []
+    with cf.ThreadPoolExecutor(max_workers=workers) as ex:
+        for l, data in enumerate(ex.map(lambda l: W.make_layer(cfg, l), range(cfg.L))):
+            dev.append(to_device(cfg, data))
+            if l < cfg.interval and not args.no_cpu_baseline:
+                host_sample.append(data)
+    torch.cuda.synchronize()
+
+    comp = Compressor(cfg)
+    d, T = cfg.d, cfg.total_tokens
+    st, sh = d, T * d
+    desc, cu, ws = comp.desc, comp.cu, comp.ws
+    names = ("score_stats", "score_emit", "select", "gather", "rebalance")
+    layers = [(x["q_win"], x["k"], x["v"]) for x in dev]
+
+    # ---- throughput: the whole loop as one HIP graph, K replays between two synchronisations
+    for _ in range(max(args.warmup, 1)):
+        comp.run(layers)
+    torch.cuda.synchronize()
+    graph = comp.capture(layers)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+
+    # ---- per-kernel durations: the same K steps launched eagerly with an event between any two calls.
+    # The GPU is first given a few ms of unrelated work so that the host has enqueued the whole step before
+    # the first kernel starts: every event-to-event span then holds kernel time only, not launch latency.
+    def one_step(events):
+        for l in range(cfg.L):
+            q, k, v = layers[l]
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+            ev[0].record()
+            dkv.dkv_score_window_stats(desc, q, k, st, sh, cu, comp.scores[l], T, ws)
+            ev[1].record()
+            dkv.dkv_score_window_emit(desc, q, k, st, sh, cu, comp.scores[l], T, ws)
+            ev[2].record()
+            comp.select(l)
+            ev[3].record()
+            comp.gather(l, k, v)
+            ev[4].record()
+            if (l + 1) % cfg.interval == 0:
+                comp.rebalance(l + 1)
+            ev[5].record()
+            events.append(ev)
+
+    ballast = torch.randn((8192, 8192), device="cuda", dtype=torch.bfloat16)
+    t0 = time.perf_counter()
+    one_step([])
+    enqueue_ms = (time.perf_counter() - t0) * 1e3
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); torch.mm(ballast, ballast); e1.record()
+    torch.cuda.synchronize()
+    n_ballast = int(2.0 * enqueue_ms / max(e0.elapsed_time(e1), 0.05)) + 2
+    events = []
+    for _ in range(args.steps):
+        for _ in range(n_ballast):
+            torch.mm(ballast, ballast)
+        one_step(events)
+        torch.cuda.synchronize()
+
+    stage_ms = {n: 0.0 for n in names}
+    launches = {n: 0 for n in names}
+    for i, ev in enumerate(events):
+        layer = i % cfg.L
+        for j, n in enumerate(names):
+            if n == "rebalance" and (layer + 1) % cfg.interval != 0:
+                continue
+            stage_ms[n] += ev[j].elapsed_time(ev[j + 1])
+            launches[n] += 1
+    stage_us_per_launch = {n: (1e3 * stage_ms[n] / launches[n] if launches[n] else 0.0) for n in names}
+    stage_ms_per_step = {n: stage_ms[n] / args.steps for n in names}
+
+    # ---- roofline of the dominant kernel: algorithmic bytes per launch / its average duration
+    elt = 2 if cfg.dtype == "bf16" else 4
+    k_bytes = cfg.Hkv * T * d * elt                 # every key row read once per sweep
+    q_bytes = cfg.n_seqs * cfg.Hq * cfg.w * d * elt
+    a_bytes = cfg.Hkv * T * 4                       # pooled fp32 scores written
+    alg = {"score_stats": k_bytes + q_bytes, "score_emit": k_bytes + q_bytes + a_bytes}
+    dom = max(alg, key=lambda n: stage_us_per_launch[n])
+    achieved = alg[dom] / (stage_us_per_launch[dom] * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(cfg.name, {}).get(dom)
+        except Exception:
+            traffic = None
+    score_us = stage_us_per_launch["score_stats"] + stage_us_per_launch["score_emit"]
+    flops_per_sweep = 2.0 * cfg.Hq * cfg.w * T * d
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "bytes_per_launch": alg[dom], "us_per_launch": stage_us_per_launch[dom],
+                # the whole score step (K counted ONCE although both sweeps read it) and its MFMA rate
+                "score_step": {"us_per_layer": score_us,
+                               "hbm_frac_k_once": (k_bytes + q_bytes + a_bytes) / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                               "mfma_tflops": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12,
+                               "mfma_frac": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+
+    out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
+           "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": cfg.dtype, "data": "synthetic",
+           "config": {"workload": cfg.name, "layers": cfg.L, "q_heads": cfg.Hq, "kv_heads": cfg.Hkv, "head_dim": d,
+                      "context": list(cfg.seqlens), "window": cfg.w, "pool": cfg.P, "mean_budget": cfg.mean_budget,
+                      "layer_max": cfg.layer_max, "interval": cfg.interval},
+           "roofline": roofline,
+           "stage_ms_per_step": stage_ms_per_step, "stage_us_per_launch": stage_us_per_launch}
+    out["eager_enqueue_ms_per_step"] = enqueue_ms
+    if host_sample:
+        out["cpu_baseline"] = _cpu_baseline(cfg, host_sample, cfg.interval)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -75,12 +75,9 @@ int dkv_version(void);
 const char* dkv_status_string(int status);
 
 /* Bytes of device workspace the stage calls need for this descriptor (0 if the descriptor is invalid).
- * Host only, launches nothing. The workspace must be 256-byte aligned. */
+ * Host only, launches nothing. The workspace must be 256-byte aligned; it needs no initialisation and carries
+ * nothing from one stage call to the next, except from dkv_score_window_stats to dkv_score_window_emit. */
 size_t dkv_workspace_bytes(const dkv_desc* desc);
-
-/* Zero the workspace's counters. Call once after allocating the workspace (and again after any call
- * that was aborted mid-flight); the stage calls leave the workspace ready for the next call. */
-int dkv_workspace_init(const dkv_desc* desc, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Observation-window scoring of ONE layer (Eq. 1-2; Algorithm 1, the softmax(...).mean(dim=-2).pooling(dim=-1) line).
@@ -100,6 +97,20 @@ int dkv_workspace_init(const dkv_desc* desc, void* workspace, size_t workspace_b
 int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                      int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                      int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two kernels of dkv_score_window as separate calls with the same arguments (Eq. 1-2): first the per-row
+ * softmax normalisers (log-sum-exp of every window row over all keys, kept in the workspace), then the scores.
+ * dkv_score_window(...) is exactly dkv_score_window_stats(...) followed by dkv_score_window_emit(...) on the same
+ * stream; the split lets a caller time the two sweeps over K separately or place other work between them.
+ * dkv_score_window_emit reads the normalisers the last dkv_score_window_stats call left in `workspace`.
+ */
+int dkv_score_window_stats(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                           int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                           int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
+int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                          int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                          int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-layer, per-KV-head top-k (Eq. 3; Algorithm 1, the A^l.topk(B^l).indices line) for layer index `layer`.

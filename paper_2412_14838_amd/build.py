@@ -38,7 +38,12 @@ def build(verbose: bool = True) -> str:
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    # Link against the HIP runtime that PyTorch loads (its own libamdhip64.so, found by name), not a second
+    # copy: streams and graph captures created by torch are then valid inside the library.
+    import torch
+    torch_lib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    cmd = ["g++", "-shared", "-fPIC", "-o", LIB, *objs, "-L" + torch_lib, "-lamdhip64",
+           "-Wl,-rpath," + torch_lib, "-Wl,-rpath,/opt/rocm/lib"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))

@@ -74,21 +74,10 @@ size_t dkv_workspace_bytes(const dkv_desc* desc) {
   return workspace_layout(*desc).total;
 }
 
-int dkv_workspace_init(const dkv_desc* desc, void* workspace, size_t workspace_bytes, void* stream) {
-  int st = validate_desc(desc);
-  if (st != DKV_OK) return st;
-  WorkspaceLayout wl;
-  st = check_workspace(*desc, workspace, workspace_bytes, wl);
-  if (st != DKV_OK) return st;
-  // the two ticket arrays (adjacent) are the only regions a call expects to find zeroed
-  const hipError_t e = launch_fill_zero(static_cast<char*>(workspace) + wl.counters, wl.lse - wl.counters,
-                                        static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
-}
-
-int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
-                     int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
-                     int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
+static int score_window_phases(int phases, const dkv_desc* desc, const void* q_win, const void* k,
+                               int64_t k_stride_token, int64_t k_stride_head, const int32_t* cu_seqlens,
+                               float* scores_out, int64_t scores_stride_head, void* workspace, size_t workspace_bytes,
+                               void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   if (!q_win || !k || !cu_seqlens || !scores_out) return DKV_ERR_INVALID_ARG;
@@ -102,14 +91,35 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
   if (desc->total_tokens == 0) return DKV_OK;
   const Params p = make_params(*desc);
   hipError_t e;
-  if (score_mfma_supported(p, desc->dtype)) {
-    e = launch_score_mfma(p, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+  if (score_mfma_supported(p, desc->dtype, k_stride_token)) {
+    e = launch_score_mfma(p, phases, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
                           static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
   } else {
-    e = launch_score_generic(p, desc->dtype, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+    e = launch_score_generic(p, phases, desc->dtype, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
                              scores_stride_head, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                     int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                     int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_window_phases(kPhaseStats | kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens,
+                             scores_out, scores_stride_head, workspace, workspace_bytes, stream);
+}
+
+int dkv_score_window_stats(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                           int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                           int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_window_phases(kPhaseStats, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, workspace, workspace_bytes, stream);
+}
+
+int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                          int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                          int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
+  return score_window_phases(kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, workspace, workspace_bytes, stream);
 }
 
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,

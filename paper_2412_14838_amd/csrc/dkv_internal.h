@@ -11,8 +11,7 @@ namespace dkv {
 // Tiling constants
 // ----------------------------------------------------------------------------------------------
 constexpr int kGenericKeys = 256;      // keys per workgroup in the generic (VALU) score kernels
-constexpr int kMfmaKeysStats = 256;    // keys per workgroup, MFMA row-statistics kernel
-constexpr int kMfmaKeysEmit = 256;     // keys computed per workgroup, MFMA score kernel (outputs = this - (P-1))
+constexpr int kMfmaMinChunk = 256;     // smallest chunk of keys per workgroup in the MFMA score kernels
 constexpr int kRadixBins = 2048;       // 11-bit digits; 3 passes cover bits 31..21, 20..10, 9..0
 constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the rebalance histogram kernels
 
@@ -20,11 +19,7 @@ constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the 
 // Workspace layout (byte offsets, all 256-byte aligned)
 // ----------------------------------------------------------------------------------------------
 struct WorkspaceLayout {
-  size_t counters;     // int32 [n_seqs][Hkv]            arrival tickets of the statistics kernel
-  size_t edge_counters;// int32 [chunks_max + 1][Hkv]    arrival tickets per chunk boundary (score kernel)
-  size_t lse;          // float [n_seqs][Hkv][rows_pad]  per-row log-sum-exp
-  size_t partials;     // float2 [chunks_max][Hkv][rows_pad]
-  size_t edges;        // float [chunks_max + 1][Hkv][128] raw sums next to each chunk boundary
+  size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t hist;         // int32 [3][n_seqs][L][kRadixBins]
   size_t state;        // int32 [n_seqs][8]              radix-select state of the rebalance
   size_t total;
@@ -34,7 +29,7 @@ struct WorkspaceLayout {
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-inline int min_stats_keys() { return kGenericKeys < kMfmaKeysStats ? kGenericKeys : kMfmaKeysStats; }
+inline int min_stats_keys() { return kGenericKeys < kMfmaMinChunk ? kGenericKeys : kMfmaMinChunk; }
 
 inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   WorkspaceLayout w{};
@@ -42,11 +37,7 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.rows_pad = (rows + 63) / 64 * 64;
   w.chunks_max = d.total_tokens / min_stats_keys() + d.n_seqs;
   size_t off = 0;
-  w.counters = off; off += align256(size_t(d.n_seqs) * d.n_kv_heads * sizeof(int32_t));
-  w.edge_counters = off; off += align256(size_t(w.chunks_max + 1) * d.n_kv_heads * sizeof(int32_t));
-  w.lse = off;      off += align256(size_t(d.n_seqs) * d.n_kv_heads * w.rows_pad * sizeof(float));
   w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
-  w.edges = off;    off += align256(size_t(w.chunks_max + 1) * d.n_kv_heads * 128 * sizeof(float));
   w.hist = off;     off += align256(size_t(3) * d.n_seqs * d.n_layers * kRadixBins * sizeof(int32_t));
   w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
   w.total = off;
@@ -70,11 +61,13 @@ struct Params {
 Params make_params(const dkv_desc& d);
 
 // Stage launchers (defined next to their kernels). Each returns hipGetLastError() of its launches.
-hipError_t launch_score_generic(const Params& p, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
+// `phases` of the score launchers: bit 0 = row-statistics kernel, bit 1 = score kernel.
+constexpr int kPhaseStats = 1, kPhaseEmit = 2;
+hipError_t launch_score_generic(const Params& p, int phases, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                                 char* ws, const WorkspaceLayout& wl, hipStream_t st);
-bool score_mfma_supported(const Params& p, int dtype);
-hipError_t launch_score_mfma(const Params& p, const void* q_win, const void* k, int64_t k_stride_token,
+bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token);
+hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                              int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                              char* ws, const WorkspaceLayout& wl, hipStream_t st);
 hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,

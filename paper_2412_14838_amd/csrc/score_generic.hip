@@ -4,10 +4,10 @@
 // through LDS 32 at a time.
 //
 // Two kernels, because a column of softmax(QK^T) summed over the rows needs every row's normaliser first:
-//   stats:  per chunk of keys, per row: running maximum m and sum l of exp(x - m); the last workgroup of each
-//           (sequence, KV head) to arrive merges the chunk partials into lse[row] = m + log(l);
-//   emit:   a[s] = row_scale * sum_rows exp(x[row, s] - lse[row]) for the chunk's keys plus a halo of (P-1)/2
-//           on each side, max-pooled over the prefix and written out.
+//   stats:  per chunk of keys, per row: maximum m and sum l of exp(x - m), one partial per (chunk, row);
+//   emit:   merges the partials of its (sequence, KV head) into lse[row] = m + log(l) (the kernel boundary is
+//           the only synchronisation between workgroups), then a[s] = row_scale * sum_rows exp(x[row, s] -
+//           lse[row]) for the chunk's keys plus a halo of (P-1)/2 on each side, max-pooled over the prefix.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -58,12 +58,9 @@ template <typename T, int D>
 __global__ __launch_bounds__(kGenericKeys) void score_stats_generic(Params p, const T* __restrict__ q_win,
                                                                     const T* __restrict__ k, int64_t k_stride_token,
                                                                     int64_t k_stride_head, const int32_t* __restrict__ cu,
-                                                                    int32_t* __restrict__ counters,
-                                                                    float* __restrict__ lse,
                                                                     float2* __restrict__ partials) {
   __shared__ float qs[kQRows * D];
   __shared__ float xs[kQRows][kGenericKeys + 1];
-  __shared__ int is_last;
   int seq, c, begin, S;
   if (!find_chunk(cu, p.n_seqs, kGenericKeys, 0, blockIdx.x, seq, c, begin, S)) return;
   const int head = blockIdx.y;
@@ -73,7 +70,6 @@ __global__ __launch_bounds__(kGenericKeys) void score_stats_generic(Params p, co
   float kreg[D];
   load_key_row<T, D>(k + (int64_t)(begin + s_ld) * k_stride_token + (int64_t)head * k_stride_head, kreg);
   const T* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * D;
-  const int n_chunks = chunks_of(S, 0, kGenericKeys);
   float2* __restrict__ part = partials + (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad;
   for (int r0 = 0; r0 < p.rows; r0 += kQRows) {
     __syncthreads();
@@ -102,35 +98,6 @@ __global__ __launch_bounds__(kGenericKeys) void score_stats_generic(Params p, co
       if (lane == 0 && r0 + rr < p.rows_pad) part[r0 + rr] = make_float2(m, l);
     }
   }
-  // ---- last workgroup of this (sequence, head) merges the chunk partials, in chunk order
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int ticket = atomicAdd(&counters[seq * p.Hkv + head], 1);
-    is_last = ticket == n_chunks - 1;
-    if (is_last) counters[seq * p.Hkv + head] = 0;          // ready for the next call
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  const int first = blockIdx.x - c;                          // linear index of this sequence's chunk 0
-  for (int r = tid; r < p.rows; r += kGenericKeys) {
-    // partials were written by other workgroups: read them past the per-CU cache
-    const float* __restrict__ pf = reinterpret_cast<const float*>(partials);
-    float m = -INFINITY;
-    for (int cc = 0; cc < n_chunks; ++cc) {
-      const int64_t e = ((((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r) * 2;
-      m = fmaxf(m, __hip_atomic_load(pf + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
-    float l = 0.0f;
-    for (int cc = 0; cc < n_chunks; ++cc) {
-      const int64_t e = ((((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r) * 2;
-      const float vm = __hip_atomic_load(pf + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float vl = __hip_atomic_load(pf + e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (vm > -INFINITY) l += vl * __expf(vm - m);
-    }
-    lse[((int64_t)seq * p.Hkv + head) * p.rows_pad + r] = m + __logf(l);
-  }
 }
 
 // grid = (chunk upper bound over prefix outputs, Hkv); block = kGenericKeys threads. Thread t owns key
@@ -139,7 +106,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, const T* __restrict__ q_win,
                                                                    const T* __restrict__ k, int64_t k_stride_token,
                                                                    int64_t k_stride_head, const int32_t* __restrict__ cu,
-                                                                   const float* __restrict__ lse,
+                                                                   const float2* __restrict__ partials,
                                                                    float* __restrict__ scores,
                                                                    int64_t scores_stride_head) {
   __shared__ float qs[kQRows * D];
@@ -156,7 +123,22 @@ __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, con
   float kreg[D];
   load_key_row<T, D>(k + (int64_t)(begin + s_ld) * k_stride_token + (int64_t)head * k_stride_head, kreg);
   const T* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * D;
-  for (int r = tid; r < p.rows; r += kGenericKeys) lse_s[r] = lse[((int64_t)seq * p.Hkv + head) * p.rows_pad + r];
+  {
+    // chunks of the statistics kernel that belong to this sequence: [first, first + n_full), in linear order
+    int first = 0;
+    for (int q = 0; q < seq; ++q) first += chunks_of(cu[q + 1] - cu[q], 0, kGenericKeys);
+    const int n_full = chunks_of(S, 0, kGenericKeys);
+    for (int r = tid; r < p.rows; r += kGenericKeys) {
+      float m = -INFINITY;
+      for (int cc = 0; cc < n_full; ++cc) m = fmaxf(m, partials[(((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r].x);
+      float l = 0.0f;
+      for (int cc = 0; cc < n_full; ++cc) {
+        const float2 v = partials[(((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r];
+        if (v.x > -INFINITY) l += v.y * __expf(v.x - m);
+      }
+      lse_s[r] = m + __logf(l);
+    }
+  }
   float a = 0.0f;
   for (int r0 = 0; r0 < p.rows; r0 += kQRows) {
     __syncthreads();
@@ -184,33 +166,33 @@ __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, con
 }
 
 template <typename T, int D>
-static hipError_t launch_generic_t(const Params& p, const void* q_win, const void* k, int64_t k_stride_token,
+static hipError_t launch_generic_t(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                                    int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                                    char* ws, const WorkspaceLayout& wl, hipStream_t st) {
-  int32_t* counters = reinterpret_cast<int32_t*>(ws + wl.counters);
-  float* lse = reinterpret_cast<float*>(ws + wl.lse);
   float2* partials = reinterpret_cast<float2*>(ws + wl.partials);
   const int chunks_stats = p.total_tokens / kGenericKeys + p.n_seqs;
-  hipLaunchKernelGGL((score_stats_generic<T, D>), dim3(chunks_stats, p.Hkv), dim3(kGenericKeys), 0, st, p,
-                     static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu, counters,
-                     lse, partials);
+  if (phases & kPhaseStats)
+    hipLaunchKernelGGL((score_stats_generic<T, D>), dim3(chunks_stats, p.Hkv), dim3(kGenericKeys), 0, st, p,
+                       static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu,
+                       partials);
   const int CO = kGenericKeys - 2 * p.half;
   const int chunks_emit = p.total_tokens / CO + p.n_seqs;
-  hipLaunchKernelGGL((score_emit_generic<T, D>), dim3(chunks_emit, p.Hkv), dim3(kGenericKeys), 0, st, p,
-                     static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu, lse, scores,
-                     scores_stride_head);
+  if (phases & kPhaseEmit)
+    hipLaunchKernelGGL((score_emit_generic<T, D>), dim3(chunks_emit, p.Hkv), dim3(kGenericKeys), 0, st, p,
+                       static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu,
+                       partials, scores, scores_stride_head);
   return hipGetLastError();
 }
 
-hipError_t launch_score_generic(const Params& p, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
+hipError_t launch_score_generic(const Params& p, int phases, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                                 char* ws, const WorkspaceLayout& wl, hipStream_t st) {
   if (dtype == DKV_F32) {
-    if (p.d == 64) return launch_generic_t<float, 64>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-    return launch_generic_t<float, 128>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+    if (p.d == 64) return launch_generic_t<float, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+    return launch_generic_t<float, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
   }
-  if (p.d == 64) return launch_generic_t<uint16_t, 64>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  return launch_generic_t<uint16_t, 128>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  if (p.d == 64) return launch_generic_t<uint16_t, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  return launch_generic_t<uint16_t, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
 }
 
 }  // namespace dkv

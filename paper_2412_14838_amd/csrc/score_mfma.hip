@@ -4,20 +4,20 @@
 // A column of softmax(QK^T) summed over the rows needs every row's normaliser before any column can be
 // finished, so the keys are swept twice (the second read is expected to come from the cache hierarchy):
 //   stats kernel: S_tile = K_tile . Q^T  (keys as the MFMA M index, rows as N: a lane holds ONE row and 16
-//                 keys, so the running row maximum / sum of exponentials is an in-lane reduction);
-//   emit kernel:  S_tile = Q . K_tile^T  (rows as M, keys as N: a lane holds ONE key and 16 rows, so the sum
-//                 over the rows is an in-lane reduction), p = exp2(S * c - lse2[row]), window/group sum,
-//                 max-pool, write.
+//                 keys, so the running row maximum / sum of exponentials is an in-lane reduction); every
+//                 workgroup writes one partial (max, sum) per row for its chunk of keys;
+//   emit kernel:  merges the chunk partials of its (sequence, head) into lse2[row] (kernel boundaries are the
+//                 only synchronisation between workgroups), then S_tile = Q . K_tile^T (rows as M, keys as N:
+//                 a lane holds ONE key and 16 rows, so the sum over the rows is an in-lane reduction),
+//                 p = exp2(S * c - lse2[row]), window/group sum, max-pool, write.
 // Both use v_mfma_f32_32x32x16_bf16 with the whole Q block of the wavefront resident in registers and K tiles
 // staged through LDS (coalesced 16-byte global loads, padded rows, 16-byte LDS reads in MFMA operand layout).
+// The MFMAs of tile i+1 are issued in the same loop body as the exponentials of tile i (two accumulator sets).
 //
 // Workgroup = RS x KS wavefronts: RS row slabs of 64 rows (2 MFMA tiles) x KS key tiles of 32 keys.
-// Every workgroup owns a contiguous chunk of `chunk` keys of one (sequence, KV head).
-//
-// Pooling across chunk boundaries: a workgroup pools the outputs whose window lies inside its chunk and
-// publishes its first/last 2*half raw sums; for every boundary the second of the two neighbours to arrive
-// (integer ticket, no waiting) pools the 2*half outputs that straddle it. Maxima are order-independent, so
-// the result does not depend on arrival order.
+// Every workgroup owns a contiguous chunk of one (sequence, KV head). The emit kernel computes (P-1)/2 extra
+// keys on each side of its output chunk, so pooling never needs another workgroup's sums; identical keys give
+// bit-identical sums whichever workgroup or lane computes them (fixed summation order per column).
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -27,32 +27,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kLdsRow = 272;          // bytes per staged key row: 256 data + 16 pad (conflict-free 16-byte reads)
 constexpr int kMaxChunk = 2048;       // largest `chunk` the launcher picks
-constexpr int kEdge = 64;             // floats reserved per boundary side (2 * half <= 62)
+constexpr int kMaxHalo = 64;          // >= 2 * half
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Chunking of n items into chunks of `chunk`, the tail merged into the last chunk when shorter than `tail_min`.
-__host__ __device__ inline int n_chunks_merged(int n, int chunk, int tail_min) {
-  if (n <= 0) return 0;
-  const int c = (n - tail_min + chunk) / chunk;
-  return c > 1 ? c : 1;
-}
-
-__device__ inline bool find_chunk_merged(const int32_t* __restrict__ cu, int n_seqs, int chunk, int tail_min,
-                                         int window_off, int b, int& seq, int& c, int& nc, int& seq_begin,
-                                         int& seq_len) {
-  int begin = cu[0];
-  for (int s = 0; s < n_seqs; ++s) {
-    const int end = cu[s + 1];
-    const int len = end - begin;
-    const int n = n_chunks_merged(len - window_off, chunk, tail_min);
-    if (b < n) { seq = s; c = b; nc = n; seq_begin = begin; seq_len = len; return true; }
-    b -= n;
-    begin = end;
-  }
-  return false;
-}
 
 template <int RS, int KS>
 struct Tile {
@@ -78,15 +56,18 @@ __device__ inline void load_q_frags(const uint16_t* __restrict__ q_head, int rs,
   }
 }
 
+// Fetches one tile of keys [row0, row0 + kKeys) (relative to the chunk start, clamped to its last row, so every
+// load stays inside the chunk and clamped rows are cache hits) into registers.
 template <int RS, int KS>
-__device__ inline void load_tile(const char* __restrict__ k_head, int64_t stride_token_b, int key0, int last_key,
+__device__ inline void load_tile(const char* __restrict__ k_chunk, uint32_t stride_token_b, int row0, int last_row,
                                  uint4 (&reg)[Tile<RS, KS>::kPieces]) {
 #pragma unroll
   for (int i = 0; i < Tile<RS, KS>::kPieces; ++i) {
     const int p = threadIdx.x + i * Tile<RS, KS>::kThreads;
-    int key = key0 + (p >> 4);
-    key = key < last_key ? key : last_key;   // clamp: loads stay inside the sequence, values are masked later
-    reg[i] = *reinterpret_cast<const uint4*>(k_head + (int64_t)key * stride_token_b + (p & 15) * 16);
+    int row = row0 + (p >> 4);
+    row = row < last_row ? row : last_row;
+    const uint32_t off = __umul24((uint32_t)row, stride_token_b) + (uint32_t)(p & 15) * 16u;
+    reg[i] = *reinterpret_cast<const uint4*>(k_chunk + off);
   }
 }
 
@@ -99,91 +80,140 @@ __device__ inline void store_tile(char* __restrict__ buf, const uint4 (&reg)[Til
   }
 }
 
+// acc[t] = (KEYS_AS_M ? K_tile . Q_t^T : Q_t . K_tile^T) for the wavefront's 32 keys and two 32-row tiles.
+template <bool KEYS_AS_M>
+__device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
+    if (KEYS_AS_M) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][j], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][j], acc[1], 0, 0, 0);
+    } else {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][j], kf, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[1][j], kf, acc[1], 0, 0, 0);
+    }
+  }
+}
+
+// Linear chunk index -> (sequence, chunk) for chunks of `chunk` items over (length - window_off) items per
+// sequence; also returns the number of chunks of (length) items in the earlier sequences (first_full) and in
+// this one (n_full): the statistics kernel cuts all S keys, the emit kernel the S' prefix outputs.
+__device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, int chunk, int window_off, int b,
+                                   int& seq, int& c, int& nc, int& seq_begin, int& seq_len, int& first_full,
+                                   int& n_full) {
+  int begin = cu[0];
+  int full = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int end = cu[s + 1];
+    const int len = end - begin;
+    const int nf = (len + chunk - 1) / chunk;
+    int items = len - window_off;
+    items = items > 0 ? items : 0;
+    const int n = (items + chunk - 1) / chunk;
+    if (b < n) {
+      seq = s; c = b; nc = n; seq_begin = begin; seq_len = len; first_full = full; n_full = nf;
+      return true;
+    }
+    b -= n;
+    full += nf;
+    begin = end;
+  }
+  return false;
+}
+
 // ------------------------------------------------------------------------------------------------------
-// Row statistics: partial (max, sum of exp2) per chunk and row, merged by the last workgroup to arrive into
-// lse2[row] = log2 sum_s exp2(c * x[row, s]) with c = softmax_scale * log2(e).
+// Row statistics: one partial (max, sum of exp2) per chunk and row, in the log2 domain:
+// y = c * x with c = softmax_scale * log2(e); partial = (max y, sum exp2(y - max y)).
+// grid = (chunk upper bound over all S keys, Hkv).
 // ------------------------------------------------------------------------------------------------------
 template <int RS, int KS>
 __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int chunk, const uint16_t* __restrict__ q_win,
                                                                  const char* __restrict__ k, int64_t stride_token_b,
                                                                  int64_t stride_head_b, const int32_t* __restrict__ cu,
-                                                                 int32_t* __restrict__ counters, float* __restrict__ lse2,
                                                                  float* __restrict__ partials) {
   using TL = Tile<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
   float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes);         // [KS][RS * 64]
-  __shared__ int is_last;
 
-  int seq, c, nc, begin, S;
-  if (!find_chunk_merged(cu, p.n_seqs, chunk, 1, 0, blockIdx.x, seq, c, nc, begin, S)) return;
+  int seq, c, nc, begin, S, first_full, n_full;
+  if (!find_chunk2(cu, p.n_seqs, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rs = wave / KS, ks = wave % KS;
+  const int rs = wave % RS, ks = wave / RS;
   const int c0 = c * chunk;
-  const int c1 = c == nc - 1 ? S : c0 + chunk;
-  const int n_iter = (c1 - c0 + TL::kKeys - 1) / TL::kKeys;
-  const int prefix = S - p.w;                       // may be negative for sequences shorter than the window
+  const int len = (c0 + chunk < S ? c0 + chunk : S) - c0;
+  const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
+  const int prefix_rel = S - p.w - c0;              // first window key, relative to the chunk (may be <= 0)
   const float cexp = p.scale * kLog2e;
 
-  const char* __restrict__ k_head = k + (int64_t)begin * stride_token_b + (int64_t)head * stride_head_b;
+  const char* __restrict__ k_chunk =
+      k + ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
+  const uint32_t stride_b = (uint32_t)stride_token_b;
+  uint4 reg[TL::kPieces];
+  load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1, reg);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
-  int limit[2];                                     // last key position visible to this lane's row (causal mask)
+  int limit[2];                                     // last key (chunk-relative) visible to this lane's row
 #pragma unroll
-  for (int t = 0; t < 2; ++t) limit[t] = prefix + (rs * 64 + t * 32 + (lane & 31)) % p.w;
+  for (int t = 0; t < 2; ++t) limit[t] = prefix_rel + (rs * 64 + t * 32 + (lane & 31)) % p.w;
+  const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 
-  uint4 reg[TL::kPieces];
-  load_tile<RS, KS>(k_head, stride_token_b, c0, S - 1, reg);
   store_tile<RS, KS>(tiles, reg);
+  load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1, reg);
+  __syncthreads();
+  floatx16 acc[2], nxt[2];
+  mfma_tile<true>(tiles + lane_tile, qf, acc);
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg);
   __syncthreads();
   for (int it = 0; it < n_iter; ++it) {
-    const int key0 = c0 + it * TL::kKeys;
-    if (it + 1 < n_iter) load_tile<RS, KS>(k_head, stride_token_b, key0 + TL::kKeys, S - 1, reg);
-    const char* tile = tiles + (it & 1) * TL::kTileBytes + (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-    floatx16 acc[2];
+    // prefetch tile it + 2 (registers), MFMAs of tile it + 1, exponentials of tile it
+    load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1, reg);
+    const int wave_row0 = it * TL::kKeys + ks * 32;
+    const bool next_active = wave_row0 + TL::kKeys < len;
+    if (next_active) mfma_tile<true>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
+    if (wave_row0 < len) {
+      const int lim_all = prefix_rel < len ? prefix_rel : len;
+      const bool need_mask = wave_row0 + 32 > lim_all;    // touches the window or runs past the chunk
+      const int kb = wave_row0 + 4 * (lane >> 5);         // + 8 * (j / 4) + j % 4
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t) {
+        if (need_mask) {
 #pragma unroll
-      for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][j], acc[0], 0, 0, 0);   // D[key][row]
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][j], acc[1], 0, 0, 0);
-    }
-    const int wave_key0 = key0 + ks * 32;
-    const bool need_mask = wave_key0 + 32 > (prefix < c1 ? prefix : c1);   // touches the window or runs past the chunk
-    const int kb = wave_key0 + 4 * (lane >> 5);                            // + 8 * (j / 4) + j % 4
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      if (need_mask) {
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int s = kb + 8 * (j >> 2) + (j & 3);
-          if (s > limit[t] || s >= c1) acc[t][j] = -INFINITY;
+          for (int j = 0; j < 16; ++j) {
+            const int s = kb + 8 * (j >> 2) + (j & 3);
+            if (s > limit[t] || s >= len) acc[t][j] = -INFINITY;
+          }
         }
-      }
-      float mx = acc[t][0];
+        float mx = fmaxf(acc[t][0], acc[t][1]);
 #pragma unroll
-      for (int j = 1; j < 16; ++j) mx = fmaxf(mx, acc[t][j]);
-      const float m_new = fmaxf(m_run[t], mx * cexp);
-      const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+        for (int j = 2; j < 16; j += 2) mx = fmaxf(mx, fmaxf(acc[t][j], acc[t][j + 1]));
+        const float m_new = fmaxf(m_run[t], mx * cexp);
+        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
 #pragma unroll
-      for (int j = 0; j < 16; j += 4) {
-        s0 += fast_exp2(fmaf(acc[t][j], cexp, -m_use));
-        s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -m_use));
-        s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -m_use));
-        s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -m_use));
+        for (int j = 0; j < 16; j += 4) {
+          s0 += fast_exp2(fmaf(acc[t][j], cexp, -m_use));
+          s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -m_use));
+          s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -m_use));
+          s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -m_use));
+        }
+        l_run[t] = l_run[t] * fast_exp2(m_run[t] - m_use) + ((s0 + s1) + (s2 + s3));
+        m_run[t] = m_new;
       }
-      l_run[t] = l_run[t] * fast_exp2(m_run[t] - m_use) + ((s0 + s1) + (s2 + s3));
-      m_run[t] = m_new;
     }
-    if (it + 1 < n_iter) store_tile<RS, KS>(tiles + ((it + 1) & 1) * TL::kTileBytes, reg);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) acc[t] = nxt[t];
+    // buffer it & 1 held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
+    store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
     __syncthreads();
   }
   // ---- merge the two half-wavefronts (same row, other keys), then the KS key tiles, then publish
@@ -196,8 +226,9 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
     if (lane < 32) stat[ks * (RS * 64) + rs * 64 + t * 32 + lane] = make_float2(M, Lsum);
   }
   __syncthreads();
-  float* __restrict__ part = partials + (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad * 2;
-  for (int r = tid; r < RS * 64 && r < p.rows_pad; r += TL::kThreads) {
+  float2* __restrict__ part =
+      reinterpret_cast<float2*>(partials) + (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad;
+  for (int r = tid; r < RS * 64; r += TL::kThreads) {
     float M = -INFINITY;
 #pragma unroll
     for (int q = 0; q < KS; ++q) M = fmaxf(M, stat[q * (RS * 64) + r].x);
@@ -208,130 +239,129 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
       const float2 v = stat[q * (RS * 64) + r];
       Lsum += v.y * fast_exp2(v.x - Mu);
     }
-    part[2 * r] = M;
-    part[2 * r + 1] = Lsum;
-  }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int ticket = atomicAdd(&counters[seq * p.Hkv + head], 1);
-    is_last = ticket == nc - 1;
-    if (is_last) counters[seq * p.Hkv + head] = 0;       // ready for the next call
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  const int first = blockIdx.x - c;                        // linear index of this sequence's chunk 0
-  for (int r = tid; r < p.rows_pad; r += TL::kThreads) {
-    float out = INFINITY;                                  // padding rows: exp2(x - inf) = 0 in the emit kernel
-    if (r < p.rows) {
-      float M = -INFINITY;
-      for (int cc = 0; cc < nc; ++cc) {
-        const int64_t e = ((((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r) * 2;
-        M = fmaxf(M, __hip_atomic_load(partials + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-      }
-      const float Mu = M == -INFINITY ? 0.0f : M;
-      float Lsum = 0.0f;
-      for (int cc = 0; cc < nc; ++cc) {
-        const int64_t e = ((((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r) * 2;
-        const float vm = __hip_atomic_load(partials + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float vl = __hip_atomic_load(partials + e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        Lsum += vl * fast_exp2(vm - Mu);
-      }
-      out = M + __log2f(Lsum);
-    }
-    lse2[((int64_t)seq * p.Hkv + head) * p.rows_pad + r] = out;
+    part[r] = make_float2(M, Lsum);
   }
 }
 
 // ------------------------------------------------------------------------------------------------------
-// Scores: a[s] = row_scale * sum_rows exp2(c * x[row, s] - lse2[row]) over the chunk, max-pooled over the prefix.
+// Scores: a[s] = row_scale * sum_rows exp2(c * x[row, s] - lse2[row]) over the chunk's outputs plus the pooling
+// halo, max-pooled over the prefix. grid = (chunk upper bound over the S' prefix outputs, Hkv).
 // ------------------------------------------------------------------------------------------------------
 template <int RS, int KS>
 __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int chunk, const uint16_t* __restrict__ q_win,
                                                                 const char* __restrict__ k, int64_t stride_token_b,
                                                                 int64_t stride_head_b, const int32_t* __restrict__ cu,
-                                                                const float* __restrict__ lse2,
-                                                                int32_t* __restrict__ edge_counters,
-                                                                float* __restrict__ edges, float* __restrict__ scores,
-                                                                int64_t scores_stride_head) {
+                                                                const float* __restrict__ partials,
+                                                                float* __restrict__ scores, int64_t scores_stride_head) {
   using TL = Tile<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
-  float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kMaxChunk + 2 * kEdge]
-  constexpr int kPartStride = kMaxChunk + 2 * kEdge;
-  __shared__ int second[2];
+  float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kPartStride]
+  constexpr int kPartStride = kMaxChunk + kMaxHalo + TL::kKeys;
+  constexpr int kRows = RS * 64;
+  float2* mstage = reinterpret_cast<float2*>(part);                            // [KS][kRows], before `part` is used
+  __shared__ __attribute__((aligned(16))) float lse_s[kRows];
 
   const int half = p.half;
-  int seq, c, nc, begin, S;
-  if (!find_chunk_merged(cu, p.n_seqs, chunk, 2 * half + 1, p.w, blockIdx.x, seq, c, nc, begin, S)) return;
+  int seq, c, nc, begin, S, first_full, n_full;
+  if (!find_chunk2(cu, p.n_seqs, chunk, p.w, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rs = wave / KS, ks = wave % KS;
+  const int rs = wave % RS, ks = wave / RS;
   const int prefix = S - p.w;                                // > 0 here
-  const int c0 = c * chunk;
-  const int c1 = c == nc - 1 ? prefix : c0 + chunk;          // the last chunk takes the merged tail
-  const int len = c1 - c0;                                   // <= chunk + 2 * half
+  const int o0 = c * chunk;                                  // outputs [o0, o1)
+  const int o1 = o0 + chunk < prefix ? o0 + chunk : prefix;
+  const int kbeg = o0 - half > 0 ? o0 - half : 0;            // keys [kbeg, kend): outputs plus halo, inside the prefix
+  const int kend = o1 + half < prefix ? o1 + half : prefix;
+  const int len = kend - kbeg;                               // <= chunk + 2 * half
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
   const float cexp = p.scale * kLog2e;
 
-  const char* __restrict__ k_head = k + (int64_t)begin * stride_token_b + (int64_t)head * stride_head_b;
+  const char* __restrict__ k_chunk =
+      k + ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
+  const uint32_t stride_b = (uint32_t)stride_token_b;
+  uint4 reg[TL::kPieces];
+  load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1, reg);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
+
+  // ---- lse2[row] of this (sequence, head) from the chunk partials of the statistics kernel
+  {
+    const int r = tid % kRows, q = tid / kRows;              // KS groups of kRows threads
+    const float2* __restrict__ src =
+        reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad + r;
+    float M = -INFINITY, Lsum = 0.0f;
+    for (int cc = q; cc < n_full; cc += KS) {
+      const float2 v = src[(int64_t)cc * p.Hkv * p.rows_pad];
+      const float Mn = fmaxf(M, v.x);
+      const float Mu = Mn == -INFINITY ? 0.0f : Mn;
+      Lsum = Lsum * fast_exp2(M - Mu) + v.y * fast_exp2(v.x - Mu);
+      M = Mn;
+    }
+    mstage[q * kRows + r] = make_float2(M, Lsum);
+    store_tile<RS, KS>(tiles, reg);
+    load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1, reg);
+    __syncthreads();
+    if (tid < kRows) {
+      float Mx = -INFINITY;
+#pragma unroll
+      for (int g = 0; g < KS; ++g) Mx = fmaxf(Mx, mstage[g * kRows + tid].x);
+      const float Mu = Mx == -INFINITY ? 0.0f : Mx;
+      float L = 0.0f;
+#pragma unroll
+      for (int g = 0; g < KS; ++g) {
+        const float2 v = mstage[g * kRows + tid];
+        L += v.y * fast_exp2(v.x - Mu);
+      }
+      // padding rows get +inf: exp2(x - inf) = 0
+      lse_s[tid] = tid < p.rows ? Mx + __log2f(L) : INFINITY;
+    }
+  }
+  const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
+  floatx16 acc[2], nxt[2];
+  mfma_tile<false>(tiles + lane_tile, qf, acc);
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg);
+  __syncthreads();
   // lse2 of the rows this lane accumulates: register j of tile t is row rs*64 + t*32 + 8*(j/4) + 4*(lane/32) + j%4
   float lse_r[2][16];
-  {
-    const float* __restrict__ src = lse2 + ((int64_t)seq * p.Hkv + head) * p.rows_pad + rs * 64 + 4 * (lane >> 5);
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int j4 = 0; j4 < 4; ++j4) {
-        const float4 v = *reinterpret_cast<const float4*>(src + t * 32 + 8 * j4);
-        lse_r[t][4 * j4] = v.x; lse_r[t][4 * j4 + 1] = v.y; lse_r[t][4 * j4 + 2] = v.z; lse_r[t][4 * j4 + 3] = v.w;
-      }
-  }
-
-  uint4 reg[TL::kPieces];
-  load_tile<RS, KS>(k_head, stride_token_b, c0, S - 1, reg);
-  store_tile<RS, KS>(tiles, reg);
-  __syncthreads();
-  for (int it = 0; it < n_iter; ++it) {
-    const int key0 = c0 + it * TL::kKeys;
-    if (it + 1 < n_iter) load_tile<RS, KS>(k_head, stride_token_b, key0 + TL::kKeys, S - 1, reg);
-    const char* tile = tiles + (it & 1) * TL::kTileBytes + (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-    floatx16 acc[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][j], kf, acc[0], 0, 0, 0);   // D[row][key]
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[1][j], kf, acc[1], 0, 0, 0);
+    for (int j4 = 0; j4 < 4; ++j4) {
+      const float4 v = *reinterpret_cast<const float4*>(&lse_s[rs * 64 + t * 32 + 8 * j4 + 4 * (lane >> 5)]);
+      lse_r[t][4 * j4] = v.x; lse_r[t][4 * j4 + 1] = v.y; lse_r[t][4 * j4 + 2] = v.z; lse_r[t][4 * j4 + 3] = v.w;
     }
-    // prefix keys are visible to every window row: no mask. Fixed summation order per column.
-    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+
+  for (int it = 0; it < n_iter; ++it) {
+    load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1, reg);
+    const int wave_row0 = it * TL::kKeys + ks * 32;
+    const bool next_active = wave_row0 + TL::kKeys < len;
+    if (next_active) mfma_tile<false>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
+    if (wave_row0 < len) {
+      // prefix keys are visible to every window row: no mask. Fixed summation order per column.
+      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int j = 0; j < 16; j += 4) {
-        s0 += fast_exp2(fmaf(acc[t][j], cexp, -lse_r[t][j]));
-        s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -lse_r[t][j + 1]));
-        s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -lse_r[t][j + 2]));
-        s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -lse_r[t][j + 3]));
-      }
-    float col = (s0 + s1) + (s2 + s3);
-    const float other = __shfl_xor(col, 32);
-    col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
-    const int local = it * TL::kKeys + ks * 32 + (lane & 31);
-    if (lane < 32 && local < kPartStride) part[rs * kPartStride + local] = col;
-    if (it + 1 < n_iter) store_tile<RS, KS>(tiles + ((it + 1) & 1) * TL::kTileBytes, reg);
+        for (int j = 0; j < 16; j += 4) {
+          s0 += fast_exp2(fmaf(acc[t][j], cexp, -lse_r[t][j]));
+          s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -lse_r[t][j + 1]));
+          s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -lse_r[t][j + 2]));
+          s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -lse_r[t][j + 3]));
+        }
+      float col = (s0 + s1) + (s2 + s3);
+      const float other = __shfl_xor(col, 32);
+      col = lane < 32 ? col + other : other + col;       // rows 0-3 mod 8 first, in both half-wavefronts
+      if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) acc[t] = nxt[t];
+    store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
     __syncthreads();
   }
-  // ---- sum the row slabs in a fixed order; positions past the chunk are ignored by the pooling
-  for (int i = tid; i < n_iter * TL::kKeys && i < kPartStride; i += TL::kThreads) {
+  // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
+  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
     float a = part[i];
 #pragma unroll
     for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
@@ -339,62 +369,22 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   }
   __syncthreads();
   float* __restrict__ out = scores + (int64_t)head * scores_stride_head + begin;
-  // ---- outputs whose pooling window lies inside this chunk (sequence ends clip the window)
-  const int lo = c == 0 ? 0 : half;
-  const int hi = c == nc - 1 ? len : len - half;
-  for (int i = lo + tid; i < hi; i += TL::kThreads) {
+  for (int s = o0 + tid; s < o1; s += TL::kThreads) {
+    const int i = s - kbeg;
     float m = part[i];
     for (int o = 1; o <= half; ++o) {
-      if (i - o >= 0) m = fmaxf(m, part[i - o]);
-      if (i + o < len) m = fmaxf(m, part[i + o]);
+      if (i - o >= 0) m = fmaxf(m, part[i - o]);           // i - o < 0 only at the start of the sequence
+      if (i + o < len) m = fmaxf(m, part[i + o]);          // i + o >= len only at the end of the prefix
     }
-    out[c0 + i] = m;
+    out[s] = m;
   }
   if (c == nc - 1)
     for (int j = tid; j < p.w; j += TL::kThreads) out[prefix + j] = -INFINITY;   // guard over the window slots
-  if (half == 0 || nc == 1) return;
-  // ---- boundaries: publish 2*half raw sums per side, the second arrival pools the straddling outputs
-  const int g = blockIdx.x;                                 // linear chunk index; boundary g = left edge of chunk g
-  const int e2 = 2 * half;
-  if (c > 0 && tid < e2) edges[(((int64_t)g) * p.Hkv + head) * (2 * kEdge) + kEdge + tid] = part[tid];
-  if (c < nc - 1 && tid >= 64 && tid < 64 + e2)
-    edges[(((int64_t)(g + 1)) * p.Hkv + head) * (2 * kEdge) + (tid - 64)] = part[len - e2 + (tid - 64)];
-  __threadfence();
-  __syncthreads();
-  if (tid < 2) {
-    const bool has = tid == 0 ? c > 0 : c < nc - 1;
-    int sec = 0;
-    if (has) {
-      int32_t* ctr = &edge_counters[((int64_t)(g + tid)) * p.Hkv + head];
-      sec = atomicAdd(ctr, 1) == 1;
-      if (sec) *ctr = 0;                                    // ready for the next call
-    }
-    second[tid] = sec;
-  }
-  __syncthreads();
-  for (int side = 0; side < 2; ++side) {
-    if (!second[side]) continue;
-    __threadfence();
-    const int gb = g + side;                                // boundary index
-    const int b = side == 0 ? c0 : c1;                      // boundary position in the sequence
-    const float* __restrict__ e = edges + (((int64_t)gb) * p.Hkv + head) * (2 * kEdge);
-    // raw[b - 2*half + i] for i in [0, 4*half): left side then right side
-    if (tid < e2) {
-      // output position b - half + tid needs raw [b - 2*half + tid, b + tid]
-      float m = -INFINITY;
-      for (int o = 0; o <= e2; ++o) {
-        const int i = tid + o;                              // index into the 4*half raw values
-        const float v = i < e2 ? __hip_atomic_load(e + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                               : __hip_atomic_load(e + kEdge + (i - e2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        m = fmaxf(m, v);
-      }
-      out[b - half + tid] = m;
-    }
-  }
 }
 
-bool score_mfma_supported(const Params& p, int dtype) {
-  return dtype == DKV_BF16 && p.d == 128 && p.rows <= 256 && p.half <= 31;
+bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token) {
+  return dtype == DKV_BF16 && p.d == 128 && p.rows <= 256 && 2 * p.half <= kMaxHalo &&
+         k_stride_token * 2 < (1 << 24);
 }
 
 static int pick_chunk(const Params& p, int keys_per_iter) {
@@ -411,18 +401,14 @@ static int pick_chunk(const Params& p, int keys_per_iter) {
 }
 
 template <int RS, int KS>
-static hipError_t launch_mfma_t(const Params& p, const void* q_win, const void* k, int64_t k_stride_token,
+static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                                 char* ws, const WorkspaceLayout& wl, hipStream_t st) {
   using TL = Tile<RS, KS>;
   const int chunk = pick_chunk(p, TL::kKeys);
-  int32_t* counters = reinterpret_cast<int32_t*>(ws + wl.counters);
-  int32_t* edge_counters = reinterpret_cast<int32_t*>(ws + wl.edge_counters);
-  float* lse2 = reinterpret_cast<float*>(ws + wl.lse);
   float* partials = reinterpret_cast<float*>(ws + wl.partials);
-  float* edges = reinterpret_cast<float*>(ws + wl.edges);
   const size_t lds_stats = 2 * TL::kTileBytes + (size_t)KS * RS * 64 * sizeof(float2);
-  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + 2 * kEdge) * sizeof(float);
+  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + TL::kKeys) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_stats_mfma<RS, KS>),
@@ -434,21 +420,23 @@ static hipError_t launch_mfma_t(const Params& p, const void* q_win, const void* 
     attr_set = true;
   }
   const int grid_x = p.total_tokens / chunk + p.n_seqs;      // upper bound on chunks over all sequences
-  hipLaunchKernelGGL((score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
-                     static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
-                     k_stride_head * 2, cu, counters, lse2, partials);
-  hipLaunchKernelGGL((score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
-                     static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
-                     k_stride_head * 2, cu, lse2, edge_counters, edges, scores, scores_stride_head);
+  if (phases & kPhaseStats)
+    hipLaunchKernelGGL((score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
+                       static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
+                       k_stride_head * 2, cu, partials);
+  if (phases & kPhaseEmit)
+    hipLaunchKernelGGL((score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
+                       static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
+                       k_stride_head * 2, cu, partials, scores, scores_stride_head);
   return hipGetLastError();
 }
 
-hipError_t launch_score_mfma(const Params& p, const void* q_win, const void* k, int64_t k_stride_token,
+hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                              int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                              char* ws, const WorkspaceLayout& wl, hipStream_t st) {
-  if (p.rows <= 64) return launch_mfma_t<1, 4>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  if (p.rows <= 128) return launch_mfma_t<2, 4>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  return launch_mfma_t<4, 2>(p, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  if (p.rows <= 64) return launch_mfma_t<1, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  if (p.rows <= 128) return launch_mfma_t<2, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  return launch_mfma_t<4, 2>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
 }
 
 }  // namespace dkv

@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libdkv.so")
 DKV_F32, DKV_BF16 = 0, 1
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
-EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_workspace_init", "dkv_score_window",
-           "dkv_select_topk", "dkv_rebalance", "dkv_gather_kv")
+EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_score_window",
+           "dkv_score_window_stats", "dkv_score_window_emit", "dkv_select_topk", "dkv_rebalance", "dkv_gather_kv")
 
 
 class dkv_desc(C.Structure):
@@ -41,6 +41,7 @@ def load() -> C.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    import torch  # noqa: F401  (loads the HIP runtime the library is linked against, before the library)
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError("libdkv.so not built: run `python -m paper_2412_14838_amd.build` (%s)" % LIB_PATH)
     lib = C.CDLL(LIB_PATH)
@@ -52,10 +53,9 @@ def load() -> C.CDLL:
     lib.dkv_status_string.argtypes = [C.c_int]
     lib.dkv_workspace_bytes.restype = SZ
     lib.dkv_workspace_bytes.argtypes = [D]
-    lib.dkv_workspace_init.restype = C.c_int
-    lib.dkv_workspace_init.argtypes = [D, P, SZ, P]
-    lib.dkv_score_window.restype = C.c_int
-    lib.dkv_score_window.argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
+    for name in ("dkv_score_window", "dkv_score_window_stats", "dkv_score_window_emit"):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
     lib.dkv_select_topk.restype = C.c_int
     lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P]
     lib.dkv_rebalance.restype = C.c_int
@@ -111,16 +111,27 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
     return int(load().dkv_workspace_bytes(C.byref(desc)))
 
 
-def dkv_workspace_init(desc, workspace, stream=None) -> None:
-    _check(load().dkv_workspace_init(C.byref(desc), _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                     _stream(stream)), "dkv_workspace_init")
-
-
 def dkv_score_window(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
                      workspace, stream=None) -> None:
     _check(load().dkv_score_window(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head, _ptr(cu_seqlens),
                                    _ptr(scores_out), scores_stride_head, _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_score_window")
+
+
+def dkv_score_window_stats(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+                           workspace, stream=None) -> None:
+    _check(load().dkv_score_window_stats(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head,
+                                         _ptr(cu_seqlens), _ptr(scores_out), scores_stride_head, _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_score_window_stats")
+
+
+def dkv_score_window_emit(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+                          workspace, stream=None) -> None:
+    _check(load().dkv_score_window_emit(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head,
+                                        _ptr(cu_seqlens), _ptr(scores_out), scores_stride_head, _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_score_window_emit")
 
 
 def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts, stream=None) -> None:
@@ -143,11 +154,9 @@ def dkv_gather_kv(desc, layer, k, v, stride_token, stride_head, cu_seqlens, idx,
 
 
 def alloc_workspace(desc, device="cuda"):
-    """Allocate (torch) and initialise the workspace the stage calls need."""
+    """Allocate (torch) the workspace the stage calls need."""
     import torch
     n = dkv_workspace_bytes(desc)
     if n == 0:
         raise DkvError(DKV_ERR_INVALID_ARG, "dkv_workspace_bytes")
-    ws = torch.empty(n, dtype=torch.uint8, device=device)
-    dkv_workspace_init(desc, ws)
-    return ws
+    return torch.empty(n, dtype=torch.uint8, device=device)

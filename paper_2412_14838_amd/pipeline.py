@@ -71,6 +71,17 @@ class Compressor:
         for l, (q, k, v) in enumerate(layers):
             self.step(l, q, k, v)
 
+    def capture(self, layers):
+        """Record the whole layer loop over resident inputs into a HIP graph (replay with .replay()).
+
+        The stage calls allocate nothing, never synchronise and clear their scratch with kernels, so the
+        loop is capturable as it stands.  Run the loop eagerly once before capturing (first launches set
+        kernel attributes)."""
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run(layers)
+        return graph
+
 
 def to_device(cfg, layer_data, device="cuda"):
     """Upload one make_layer() result in the workload's storage type (values are exactly representable)."""

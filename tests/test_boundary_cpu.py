@@ -69,7 +69,6 @@ def test_workspace_bytes(lib):
 def test_bad_descriptors_are_rejected(lib, bad, status):
     d = _good(**bad)
     fake = C.c_void_p(0x1000)
-    assert lib.dkv_workspace_init(C.byref(d), fake, 1 << 30, None) == status
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 64 * 1024, fake, fake, 1024, fake, 1 << 30, None) == status
     assert lib.dkv_select_topk(C.byref(d), 0, fake, 1024, fake, fake, fake, None) == status
     assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 1 << 30, None) == status
