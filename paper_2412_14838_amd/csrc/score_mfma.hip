@@ -56,27 +56,39 @@ __device__ inline void load_q_frags(const uint16_t* __restrict__ q_head, int rs,
   }
 }
 
+// One tile of keys in flight between global memory and LDS: kPieces 16-byte pieces per thread, held as ONE
+// vector value (a plain array would be demoted to scratch memory across the loop).
+template <int N> struct PieceVec;
+template <> struct PieceVec<2> { typedef uint32_t type __attribute__((ext_vector_type(8))); };
+template <> struct PieceVec<4> { typedef uint32_t type __attribute__((ext_vector_type(16))); };
+template <> struct PieceVec<8> { typedef uint32_t type __attribute__((ext_vector_type(32))); };
+
 // Fetches one tile of keys [row0, row0 + kKeys) (relative to the chunk start, clamped to its last row, so every
 // load stays inside the chunk and clamped rows are cache hits) into registers.
 template <int RS, int KS>
-__device__ inline void load_tile(const char* __restrict__ k_chunk, uint32_t stride_token_b, int row0, int last_row,
-                                 uint4 (&reg)[Tile<RS, KS>::kPieces]) {
+__device__ inline typename PieceVec<Tile<RS, KS>::kPieces>::type load_tile(const char* __restrict__ k_chunk,
+                                                                            uint32_t stride_token_b, int row0,
+                                                                            int last_row) {
+  typename PieceVec<Tile<RS, KS>::kPieces>::type reg;
 #pragma unroll
   for (int i = 0; i < Tile<RS, KS>::kPieces; ++i) {
     const int p = threadIdx.x + i * Tile<RS, KS>::kThreads;
     int row = row0 + (p >> 4);
     row = row < last_row ? row : last_row;
     const uint32_t off = __umul24((uint32_t)row, stride_token_b) + (uint32_t)(p & 15) * 16u;
-    reg[i] = *reinterpret_cast<const uint4*>(k_chunk + off);
+    const uint4 v = *reinterpret_cast<const uint4*>(k_chunk + off);
+    reg[4 * i] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
   }
+  return reg;
 }
 
 template <int RS, int KS>
-__device__ inline void store_tile(char* __restrict__ buf, const uint4 (&reg)[Tile<RS, KS>::kPieces]) {
+__device__ inline void store_tile(char* __restrict__ buf, typename PieceVec<Tile<RS, KS>::kPieces>::type reg) {
 #pragma unroll
   for (int i = 0; i < Tile<RS, KS>::kPieces; ++i) {
     const int p = threadIdx.x + i * Tile<RS, KS>::kThreads;
-    *reinterpret_cast<uint4*>(buf + (p >> 4) * kLdsRow + (p & 15) * 16) = reg[i];
+    *reinterpret_cast<uint4*>(buf + (p >> 4) * kLdsRow + (p & 15) * 16) =
+        make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
   }
 }
 
@@ -155,8 +167,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const char* __restrict__ k_chunk =
       k + ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
-  uint4 reg[TL::kPieces];
-  load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1, reg);
+  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
@@ -168,7 +179,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 
   store_tile<RS, KS>(tiles, reg);
-  load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1, reg);
+  reg = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   __syncthreads();
   floatx16 acc[2], nxt[2];
   mfma_tile<true>(tiles + lane_tile, qf, acc);
@@ -176,7 +187,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   __syncthreads();
   for (int it = 0; it < n_iter; ++it) {
     // prefetch tile it + 2 (registers), MFMAs of tile it + 1, exponentials of tile it
-    load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1, reg);
+    reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
     const bool next_active = wave_row0 + TL::kKeys < len;
     if (next_active) mfma_tile<true>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
@@ -280,8 +291,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const char* __restrict__ k_chunk =
       k + ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
-  uint4 reg[TL::kPieces];
-  load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1, reg);
+  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
     mstage[q * kRows + r] = make_float2(M, Lsum);
     store_tile<RS, KS>(tiles, reg);
-    load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1, reg);
+    reg = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
     __syncthreads();
     if (tid < kRows) {
       float Mx = -INFINITY;
@@ -334,7 +344,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
 
   for (int it = 0; it < n_iter; ++it) {
-    load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1, reg);
+    reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
     const bool next_active = wave_row0 + TL::kKeys < len;
     if (next_active) mfma_tile<false>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
