@@ -43,7 +43,7 @@ enum {
 };
 
 /* Limits of this build (checked by every call). */
-#define DKV_MAX_LAYER_MAX 4096 /* B^l                                        */
+#define DKV_MAX_LAYER_MAX 2048 /* B^l                                        */
 #define DKV_MAX_POOL 63        /* pooling kernel size                        */
 #define DKV_MAX_ROWS 256       /* G * window: score rows per KV head         */
 #define DKV_MAX_SEQS 4096

@@ -12,6 +12,7 @@ namespace dkv {
 
 constexpr int kDecThreads = 1024;
 constexpr int kDecWaves = kDecThreads / 64;
+constexpr int kScanCopies = 4;   // interleaved copies of the LDS histogram: lanes sharing a digit spread over 4 words
 
 // state[seq][8]: 0 prefix bits of T found so far, 1 remaining rank, 2..4 chosen digit of pass 0..2, 5 kg
 __device__ inline int digit_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv
                                                              const float* __restrict__ scores_all,
                                                              const int32_t* __restrict__ cu, int32_t* __restrict__ hist,
                                                              const int32_t* __restrict__ state) {
-  __shared__ int h[kRadixBins];
+  __shared__ int h[kRadixBins * kScanCopies];
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kRebalanceChunk, w, blockIdx.x, seq, c, begin, len)) return;
   const int head = blockIdx.y, layer = blockIdx.z;
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv
     if (state[seq * 8 + 5] == 0) return;   // kg == 0: nothing to select
     prefix = (uint32_t)state[seq * 8 + 0];
   }
-  for (int b = threadIdx.x; b < kRadixBins; b += 256) h[b] = 0;
+  for (int b = threadIdx.x; b < kRadixBins * kScanCopies; b += 256) h[b] = 0;
   __syncthreads();
   const uint32_t* __restrict__ row =
       reinterpret_cast<const uint32_t*>(scores_all + ((int64_t)layer * Hkv + head) * total_tokens + begin);
@@ -45,12 +46,14 @@ __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv
   for (int i = i0 + threadIdx.x; i < i1; i += 256) {
     const uint32_t u = row[i];
     const bool match = PASS == 0 ? true : ((u >> ushift) == (prefix >> ushift));
-    if (match) atomicAdd(&h[(u >> shift) & (kRadixBins - 1)], 1);
+    if (match) atomicAdd(&h[((u >> shift) & (kRadixBins - 1)) * kScanCopies + (threadIdx.x & (kScanCopies - 1))], 1);
   }
   __syncthreads();
   int32_t* __restrict__ g = hist + (((int64_t)PASS * n_seqs + seq) * L + layer) * kRadixBins;
   for (int b = threadIdx.x; b < kRadixBins; b += 256) {
-    const int v = h[b];
+    int v = 0;
+#pragma unroll
+    for (int c2 = 0; c2 < kScanCopies; ++c2) v += h[b * kScanCopies + c2];
     if (v) atomicAdd(&g[b], v);
   }
 }

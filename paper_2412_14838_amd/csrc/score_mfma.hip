@@ -112,6 +112,18 @@ __device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&q
   }
 }
 
+// Scheduling hint for a block that holds the 16 MFMAs of the next tile (with their 8 LDS reads) and the
+// exponentials of the current one: issue them interleaved, so that the matrix pipe and the vector ALU of the
+// SIMD are busy at the same time within one wavefront.
+__device__ inline void interleave_mfma_valu() {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, 20, 0);  // 20 VALU
+  }
+}
+
 // Linear chunk index -> (sequence, chunk) for chunks of `chunk` items over (length - window_off) items per
 // sequence; also returns the number of chunks of (length) items in the earlier sequences (first_full) and in
 // this one (n_full): the statistics kernel cuts all S keys, the emit kernel the S' prefix outputs.
@@ -185,47 +197,49 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   mfma_tile<true>(tiles + lane_tile, qf, acc);
   store_tile<RS, KS>(tiles + TL::kTileBytes, reg);
   __syncthreads();
-  for (int it = 0; it < n_iter; ++it) {
-    // prefetch tile it + 2 (registers), MFMAs of tile it + 1, exponentials of tile it
+  const int lim_all = prefix_rel < len ? prefix_rel : len;
+  // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
+  // Tiles past the chunk are fully masked (they add exp2(-inf) = 0), so the step is branch-free but for the mask.
+  auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
     reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
-    const bool next_active = wave_row0 + TL::kKeys < len;
-    if (next_active) mfma_tile<true>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
-    if (wave_row0 < len) {
-      const int lim_all = prefix_rel < len ? prefix_rel : len;
-      const bool need_mask = wave_row0 + 32 > lim_all;    // touches the window or runs past the chunk
-      const int kb = wave_row0 + 4 * (lane >> 5);         // + 8 * (j / 4) + j % 4
+    if (wave_row0 + 32 > lim_all) {                      // touches the window or runs past the chunk
+      const int kb = wave_row0 + 4 * (lane >> 5);        // + 8 * (j / 4) + j % 4
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        if (need_mask) {
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const int s = kb + 8 * (j >> 2) + (j & 3);
-            if (s > limit[t] || s >= len) acc[t][j] = -INFINITY;
-          }
+        for (int j = 0; j < 16; ++j) {
+          const int s = kb + 8 * (j >> 2) + (j & 3);
+          if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
         }
-        float mx = fmaxf(acc[t][0], acc[t][1]);
-#pragma unroll
-        for (int j = 2; j < 16; j += 2) mx = fmaxf(mx, fmaxf(acc[t][j], acc[t][j + 1]));
-        const float m_new = fmaxf(m_run[t], mx * cexp);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-#pragma unroll
-        for (int j = 0; j < 16; j += 4) {
-          s0 += fast_exp2(fmaf(acc[t][j], cexp, -m_use));
-          s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -m_use));
-          s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -m_use));
-          s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -m_use));
-        }
-        l_run[t] = l_run[t] * fast_exp2(m_run[t] - m_use) + ((s0 + s1) + (s2 + s3));
-        m_run[t] = m_new;
-      }
     }
+    mfma_tile<true>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, b);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) acc[t] = nxt[t];
+    for (int t = 0; t < 2; ++t) {
+      float mx = fmaxf(a[t][0], a[t][1]);
+#pragma unroll
+      for (int j = 2; j < 16; j += 2) mx = fmaxf(mx, fmaxf(a[t][j], a[t][j + 1]));
+      const float m_new = fmaxf(m_run[t], mx * cexp);
+      const float m_use = m_new == -INFINITY ? 0.0f : m_new;
+      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 16; j += 4) {
+        s0 += fast_exp2(fmaf(a[t][j], cexp, -m_use));
+        s1 += fast_exp2(fmaf(a[t][j + 1], cexp, -m_use));
+        s2 += fast_exp2(fmaf(a[t][j + 2], cexp, -m_use));
+        s3 += fast_exp2(fmaf(a[t][j + 3], cexp, -m_use));
+      }
+      l_run[t] = l_run[t] * fast_exp2(m_run[t] - m_use) + ((s0 + s1) + (s2 + s3));
+      m_run[t] = m_new;
+    }
+    interleave_mfma_valu();
     // buffer it & 1 held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
     store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
     __syncthreads();
+  };
+  for (int it = 0; it < n_iter; it += 2) {
+    step(it, acc, nxt);
+    step(it + 1, nxt, acc);
   }
   // ---- merge the two half-wavefronts (same row, other keys), then the KS key tiles, then publish
 #pragma unroll
@@ -268,7 +282,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
   float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kPartStride]
-  constexpr int kPartStride = kMaxChunk + kMaxHalo + TL::kKeys;
+  constexpr int kPartStride = kMaxChunk + kMaxHalo + 2 * TL::kKeys;
   constexpr int kRows = RS * 64;
   float2* mstage = reinterpret_cast<float2*>(part);                            // [KS][kRows], before `part` is used
   __shared__ __attribute__((aligned(16))) float lse_s[kRows];
@@ -343,35 +357,37 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
       lse_r[t][4 * j4] = v.x; lse_r[t][4 * j4 + 1] = v.y; lse_r[t][4 * j4 + 2] = v.z; lse_r[t][4 * j4 + 3] = v.w;
     }
 
-  for (int it = 0; it < n_iter; ++it) {
+  // One step: prefetch tile it + 2, MFMAs of tile it + 1 into `b`, exponentials and column sums of tile it
+  // from `a`. Prefix keys are visible to every window row: no mask; columns past the computed range are
+  // discarded below. Fixed summation order per column.
+  auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
     reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
-    const bool next_active = wave_row0 + TL::kKeys < len;
-    if (next_active) mfma_tile<false>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, nxt);
-    if (wave_row0 < len) {
-      // prefix keys are visible to every window row: no mask. Fixed summation order per column.
-      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    mfma_tile<false>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, b);
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int j = 0; j < 16; j += 4) {
-          s0 += fast_exp2(fmaf(acc[t][j], cexp, -lse_r[t][j]));
-          s1 += fast_exp2(fmaf(acc[t][j + 1], cexp, -lse_r[t][j + 1]));
-          s2 += fast_exp2(fmaf(acc[t][j + 2], cexp, -lse_r[t][j + 2]));
-          s3 += fast_exp2(fmaf(acc[t][j + 3], cexp, -lse_r[t][j + 3]));
-        }
-      float col = (s0 + s1) + (s2 + s3);
-      const float other = __shfl_xor(col, 32);
-      col = lane < 32 ? col + other : other + col;       // rows 0-3 mod 8 first, in both half-wavefronts
-      if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
-    }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) acc[t] = nxt[t];
+      for (int j = 0; j < 16; j += 4) {
+        s0 += fast_exp2(fmaf(a[t][j], cexp, -lse_r[t][j]));
+        s1 += fast_exp2(fmaf(a[t][j + 1], cexp, -lse_r[t][j + 1]));
+        s2 += fast_exp2(fmaf(a[t][j + 2], cexp, -lse_r[t][j + 2]));
+        s3 += fast_exp2(fmaf(a[t][j + 3], cexp, -lse_r[t][j + 3]));
+      }
+    interleave_mfma_valu();
+    float col = (s0 + s1) + (s2 + s3);
+    const float other = __shfl_xor(col, 32);
+    col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
+    if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
     store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
     __syncthreads();
+  };
+  for (int it = 0; it < n_iter; it += 2) {
+    step(it, acc, nxt);
+    step(it + 1, nxt, acc);
   }
   // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
-  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
+  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {   // steps past n_iter wrote beyond this range
     float a = part[i];
 #pragma unroll
     for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
@@ -418,7 +434,7 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
   const int chunk = pick_chunk(p, TL::kKeys);
   float* partials = reinterpret_cast<float*>(ws + wl.partials);
   const size_t lds_stats = 2 * TL::kTileBytes + (size_t)KS * RS * 64 * sizeof(float2);
-  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + TL::kKeys) * sizeof(float);
+  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + 2 * TL::kKeys) * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_stats_mfma<RS, KS>),

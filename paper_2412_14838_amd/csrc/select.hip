@@ -1,13 +1,24 @@
 // Per-layer, per-KV-head top-k (Eq. 3; Algorithm 1: indices <- A^l.topk(B^l, dim=-1).indices).
-// One workgroup per (sequence, KV head): an LDS radix-select over the fp32 bit patterns finds the k-th
-// largest score, a wavefront-ballot compaction collects the winners (ties to the lower position), and a
-// bitonic sort orders them by (score descending, position ascending).
+// One workgroup per (sequence, KV head):
+//   1. LDS radix-select (3 digits of 11/11/10 bits of the fp32 pattern; scores are >= 0 so patterns order like
+//      values) finds the k-th largest score T. The digit histogram is kept in 8 interleaved copies so that
+//      lanes whose scores share a digit do not serialise on one LDS word.
+//   2. wavefront-ballot compaction collects the winners: everything above T, and the first (k - #above)
+//      elements equal to T in position order (ties go to the lower position).
+//   3. a bitonic sort of 64-bit keys (~score bits, position) orders them by (score descending, position
+//      ascending). Each thread holds two keys in registers; exchanges inside a wavefront use lane shuffles,
+//      only the 14 exchanges that cross wavefronts go through LDS and a workgroup barrier.
 #include "dkv_internal.h"
 
 namespace dkv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kHistCopies = 8;
+constexpr int kSelPerThread = 32;                              // row positions a thread keeps in registers
+constexpr int kSelResident = kSelPerThread * kSelThreads;      // 32768 positions
+
+typedef unsigned long long u64;
 
 __device__ inline int wave_inclusive_scan(int v) {
   const int lane = threadIdx.x & 63;
@@ -31,16 +42,40 @@ __device__ inline int block_exclusive_scan(int v, int* scratch) {
   return base + incl - v;
 }
 
-// Finds the bin that holds the `rem`-th largest element, given a histogram over kRadixBins digit values.
-// Returns via shared `out[0]` = bin, `out[1]` = number of elements in higher bins. Bins are scanned from the top.
-__device__ inline void pick_bin_desc(const int* __restrict__ hist, int rem, int* scratch, int* out) {
-  static_assert(kRadixBins == 2 * kSelThreads, "two bins per thread");
-  const int hi = kRadixBins - 1 - 2 * threadIdx.x, lo = hi - 1;
-  const int c_hi = hist[hi], c_lo = hist[lo];
-  const int above = block_exclusive_scan(c_hi + c_lo, scratch);
-  if (above < rem && rem <= above + c_hi) { out[0] = hi; out[1] = above; }
-  else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { out[0] = lo; out[1] = above + c_hi; }
-  __syncthreads();
+__device__ inline u64 shfl_xor_u64(u64 v, int mask) {
+  const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
+  return ((u64)hi << 32) | lo;
+}
+
+// Bitonic sort of 2 * kSelThreads = 2048 keys, ascending; thread t holds elements t (k0) and t + 1024 (k1).
+// `n_sort` (power of two, 2..2048) is the number of leading elements that matter: the rest are ~0 pads, and
+// stages larger than n_sort are skipped for them by construction (pads never move below a real key).
+__device__ inline void bitonic_sort_2048(u64& k0, u64& k1, u64* __restrict__ xchg, int n_sort) {
+  const int t = threadIdx.x;
+  for (int size = 2; size <= n_sort; size <<= 1) {
+    // element e sorts ascending in this stage iff (e & size) == 0; at size 2048 everything is ascending
+    const bool up0 = (t & size) == 0;
+    const bool up1 = size == 2048 ? true : (((t + 1024) & size) == 0);
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      if (stride == 1024) {                         // partner is the thread's other element
+        const u64 lo = k0 < k1 ? k0 : k1, hi = k0 < k1 ? k1 : k0;
+        k0 = lo; k1 = hi;                           // only reached at size 2048: ascending
+      } else if (stride >= 64) {                    // partner lives in another wavefront
+        xchg[t] = k0; xchg[t + 1024] = k1;
+        __syncthreads();
+        const u64 p0 = xchg[t ^ stride], p1 = xchg[(t ^ stride) + 1024];
+        __syncthreads();
+        const bool lower = (t & stride) == 0;       // this thread holds the lower-indexed element of the pair
+        k0 = (lower == up0) ? (k0 < p0 ? k0 : p0) : (k0 < p0 ? p0 : k0);
+        k1 = (lower == up1) ? (k1 < p1 ? k1 : p1) : (k1 < p1 ? p1 : k1);
+      } else {                                      // partner is a lane of this wavefront
+        const u64 p0 = shfl_xor_u64(k0, stride), p1 = shfl_xor_u64(k1, stride);
+        const bool lower = (t & stride) == 0;
+        k0 = (lower == up0) ? (k0 < p0 ? k0 : p0) : (k0 < p0 ? p0 : k0);
+        k1 = (lower == up1) ? (k1 < p1 ? k1 : p1) : (k1 < p1 ? p1 : k1);
+      }
+    }
+  }
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer,
@@ -49,8 +84,9 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
                                                                   const int32_t* __restrict__ cu,
                                                                   int32_t* __restrict__ idx_out,
                                                                   int32_t* __restrict__ counts) {
-  __shared__ unsigned long long keys[DKV_MAX_LAYER_MAX];
-  __shared__ int hist[kRadixBins];
+  extern __shared__ __attribute__((aligned(16))) char sel_smem[];
+  u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
+  int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
   __shared__ int scratch[kSelWaves];
   __shared__ int picked[2];
   __shared__ int n_greater_slots;
@@ -70,22 +106,47 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   }
   const uint32_t* __restrict__ row = reinterpret_cast<const uint32_t*>(scores + (int64_t)head * scores_stride_head + begin);
 
-  // ---- radix select: the k-th largest bit pattern (scores are >= 0, so patterns order like the values)
+  // The first kSelResident positions of the row live in registers for all passes: thread t holds positions
+  // j * 1024 + t (coalesced loads, issued back to back). Longer rows re-read their tail from memory.
+  uint32_t v[kSelPerThread];
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    const int i = j * kSelThreads + tid;
+    v[j] = i < n ? row[i] : 0u;
+  }
+  const int n_res = n < kSelResident ? n : kSelResident;   // positions held in registers
+
+  // ---- radix select: the k-th largest bit pattern
   uint32_t prefix = 0;
   int rem = k;
 #pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
     const int hshift = pass == 0 ? 32 : (pass == 1 ? 21 : 10);   // bits above this digit
-    for (int b = tid; b < kRadixBins; b += kSelThreads) hist[b] = 0;
+    for (int b = tid; b < kRadixBins * kHistCopies; b += kSelThreads) hist[b] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += kSelThreads) {
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+      const uint32_t u = v[j];
+      const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
+      if (j * kSelThreads + tid < n_res && match)
+        atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * kHistCopies + (lane & (kHistCopies - 1))], 1);
+    }
+    for (int i = kSelResident + tid; i < n; i += kSelThreads) {
       const uint32_t u = row[i];
       const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
-      if (match) atomicAdd(&hist[(u >> shift) & (kRadixBins - 1)], 1);
+      if (match) atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * kHistCopies + (lane & (kHistCopies - 1))], 1);
     }
     __syncthreads();
-    pick_bin_desc(hist, rem, scratch, picked);
+    // thread t owns digits 2047 - 2t and 2046 - 2t (scanned from the top)
+    const int hi = kRadixBins - 1 - 2 * tid, lo = hi - 1;
+    int c_hi = 0, c_lo = 0;
+#pragma unroll
+    for (int c = 0; c < kHistCopies; ++c) { c_hi += hist[hi * kHistCopies + c]; c_lo += hist[lo * kHistCopies + c]; }
+    const int above = block_exclusive_scan(c_hi + c_lo, scratch);
+    if (above < rem && rem <= above + c_hi) { picked[0] = hi; picked[1] = above; }
+    else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { picked[0] = lo; picked[1] = above + c_hi; }
+    __syncthreads();
     prefix |= (uint32_t)picked[0] << shift;
     rem -= picked[1];
     __syncthreads();
@@ -94,70 +155,108 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   const int need_eq = rem;        // how many elements equal to T are taken (>= 1)
   const int n_gt = k - need_eq;   // elements strictly greater than T
 
-  // ---- compaction. Each wavefront walks a contiguous segment in 64-wide coalesced steps.
+  // ---- compaction: everything above T (any order: the sort fixes it), and the first need_eq elements equal
+  // to T in position order. Position order of the resident part is (j, wavefront, lane).
+  int* eq_base = hist;            // [kSelPerThread][kSelWaves] counts, then exclusive prefix sums (reuses hist)
   if (tid == 0) n_greater_slots = 0;
+  for (int j = k + tid; j < 2048; j += kSelThreads) keys[j] = ~0ull;      // pads sort to the end
   __syncthreads();
-  int seg = (n + kSelWaves - 1) / kSelWaves;
-  seg = (seg + 63) / 64 * 64;
-  const int seg_begin = wv * seg;
-  const int seg_end = seg_begin + seg < n ? seg_begin + seg : n;
-  int eq_count = 0;
-  for (int i0 = seg_begin; i0 < seg_end; i0 += 64) {
-    const int i = i0 + lane;
-    const uint32_t u = i < seg_end ? row[i] : 0u;
-    const bool gt = i < seg_end && u > T;
-    const bool eq = i < seg_end && u == T;
-    const unsigned long long gmask = __ballot(gt);
-    eq_count += __popcll(__ballot(eq));
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    const int i = j * kSelThreads + tid;
+    const uint32_t u = v[j];
+    const bool gt = i < n_res && u > T;
+    const bool eq = i < n_res && u == T;
+    const unsigned long long gmask = __ballot(gt), emask = __ballot(eq);
+    if (lane == 0) eq_base[j * kSelWaves + wv] = __popcll(emask);
     if (gmask) {
       int base = 0;
       if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
       base = __shfl(base, 0);
-      if (gt) {
-        const int slot = base + __popcll(gmask & ((1ull << lane) - 1ull));
-        keys[slot] = ((unsigned long long)(~u) << 32) | (uint32_t)i;
-      }
+      if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
     }
   }
-  if (lane == 0) wave_eq[wv] = eq_count;
   __syncthreads();
-  int running = 0;
-  for (int i = 0; i < wv; ++i) running += wave_eq[i];
-  // equal elements are taken in position order until need_eq are placed
-  for (int i0 = seg_begin; i0 < seg_end && running < need_eq; i0 += 64) {
-    const int i = i0 + lane;
-    const bool eq = i < seg_end && row[i] == T;
+  {
+    static_assert(kSelPerThread * kSelWaves <= kSelThreads, "one count per thread");
+    const int c = tid < kSelPerThread * kSelWaves ? eq_base[tid] : 0;
+    const int ex = block_exclusive_scan(c, scratch);
+    if (tid < kSelPerThread * kSelWaves) eq_base[tid] = ex;
+    if (tid == kSelPerThread * kSelWaves - 1) picked[0] = ex + c;   // equal elements in the resident part
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    const int i = j * kSelThreads + tid;
+    const bool eq = i < n_res && v[j] == T;
     const unsigned long long emask = __ballot(eq);
     if (eq) {
-      const int rank = running + __popcll(emask & ((1ull << lane) - 1ull));
-      if (rank < need_eq) keys[n_gt + rank] = ((unsigned long long)(~T) << 32) | (uint32_t)i;
+      const int rank = eq_base[j * kSelWaves + wv] + __popcll(emask & ((1ull << lane) - 1ull));
+      if (rank < need_eq) keys[n_gt + rank] = ((u64)(~T) << 32) | (uint32_t)i;
     }
-    running += __popcll(emask);
   }
-  int KP = 2;
-  while (KP < k) KP <<= 1;
-  for (int j = k + tid; j < KP; j += kSelThreads) keys[j] = ~0ull;
+  if (n > kSelResident) {
+    // tail of a long row: contiguous segments per wavefront, walked in 64-wide coalesced steps
+    const int eq_resident = picked[0];
+    const int tail = n - kSelResident;
+    int seg = (tail + kSelWaves - 1) / kSelWaves;
+    seg = (seg + 63) / 64 * 64;
+    const int seg_begin = kSelResident + wv * seg;
+    const int seg_end = seg_begin + seg < n ? seg_begin + seg : n;
+    int eq_count = 0;
+    for (int i0 = seg_begin; i0 < seg_end; i0 += 64) {
+      const int i = i0 + lane;
+      const uint32_t u = i < seg_end ? row[i] : 0u;
+      const bool gt = i < seg_end && u > T;
+      const bool eq = i < seg_end && u == T;
+      const unsigned long long gmask = __ballot(gt);
+      eq_count += __popcll(__ballot(eq));
+      if (gmask) {
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
+        base = __shfl(base, 0);
+        if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
+      }
+    }
+    if (lane == 0) wave_eq[wv] = eq_count;
+    __syncthreads();
+    int running = eq_resident;
+    for (int i = 0; i < wv; ++i) running += wave_eq[i];
+    for (int i0 = seg_begin; i0 < seg_end && running < need_eq; i0 += 64) {
+      const int i = i0 + lane;
+      const bool eq = i < seg_end && row[i] == T;
+      const unsigned long long emask = __ballot(eq);
+      if (eq) {
+        const int rank = running + __popcll(emask & ((1ull << lane) - 1ull));
+        if (rank < need_eq) keys[n_gt + rank] = ((u64)(~T) << 32) | (uint32_t)i;
+      }
+      running += __popcll(emask);
+    }
+  }
   __syncthreads();
 
-  // ---- bitonic sort of KP composite keys (ascending = score descending, position ascending)
-  for (int size = 2; size <= KP; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < (KP >> 1); t += kSelThreads) {
-        const int lo = 2 * t - (t & (stride - 1));
-        const int hi = lo + stride;
-        const bool up = (lo & size) == 0;
-        const unsigned long long a = keys[lo], b = keys[hi];
-        if ((a > b) == up) { keys[lo] = b; keys[hi] = a; }
-      }
-      __syncthreads();
-    }
-  }
-  for (int j = tid; j < layer_max; j += kSelThreads) out[j] = j < k ? (int32_t)(uint32_t)keys[j] : -1;
+  // ---- order the k winners: (score descending, position ascending) = ascending composite key
+  int n_sort = 2;
+  while (n_sort < k) n_sort <<= 1;
+  u64 k0 = keys[tid], k1 = keys[tid + 1024];
+  __syncthreads();
+  bitonic_sort_2048(k0, k1, keys, n_sort);
+  if (tid < layer_max) out[tid] = tid < k ? (int32_t)(uint32_t)k0 : -1;
+  if (tid + 1024 < layer_max) out[tid + 1024] = tid + 1024 < k ? (int32_t)(uint32_t)k1 : -1;
+  for (int j = 2048 + tid; j < layer_max; j += kSelThreads) out[j] = -1;
 }
 
 hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,
                          const int32_t* cu, int32_t* idx_out, int32_t* counts, hipStream_t st) {
-  hipLaunchKernelGGL(select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), 0, st, p.Hkv, p.w, p.layer_max,
+  const size_t lds = 2048 * sizeof(u64) + (size_t)kRadixBins * kHistCopies * sizeof(int);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_topk_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max,
                      p.L, layer, scores, scores_stride_head, cu, idx_out, counts);
   return hipGetLastError();
 }

@@ -135,7 +135,7 @@ def test_select_topk_bit_exact(dkv, case):
 
 def test_select_topk_large_k_and_long_rows(dkv):
     """Maximum layer_max, a 40000-position row, k > S' and k == S'."""
-    cfg = small_cfg("long", Hq=2, Hkv=2, seqlens=(40000, 4096 + 32, 3000), layer_max=4096, mean_budget=512, L=1,
+    cfg = small_cfg("long", Hq=2, Hkv=2, seqlens=(40000, 2048 + 32, 1000), layer_max=2048, mean_budget=512, L=1,
                     interval=1)
     comp = Compressor(cfg, keep_cache=False)
     cu = cfg.cu_seqlens
