@@ -4,7 +4,7 @@
 A step = one pass of Algorithm 1's layer loop over one synthetic batch: for every layer score (two kernels),
 select, gather, and the progressive update every `interval` layers.  All inputs are resident in HBM before
 the timed region.  Prints ONE JSON line: context tokens compressed per second, the roofline of the dominant
-kernel (timed live with events on the launch stream) and the CPU oracle timed on a bounded sample.
+kernel (timed live with HIP events attached to its launches) and the CPU oracle timed on a bounded sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
@@ -24,15 +24,24 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
-def _cpu_baseline(cfg, host_layers, n_layers):
-    """The oracle as it stands on the first `n_layers` layers (one progressive update included)."""
+def _cpu_baseline(cfg, host_layers, target_s=12.0):
+    """The oracle as it stands on the first layers of the workload (whole update intervals), sized by a
+    one-interval pilot so that the measured run takes about `target_s` seconds of CPU time."""
     from oracle import dkv_oracle as O
     cu = cfg.cu_seqlens
-    t0 = time.perf_counter()
-    for s in range(cfg.n_seqs):
-        layers = [(d["q_win"][s], d["k"][:, cu[s]:cu[s + 1]], d["v"][:, cu[s]:cu[s + 1]]) for d in host_layers[:n_layers]]
-        O.compress(layers, cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval)
-    dt = time.perf_counter() - t0
+
+    def run(n_layers):
+        t0 = time.perf_counter()
+        for s in range(cfg.n_seqs):
+            layers = [(d["q_win"][s], d["k"][:, cu[s]:cu[s + 1]], d["v"][:, cu[s]:cu[s + 1]])
+                      for d in host_layers[:n_layers]]
+            O.compress(layers, cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval)
+        return time.perf_counter() - t0
+
+    pilot = run(cfg.interval)
+    blocks = max(1, min(len(host_layers) // cfg.interval, int(target_s / max(pilot, 1e-3))))
+    n_layers = blocks * cfg.interval
+    dt = run(n_layers) if blocks > 1 else pilot
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -40,8 +49,8 @@ def _cpu_baseline(cfg, host_layers, n_layers):
         cores = len(os.sched_getaffinity(0))
     tokens_per_s = cfg.total_tokens / (dt * cfg.L / n_layers)
     return {"value": tokens_per_s, "unit": "context tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "first %d of %d layers of the same workload (scoring, selection, gather, one progressive update), "
-                      "%.1f s of CPU time, scaled by L/%d" % (n_layers, cfg.L, dt, n_layers)}
+            "sample": "first %d of %d layers of the same workload (scoring, selection, gather, %d progressive "
+                      "update(s)), %.1f s of CPU time, scaled by L/%d" % (n_layers, cfg.L, blocks, dt, n_layers)}
 
 
 def main():
@@ -68,7 +77,7 @@ def main():
     with cf.ThreadPoolExecutor(max_workers=workers) as ex:
         for l, data in enumerate(ex.map(lambda l: W.make_layer(cfg, l), range(cfg.L))):
             dev.append(to_device(cfg, data))
-            if l < cfg.interval and not args.no_cpu_baseline:
+            if not args.no_cpu_baseline and (l + 1) * cfg.Hkv * cfg.total_tokens * cfg.d * 8 < 12e9:
                 host_sample.append(data)
     torch.cuda.synchronize()
 
@@ -76,7 +85,6 @@ def main():
     d, T = cfg.d, cfg.total_tokens
     st, sh = d, T * d
     desc, cu, ws = comp.desc, comp.cu, comp.ws
-    names = ("score_stats", "score_emit", "select", "gather", "rebalance")
     layers = [(x["q_win"], x["k"], x["v"]) for x in dev]
 
     # ---- throughput: the whole loop as one HIP graph, K replays between two synchronisations
@@ -93,54 +101,25 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
 
-    # ---- per-kernel durations: the same K steps launched eagerly with an event between any two calls.
-    # The GPU is first given a few ms of unrelated work so that the host has enqueued the whole step before
-    # the first kernel starts: every event-to-event span then holds kernel time only, not launch latency.
-    def one_step(events):
-        for l in range(cfg.L):
-            q, k, v = layers[l]
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
-            ev[0].record()
-            dkv.dkv_score_window_stats(desc, q, k, st, sh, cu, comp.scores[l], T, ws)
-            ev[1].record()
-            dkv.dkv_score_window_emit(desc, q, k, st, sh, cu, comp.scores[l], T, ws)
-            ev[2].record()
-            comp.select(l)
-            ev[3].record()
-            comp.gather(l, k, v)
-            ev[4].record()
-            if (l + 1) % cfg.interval == 0:
-                comp.rebalance(l + 1)
-            ev[5].record()
-            events.append(ev)
-
-    ballast = torch.randn((8192, 8192), device="cuda", dtype=torch.bfloat16)
+    # ---- per-kernel durations: the same K steps launched eagerly inside a profiling session of the library:
+    # every launch carries its own start/stop HIP event pair on the launch stream (events cannot be read back
+    # from inside a replayed graph), so each figure is the kernel's own duration, launch gaps excluded.
+    launches_per_step = 4 * cfg.L + 7 * (cfg.L // cfg.interval)
+    capacity = launches_per_step * args.steps + 16
+    dkv.dkv_profile_begin(capacity)
     t0 = time.perf_counter()
-    one_step([])
-    enqueue_ms = (time.perf_counter() - t0) * 1e3
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(); torch.mm(ballast, ballast); e1.record()
-    torch.cuda.synchronize()
-    n_ballast = int(2.0 * enqueue_ms / max(e0.elapsed_time(e1), 0.05)) + 2
-    events = []
     for _ in range(args.steps):
-        for _ in range(n_ballast):
-            torch.mm(ballast, ballast)
-        one_step(events)
-        torch.cuda.synchronize()
-
-    stage_ms = {n: 0.0 for n in names}
-    launches = {n: 0 for n in names}
-    for i, ev in enumerate(events):
-        layer = i % cfg.L
-        for j, n in enumerate(names):
-            if n == "rebalance" and (layer + 1) % cfg.interval != 0:
-                continue
-            stage_ms[n] += ev[j].elapsed_time(ev[j + 1])
-            launches[n] += 1
-    stage_us_per_launch = {n: (1e3 * stage_ms[n] / launches[n] if launches[n] else 0.0) for n in names}
-    stage_ms_per_step = {n: stage_ms[n] / args.steps for n in names}
+        comp.run(layers)
+    enqueue_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    torch.cuda.synchronize()
+    records = dkv.dkv_profile_end(capacity)
+    kernel_us, kernel_n = {}, {}
+    for name, us in records:
+        kernel_us[name] = kernel_us.get(name, 0.0) + us
+        kernel_n[name] = kernel_n.get(name, 0) + 1
+    kernel_us_per_launch = {n: kernel_us[n] / kernel_n[n] for n in kernel_us}
+    kernel_ms_per_step = {n: kernel_us[n] / 1e3 / args.steps for n in kernel_us}
+    stage_us_per_launch = kernel_us_per_launch
 
     # ---- roofline of the dominant kernel: algorithmic bytes per launch / its average duration
     elt = 2 if cfg.dtype == "bf16" else 4
@@ -176,10 +155,11 @@ def main():
                       "context": list(cfg.seqlens), "window": cfg.w, "pool": cfg.P, "mean_budget": cfg.mean_budget,
                       "layer_max": cfg.layer_max, "interval": cfg.interval},
            "roofline": roofline,
-           "stage_ms_per_step": stage_ms_per_step, "stage_us_per_launch": stage_us_per_launch}
+           "kernel_us_per_launch": kernel_us_per_launch, "kernel_ms_per_step": kernel_ms_per_step,
+           "kernel_ms_per_step_total": sum(kernel_ms_per_step.values())}
     out["eager_enqueue_ms_per_step"] = enqueue_ms
     if host_sample:
-        out["cpu_baseline"] = _cpu_baseline(cfg, host_sample, cfg.interval)
+        out["cpu_baseline"] = _cpu_baseline(cfg, host_sample)
     print(json.dumps(out))
 
 

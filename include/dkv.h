@@ -68,6 +68,18 @@ typedef struct dkv_desc {
   float row_scale;      /* 0 => 1: scores are SUMS over the window rows; 1/ws gives the listing's mean */
 } dkv_desc;
 
+/* Kernel identifiers reported by dkv_profile_end(). */
+enum {
+  DKV_KERNEL_SCORE_STATS = 0,     /* first sweep over K: row statistics              */
+  DKV_KERNEL_SCORE_EMIT = 1,      /* second sweep over K: scores, window sum, pooling */
+  DKV_KERNEL_SELECT = 2,
+  DKV_KERNEL_GATHER = 3,
+  DKV_KERNEL_REBALANCE_HIST = 4,
+  DKV_KERNEL_REBALANCE_DECIDE = 5,
+  DKV_KERNEL_REBALANCE_FINAL = 6,
+  DKV_KERNEL_FILL = 7
+};
+
 /* Library version (DKV_VERSION it was built with). Host only. */
 int dkv_version(void);
 
@@ -78,6 +90,17 @@ const char* dkv_status_string(int status);
  * Host only, launches nothing. The workspace must be 256-byte aligned; it needs no initialisation and carries
  * nothing from one stage call to the next, except from dkv_score_window_stats to dkv_score_window_emit. */
 size_t dkv_workspace_bytes(const dkv_desc* desc);
+
+/*
+ * Per-kernel timing (a measurement aid, not part of the method). Between dkv_profile_begin(capacity) and
+ * dkv_profile_end(...) every kernel the library launches (up to `capacity`) carries a start/stop HIP event pair
+ * on its launch stream; dkv_profile_end waits for them, writes the kernel identifiers and durations of the
+ * first min(n, max_out) launches in launch order and returns n, the number of launches recorded (or a negative
+ * status). The session is process-wide state of the library: one session at a time, not during stream capture,
+ * and not concurrently with stage calls from other threads.
+ */
+int dkv_profile_begin(int32_t capacity);
+int dkv_profile_end(int32_t* kernel_ids_out /* host */, float* microseconds_out /* host */, int32_t max_out);
 
 /*
  * Observation-window scoring of ONE layer (Eq. 1-2; Algorithm 1, the softmax(...).mean(dim=-2).pooling(dim=-1) line).

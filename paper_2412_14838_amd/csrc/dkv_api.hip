@@ -5,6 +5,8 @@
 
 namespace dkv {
 
+ProfileSession g_profile;
+
 int validate_desc(const dkv_desc* d) {
   if (d == nullptr) return DKV_ERR_INVALID_ARG;
   if (d->n_layers < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->window < 1 || d->n_seqs < 1) return DKV_ERR_INVALID_ARG;
@@ -67,6 +69,43 @@ const char* dkv_status_string(int status) {
     case DKV_ERR_LAUNCH: return "kernel launch failed";
     default: return "unknown status";
   }
+}
+
+int dkv_profile_begin(int32_t capacity) {
+  if (capacity < 1 || g_profile.capacity != 0) return DKV_ERR_INVALID_ARG;
+  g_profile.start = new hipEvent_t[capacity];
+  g_profile.stop = new hipEvent_t[capacity];
+  g_profile.kernel_id = new int32_t[capacity];
+  for (int i = 0; i < capacity; ++i) {
+    if (hipEventCreate(&g_profile.start[i]) != hipSuccess || hipEventCreate(&g_profile.stop[i]) != hipSuccess) {
+      for (int j = 0; j <= i; ++j) { (void)hipEventDestroy(g_profile.start[j]); if (j < i) (void)hipEventDestroy(g_profile.stop[j]); }
+      delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
+      g_profile = ProfileSession{};
+      return DKV_ERR_LAUNCH;
+    }
+  }
+  g_profile.count = 0;
+  g_profile.capacity = capacity;
+  return DKV_OK;
+}
+
+int dkv_profile_end(int32_t* kernel_ids_out, float* microseconds_out, int32_t max_out) {
+  if (g_profile.capacity == 0) return DKV_ERR_INVALID_ARG;
+  const int n = g_profile.count;
+  int status = DKV_OK;
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(g_profile.stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_profile.start[i], g_profile.stop[i]) != hipSuccess) status = DKV_ERR_LAUNCH;
+    if (i < max_out && kernel_ids_out && microseconds_out) {
+      kernel_ids_out[i] = g_profile.kernel_id[i];
+      microseconds_out[i] = ms * 1000.0f;
+    }
+  }
+  for (int i = 0; i < g_profile.capacity; ++i) { (void)hipEventDestroy(g_profile.start[i]); (void)hipEventDestroy(g_profile.stop[i]); }
+  delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
+  g_profile = ProfileSession{};
+  return status == DKV_OK ? n : status;
 }
 
 size_t dkv_workspace_bytes(const dkv_desc* desc) {

@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libdkv.so (host side + device helpers).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include "../../include/dkv.h"
@@ -42,6 +43,31 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
   w.total = off;
   return w;
+}
+
+// ----------------------------------------------------------------------------------------------
+// Kernel launch: every kernel of the library goes through launch(), so that dkv_profile_begin() can attach a
+// start/stop event pair to each launch (hipExtLaunchKernelGGL) and dkv_profile_end() can report true kernel
+// durations on the launch stream. Outside a profiling session this is a plain hipLaunchKernelGGL.
+// ----------------------------------------------------------------------------------------------
+struct ProfileSession {
+  hipEvent_t* start = nullptr;
+  hipEvent_t* stop = nullptr;
+  int32_t* kernel_id = nullptr;
+  int capacity = 0;
+  int count = 0;
+};
+extern ProfileSession g_profile;
+
+template <typename Kernel, typename... Args>
+inline void launch(int kernel_id, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, Args... args) {
+  if (g_profile.count < g_profile.capacity) {
+    const int i = g_profile.count++;
+    g_profile.kernel_id[i] = kernel_id;
+    hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, st, g_profile.start[i], g_profile.stop[i], 0, args...);
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, args...);
+  }
 }
 
 // Host-side descriptor validation shared by every entry point. Returns DKV_OK or a negative status.

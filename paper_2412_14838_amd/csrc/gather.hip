@@ -49,17 +49,17 @@ hipError_t launch_gather(const Params& p, int elt_bytes, int layer, const void* 
   const int row_bytes = p.d * elt_bytes;          // 128, 256 or 512
   const int lanes = row_bytes / 16;               // 8, 16 or 32
   const int slots = p.w + p.layer_max;
-  auto launch = [&](auto kernel, int LANES) {
+  auto go = [&](auto kernel, int LANES) {
     const int rows = 256 / LANES;
     dim3 grid((slots + rows - 1) / rows, p.Hkv, p.n_seqs);
-    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, layer, row_bytes,
+    launch(DKV_KERNEL_GATHER, kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, layer, row_bytes,
                        static_cast<const char*>(k), static_cast<const char*>(v), stride_token * elt_bytes,
                        stride_head * elt_bytes, cu, idx, counts, static_cast<char*>(k_out), static_cast<char*>(v_out),
                        out_stride_seq * elt_bytes, out_stride_head * elt_bytes);
   };
-  if (lanes <= 8) launch(gather_kernel<8>, 8);
-  else if (lanes <= 16) launch(gather_kernel<16>, 16);
-  else launch(gather_kernel<32>, 32);
+  if (lanes <= 8) go(gather_kernel<8>, 8);
+  else if (lanes <= 16) go(gather_kernel<16>, 16);
+  else go(gather_kernel<32>, 32);
   return hipGetLastError();
 }
 
@@ -72,7 +72,7 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
   if (n_words == 0) return hipSuccess;
   size_t blocks = (n_words + 255) / 256;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint32_t*>(ptr), n_words);
+  launch(DKV_KERNEL_FILL, fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint32_t*>(ptr), n_words);
   return hipGetLastError();
 }
 

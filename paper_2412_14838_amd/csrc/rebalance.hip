@@ -200,17 +200,17 @@ hipError_t launch_rebalance(const Params& p, int layers_done, const float* score
   if (e != hipSuccess) return e;
   const int chunks = p.total_tokens / kRebalanceChunk + p.n_seqs;
   const dim3 grid(chunks, p.Hkv, layers_done);
-  hipLaunchKernelGGL(rebalance_hist_kernel<0>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
+  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<0>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
                      scores_all, cu, hist, state);
-  hipLaunchKernelGGL(rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 0, p.n_seqs, p.L, layers_done,
+  launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 0, p.n_seqs, p.L, layers_done,
                      p.w, p.Hkv, p.mean_budget, cu, hist, state);
-  hipLaunchKernelGGL(rebalance_hist_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
+  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
                      scores_all, cu, hist, state);
-  hipLaunchKernelGGL(rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 1, p.n_seqs, p.L, layers_done,
+  launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 1, p.n_seqs, p.L, layers_done,
                      p.w, p.Hkv, p.mean_budget, cu, hist, state);
-  hipLaunchKernelGGL(rebalance_hist_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
+  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
                      scores_all, cu, hist, state);
-  hipLaunchKernelGGL(rebalance_final_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, p.n_seqs, p.L, layers_done, p.w,
+  launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, p.n_seqs, p.L, layers_done, p.w,
                      p.Hkv, p.mean_budget, p.layer_max, cu, hist, state, counts, budgets_out, hits_out);
   return hipGetLastError();
 }

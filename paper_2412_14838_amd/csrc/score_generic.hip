@@ -172,13 +172,13 @@ static hipError_t launch_generic_t(const Params& p, int phases, const void* q_wi
   float2* partials = reinterpret_cast<float2*>(ws + wl.partials);
   const int chunks_stats = p.total_tokens / kGenericKeys + p.n_seqs;
   if (phases & kPhaseStats)
-    hipLaunchKernelGGL((score_stats_generic<T, D>), dim3(chunks_stats, p.Hkv), dim3(kGenericKeys), 0, st, p,
+    launch(DKV_KERNEL_SCORE_STATS, (score_stats_generic<T, D>), dim3(chunks_stats, p.Hkv), dim3(kGenericKeys), 0, st, p,
                        static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu,
                        partials);
   const int CO = kGenericKeys - 2 * p.half;
   const int chunks_emit = p.total_tokens / CO + p.n_seqs;
   if (phases & kPhaseEmit)
-    hipLaunchKernelGGL((score_emit_generic<T, D>), dim3(chunks_emit, p.Hkv), dim3(kGenericKeys), 0, st, p,
+    launch(DKV_KERNEL_SCORE_EMIT, (score_emit_generic<T, D>), dim3(chunks_emit, p.Hkv), dim3(kGenericKeys), 0, st, p,
                        static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu,
                        partials, scores, scores_stride_head);
   return hipGetLastError();

@@ -447,11 +447,11 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
   }
   const int grid_x = p.total_tokens / chunk + p.n_seqs;      // upper bound on chunks over all sequences
   if (phases & kPhaseStats)
-    hipLaunchKernelGGL((score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
+    launch(DKV_KERNEL_SCORE_STATS, (score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
                        static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
                        k_stride_head * 2, cu, partials);
   if (phases & kPhaseEmit)
-    hipLaunchKernelGGL((score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
+    launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
                        static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
                        k_stride_head * 2, cu, partials, scores, scores_stride_head);
   return hipGetLastError();

@@ -256,7 +256,7 @@ hipError_t launch_select(const Params& p, int layer, const float* scores, int64_
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max,
+  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max,
                      p.L, layer, scores, scores_stride_head, cu, idx_out, counts);
   return hipGetLastError();
 }

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libdkv.so")
 DKV_F32, DKV_BF16 = 0, 1
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
-EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_score_window",
+EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_stats", "dkv_score_window_emit", "dkv_select_topk", "dkv_rebalance", "dkv_gather_kv")
 
 
@@ -53,6 +53,10 @@ def load() -> C.CDLL:
     lib.dkv_status_string.argtypes = [C.c_int]
     lib.dkv_workspace_bytes.restype = SZ
     lib.dkv_workspace_bytes.argtypes = [D]
+    lib.dkv_profile_begin.restype = C.c_int
+    lib.dkv_profile_begin.argtypes = [I32]
+    lib.dkv_profile_end.restype = C.c_int
+    lib.dkv_profile_end.argtypes = [P, P, I32]
     for name in ("dkv_score_window", "dkv_score_window_stats", "dkv_score_window_emit"):
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
@@ -109,6 +113,24 @@ def dkv_status_string(status: int) -> str:
 
 def dkv_workspace_bytes(desc: dkv_desc) -> int:
     return int(load().dkv_workspace_bytes(C.byref(desc)))
+
+
+KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_decide",
+                "rebalance_final", "fill")
+
+
+def dkv_profile_begin(capacity: int) -> None:
+    _check(load().dkv_profile_begin(capacity), "dkv_profile_begin")
+
+
+def dkv_profile_end(capacity: int):
+    """Returns [(kernel name, microseconds)] of the launches recorded since dkv_profile_begin, in launch order."""
+    ids = (C.c_int32 * capacity)()
+    us = (C.c_float * capacity)()
+    n = load().dkv_profile_end(ids, us, capacity)
+    if n < 0:
+        raise DkvError(n, "dkv_profile_end")
+    return [(KERNEL_NAMES[ids[i]], float(us[i])) for i in range(min(n, capacity))]
 
 
 def dkv_score_window(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
