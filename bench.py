@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="mistral_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device copies (a kernel of known traffic, to scale profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU (the path has no cross-GPU step); run with --gpus 1")
@@ -133,7 +135,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(cfg.name, {}).get(dom)
+            traffic = json.load(open(tpath)).get(cfg.name, {}).get(dom, {}).get("total_bytes")
         except Exception:
             traffic = None
     score_us = stage_us_per_launch["score_stats"] + stage_us_per_launch["score_emit"]
@@ -158,6 +160,13 @@ def main():
            "kernel_us_per_launch": kernel_us_per_launch, "kernel_ms_per_step": kernel_ms_per_step,
            "kernel_ms_per_step_total": sum(kernel_ms_per_step.values())}
     out["eager_enqueue_ms_per_step"] = enqueue_ms
+    if args.copy_calibration:
+        x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        del x, y
     if host_sample:
         out["cpu_baseline"] = _cpu_baseline(cfg, host_sample)
     print(json.dumps(out))
