@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="mistral_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="select/gather/rebalance of layer l on a second stream, next to the scoring of layer l+1")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale profiler counters)")
     args = ap.parse_args()
@@ -93,7 +95,7 @@ def main():
     for _ in range(max(args.warmup, 1)):
         comp.run(layers)
     torch.cuda.synchronize()
-    graph = comp.capture(layers)
+    graph = comp.capture(layers, overlap=args.overlap)
     graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -152,7 +154,7 @@ def main():
     out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": cfg.dtype, "data": "synthetic",
+           "dtype": cfg.dtype, "data": "synthetic", "streams": 2 if args.overlap else 1,
            "config": {"workload": cfg.name, "layers": cfg.L, "q_heads": cfg.Hq, "kv_heads": cfg.Hkv, "head_dim": d,
                       "context": list(cfg.seqlens), "window": cfg.w, "pool": cfg.P, "mean_budget": cfg.mean_budget,
                       "layer_max": cfg.layer_max, "interval": cfg.interval},

@@ -23,6 +23,7 @@ struct WorkspaceLayout {
   size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t hist;         // int32 [3][n_seqs][L][kRadixBins]
   size_t state;        // int32 [n_seqs][8]              radix-select state of the rebalance
+  size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
   size_t total;
   int rows_pad;        // G*w rounded up to 64
   int chunks_max;      // upper bound on statistics chunks over all sequences
@@ -41,6 +42,7 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
   w.hist = off;     off += align256(size_t(3) * d.n_seqs * d.n_layers * kRadixBins * sizeof(int32_t));
   w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
+  w.above = off;    off += align256(size_t(d.n_seqs) * d.n_layers * sizeof(int32_t));
   w.total = off;
   return w;
 }

@@ -3,7 +3,8 @@
 // The global top-kg over the concatenated scores of the layers processed so far only matters through its
 // per-layer hit counts, so no element is ever moved: a 3-digit radix select (11 + 11 + 10 bits of the fp32
 // pattern, scores are >= 0) finds the kg-th largest value T from per-(sequence, layer) digit histograms.
-// Many workgroups build the histograms (the scan of all scores is bandwidth work); a single workgroup per
+// Many workgroups build the histograms (the scan of all scores is bandwidth work) and, from the second pass on,
+// also count per layer the elements that the digits found so far already place above T; a single workgroup per
 // sequence takes every decision: the digit of T after each pass, then cnt_i = #{> T in layer i} + the share
 // of the elements equal to T that the tie rule (lower layer first) gives to layer i, then Z, Z' and counts.
 #include "dkv_internal.h"
@@ -24,8 +25,10 @@ template <int PASS>
 __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
                                                              const float* __restrict__ scores_all,
                                                              const int32_t* __restrict__ cu, int32_t* __restrict__ hist,
-                                                             const int32_t* __restrict__ state) {
+                                                             const int32_t* __restrict__ state,
+                                                             int32_t* __restrict__ above) {
   __shared__ int h[kRadixBins * kScanCopies];
+  __shared__ int n_above;
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kRebalanceChunk, w, blockIdx.x, seq, c, begin, len)) return;
   const int head = blockIdx.y, layer = blockIdx.z;
@@ -38,17 +41,31 @@ __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv
     prefix = (uint32_t)state[seq * 8 + 0];
   }
   for (int b = threadIdx.x; b < kRadixBins * kScanCopies; b += 256) h[b] = 0;
+  if (threadIdx.x == 0) n_above = 0;
   __syncthreads();
   const uint32_t* __restrict__ row =
       reinterpret_cast<const uint32_t*>(scores_all + ((int64_t)layer * Hkv + head) * total_tokens + begin);
   constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
   constexpr int ushift = PASS == 0 ? 0 : (PASS == 1 ? 21 : 10);
+  int mine = 0;   // elements of this thread that the digits found so far place above T
   for (int i = i0 + threadIdx.x; i < i1; i += 256) {
     const uint32_t u = row[i];
     const bool match = PASS == 0 ? true : ((u >> ushift) == (prefix >> ushift));
     if (match) atomicAdd(&h[((u >> shift) & (kRadixBins - 1)) * kScanCopies + (threadIdx.x & (kScanCopies - 1))], 1);
+    if (PASS > 0) {
+      // the digit chosen by the previous pass sits just above this pass's digit: equal higher bits, larger digit
+      constexpr int pshift = PASS == 1 ? 21 : 10;
+      const bool higher_equal = PASS == 1 ? true : ((u >> 21) == (prefix >> 21));
+      if (higher_equal && (u >> pshift) > (prefix >> pshift)) ++mine;
+    }
+  }
+  if (PASS > 0) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
   }
   __syncthreads();
+  if (PASS > 0 && threadIdx.x == 0 && n_above) atomicAdd(&above[seq * L + layer], n_above);
   int32_t* __restrict__ g = hist + (((int64_t)PASS * n_seqs + seq) * L + layer) * kRadixBins;
   for (int b = threadIdx.x; b < kRadixBins; b += 256) {
     int v = 0;
@@ -94,9 +111,11 @@ __device__ inline void decide_digit(int pass, int seq, int n_seqs, int L, int la
   const int hi = kRadixBins - 1 - 2 * tid, lo = hi - 1;
   int c_hi = 0, c_lo = 0;
   const int32_t* __restrict__ g = hist + ((int64_t)pass * n_seqs + seq) * L * kRadixBins;
-  for (int i = 0; i < layers_done; ++i) {
-    c_hi += g[(int64_t)i * kRadixBins + hi];
-    c_lo += g[(int64_t)i * kRadixBins + lo];
+#pragma unroll 8
+  for (int i = 0; i < layers_done; ++i) {   // bins lo, hi are adjacent: one 8-byte load per layer
+    const int2 v = *reinterpret_cast<const int2*>(g + (int64_t)i * kRadixBins + lo);
+    c_lo += v.x;
+    c_hi += v.y;
   }
   const int v = c_hi + c_lo;
   const int incl = wave_inclusive_scan_i(v);
@@ -134,6 +153,7 @@ __global__ __launch_bounds__(kDecThreads) void rebalance_final_kernel(int n_seqs
                                                                       const int32_t* __restrict__ cu,
                                                                       const int32_t* __restrict__ hist,
                                                                       int32_t* __restrict__ state,
+                                                                      const int32_t* __restrict__ above,
                                                                       int32_t* __restrict__ counts,
                                                                       int32_t* __restrict__ budgets_out,
                                                                       int32_t* __restrict__ hits_out) {
@@ -146,48 +166,57 @@ __global__ __launch_bounds__(kDecThreads) void rebalance_final_kernel(int n_seqs
   const int digit0 = state[seq * 8 + 2], digit1 = state[seq * 8 + 3];
   decide_digit(2, seq, n_seqs, L, layers_done, w, Hkv, mean_budget, cu, hist, state, scratch, sh);
   const int digit[3] = {digit0, digit1, sh[0]};
+  (void)digit0; (void)digit1;
   const int need_eq = sh[1];   // elements equal to T that belong to the top-kg
   const int kg = sh[2];
-  // per layer: elements above T = sum over passes of the bins above the chosen digit; equal = chosen bin of pass 2
+  // per layer: elements above T = those counted by the scan kernels of passes 1 and 2 (higher digits larger)
+  // + the last-digit bins above the chosen one; equal to T = the chosen last-digit bin
   for (int i = wv; i < layers_done; i += kDecWaves) {
     int acc = 0;
-    for (int pass = 0; pass < 3; ++pass) {
-      const int32_t* __restrict__ g = hist + (((int64_t)pass * n_seqs + seq) * L + i) * kRadixBins;
-      for (int b = digit[pass] + 1 + lane; b < kRadixBins; b += 64) acc += g[b];
-    }
+    const int32_t* __restrict__ g = hist + (((int64_t)2 * n_seqs + seq) * L + i) * kRadixBins;
+    for (int b = digit[2] + 1 + lane; b < 1024; b += 64) acc += g[b];     // the last digit has 10 bits
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
     if (lane == 0) {
-      gt[i] = acc;
-      eq[i] = hist[(((int64_t)2 * n_seqs + seq) * L + i) * kRadixBins + digit[2]];
+      gt[i] = acc + above[seq * L + i];
+      eq[i] = g[digit[2]];
     }
   }
+  __shared__ int cur[DKV_MAX_LAYERS];
+  for (int i = tid; i < layers_done; i += kDecThreads) cur[i] = counts[seq * L + i];
   __syncthreads();
-  if (tid == 0) {
+  __shared__ long long red[2];   // max cnt, sum Z
+  if (tid == 0) {   // Phi: ties go to the lower flat index, i.e. earlier layers first (a serial prefix over L ints)
     long long cmax = 0;
     int left = need_eq;
-    for (int i = 0; i < layers_done; ++i) {   // ties go to the lower flat index: earlier layers first
+    for (int i = 0; i < layers_done; ++i) {
       int take = 0;
       if (kg > 0) { take = eq[i] < left ? eq[i] : left; left -= take; }
       const int c = kg > 0 ? gt[i] + take : 0;
       gt[i] = c;
       cmax = c > cmax ? c : cmax;
     }
+    red[0] = cmax;
+  }
+  __syncthreads();
+  const long long cmax = red[0];
+  for (int i = tid; i < layers_done; i += kDecThreads)
+    eq[i] = cmax > 0 ? (int)(((long long)layer_max * gt[i]) / cmax) : 0;          // Eq. 5, exact floor
+  __syncthreads();
+  if (tid == 0) {
     long long zsum = 0;
-    for (int i = 0; i < layers_done; ++i) {
-      const long long z = cmax > 0 ? ((long long)layer_max * gt[i]) / cmax : 0;   // Eq. 5, exact floor
-      eq[i] = (int)z;
-      zsum += z;
-    }
-    const long long B = (long long)mean_budget * L;                               // Eq. 6: B = (wt - ws) * L
-    for (int i = 0; i < layers_done; ++i) {
-      const long long zp = zsum > 0 ? ((long long)eq[i] * B) / zsum : 0;
-      const int zpi = zp > 0x7fffffffLL ? 0x7fffffff : (int)zp;
-      if (budgets_out) budgets_out[seq * L + i] = zpi;
-      if (hits_out) hits_out[seq * L + i] = gt[i];
-      const int cur = counts[seq * L + i];
-      counts[seq * L + i] = cur < zpi ? cur : zpi;                                // truncation never grows a layer
-    }
+    for (int i = 0; i < layers_done; ++i) zsum += eq[i];
+    red[1] = zsum;
+  }
+  __syncthreads();
+  const long long zsum = red[1];
+  const long long B = (long long)mean_budget * L;                                 // Eq. 6: B = (wt - ws) * L
+  for (int i = tid; i < layers_done; i += kDecThreads) {
+    const long long zp = zsum > 0 ? ((long long)eq[i] * B) / zsum : 0;            // exact floor
+    const int zpi = zp > 0x7fffffffLL ? 0x7fffffff : (int)zp;
+    if (budgets_out) budgets_out[seq * L + i] = zpi;
+    if (hits_out) hits_out[seq * L + i] = gt[i];
+    counts[seq * L + i] = cur[i] < zpi ? cur[i] : zpi;                            // truncation never grows a layer
   }
 }
 
@@ -196,22 +225,23 @@ hipError_t launch_rebalance(const Params& p, int layers_done, const float* score
                             const WorkspaceLayout& wl, hipStream_t st) {
   int32_t* hist = reinterpret_cast<int32_t*>(ws + wl.hist);
   int32_t* state = reinterpret_cast<int32_t*>(ws + wl.state);
+  int32_t* above = reinterpret_cast<int32_t*>(ws + wl.above);
   hipError_t e = launch_fill_zero(ws + wl.hist, wl.total - wl.hist, st);
   if (e != hipSuccess) return e;
   const int chunks = p.total_tokens / kRebalanceChunk + p.n_seqs;
   const dim3 grid(chunks, p.Hkv, layers_done);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<0>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state);
+                     scores_all, cu, hist, state, above);
   launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 0, p.n_seqs, p.L, layers_done,
                      p.w, p.Hkv, p.mean_budget, cu, hist, state);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state);
+                     scores_all, cu, hist, state, above);
   launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 1, p.n_seqs, p.L, layers_done,
                      p.w, p.Hkv, p.mean_budget, cu, hist, state);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state);
+                     scores_all, cu, hist, state, above);
   launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, p.n_seqs, p.L, layers_done, p.w,
-                     p.Hkv, p.mean_budget, p.layer_max, cu, hist, state, counts, budgets_out, hits_out);
+                     p.Hkv, p.mean_budget, p.layer_max, cu, hist, state, above, counts, budgets_out, hits_out);
   return hipGetLastError();
 }
 

@@ -66,12 +66,35 @@ class Compressor:
         if (layer + 1) % self.cfg.interval == 0:
             self.rebalance(layer + 1)
 
-    def run(self, layers):
-        """layers: sequence of (q_win, k, v) device tensors, one per layer."""
-        for l, (q, k, v) in enumerate(layers):
-            self.step(l, q, k, v)
+    def run(self, layers, overlap=False):
+        """layers: sequence of (q_win, k, v) device tensors, one per layer.
 
-    def capture(self, layers):
+        overlap=True issues select / gather / rebalance of layer l on a second stream (default priority), so
+        that they run next to the scoring of layer l+1, as they would next to the next layer's forward pass
+        in a real prefill; scoring itself stays in layer order on the current stream."""
+        if not overlap:
+            for l, (q, k, v) in enumerate(layers):
+                self.step(l, q, k, v)
+            return
+        main = torch.cuda.current_stream()
+        if getattr(self, "_side", None) is None:
+            self._side = torch.cuda.Stream()
+        side = self._side
+        side.wait_stream(main)
+        for l, (q, k, v) in enumerate(layers):
+            self.score(l, q, k)
+            scored = torch.cuda.Event()
+            scored.record(main)
+            side.wait_event(scored)
+            with torch.cuda.stream(side):
+                self.select(l)
+                if self.keep_cache:
+                    self.gather(l, k, v)
+                if (l + 1) % self.cfg.interval == 0:
+                    self.rebalance(l + 1)
+        main.wait_stream(side)
+
+    def capture(self, layers, overlap=False):
         """Record the whole layer loop over resident inputs into a HIP graph (replay with .replay()).
 
         The stage calls allocate nothing, never synchronise and clear their scratch with kernels, so the
@@ -79,7 +102,7 @@ class Compressor:
         kernel attributes)."""
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            self.run(layers)
+            self.run(layers, overlap=overlap)
         return graph
 
 
