@@ -92,36 +92,37 @@ __device__ inline void store_tile(char* __restrict__ buf, typename PieceVec<Tile
   }
 }
 
-// acc[t] = (KEYS_AS_M ? K_tile . Q_t^T : Q_t . K_tile^T) for the wavefront's 32 keys and two 32-row tiles.
+// The 8 K fragments (one per 16-wide slice of the head dimension) of the wavefront's 32 keys, read from an LDS
+// tile in MFMA operand layout. Issued together so that the LDS latency is paid once per tile.
+__device__ inline void read_k_frags(const char* __restrict__ tile, bf16x8 (&kf)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) kf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
+}
+
+// Slice j of the two accumulators: acc[t] (+)= (KEYS_AS_M ? K_tile . Q_t^T : Q_t . K_tile^T) over head dims 16j..16j+15.
 template <bool KEYS_AS_M>
-__device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
+__device__ inline void mfma_slice(int j, const bf16x8 (&kf)[8], const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
+  if (j == 0) {
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[t][j] = 0.0f;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
-    if (KEYS_AS_M) {
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][j], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][j], acc[1], 0, 0, 0);
-    } else {
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][j], kf, acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[1][j], kf, acc[1], 0, 0, 0);
-    }
+      for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+  }
+  if (KEYS_AS_M) {
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[0][j], acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[1][j], acc[1], 0, 0, 0);
+  } else {
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][j], kf[j], acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[1][j], kf[j], acc[1], 0, 0, 0);
   }
 }
 
-// Scheduling hint for a block that holds the 16 MFMAs of the next tile (with their 8 LDS reads) and the
-// exponentials of the current one: issue them interleaved, so that the matrix pipe and the vector ALU of the
-// SIMD are busy at the same time within one wavefront.
-__device__ inline void interleave_mfma_valu() {
+template <bool KEYS_AS_M>
+__device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
+  bf16x8 kf[8];
+  read_k_frags(tile, kf);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
-    __builtin_amdgcn_sched_group_barrier(0x002, 20, 0);  // 20 VALU
-  }
+  for (int j = 0; j < 8; ++j) mfma_slice<KEYS_AS_M>(j, kf, qf, acc);
 }
 
 // Linear chunk index -> (sequence, chunk) for chunks of `chunk` items over (length - window_off) items per
@@ -213,26 +214,33 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
           if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
         }
     }
-    mfma_tile<true>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, b);
+    // 8 slices: two MFMAs of tile it + 1 each, interleaved with one eighth of the exponentials of tile it, so
+    // that the matrix pipe and the vector ALU are busy together within one wavefront
+    bf16x8 kf[8];
+    read_k_frags(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, kf);
+    float m_use[2], s0, s1, s2, s3;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      float mx = fmaxf(a[t][0], a[t][1]);
+    for (int j = 0; j < 8; ++j) {
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice<true>(j, kf, qf, b);
+      const int t = j >> 2, e = (j & 3) * 4;
+      if ((j & 3) == 0) {   // row maximum of tile t, new running maximum
+        float mx = fmaxf(a[t][0], a[t][1]);
 #pragma unroll
-      for (int j = 2; j < 16; j += 2) mx = fmaxf(mx, fmaxf(a[t][j], a[t][j + 1]));
-      const float m_new = fmaxf(m_run[t], mx * cexp);
-      const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-#pragma unroll
-      for (int j = 0; j < 16; j += 4) {
-        s0 += fast_exp2(fmaf(a[t][j], cexp, -m_use));
-        s1 += fast_exp2(fmaf(a[t][j + 1], cexp, -m_use));
-        s2 += fast_exp2(fmaf(a[t][j + 2], cexp, -m_use));
-        s3 += fast_exp2(fmaf(a[t][j + 3], cexp, -m_use));
+        for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(a[t][i], a[t][i + 1]));
+        const float m_new = fmaxf(m_run[t], mx * cexp);
+        m_use[t] = m_new == -INFINITY ? 0.0f : m_new;
+        l_run[t] *= fast_exp2(m_run[t] - m_use[t]);
+        m_run[t] = m_new;
+        s0 = s1 = s2 = s3 = 0.0f;
       }
-      l_run[t] = l_run[t] * fast_exp2(m_run[t] - m_use) + ((s0 + s1) + (s2 + s3));
-      m_run[t] = m_new;
+      s0 += fast_exp2(fmaf(a[t][e], cexp, -m_use[t]));
+      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -m_use[t]));
+      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -m_use[t]));
+      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -m_use[t]));
+      if ((j & 3) == 3) l_run[t] += (s0 + s1) + (s2 + s3);
     }
-    interleave_mfma_valu();
+    __builtin_amdgcn_sched_barrier(0);
     // buffer it & 1 held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
     store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
     __syncthreads();
@@ -363,18 +371,20 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
     reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
-    mfma_tile<false>(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, qf, b);
+    bf16x8 kf[8];
+    read_k_frags(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, kf);
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int j = 0; j < 16; j += 4) {
-        s0 += fast_exp2(fmaf(a[t][j], cexp, -lse_r[t][j]));
-        s1 += fast_exp2(fmaf(a[t][j + 1], cexp, -lse_r[t][j + 1]));
-        s2 += fast_exp2(fmaf(a[t][j + 2], cexp, -lse_r[t][j + 2]));
-        s3 += fast_exp2(fmaf(a[t][j + 3], cexp, -lse_r[t][j + 3]));
-      }
-    interleave_mfma_valu();
+    for (int j = 0; j < 8; ++j) {   // two MFMAs of tile it + 1, then one eighth of the exponentials of tile it
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice<false>(j, kf, qf, b);
+      const int t = j >> 2, e = (j & 3) * 4;
+      s0 += fast_exp2(fmaf(a[t][e], cexp, -lse_r[t][e]));
+      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -lse_r[t][e + 1]));
+      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -lse_r[t][e + 2]));
+      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -lse_r[t][e + 3]));
+    }
+    __builtin_amdgcn_sched_barrier(0);
     float col = (s0 + s1) + (s2 + s3);
     const float other = __shfl_xor(col, 32);
     col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
