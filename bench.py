@@ -108,7 +108,7 @@ def main():
     # ---- per-kernel durations: the same K steps launched eagerly inside a profiling session of the library:
     # every launch carries its own start/stop HIP event pair on the launch stream (events cannot be read back
     # from inside a replayed graph), so each figure is the kernel's own duration, launch gaps excluded.
-    launches_per_step = 4 * cfg.L + 7 * (cfg.L // cfg.interval)
+    launches_per_step = 5 * cfg.L + 7 * (cfg.L // cfg.interval)
     capacity = launches_per_step * args.steps + 16
     dkv.dkv_profile_begin(capacity)
     t0 = time.perf_counter()

@@ -77,7 +77,8 @@ enum {
   DKV_KERNEL_REBALANCE_HIST = 4,
   DKV_KERNEL_REBALANCE_DECIDE = 5,
   DKV_KERNEL_REBALANCE_FINAL = 6,
-  DKV_KERNEL_FILL = 7
+  DKV_KERNEL_FILL = 7,
+  DKV_KERNEL_SELECT_ORDER = 8
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */
@@ -143,9 +144,11 @@ int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k
  * scores     as written by dkv_score_window for this layer.
  * idx_out    int32 [n_seqs][Hkv][layer_max], sequence-local positions; entries >= k are set to -1.
  * counts     int32 [n_seqs][L]; counts[q][layer] = k is written.
+ * Two kernels are enqueued (selection of the winners, then their ordering).
  */
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,
-                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* stream);
+                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* workspace,
+                    size_t workspace_bytes, void* stream);
 
 /*
  * Progressive cache update after `layers_done` layers (Section 4.2, Eq. 4-6; Update_Buffer_Length and the

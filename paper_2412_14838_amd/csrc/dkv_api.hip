@@ -162,15 +162,19 @@ int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k
 }
 
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,
-                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* stream) {
+                    const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* workspace,
+                    size_t workspace_bytes, void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   if (!scores || !cu_seqlens || !idx_out || !counts) return DKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= desc->n_layers) return DKV_ERR_INVALID_ARG;
   if (scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
   const Params p = make_params(*desc);
   const hipError_t e = launch_select(p, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts,
-                                     static_cast<hipStream_t>(stream));
+                                     static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 

@@ -180,7 +180,9 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const char* __restrict__ k_chunk =
       k + ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
+  // All first loads are issued together (two key tiles, then the Q block): one memory latency, not three.
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
@@ -192,12 +194,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 
   store_tile<RS, KS>(tiles, reg);
-  reg = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
   __syncthreads();
   floatx16 acc[2], nxt[2];
   mfma_tile<true>(tiles + lane_tile, qf, acc);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg);
-  __syncthreads();
+  __syncthreads();                                  // buffer 0 is rewritten by the first step
   const int lim_all = prefix_rel < len ? prefix_rel : len;
   // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
   // Tiles past the chunk are fully masked (they add exp2(-inf) = 0), so the step is branch-free but for the mask.
@@ -313,7 +314,9 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const char* __restrict__ k_chunk =
       k + ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
+  // All first loads are issued together (two key tiles, the Q block, the row statistics): one memory latency.
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
@@ -324,6 +327,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     const float2* __restrict__ src =
         reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad + r;
     float M = -INFINITY, Lsum = 0.0f;
+#pragma unroll 4
     for (int cc = q; cc < n_full; cc += KS) {
       const float2 v = src[(int64_t)cc * p.Hkv * p.rows_pad];
       const float Mn = fmaxf(M, v.x);
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
     mstage[q * kRows + r] = make_float2(M, Lsum);
     store_tile<RS, KS>(tiles, reg);
-    reg = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
+    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
     __syncthreads();
     if (tid < kRows) {
       float Mx = -INFINITY;
@@ -353,7 +357,6 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
   floatx16 acc[2], nxt[2];
   mfma_tile<false>(tiles + lane_tile, qf, acc);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg);
   __syncthreads();
   // lse2 of the rows this lane accumulates: register j of tile t is row rs*64 + t*32 + 8*(j/4) + 4*(lane/32) + j%4
   float lse_r[2][16];

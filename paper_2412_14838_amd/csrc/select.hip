@@ -5,9 +5,10 @@
 //      lanes whose scores share a digit do not serialise on one LDS word.
 //   2. wavefront-ballot compaction collects the winners: everything above T, and the first (k - #above)
 //      elements equal to T in position order (ties go to the lower position).
-//   3. a bitonic sort of 64-bit keys (~score bits, position) orders them by (score descending, position
-//      ascending). Each thread holds two keys in registers; exchanges inside a wavefront use lane shuffles,
-//      only the 14 exchanges that cross wavefronts go through LDS and a workgroup barrier.
+//   3. the k winners are written as 64-bit keys (~score bits, position), unordered, to the workspace.
+// A second kernel orders them by (score descending, position ascending) = ascending key, by counting: the rank
+// of a key is the number of smaller keys (keys are unique). That is k^2 comparisons, but they spread over the
+// whole GPU (k/64 workgroups per row) instead of a sorting network on the one CU that holds the row.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -42,48 +43,13 @@ __device__ inline int block_exclusive_scan(int v, int* scratch) {
   return base + incl - v;
 }
 
-__device__ inline u64 shfl_xor_u64(u64 v, int mask) {
-  const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
-  return ((u64)hi << 32) | lo;
-}
-
-// Bitonic sort of 2 * kSelThreads = 2048 keys, ascending; thread t holds elements t (k0) and t + 1024 (k1).
-// `n_sort` (power of two, 2..2048) is the number of leading elements that matter: the rest are ~0 pads, and
-// stages larger than n_sort are skipped for them by construction (pads never move below a real key).
-__device__ inline void bitonic_sort_2048(u64& k0, u64& k1, u64* __restrict__ xchg, int n_sort) {
-  const int t = threadIdx.x;
-  for (int size = 2; size <= n_sort; size <<= 1) {
-    // element e sorts ascending in this stage iff (e & size) == 0; at size 2048 everything is ascending
-    const bool up0 = (t & size) == 0;
-    const bool up1 = size == 2048 ? true : (((t + 1024) & size) == 0);
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      if (stride == 1024) {                         // partner is the thread's other element
-        const u64 lo = k0 < k1 ? k0 : k1, hi = k0 < k1 ? k1 : k0;
-        k0 = lo; k1 = hi;                           // only reached at size 2048: ascending
-      } else if (stride >= 64) {                    // partner lives in another wavefront
-        xchg[t] = k0; xchg[t + 1024] = k1;
-        __syncthreads();
-        const u64 p0 = xchg[t ^ stride], p1 = xchg[(t ^ stride) + 1024];
-        __syncthreads();
-        const bool lower = (t & stride) == 0;       // this thread holds the lower-indexed element of the pair
-        k0 = (lower == up0) ? (k0 < p0 ? k0 : p0) : (k0 < p0 ? p0 : k0);
-        k1 = (lower == up1) ? (k1 < p1 ? k1 : p1) : (k1 < p1 ? p1 : k1);
-      } else {                                      // partner is a lane of this wavefront
-        const u64 p0 = shfl_xor_u64(k0, stride), p1 = shfl_xor_u64(k1, stride);
-        const bool lower = (t & stride) == 0;
-        k0 = (lower == up0) ? (k0 < p0 ? k0 : p0) : (k0 < p0 ? p0 : k0);
-        k1 = (lower == up1) ? (k1 < p1 ? k1 : p1) : (k1 < p1 ? p1 : k1);
-      }
-    }
-  }
-}
-
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer,
                                                                   const float* __restrict__ scores,
                                                                   int64_t scores_stride_head,
                                                                   const int32_t* __restrict__ cu,
                                                                   int32_t* __restrict__ idx_out,
-                                                                  int32_t* __restrict__ counts) {
+                                                                  int32_t* __restrict__ counts,
+                                                                  u64* __restrict__ keys_out) {
   extern __shared__ __attribute__((aligned(16))) char sel_smem[];
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
@@ -235,19 +201,55 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   }
   __syncthreads();
 
-  // ---- order the k winners: (score descending, position ascending) = ascending composite key
-  int n_sort = 2;
-  while (n_sort < k) n_sort <<= 1;
-  u64 k0 = keys[tid], k1 = keys[tid + 1024];
+  // ---- hand the k winners to the ordering kernel
+  u64* __restrict__ dst = keys_out + ((int64_t)seq * Hkv + head) * DKV_MAX_LAYER_MAX;
+  for (int j = tid; j < k; j += kSelThreads) dst[j] = keys[j];
+}
+
+// Orders the winners of one (sequence, KV head) by counting. grid = (ceil(layer_max / 64), Hkv, n_seqs), 256 threads:
+// lane l of every wavefront owns candidate blockIdx.x * 64 + l, wavefront g counts the smaller keys among
+// candidates [g * k/4, (g+1) * k/4) (all lanes read the same LDS word: a broadcast); the four partial counts add
+// up to the rank, which is the candidate's place in idx_out.
+__global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int layer_max,
+                                                           const int32_t* __restrict__ cu,
+                                                           const u64* __restrict__ keys_in,
+                                                           int32_t* __restrict__ idx_out) {
+  __shared__ u64 keys[DKV_MAX_LAYER_MAX];
+  __shared__ int partial[4][64];
+  const int seq = blockIdx.z, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
+  const int S = cu[seq + 1] - cu[seq];
+  const int n = S > w ? S - w : 0;
+  const int k = layer_max < n ? layer_max : n;
+  int32_t* __restrict__ out = idx_out + ((int64_t)seq * Hkv + head) * layer_max;
+  const int e0 = blockIdx.x * 64;
+  // slots past k hold -1 (each workgroup clears the ones in its own range)
+  if (tid < 64 && e0 + tid >= k && e0 + tid < layer_max) out[e0 + tid] = -1;
+  if (e0 >= k) return;
+  const u64* __restrict__ src = keys_in + ((int64_t)seq * Hkv + head) * DKV_MAX_LAYER_MAX;
+  for (int j = tid; j < k; j += 256) keys[j] = src[j];
   __syncthreads();
-  bitonic_sort_2048(k0, k1, keys, n_sort);
-  if (tid < layer_max) out[tid] = tid < k ? (int32_t)(uint32_t)k0 : -1;
-  if (tid + 1024 < layer_max) out[tid + 1024] = tid + 1024 < k ? (int32_t)(uint32_t)k1 : -1;
-  for (int j = 2048 + tid; j < layer_max; j += kSelThreads) out[j] = -1;
+  const int e = e0 + lane;
+  const u64 mine = e < k ? keys[e] : ~0ull;
+  const int quarter = (k + 3) / 4;
+  const int j0 = g * quarter, j1 = (g + 1) * quarter < k ? (g + 1) * quarter : k;
+  int smaller = 0;
+  int j = j0;
+  for (; j + 8 <= j1; j += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) smaller += keys[j + u] < mine ? 1 : 0;
+  }
+  for (; j < j1; ++j) smaller += keys[j] < mine ? 1 : 0;
+  partial[g][lane] = smaller;
+  __syncthreads();
+  if (g == 0 && e < k) {
+    const int rank = partial[0][lane] + partial[1][lane] + partial[2][lane] + partial[3][lane];
+    out[rank] = (int32_t)(uint32_t)mine;
+  }
 }
 
 hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,
-                         const int32_t* cu, int32_t* idx_out, int32_t* counts, hipStream_t st) {
+                         const int32_t* cu, int32_t* idx_out, int32_t* counts, char* ws, const WorkspaceLayout& wl,
+                         hipStream_t st) {
   const size_t lds = 2048 * sizeof(u64) + (size_t)kRadixBins * kHistCopies * sizeof(int);
   static bool attr_set = false;
   if (!attr_set) {
@@ -256,8 +258,11 @@ hipError_t launch_select(const Params& p, int layer, const float* scores, int64_
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max,
-                     p.L, layer, scores, scores_stride_head, cu, idx_out, counts);
+  u64* keys = reinterpret_cast<u64*>(ws + wl.select_keys);
+  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w,
+         p.layer_max, p.L, layer, scores, scores_stride_head, cu, idx_out, counts, keys);
+  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + 63) / 64, p.Hkv, p.n_seqs), dim3(256), 0, st,
+         p.Hkv, p.w, p.layer_max, cu, keys, idx_out);
   return hipGetLastError();
 }
 

@@ -61,7 +61,7 @@ def load() -> C.CDLL:
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
     lib.dkv_select_topk.restype = C.c_int
-    lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P]
+    lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P, SZ, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
@@ -116,7 +116,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_decide",
-                "rebalance_final", "fill")
+                "rebalance_final", "fill", "select_order")
 
 
 def dkv_profile_begin(capacity: int) -> None:
@@ -156,9 +156,11 @@ def dkv_score_window_emit(desc, q_win, k, k_stride_token, k_stride_head, cu_seql
            "dkv_score_window_emit")
 
 
-def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts, stream=None) -> None:
+def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts, workspace,
+                    stream=None) -> None:
     _check(load().dkv_select_topk(C.byref(desc), layer, _ptr(scores), scores_stride_head, _ptr(cu_seqlens),
-                                  _ptr(idx_out), _ptr(counts), _stream(stream)), "dkv_select_topk")
+                                  _ptr(idx_out), _ptr(counts), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_select_topk")
 
 
 def dkv_rebalance(desc, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out, workspace,

@@ -45,7 +45,7 @@ class Compressor:
 
     def select(self, layer, stream=None):
         dkv.dkv_select_topk(self.desc, layer, self.scores[layer], self.cfg.total_tokens, self.cu, self.idx[layer],
-                            self.counts, stream)
+                            self.counts, self.ws, stream)
 
     def gather(self, layer, k, v, stride_token=None, stride_head=None, stream=None):
         d = self.cfg.d

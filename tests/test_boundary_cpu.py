@@ -70,7 +70,7 @@ def test_bad_descriptors_are_rejected(lib, bad, status):
     d = _good(**bad)
     fake = C.c_void_p(0x1000)
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 64 * 1024, fake, fake, 1024, fake, 1 << 30, None) == status
-    assert lib.dkv_select_topk(C.byref(d), 0, fake, 1024, fake, fake, fake, None) == status
+    assert lib.dkv_select_topk(C.byref(d), 0, fake, 1024, fake, fake, fake, fake, 1 << 30, None) == status
     assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 1 << 30, None) == status
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64,
                              272 * 64, None) == status
@@ -85,7 +85,7 @@ def test_bad_call_arguments_are_rejected(lib):
     # null pointers
     assert lib.dkv_score_window(C.byref(d), None, fake, 64, 65536, fake, fake, 1024, fake, need, None) == inv
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, None, fake, 1024, fake, need, None) == inv
-    assert lib.dkv_select_topk(C.byref(d), 0, None, 1024, fake, fake, fake, None) == inv
+    assert lib.dkv_select_topk(C.byref(d), 0, None, 1024, fake, fake, fake, fake, need, None) == inv
     assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, None, None, None, fake, need, None) == inv
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, None, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64, 272 * 64,
                              None) == inv
@@ -101,8 +101,8 @@ def test_bad_call_arguments_are_rejected(lib):
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, C.c_void_p(0x1010), need, None) == wsp
     assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 16, None) == wsp
     # layer / layers_done out of range or not a multiple of the interval
-    assert lib.dkv_select_topk(C.byref(d), 4, fake, 1024, fake, fake, fake, None) == inv
-    assert lib.dkv_select_topk(C.byref(d), -1, fake, 1024, fake, fake, fake, None) == inv
+    assert lib.dkv_select_topk(C.byref(d), 4, fake, 1024, fake, fake, fake, fake, need, None) == inv
+    assert lib.dkv_select_topk(C.byref(d), -1, fake, 1024, fake, fake, fake, fake, need, None) == inv
     for bad_l in (0, 1, 3, 6):
         assert lib.dkv_rebalance(C.byref(d), bad_l, fake, fake, fake, None, None, fake, need, None) == inv
     # output block too small for window + layer_max rows
@@ -115,4 +115,4 @@ def test_bad_call_arguments_are_rejected(lib):
 def test_binding_raises_on_error():
     d = _good(pool_kernel=2)
     with pytest.raises(dkv.DkvError):
-        dkv._check(dkv.load().dkv_select_topk(C.byref(d), 0, None, 0, None, None, None, None), "dkv_select_topk")
+        dkv._check(dkv.load().dkv_select_topk(C.byref(d), 0, None, 0, None, None, None, None, 0, None), "dkv_select_topk")
