@@ -47,11 +47,12 @@ __global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv
       reinterpret_cast<const uint32_t*>(scores_all + ((int64_t)layer * Hkv + head) * total_tokens + begin);
   constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
   constexpr int ushift = PASS == 0 ? 0 : (PASS == 1 ? 21 : 10);
+  constexpr uint32_t dmask = PASS == 2 ? 1023u : (uint32_t)(kRadixBins - 1);   // the last digit has 10 bits only
   int mine = 0;   // elements of this thread that the digits found so far place above T
   for (int i = i0 + threadIdx.x; i < i1; i += 256) {
     const uint32_t u = row[i];
     const bool match = PASS == 0 ? true : ((u >> ushift) == (prefix >> ushift));
-    if (match) atomicAdd(&h[((u >> shift) & (kRadixBins - 1)) * kScanCopies + (threadIdx.x & (kScanCopies - 1))], 1);
+    if (match) atomicAdd(&h[((u >> shift) & dmask) * kScanCopies + (threadIdx.x & (kScanCopies - 1))], 1);
     if (PASS > 0) {
       // the digit chosen by the previous pass sits just above this pass's digit: equal higher bits, larger digit
       constexpr int pshift = PASS == 1 ? 21 : 10;

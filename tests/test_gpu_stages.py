@@ -247,6 +247,11 @@ def test_rebalance_skewed_and_tied_scores(dkv):
     variants.append(np.full((cfg.L, cfg.Hkv, T), 0.5, dtype=np.float32))
     variants.append((rng.integers(0, 3, size=(cfg.L, cfg.Hkv, T)) / 2).astype(np.float32))
     variants.append(np.abs(rng.standard_normal((cfg.L, cfg.Hkv, T))).astype(np.float32) * np.array([1, 3, 0.2, 1], dtype=np.float32)[:, None, None])
+    # values that share the two upper radix digits of the threshold (11 + 11 bits), so that the last 10-bit digit
+    # decides; the middle digit once odd, once even
+    for mid in (0xd7, 0xd6):
+        bits = (0x1e6 << 21) | (mid << 10) | rng.integers(0, 1024, size=(cfg.L, cfg.Hkv, T))
+        variants.append(bits.astype(np.uint32).view(np.float32))
     for A in variants:
         comp = Compressor(cfg, keep_cache=False)
         comp.scores.copy_(torch.from_numpy(A))
