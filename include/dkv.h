@@ -48,6 +48,7 @@ enum {
 #define DKV_MAX_ROWS 256       /* G * window: score rows per KV head         */
 #define DKV_MAX_SEQS 4096
 #define DKV_MAX_LAYERS 512
+#define DKV_MAX_SELECT_LAYERS 8   /* layers one dkv_select_topk_layers call may cover */
 
 /* Problem descriptor (host memory, read during the call only). Symbols as in Algorithm 1. */
 typedef struct dkv_desc {
@@ -151,6 +152,21 @@ int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, in
                     size_t workspace_bytes, void* stream);
 
 /*
+ * The same selection (Eq. 3) for the n_layers consecutive layers [layer_begin, layer_begin + n_layers) in one
+ * call: the selection of a layer depends on that layer's scores only, so a caller that keeps the scores of a
+ * few layers (the progressive update needs them anyway) can select them together; one row per (layer,
+ * sequence, KV head) then gives the GPU layers-times more workgroups than a single layer does. Results are
+ * identical to n_layers dkv_select_topk calls.
+ * n_layers    1 .. DKV_MAX_SELECT_LAYERS, layer_begin + n_layers <= L.
+ * scores_all  fp32 [L][Hkv][total_tokens] contiguous, as for dkv_rebalance.
+ * idx_all     int32 [L][n_seqs][Hkv][layer_max]; the blocks of the selected layers are written.
+ * counts      int32 [n_seqs][L]; counts[q][layer] = k is written for the selected layers.
+ */
+int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const float* scores_all,
+                           const int32_t* cu_seqlens, int32_t* idx_all, int32_t* counts, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
  * Progressive cache update after `layers_done` layers (Section 4.2, Eq. 4-6; Update_Buffer_Length and the
  * truncation loop of Algorithm 1). Per sequence: the kg = min(mean_budget * Hkv * l, l * Hkv * S') largest
  * entries of the scores of layers [0, l) (ties to the lower (layer, head, position)) are counted per layer
@@ -180,6 +196,23 @@ int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores
 int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void* v, int64_t stride_token,
                   int64_t stride_head, const int32_t* cu_seqlens, const int32_t* idx, const int32_t* counts,
                   void* k_out, void* v_out, int64_t out_stride_seq, int64_t out_stride_head, void* stream);
+
+/*
+ * The same compaction (Algorithm 1, the two cat(gather(...), window) lines) for the n_layers consecutive layers
+ * [layer_begin, layer_begin + n_layers) in one call, for a caller that selected them together
+ * (dkv_select_topk_layers) and still holds their K and V. Results are identical to n_layers dkv_gather_kv calls.
+ * h_k_layers, h_v_layers  HOST arrays of n_layers DEVICE pointers: K and V of layer layer_begin + i, all with the
+ *                         strides given; the arrays are read during the call only.
+ * idx_all                 int32 [L][n_seqs][Hkv][layer_max], as written by dkv_select_topk_layers.
+ * k_out_all, v_out_all    element (layer, q, h, slot, j) at
+ *                         out[layer * out_stride_layer + q * out_stride_seq + h * out_stride_head + slot * d + j].
+ * n_layers                1 .. DKV_MAX_SELECT_LAYERS, layer_begin + n_layers <= L.
+ */
+int dkv_gather_kv_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* const* h_k_layers,
+                         const void* const* h_v_layers, int64_t stride_token, int64_t stride_head,
+                         const int32_t* cu_seqlens, const int32_t* idx_all, const int32_t* counts, void* k_out_all,
+                         void* v_out_all, int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head,
+                         void* stream);
 
 #ifdef __cplusplus
 }

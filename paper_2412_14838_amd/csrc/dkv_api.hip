@@ -173,7 +173,28 @@ int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, in
   st = check_workspace(*desc, workspace, workspace_bytes, wl);
   if (st != DKV_OK) return st;
   const Params p = make_params(*desc);
-  const hipError_t e = launch_select(p, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts,
+  const hipError_t e = launch_select(p, layer, 1, scores, scores_stride_head, 0, cu_seqlens, idx_out, 0, counts,
+                                     static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const float* scores_all,
+                           const int32_t* cu_seqlens, int32_t* idx_all, int32_t* counts, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!scores_all || !cu_seqlens || !idx_all || !counts) return DKV_ERR_INVALID_ARG;
+  if (n_layers < 1 || n_layers > DKV_MAX_SELECT_LAYERS) return DKV_ERR_INVALID_ARG;
+  if (layer_begin < 0 || layer_begin + n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  const Params p = make_params(*desc);
+  const int64_t scores_stride_layer = (int64_t)desc->n_kv_heads * desc->total_tokens;
+  const int64_t idx_stride_layer = (int64_t)desc->n_seqs * desc->n_kv_heads * desc->layer_max;
+  const hipError_t e = launch_select(p, layer_begin, n_layers, scores_all + layer_begin * scores_stride_layer,
+                                     desc->total_tokens, scores_stride_layer, cu_seqlens,
+                                     idx_all + layer_begin * idx_stride_layer, idx_stride_layer, counts,
                                      static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
@@ -209,8 +230,43 @@ int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void
   if (out_stride_head < block || out_stride_seq < out_stride_head * desc->n_kv_heads) return DKV_ERR_INVALID_ARG;
   if ((out_stride_head * elt) % 16 != 0 || (out_stride_seq * elt) % 16 != 0) return DKV_ERR_INVALID_ARG;
   const Params p = make_params(*desc);
-  const hipError_t e = launch_gather(p, (int)elt, layer, k, v, stride_token, stride_head, cu_seqlens, idx, counts,
-                                     k_out, v_out, out_stride_seq, out_stride_head, static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_gather(p, (int)elt, layer, 1, &k, &v, stride_token, stride_head, cu_seqlens, idx, 0,
+                                     counts, k_out, v_out, 0, out_stride_seq, out_stride_head,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_gather_kv_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* const* h_k_layers,
+                         const void* const* h_v_layers, int64_t stride_token, int64_t stride_head,
+                         const int32_t* cu_seqlens, const int32_t* idx_all, const int32_t* counts, void* k_out_all,
+                         void* v_out_all, int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head,
+                         void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!h_k_layers || !h_v_layers || !cu_seqlens || !idx_all || !counts || !k_out_all || !v_out_all)
+    return DKV_ERR_INVALID_ARG;
+  if (n_layers < 1 || n_layers > DKV_MAX_SELECT_LAYERS) return DKV_ERR_INVALID_ARG;
+  if (layer_begin < 0 || layer_begin + n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  for (int i = 0; i < n_layers; ++i)
+    if (!h_k_layers[i] || !h_v_layers[i] || !aligned16(h_k_layers[i]) || !aligned16(h_v_layers[i]))
+      return DKV_ERR_INVALID_ARG;
+  if (!aligned16(k_out_all) || !aligned16(v_out_all)) return DKV_ERR_INVALID_ARG;
+  st = check_kv_strides(*desc, stride_token, stride_head);
+  if (st != DKV_OK) return st;
+  const int64_t elt = desc->dtype == DKV_BF16 ? 2 : 4;
+  const int64_t block = (int64_t)(desc->window + desc->layer_max) * desc->head_dim;
+  if (out_stride_head < block || out_stride_seq < out_stride_head * desc->n_kv_heads) return DKV_ERR_INVALID_ARG;
+  if (out_stride_layer < out_stride_seq * desc->n_seqs) return DKV_ERR_INVALID_ARG;
+  if ((out_stride_head * elt) % 16 != 0 || (out_stride_seq * elt) % 16 != 0 || (out_stride_layer * elt) % 16 != 0)
+    return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const int64_t idx_stride_layer = (int64_t)desc->n_seqs * desc->n_kv_heads * desc->layer_max;
+  const hipError_t e = launch_gather(
+      p, (int)elt, layer_begin, n_layers, h_k_layers, h_v_layers, stride_token, stride_head, cu_seqlens,
+      idx_all + layer_begin * idx_stride_layer, idx_stride_layer, counts,
+      static_cast<char*>(k_out_all) + layer_begin * out_stride_layer * elt,
+      static_cast<char*>(v_out_all) + layer_begin * out_stride_layer * elt, out_stride_layer, out_stride_seq,
+      out_stride_head, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 

@@ -21,7 +21,7 @@ constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the 
 // ----------------------------------------------------------------------------------------------
 struct WorkspaceLayout {
   size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
-  size_t select_keys;  // uint64 [n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
+  size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
   size_t hist;         // int32 [3][n_seqs][L][kRadixBins]
   size_t state;        // int32 [n_seqs][8]              radix-select state of the rebalance
   size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
@@ -41,7 +41,7 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.chunks_max = d.total_tokens / min_stats_keys() + d.n_seqs;
   size_t off = 0;
   w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
-  w.select_keys = off; off += align256(size_t(d.n_seqs) * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
+  w.select_keys = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
   w.hist = off;     off += align256(size_t(3) * d.n_seqs * d.n_layers * kRadixBins * sizeof(int32_t));
   w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
   w.above = off;    off += align256(size_t(d.n_seqs) * d.n_layers * sizeof(int32_t));
@@ -100,15 +100,16 @@ bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token);
 hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                              int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                              char* ws, const WorkspaceLayout& wl, hipStream_t st);
-hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,
-                         const int32_t* cu, int32_t* idx_out, int32_t* counts, char* ws, const WorkspaceLayout& wl,
-                         hipStream_t st);
+hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
+                         int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,
+                         int32_t* counts, char* ws, const WorkspaceLayout& wl, hipStream_t st);
 hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
                             int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
                             const WorkspaceLayout& wl, hipStream_t st);
-hipError_t launch_gather(const Params& p, int elt_bytes, int layer, const void* k, const void* v, int64_t stride_token,
-                         int64_t stride_head, const int32_t* cu, const int32_t* idx, const int32_t* counts, void* k_out,
-                         void* v_out, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st);
+hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers, const void* const* k_layers,
+                         const void* const* v_layers, int64_t stride_token, int64_t stride_head, const int32_t* cu,
+                         const int32_t* idx, int64_t idx_stride_layer, const int32_t* counts, void* k_out, void* v_out,
+                         int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 // ----------------------------------------------------------------------------------------------

@@ -43,13 +43,17 @@ __device__ inline int block_exclusive_scan(int v, int* scratch) {
   return base + incl - v;
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer,
-                                                                  const float* __restrict__ scores,
+// grid = (Hkv, n_seqs, layers of the call); blockIdx.z picks the layer: its scores, index list and key block lie
+// blockIdx.z layer strides behind the pointers passed in.
+__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer0,
+                                                                  const float* __restrict__ scores0,
                                                                   int64_t scores_stride_head,
+                                                                  int64_t scores_stride_layer,
                                                                   const int32_t* __restrict__ cu,
-                                                                  int32_t* __restrict__ idx_out,
+                                                                  int32_t* __restrict__ idx_out0,
+                                                                  int64_t idx_stride_layer,
                                                                   int32_t* __restrict__ counts,
-                                                                  u64* __restrict__ keys_out) {
+                                                                  u64* __restrict__ keys_out0) {
   extern __shared__ __attribute__((aligned(16))) char sel_smem[];
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
@@ -59,6 +63,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   __shared__ int wave_eq[kSelWaves];
 
   const int seq = blockIdx.y, head = blockIdx.x;
+  const int layer = layer0 + blockIdx.z;
+  const float* __restrict__ scores = scores0 + (int64_t)blockIdx.z * scores_stride_layer;
+  int32_t* __restrict__ idx_out = idx_out0 + (int64_t)blockIdx.z * idx_stride_layer;
+  u64* __restrict__ keys_out = keys_out0 + (int64_t)blockIdx.z * gridDim.y * Hkv * DKV_MAX_LAYER_MAX;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int begin = cu[seq];
   const int S = cu[seq + 1] - begin;
@@ -206,17 +214,21 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   for (int j = tid; j < k; j += kSelThreads) dst[j] = keys[j];
 }
 
-// Orders the winners of one (sequence, KV head) by counting. grid = (ceil(layer_max / 64), Hkv, n_seqs), 256 threads:
+// Orders the winners of one (layer, sequence, KV head) by counting. grid = (ceil(layer_max / 64), Hkv, n_seqs * layers),
+// 256 threads:
 // lane l of every wavefront owns candidate blockIdx.x * 64 + l, wavefront g counts the smaller keys among
 // candidates [g * k/4, (g+1) * k/4) (all lanes read the same LDS word: a broadcast); the four partial counts add
 // up to the rank, which is the candidate's place in idx_out.
-__global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int layer_max,
+__global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int layer_max, int n_seqs,
                                                            const int32_t* __restrict__ cu,
-                                                           const u64* __restrict__ keys_in,
-                                                           int32_t* __restrict__ idx_out) {
+                                                           const u64* __restrict__ keys_in0,
+                                                           int32_t* __restrict__ idx_out0, int64_t idx_stride_layer) {
   __shared__ u64 keys[DKV_MAX_LAYER_MAX];
   __shared__ int partial[4][64];
-  const int seq = blockIdx.z, head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
+  const int seq = blockIdx.z % n_seqs, lz = blockIdx.z / n_seqs;
+  const int head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
+  const u64* __restrict__ keys_in = keys_in0 + (int64_t)lz * n_seqs * Hkv * DKV_MAX_LAYER_MAX;
+  int32_t* __restrict__ idx_out = idx_out0 + (int64_t)lz * idx_stride_layer;
   const int S = cu[seq + 1] - cu[seq];
   const int n = S > w ? S - w : 0;
   const int k = layer_max < n ? layer_max : n;
@@ -247,9 +259,9 @@ __global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int l
   }
 }
 
-hipError_t launch_select(const Params& p, int layer, const float* scores, int64_t scores_stride_head,
-                         const int32_t* cu, int32_t* idx_out, int32_t* counts, char* ws, const WorkspaceLayout& wl,
-                         hipStream_t st) {
+hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
+                         int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,
+                         int32_t* counts, char* ws, const WorkspaceLayout& wl, hipStream_t st) {
   const size_t lds = 2048 * sizeof(u64) + (size_t)kRadixBins * kHistCopies * sizeof(int);
   static bool attr_set = false;
   if (!attr_set) {
@@ -259,10 +271,11 @@ hipError_t launch_select(const Params& p, int layer, const float* scores, int64_
     attr_set = true;
   }
   u64* keys = reinterpret_cast<u64*>(ws + wl.select_keys);
-  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs), dim3(kSelThreads), lds, st, p.Hkv, p.w,
-         p.layer_max, p.L, layer, scores, scores_stride_head, cu, idx_out, counts, keys);
-  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + 63) / 64, p.Hkv, p.n_seqs), dim3(256), 0, st,
-         p.Hkv, p.w, p.layer_max, cu, keys, idx_out);
+  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st, p.Hkv, p.w,
+         p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts,
+         keys);
+  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + 63) / 64, p.Hkv, p.n_seqs * n_layers),
+         dim3(256), 0, st, p.Hkv, p.w, p.layer_max, p.n_seqs, cu, keys, idx_out, idx_stride_layer);
   return hipGetLastError();
 }
 

@@ -14,10 +14,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdkv.so")
 
 DKV_F32, DKV_BF16 = 0, 1
+DKV_MAX_SELECT_LAYERS = 8
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
-           "dkv_score_window_stats", "dkv_score_window_emit", "dkv_select_topk", "dkv_rebalance", "dkv_gather_kv")
+           "dkv_score_window_stats", "dkv_score_window_emit", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
+           "dkv_gather_kv", "dkv_gather_kv_layers")
 
 
 class dkv_desc(C.Structure):
@@ -62,6 +64,10 @@ def load() -> C.CDLL:
         getattr(lib, name).argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
     lib.dkv_select_topk.restype = C.c_int
     lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P, SZ, P]
+    lib.dkv_select_topk_layers.restype = C.c_int
+    lib.dkv_select_topk_layers.argtypes = [D, I32, I32, P, P, P, P, P, SZ, P]
+    lib.dkv_gather_kv_layers.restype = C.c_int
+    lib.dkv_gather_kv_layers.argtypes = [D, I32, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, I64, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
@@ -161,6 +167,26 @@ def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out
     _check(load().dkv_select_topk(C.byref(desc), layer, _ptr(scores), scores_stride_head, _ptr(cu_seqlens),
                                   _ptr(idx_out), _ptr(counts), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_select_topk")
+
+
+def dkv_select_topk_layers(desc, layer_begin, n_layers, scores_all, cu_seqlens, idx_all, counts, workspace,
+                           stream=None) -> None:
+    _check(load().dkv_select_topk_layers(C.byref(desc), layer_begin, n_layers, _ptr(scores_all), _ptr(cu_seqlens),
+                                         _ptr(idx_all), _ptr(counts), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_select_topk_layers")
+
+
+def dkv_gather_kv_layers(desc, layer_begin, k_layers, v_layers, stride_token, stride_head, cu_seqlens, idx_all, counts,
+                         k_out_all, v_out_all, out_stride_layer, out_stride_seq, out_stride_head, stream=None) -> None:
+    """k_layers, v_layers: sequences of device tensors, one per layer of the call."""
+    n = len(k_layers)
+    ks = (C.c_void_p * n)(*[t.data_ptr() for t in k_layers])
+    vs = (C.c_void_p * n)(*[t.data_ptr() for t in v_layers])
+    _check(load().dkv_gather_kv_layers(C.byref(desc), layer_begin, n, ks, vs, stride_token, stride_head,
+                                       _ptr(cu_seqlens), _ptr(idx_all), _ptr(counts), _ptr(k_out_all), _ptr(v_out_all),
+                                       out_stride_layer, out_stride_seq, out_stride_head, _stream(stream)),
+           "dkv_gather_kv_layers")
 
 
 def dkv_rebalance(desc, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out, workspace,

@@ -7,6 +7,11 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
     budgets  int32 [n_seqs][L]                 Z' of the latest update;  hits: cnt of the latest update
     kb, vb   [L][n_seqs][Hkv][w + layer_max][d] compressed cache: window rows first, then retained rows;
              layer i of sequence q holds w + counts[q][i] valid rows per head.
+
+Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
+grouped (`group` > 1): a layer is scored when it arrives, and the selection and compaction of up to `group`
+layers are issued together when the group is full, at an update boundary, or at the last layer; the caller then
+holds the K and V of a group's layers until that point.
 """
 from __future__ import annotations
 
@@ -16,8 +21,10 @@ from . import dkv
 
 
 class Compressor:
-    def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None):
+    def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None, group=1):
         self.cfg = cfg
+        self.group = max(1, min(int(group), dkv.DKV_MAX_SELECT_LAYERS))
+        self._pending = []
         self.device = device
         self.desc = dkv.desc_from_workload(cfg, **(desc_override or {}))
         self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -54,16 +61,43 @@ class Compressor:
         dkv.dkv_gather_kv(self.desc, layer, k, v, st, sh, self.cu, self.idx[layer], self.counts, self.kb[layer],
                           self.vb[layer], self.cfg.Hkv * self.slots * d, self.slots * d, stream)
 
+    def select_layers(self, layer_begin, n_layers, stream=None):
+        dkv.dkv_select_topk_layers(self.desc, layer_begin, n_layers, self.scores, self.cu, self.idx, self.counts,
+                                   self.ws, stream)
+
+    def gather_layers(self, layer_begin, ks, vs, stride_token=None, stride_head=None, stream=None):
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_gather_kv_layers(self.desc, layer_begin, ks, vs, st, sh, self.cu, self.idx, self.counts, self.kb,
+                                 self.vb, self.cfg.n_seqs * self.cfg.Hkv * self.slots * d,
+                                 self.cfg.Hkv * self.slots * d, self.slots * d, stream)
+
     def rebalance(self, layers_done, stream=None):
         dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
                           stream)
 
     def step(self, layer, q_win, k, v, **strides):
+        if self.group > 1:
+            return self._step_grouped(layer, q_win, k, v, **strides)
         self.score(layer, q_win, k, **strides)
         self.select(layer)
         if self.keep_cache:
             self.gather(layer, k, v, **strides)
         if (layer + 1) % self.cfg.interval == 0:
+            self.rebalance(layer + 1)
+
+    def _step_grouped(self, layer, q_win, k, v, **strides):
+        self.score(layer, q_win, k, **strides)
+        self._pending.append((layer, k, v))
+        boundary = (layer + 1) % self.cfg.interval == 0
+        if len(self._pending) == self.group or boundary or layer == self.cfg.L - 1:
+            first, n = self._pending[0][0], len(self._pending)
+            self.select_layers(first, n)
+            if self.keep_cache:
+                self.gather_layers(first, [e[1] for e in self._pending], [e[2] for e in self._pending], **strides)
+            self._pending = []      # the caller may release K and V of these layers now
+        if boundary:
             self.rebalance(layer + 1)
 
     def run(self, layers, overlap=False):

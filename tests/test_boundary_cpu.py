@@ -74,6 +74,10 @@ def test_bad_descriptors_are_rejected(lib, bad, status):
     assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 1 << 30, None) == status
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64,
                              272 * 64, None) == status
+    ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib.dkv_select_topk_layers(C.byref(d), 0, 2, fake, fake, fake, fake, fake, 1 << 30, None) == status
+    assert lib.dkv_gather_kv_layers(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, fake, fake, fake, fake,
+                                    2 * 272 * 64, 2 * 272 * 64, 272 * 64, None) == status
 
 
 def test_bad_call_arguments_are_rejected(lib):
@@ -110,6 +114,33 @@ def test_bad_call_arguments_are_rejected(lib):
                              None) == inv
     assert lib.dkv_gather_kv(C.byref(d), 9, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64, 272 * 64,
                              None) == inv
+
+
+def test_layer_batched_calls_reject_bad_ranges(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    ptrs = (C.c_void_p * 9)(*([0x1000] * 9))
+    bad = (C.c_void_p * 2)(0x1000, 0)          # a null layer pointer
+    odd = (C.c_void_p * 2)(0x1000, 0x1008)     # a misaligned layer pointer
+    sl, sq, sh = 2 * 272 * 64, 2 * 272 * 64, 272 * 64
+    for begin, n in ((0, 0), (0, 9), (3, 2), (-1, 1), (4, 1)):
+        assert lib.dkv_select_topk_layers(C.byref(d), begin, n, fake, fake, fake, fake, fake, need, None) == inv
+        assert lib.dkv_gather_kv_layers(C.byref(d), begin, n, ptrs, ptrs, 64, 65536, fake, fake, fake, fake, fake,
+                                        sl, sq, sh, None) == inv
+    assert lib.dkv_select_topk_layers(C.byref(d), 0, 2, None, fake, fake, fake, fake, need, None) == inv
+    assert lib.dkv_select_topk_layers(C.byref(d), 0, 2, fake, fake, fake, fake, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
+    for arr in (bad, odd):
+        assert lib.dkv_gather_kv_layers(C.byref(d), 0, 2, arr, ptrs, 64, 65536, fake, fake, fake, fake, fake,
+                                        sl, sq, sh, None) == inv
+        assert lib.dkv_gather_kv_layers(C.byref(d), 0, 2, ptrs, arr, 64, 65536, fake, fake, fake, fake, fake,
+                                        sl, sq, sh, None) == inv
+    assert lib.dkv_gather_kv_layers(C.byref(d), 0, 2, None, ptrs, 64, 65536, fake, fake, fake, fake, fake,
+                                    sl, sq, sh, None) == inv
+    # layer stride smaller than one layer's block
+    assert lib.dkv_gather_kv_layers(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, fake, fake, fake, fake,
+                                    sq - 64, sq, sh, None) == inv
 
 
 def test_binding_raises_on_error():

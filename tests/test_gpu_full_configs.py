@@ -25,9 +25,9 @@ SCORE_RTOL = 2e-3
 BAND_RTOL = 1e-5
 
 
-def run_config(cfg, sample_layers):
+def run_config(cfg, sample_layers, group=1):
     workers = min(16, len(os.sched_getaffinity(0)))
-    comp = Compressor(cfg)
+    comp = Compressor(cfg, group=group)
     host, snaps = {}, {}
     with cf.ThreadPoolExecutor(max_workers=workers) as ex:
         for l, data in enumerate(ex.map(lambda l: W.make_layer(cfg, l), range(cfg.L))):
@@ -43,8 +43,8 @@ def run_config(cfg, sample_layers):
     return comp, host, snaps
 
 
-def check_config(cfg, sample_layers, sample_heads, sample_seqs, chain_budgets=False):
-    comp, host, snaps = run_config(cfg, sample_layers)
+def check_config(cfg, sample_layers, sample_heads, sample_seqs, chain_budgets=False, group=1):
+    comp, host, snaps = run_config(cfg, sample_layers, group)
     cu, w = cfg.cu_seqlens, cfg.w
     scores = comp.scores.cpu().numpy()
     idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
@@ -134,17 +134,17 @@ def test_full_llama3_8b_8k(dkv):
 
 def test_full_mistral_7b_32k(dkv):
     cfg = W.standard_configs()["mistral_7b_32k"]
-    check_config(cfg, [0, cfg.L - 1], [1, 7], [0])
+    check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=4)     # the schedule bench.py times
 
 
 def test_full_qwen2_7b_32k_extreme(dkv):
     cfg = W.standard_configs()["qwen2_7b_32k_extreme"]
-    check_config(cfg, [3, cfg.L - 1], [0, 3], [0])
+    check_config(cfg, [3, cfg.L - 1], [0, 3], [0], group=3)     # groups of 3 and 1 between the updates
 
 
 def test_full_ragged_batch8(dkv):
     cfg = W.standard_configs()["ragged_batch8"]
-    check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7])
+    check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7], group=4)
 
 
 def test_calibrated_planting_gives_layer_varying_budgets(dkv):
@@ -156,17 +156,24 @@ def test_calibrated_planting_gives_layer_varying_budgets(dkv):
     assert len(set(n)) > 1 and sum(n) <= cfg.global_budget
 
 
-def test_graph_replay_matches_eager(dkv):
+@pytest.mark.parametrize("group", [1, 4])
+def test_graph_replay_matches_eager(dkv, group):
     """The whole loop captured as a HIP graph and replayed several times, with eager work and synchronisations
-    between the replays, reproduces the eager results bit for bit on every replay."""
+    between the replays, reproduces the eager results bit for bit on every replay (layer by layer, and with the
+    selection and compaction of four layers issued together)."""
     cfg = W.standard_configs()["llama3_8b_8k"].with_(L=8, interval=4)
     layers = []
     for l in range(cfg.L):
         dev = to_device(cfg, W.make_layer(cfg, l))
         layers.append((dev["q_win"], dev["k"], dev["v"]))
-    comp = Compressor(cfg)
+    ref = Compressor(cfg)
+    ref.run(layers)
+    comp = Compressor(cfg, group=group)
     comp.run(layers)
     torch.cuda.synchronize()
+    for a, b in zip((ref.scores, ref.idx, ref.counts, ref.budgets, ref.hits, ref.kb, ref.vb),
+                    (comp.scores, comp.idx, comp.counts, comp.budgets, comp.hits, comp.kb, comp.vb)):
+        assert torch.equal(a, b)                        # both schedules give the same results
     want = [t.clone() for t in (comp.scores, comp.idx, comp.counts, comp.budgets, comp.hits, comp.kb, comp.vb)]
     graph = comp.capture(layers)
     for rep in range(4):

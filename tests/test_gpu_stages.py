@@ -286,3 +286,37 @@ def test_sequence_not_longer_than_window(dkv):
     # 20 tokens < window 32: the existing rows land in the last 20 window slots
     assert (kb[2][:, :12] == -5.0).all() and (kb[2][:, 32:] == -5.0).all()
     assert np.array_equal(kb[2][:, 12:32], data["k"][:, cu[2]:cu[3]])
+
+
+def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
+    """dkv_select_topk_layers / dkv_gather_kv_layers over layers [1, 4) of a ragged batch give, bit for bit, what
+    per-layer calls give (which the tests above check against the oracle); other layers' blocks stay untouched."""
+    cfg = small_cfg("batched", L=5, interval=5, seqlens=(700, 90, 1500), layer_max=128, mean_budget=40)
+    one, many = Compressor(cfg), Compressor(cfg)
+    kinds = _tie_heavy_scores(cfg, 11)
+    A = np.stack([kinds[i] for i in (0, 4, 1, 2, 5)])        # one kind of score row per layer
+    cu = cfg.cu_seqlens
+    for s in range(cfg.n_seqs):
+        A[:, :, cu[s + 1] - cfg.w:cu[s + 1]] = -np.inf
+    kv = [to_device(cfg, W.make_layer(cfg, l)) for l in range(cfg.L)]
+    for comp in (one, many):
+        comp.scores.copy_(torch.from_numpy(A))
+        comp.kb.fill_(-7.0)
+        comp.vb.fill_(-7.0)
+        comp.counts.fill_(-3)
+    for l in (1, 2, 3):
+        one.select(l)
+        one.gather(l, kv[l]["k"], kv[l]["v"])
+    many.select_layers(1, 3)
+    many.gather_layers(1, [kv[l]["k"] for l in (1, 2, 3)], [kv[l]["v"] for l in (1, 2, 3)])
+    torch.cuda.synchronize()
+    for a, b in ((one.idx, many.idx), (one.counts, many.counts), (one.kb, many.kb), (one.vb, many.vb)):
+        assert torch.equal(a, b)
+    assert (many.idx[0] == -1).all() and (many.idx[4] == -1).all()
+    assert (many.counts[:, 0] == -3).all() and (many.counts[:, 4] == -3).all() and (many.counts[:, 1:4] >= 0).all()
+    assert (many.kb[0] == -7.0).all() and (many.kb[4] == -7.0).all()
+    # and against the oracle directly, for one layer of the batch
+    for s in range(cfg.n_seqs):
+        pre = cfg.seqlens[s] - cfg.w
+        ref = O.select_topk(A[2][:, cu[s]:cu[s] + pre], cfg.layer_max)
+        assert np.array_equal(many.idx[2, s][:, :ref.shape[1]].cpu().numpy(), ref)
