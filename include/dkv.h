@@ -76,7 +76,7 @@ enum {
   DKV_KERNEL_SELECT = 2,
   DKV_KERNEL_GATHER = 3,
   DKV_KERNEL_REBALANCE_HIST = 4,
-  DKV_KERNEL_REBALANCE_DECIDE = 5,
+  DKV_KERNEL_REBALANCE_SCAN = 5,
   DKV_KERNEL_REBALANCE_FINAL = 6,
   DKV_KERNEL_FILL = 7,
   DKV_KERNEL_SELECT_ORDER = 8
@@ -173,10 +173,16 @@ int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_
  * (cnt_i), then Z_i = floor(layer_max * cnt_i / max cnt), Z'_i = floor(Z_i * mean_budget * L / sum Z)
  * (exact integers), and counts[q][i] <- min(counts[q][i], Z'_i) for i < l.
  * layers_done  l: a positive multiple of desc->interval, <= L.
- * scores_all   fp32 [L][Hkv][total_tokens] contiguous (layer i at scores_all + i * Hkv * total_tokens).
+ * scores_all   fp32 [L][Hkv][total_tokens] contiguous (layer i at scores_all + i * Hkv * total_tokens), 16-byte
+ *              aligned.
  * counts       int32 [n_seqs][L], updated in place for layers < l.
  * budgets_out  int32 [n_seqs][L]: Z' for layers < l (others untouched). May be NULL.
  * hits_out     int32 [n_seqs][L]: cnt for layers < l. May be NULL.
+ * A layer's scores do not change once written, so the call keeps a histogram of the layers it has scanned in the
+ * workspace and the next call of the same prefill (layers_done + interval, same scores_all, same workspace)
+ * extends it instead of recounting; a call with any other history, and every call with layers_done == interval,
+ * recounts from scratch. Hence: do not rewrite the scores of layers < l between the calls of one prefill, and
+ * do not share one workspace between prefills that are in flight together.
  */
 int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
                   int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,

@@ -204,7 +204,7 @@ int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores
                   size_t workspace_bytes, void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
-  if (!scores_all || !cu_seqlens || !counts) return DKV_ERR_INVALID_ARG;
+  if (!scores_all || !cu_seqlens || !counts || !aligned16(scores_all)) return DKV_ERR_INVALID_ARG;
   if (layers_done < 1 || layers_done > desc->n_layers || layers_done % desc->interval != 0) return DKV_ERR_INVALID_ARG;
   WorkspaceLayout wl;
   st = check_workspace(*desc, workspace, workspace_bytes, wl);

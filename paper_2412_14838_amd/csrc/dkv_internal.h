@@ -14,7 +14,6 @@ namespace dkv {
 constexpr int kGenericKeys = 256;      // keys per workgroup in the generic (VALU) score kernels
 constexpr int kMfmaMinChunk = 256;     // smallest chunk of keys per workgroup in the MFMA score kernels
 constexpr int kRadixBins = 2048;       // 11-bit digits; 3 passes cover bits 31..21, 20..10, 9..0
-constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the rebalance histogram kernels
 
 // ----------------------------------------------------------------------------------------------
 // Workspace layout (byte offsets, all 256-byte aligned)
@@ -22,8 +21,12 @@ constexpr int kRebalanceChunk = 8192;  // prefix positions per workgroup in the 
 struct WorkspaceLayout {
   size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
-  size_t hist;         // int32 [3][n_seqs][L][kRadixBins]
-  size_t state;        // int32 [n_seqs][8]              radix-select state of the rebalance
+  // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
+  size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
+  size_t tot0;         // int32 [n_seqs][kRadixBins]     top digit
+  size_t tot1;         // int32 [n_seqs][kRadixBins]     middle digit, elements sharing the threshold's top digit
+  size_t tot2;         // int32 [n_seqs][1024]           last digit, elements sharing the two digits above
+  size_t hist2;        // int32 [n_seqs][L][1024]        the same per layer
   size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
   size_t total;
   int rows_pad;        // G*w rounded up to 64
@@ -42,8 +45,11 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   size_t off = 0;
   w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
   w.select_keys = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
-  w.hist = off;     off += align256(size_t(3) * d.n_seqs * d.n_layers * kRadixBins * sizeof(int32_t));
-  w.state = off;    off += align256(size_t(d.n_seqs) * 8 * sizeof(int32_t));
+  w.header = off;   off += align256(8 * sizeof(int32_t));
+  w.tot0 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
+  w.tot1 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));   // tot1 .. above: cleared per call
+  w.tot2 = off;     off += align256(size_t(d.n_seqs) * 1024 * sizeof(int32_t));
+  w.hist2 = off;    off += align256(size_t(d.n_seqs) * d.n_layers * 1024 * sizeof(int32_t));
   w.above = off;    off += align256(size_t(d.n_seqs) * d.n_layers * sizeof(int32_t));
   w.total = off;
   return w;
@@ -110,7 +116,6 @@ hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers
                          const void* const* v_layers, int64_t stride_token, int64_t stride_head, const int32_t* cu,
                          const int32_t* idx, int64_t idx_stride_layer, const int32_t* counts, void* k_out, void* v_out,
                          int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st);
-hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
 
 // ----------------------------------------------------------------------------------------------
 // Device helpers

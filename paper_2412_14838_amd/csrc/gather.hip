@@ -82,17 +82,4 @@ hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t n_words) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256) p[i] = 0u;
-}
-
-hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
-  const size_t n_words = bytes / 4;
-  if (n_words == 0) return hipSuccess;
-  size_t blocks = (n_words + 255) / 256;
-  if (blocks > 2048) blocks = 2048;
-  launch(DKV_KERNEL_FILL, fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint32_t*>(ptr), n_words);
-  return hipGetLastError();
-}
-
 }  // namespace dkv

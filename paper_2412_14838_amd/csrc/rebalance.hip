@@ -2,79 +2,98 @@
 //
 // The global top-kg over the concatenated scores of the layers processed so far only matters through its
 // per-layer hit counts, so no element is ever moved: a 3-digit radix select (11 + 11 + 10 bits of the fp32
-// pattern, scores are >= 0) finds the kg-th largest value T from per-(sequence, layer) digit histograms.
-// Many workgroups build the histograms (the scan of all scores is bandwidth work) and, from the second pass on,
-// also count per layer the elements that the digits found so far already place above T; a single workgroup per
-// sequence takes every decision: the digit of T after each pass, then cnt_i = #{> T in layer i} + the share
-// of the elements equal to T that the tie rule (lower layer first) gives to layer i, then Z, Z' and counts.
+// pattern, scores are >= 0) finds the kg-th largest value T from digit histograms summed over all layers.
+//
+//   clear   zeroes the histograms of this call.
+//   hist0   histogram of the top digit. A layer's scores never change once written, so the histogram is kept in
+//           the workspace and a call only adds the layers that the previous call (layers_done - interval, same
+//           score tensor, recorded in a small header) had not seen; any other history means a full recount.
+//   scan1   every workgroup first derives digit 0 of T from the top-digit histogram (a 2048-bin scan, cheaper
+//           than a kernel of its own), then histograms the middle digit of the elements that share digit 0 and
+//           counts, per layer, the elements whose digit 0 is larger (they are above T).
+//   scan2   the same one digit down: derives digits 0 and 1, histograms the last digit (per layer and in
+//           total), counts per layer the elements that share digit 0 and have a larger middle digit.
+//   final   one workgroup per sequence: digit 2, then cnt_i = #{> T in layer i} + the share of the elements
+//           equal to T that the tie rule (lower layer first) gives to layer i, then Z, Z' and counts.
+// The scans read the scores as 16-byte vectors, all loads of a workgroup's chunk in flight together.
 #include "dkv_internal.h"
 
 namespace dkv {
 
-constexpr int kDecThreads = 1024;
-constexpr int kDecWaves = kDecThreads / 64;
-constexpr int kScanCopies = 4;   // interleaved copies of the LDS histogram: lanes sharing a digit spread over 4 words
+constexpr int kFinalThreads = 1024;
+constexpr int kHist0Copies = 4;      // interleaved LDS copies of the top-digit histogram (every element lands there)
+constexpr int kHist0Chunk = 8192;    // prefix positions per workgroup, top-digit histogram
+constexpr int kScanChunk = 16384;    // prefix positions per workgroup, scans 1 and 2
+constexpr int kLowBins = 1024;       // the last digit has 10 bits
+constexpr uint32_t kHeaderMagic = 0x646b7631u;
 
-// state[seq][8]: 0 prefix bits of T found so far, 1 remaining rank, 2..4 chosen digit of pass 0..2, 5 kg
-__device__ inline int digit_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+// header[0] magic, [1] layers_done of the last completed call, [2..3] its score tensor, [4] interval, [5] n_seqs,
+// [6] total_tokens. Layers below the returned value already are in the top-digit histogram.
+__device__ inline int layers_already_counted(const int32_t* __restrict__ header, const float* scores_all,
+                                             int layers_done, int interval, int n_seqs, int total_tokens) {
+  const uint64_t ptr = reinterpret_cast<uint64_t>(scores_all);
+  const bool same = (uint32_t)header[0] == kHeaderMagic && header[1] == layers_done - interval &&
+                    (uint32_t)header[2] == (uint32_t)ptr && (uint32_t)header[3] == (uint32_t)(ptr >> 32) &&
+                    header[4] == interval && header[5] == n_seqs && header[6] == total_tokens;
+  return same && layers_done > interval ? layers_done - interval : 0;
+}
 
-// grid = (chunk upper bound, Hkv, layers_done); block 256. Adds the digit histogram of one chunk of one
-// (sequence, head, layer) row into hist[pass][seq][layer][*]. Elements whose higher bits differ from the
-// prefix found by the earlier passes are skipped.
-template <int PASS>
-__global__ __launch_bounds__(256) void rebalance_hist_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
-                                                             const float* __restrict__ scores_all,
-                                                             const int32_t* __restrict__ cu, int32_t* __restrict__ hist,
-                                                             const int32_t* __restrict__ state,
-                                                             int32_t* __restrict__ above) {
-  __shared__ int h[kRadixBins * kScanCopies];
-  __shared__ int n_above;
-  int seq, c, begin, len;
-  if (!find_chunk(cu, n_seqs, kRebalanceChunk, w, blockIdx.x, seq, c, begin, len)) return;
-  const int head = blockIdx.y, layer = blockIdx.z;
-  const int n = len - w;
-  const int i0 = c * kRebalanceChunk;
-  const int i1 = i0 + kRebalanceChunk < n ? i0 + kRebalanceChunk : n;
-  uint32_t prefix = 0;
-  if (PASS > 0) {
-    if (state[seq * 8 + 5] == 0) return;   // kg == 0: nothing to select
-    prefix = (uint32_t)state[seq * 8 + 0];
-  }
-  for (int b = threadIdx.x; b < kRadixBins * kScanCopies; b += 256) h[b] = 0;
-  if (threadIdx.x == 0) n_above = 0;
-  __syncthreads();
-  const uint32_t* __restrict__ row =
-      reinterpret_cast<const uint32_t*>(scores_all + ((int64_t)layer * Hkv + head) * total_tokens + begin);
-  constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
-  constexpr int ushift = PASS == 0 ? 0 : (PASS == 1 ? 21 : 10);
-  constexpr uint32_t dmask = PASS == 2 ? 1023u : (uint32_t)(kRadixBins - 1);   // the last digit has 10 bits only
-  int mine = 0;   // elements of this thread that the digits found so far place above T
-  for (int i = i0 + threadIdx.x; i < i1; i += 256) {
-    const uint32_t u = row[i];
-    const bool match = PASS == 0 ? true : ((u >> ushift) == (prefix >> ushift));
-    if (match) atomicAdd(&h[((u >> shift) & dmask) * kScanCopies + (threadIdx.x & (kScanCopies - 1))], 1);
-    if (PASS > 0) {
-      // the digit chosen by the previous pass sits just above this pass's digit: equal higher bits, larger digit
-      constexpr int pshift = PASS == 1 ? 21 : 10;
-      const bool higher_equal = PASS == 1 ? true : ((u >> 21) == (prefix >> 21));
-      if (higher_equal && (u >> pshift) > (prefix >> pshift)) ++mine;
+__global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restrict__ always, size_t always_words,
+                                                              uint32_t* __restrict__ tot0, size_t tot0_words,
+                                                              const int32_t* __restrict__ header,
+                                                              const float* scores_all, int layers_done, int interval,
+                                                              int n_seqs, int total_tokens) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < always_words; i += stride) always[i] = 0u;
+  if (layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens) == 0)
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < tot0_words; i += stride) tot0[i] = 0u;
+}
+
+// A workgroup's chunk of one (layer, head, sequence) score row as 16-byte vectors: element e of the score tensor
+// is covered by vector e / 4, thread t takes vectors t, t + 256, ... counted from the first one that touches the
+// chunk. ok[j] has bit q set when lane q of vector j lies inside the chunk [e_lo, e_hi): 0xf for all but the
+// vectors on the chunk's two edges, which the consumers treat element by element.
+template <int NV>
+struct ChunkVectors {
+  uint4 v[NV];
+  uint32_t ok[NV];
+};
+
+// n_elems: elements of the whole score tensor; its last, partial vector (if any) is read element by element.
+template <int NV>
+__device__ inline void load_chunk(const float* __restrict__ scores_all, int64_t n_elems, int64_t e_lo, int64_t e_hi,
+                                  ChunkVectors<NV>& cv) {
+  const uint32_t* __restrict__ base = reinterpret_cast<const uint32_t*>(scores_all);
+  const int64_t a_lo = e_lo & ~int64_t(3);
+  const uint32_t* __restrict__ row = base + a_lo;
+  const int lo_rel = (int)(e_lo - a_lo), hi_rel = (int)(e_hi - a_lo);      // chunk = [lo_rel, hi_rel) from a_lo
+  const int64_t whole = (n_elems & ~int64_t(3)) - a_lo;                    // vectors below this are whole
+  const int whole_rel = whole > (int64_t)0x7fffffff ? 0x7fffffff : (int)whole;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) cv.v[j] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int rel = 4 * (threadIdx.x + 256 * j);
+    int first = lo_rel - rel, last = hi_rel - rel;                         // valid lanes [first, last) of 0..4
+    first = first < 0 ? 0 : (first > 4 ? 4 : first);
+    last = last < 0 ? 0 : (last > 4 ? 4 : last);
+    const uint32_t ok = last > first ? ((1u << last) - 1u) & ~((1u << first) - 1u) : 0u;
+    cv.ok[j] = ok;
+    if (ok) {
+      if (rel + 4 <= whole_rel) {
+        cv.v[j] = *reinterpret_cast<const uint4*>(row + rel);
+      } else {                                                             // the tensor's last, partial vector
+        uint32_t e[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (ok >> q & 1) e[q] = row[rel + q];
+        cv.v[j] = make_uint4(e[0], e[1], e[2], e[3]);
+      }
     }
   }
-  if (PASS > 0) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
-  }
-  __syncthreads();
-  if (PASS > 0 && threadIdx.x == 0 && n_above) atomicAdd(&above[seq * L + layer], n_above);
-  int32_t* __restrict__ g = hist + (((int64_t)PASS * n_seqs + seq) * L + layer) * kRadixBins;
-  for (int b = threadIdx.x; b < kRadixBins; b += 256) {
-    int v = 0;
-#pragma unroll
-    for (int c2 = 0; c2 < kScanCopies; ++c2) v += h[b * kScanCopies + c2];
-    if (v) atomicAdd(&g[b], v);
-  }
 }
+
+__device__ inline uint32_t lane_of(const uint4& v, int q) { return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w)); }
 
 __device__ inline int wave_inclusive_scan_i(int v) {
   const int lane = threadIdx.x & 63;
@@ -86,163 +105,322 @@ __device__ inline int wave_inclusive_scan_i(int v) {
   return v;
 }
 
-// Single workgroup per sequence: sums the per-layer histograms of `pass`, finds the digit that holds the
-// remaining rank and records it in state[] (for later kernels) and in sh[] (for this workgroup):
-// sh[0] digit, sh[1] remaining rank after this pass, sh[2] kg. Shared by the decide and the final kernel.
-__device__ inline void decide_digit(int pass, int seq, int n_seqs, int L, int layers_done, int w, int Hkv,
-                                    int mean_budget, const int32_t* __restrict__ cu,
-                                    const int32_t* __restrict__ hist, int32_t* __restrict__ state, int* scratch,
-                                    int* sh) {
-  static_assert(kRadixBins == 2 * kDecThreads, "two bins per thread");
+// A thread's share of a histogram of NB bins for a workgroup of NT threads: thread t owns the NB / NT bins just
+// below those of thread t - 1 (thread 0 the top ones).
+template <int NT, int NB>
+struct Bins {
+  int c[NB / NT];
+};
+
+template <int NT, int NB>
+__device__ inline Bins<NT, NB> load_bins(const int32_t* __restrict__ tot) {
+  constexpr int PER = NB / NT;
+  Bins<NT, NB> b;
+  const int base = NB - PER * ((int)threadIdx.x + 1);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) b.c[i] = tot[base + i];
+  return b;
+}
+
+// The digit that holds the rem-th largest element of the histogram, and the rank that remains inside it (both 0
+// when rem <= 0). scratch: NT / 64 ints, sh: 2 ints (LDS). Starts and ends with a barrier.
+template <int NT, int NB>
+__device__ inline void pick_digit(const Bins<NT, NB>& bins, int rem, int* scratch, int* sh, int& digit, int& rem_out) {
+  constexpr int PER = NB / NT;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  int rem, kg;
-  uint32_t prefix = 0;
-  if (pass == 0) {
-    const int len = cu[seq + 1] - cu[seq];
-    const long long n = len > w ? len - w : 0;
-    const long long want = (long long)mean_budget * Hkv * layers_done;
-    const long long have = n * Hkv * layers_done;
-    kg = (int)(want < have ? want : have);
-    rem = kg;
-  } else {   // written by the previous kernel of this call
-    prefix = (uint32_t)state[seq * 8 + 0];
-    rem = state[seq * 8 + 1];
-    kg = state[seq * 8 + 5];
+  const int base = NB - PER * (tid + 1);
+  int sum = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) sum += bins.c[i];
+  const int incl = wave_inclusive_scan_i(sum);
+  if (lane == 63) scratch[wv] = incl;
+  if (tid == 0) { sh[0] = 0; sh[1] = 0; }
+  __syncthreads();
+  int above = incl - sum;
+  for (int i = 0; i < wv; ++i) above += scratch[i];
+  if (rem > 0 && above < rem && rem <= above + sum) {      // exactly one thread owns the bin
+    int a = above;
+#pragma unroll
+    for (int i = PER - 1; i >= 0; --i) {
+      if (rem > a && rem <= a + bins.c[i]) { sh[0] = base + i; sh[1] = rem - a; }
+      a += bins.c[i];
+    }
   }
-  const int hi = kRadixBins - 1 - 2 * tid, lo = hi - 1;
-  int c_hi = 0, c_lo = 0;
-  const int32_t* __restrict__ g = hist + ((int64_t)pass * n_seqs + seq) * L * kRadixBins;
-#pragma unroll 8
-  for (int i = 0; i < layers_done; ++i) {   // bins lo, hi are adjacent: one 8-byte load per layer
-    const int2 v = *reinterpret_cast<const int2*>(g + (int64_t)i * kRadixBins + lo);
-    c_lo += v.x;
-    c_hi += v.y;
+  __syncthreads();
+  digit = sh[0];
+  rem_out = sh[1];
+  __syncthreads();                                          // scratch and sh may be reused
+}
+
+__device__ inline int global_k(const int32_t* __restrict__ cu, int seq, int w, int Hkv, int mean_budget,
+                               int layers_done) {
+  const int len = cu[seq + 1] - cu[seq];
+  const long long n = len > w ? len - w : 0;
+  const long long want = (long long)mean_budget * Hkv * layers_done;
+  const long long have = n * Hkv * layers_done;
+  return (int)(want < have ? want : have);                  // kg of Eq. 4, clamped to the population
+}
+
+// Top-digit histogram of the layers not yet counted. grid = (chunk upper bound, Hkv, layers_done), 256 threads.
+__global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
+                                                              int layers_done, int interval,
+                                                              const float* __restrict__ scores_all,
+                                                              const int32_t* __restrict__ cu,
+                                                              const int32_t* __restrict__ header,
+                                                              int32_t* __restrict__ tot0) {
+  __shared__ int h[kRadixBins * kHist0Copies];
+  const int head = blockIdx.y, layer = blockIdx.z;
+  if (layer < layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens)) return;
+  int seq, c, begin, len;
+  if (!find_chunk(cu, n_seqs, kHist0Chunk, w, blockIdx.x, seq, c, begin, len)) return;
+  const int n = len - w;
+  const int i0 = c * kHist0Chunk;
+  const int i1 = i0 + kHist0Chunk < n ? i0 + kHist0Chunk : n;
+  constexpr int NV = kHist0Chunk / 4 / 256 + 1;
+  ChunkVectors<NV> cv;
+  const int64_t e_lo = ((int64_t)layer * Hkv + head) * total_tokens + begin + i0;
+  load_chunk<NV>(scores_all, (int64_t)L * Hkv * total_tokens, e_lo, e_lo + (i1 - i0), cv);
+  for (int b = threadIdx.x; b < kRadixBins * kHist0Copies; b += 256) h[b] = 0;
+  __syncthreads();
+  int* __restrict__ hc = h + (threadIdx.x & (kHist0Copies - 1));
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    if (cv.ok[j] == 0xf) {
+      atomicAdd(&hc[(cv.v[j].x >> 21) * kHist0Copies], 1);
+      atomicAdd(&hc[(cv.v[j].y >> 21) * kHist0Copies], 1);
+      atomicAdd(&hc[(cv.v[j].z >> 21) * kHist0Copies], 1);
+      atomicAdd(&hc[(cv.v[j].w >> 21) * kHist0Copies], 1);
+    } else if (cv.ok[j]) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (cv.ok[j] >> q & 1) atomicAdd(&hc[(lane_of(cv.v[j], q) >> 21) * kHist0Copies], 1);
+    }
   }
-  const int v = c_hi + c_lo;
+  __syncthreads();
+  int32_t* __restrict__ g = tot0 + (int64_t)seq * kRadixBins;
+  for (int b = threadIdx.x; b < kRadixBins; b += 256) {
+    int v = 0;
+#pragma unroll
+    for (int c2 = 0; c2 < kHist0Copies; ++c2) v += h[b * kHist0Copies + c2];
+    if (v) atomicAdd(&g[b], v);
+  }
+}
+
+// Scans 1 and 2. grid = (chunk upper bound, Hkv, layers_done), 256 threads.
+//   PASS 1: histogram of the middle digit over elements with digit 0 == d0 -> tot1; above[layer] += #{digit 0 > d0}
+//   PASS 2: histogram of the last digit over elements with digits (0, 1) == (d0, d1) -> tot2 and hist2[layer];
+//           above[layer] += #{digit 0 == d0, digit 1 > d1}
+template <int PASS>
+__global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
+                                                             int mean_budget, int layers_done,
+                                                             const float* __restrict__ scores_all,
+                                                             const int32_t* __restrict__ cu,
+                                                             const int32_t* __restrict__ tot0,
+                                                             int32_t* __restrict__ tot1, int32_t* __restrict__ tot2,
+                                                             int32_t* __restrict__ hist2, int32_t* __restrict__ above) {
+  constexpr int BINS = PASS == 1 ? kRadixBins : kLowBins;
+  __shared__ int h[BINS];
+  __shared__ int scratch[4];
+  __shared__ int sh[2];
+  __shared__ int n_above;
+  int seq, c, begin, len;
+  if (!find_chunk(cu, n_seqs, kScanChunk, w, blockIdx.x, seq, c, begin, len)) return;
+  const int head = blockIdx.y, layer = blockIdx.z;
+  const int n = len - w;
+  const int i0 = c * kScanChunk;
+  const int i1 = i0 + kScanChunk < n ? i0 + kScanChunk : n;
+  constexpr int NV = kScanChunk / 4 / 256 + 1;
+  ChunkVectors<NV> cv;
+  const int64_t e_lo = ((int64_t)layer * Hkv + head) * total_tokens + begin + i0;
+  // everything this workgroup reads from memory is requested here, before the first wait
+  const Bins<256, kRadixBins> bins0 = load_bins<256, kRadixBins>(tot0 + (int64_t)seq * kRadixBins);
+  Bins<256, kRadixBins> bins1;
+  if (PASS == 2) bins1 = load_bins<256, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
+  load_chunk<NV>(scores_all, (int64_t)L * Hkv * total_tokens, e_lo, e_lo + (i1 - i0), cv);
+  for (int b = threadIdx.x; b < BINS; b += 256) h[b] = 0;
+  if (threadIdx.x == 0) n_above = 0;
+  int rem = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
+  int d0, d1 = 0;
+  pick_digit<256, kRadixBins>(bins0, rem, scratch, sh, d0, rem);
+  if (PASS == 2) pick_digit<256, kRadixBins>(bins1, rem, scratch, sh, d1, rem);
+  // (pick_digit ends with a barrier: h and n_above are cleared for everyone)
+  // PASS 1 looks at the top digit p = u >> 21, PASS 2 at the top two p = u >> 10; an element is "above" when
+  // p lies in (key, end): PASS 1 any larger top digit, PASS 2 a larger middle digit under the same top digit.
+  constexpr int SH = PASS == 1 ? 21 : 10;
+  const uint32_t key = PASS == 1 ? (uint32_t)d0 : (((uint32_t)d0 << 11) | (uint32_t)d1);
+  const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((uint32_t)d0 + 1u) << 11);
+  const uint32_t span = end - key - 1u;   // p in (key, end)  <=>  p - key - 1 < span (unsigned)
+  auto bin_of = [](uint32_t u) { return PASS == 1 ? ((u >> 10) & (uint32_t)(kRadixBins - 1)) : (u & (uint32_t)(kLowBins - 1)); };
+  int mine = 0;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    if (cv.ok[j] == 0xf) {
+      const uint32_t p0 = cv.v[j].x >> SH, p1 = cv.v[j].y >> SH, p2 = cv.v[j].z >> SH, p3 = cv.v[j].w >> SH;
+      mine += (p0 - key - 1u < span) + (p1 - key - 1u < span) + (p2 - key - 1u < span) + (p3 - key - 1u < span);
+      if (p0 == key || p1 == key || p2 == key || p3 == key) {       // rare: a few elements in a thousand
+        if (p0 == key) atomicAdd(&h[bin_of(cv.v[j].x)], 1);
+        if (p1 == key) atomicAdd(&h[bin_of(cv.v[j].y)], 1);
+        if (p2 == key) atomicAdd(&h[bin_of(cv.v[j].z)], 1);
+        if (p3 == key) atomicAdd(&h[bin_of(cv.v[j].w)], 1);
+      }
+    } else if (cv.ok[j]) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (!(cv.ok[j] >> q & 1)) continue;
+        const uint32_t u = lane_of(cv.v[j], q), pq = u >> SH;
+        mine += pq - key - 1u < span;
+        if (pq == key) atomicAdd(&h[bin_of(u)], 1);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
+  __syncthreads();
+  if (threadIdx.x == 0 && n_above) atomicAdd(&above[seq * L + layer], n_above);
+  for (int b = threadIdx.x; b < BINS; b += 256) {
+    const int v = h[b];
+    if (!v) continue;
+    if (PASS == 1) {
+      atomicAdd(&tot1[(int64_t)seq * kRadixBins + b], v);
+    } else {
+      atomicAdd(&tot2[(int64_t)seq * kLowBins + b], v);
+      atomicAdd(&hist2[((int64_t)seq * L + layer) * kLowBins + b], v);
+    }
+  }
+}
+
+// Exclusive prefix sum and total of one int per thread over the kFinalThreads threads.
+__device__ inline int block_exclusive_scan_final(int v, int* scratch, int& total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int incl = wave_inclusive_scan_i(v);
   if (lane == 63) scratch[wv] = incl;
-  if (tid == 0) { sh[0] = 0; sh[1] = 0; sh[2] = kg; }
   __syncthreads();
-  int above = incl - v;
-  for (int i = 0; i < wv; ++i) above += scratch[i];
-  if (rem > 0) {   // exactly one thread owns the bin that holds the rem-th largest element
-    if (above < rem && rem <= above + c_hi) { sh[0] = hi; sh[1] = rem - above; }
-    else if (above + c_hi < rem && rem <= above + v) { sh[0] = lo; sh[1] = rem - above - c_hi; }
+  int base = 0, all = 0;
+  for (int i = 0; i < kFinalThreads / 64; ++i) {
+    const int s = scratch[i];
+    if (i < wv) base += s;
+    all += s;
   }
   __syncthreads();
-  if (tid == 0) {
-    state[seq * 8 + 0] = (int32_t)(prefix | ((uint32_t)sh[0] << digit_shift(pass)));
-    state[seq * 8 + 1] = sh[1];
-    state[seq * 8 + 2 + pass] = sh[0];
-    state[seq * 8 + 5] = kg;
-  }
+  total = all;
+  return base + incl - v;
 }
 
-__global__ __launch_bounds__(kDecThreads) void rebalance_decide_kernel(int pass, int n_seqs, int L, int layers_done,
-                                                                       int w, int Hkv, int mean_budget,
-                                                                       const int32_t* __restrict__ cu,
-                                                                       const int32_t* __restrict__ hist,
-                                                                       int32_t* __restrict__ state) {
-  __shared__ int scratch[kDecWaves];
-  __shared__ int sh[3];
-  decide_digit(pass, blockIdx.x, n_seqs, L, layers_done, w, Hkv, mean_budget, cu, hist, state, scratch, sh);
-}
-
-// Last pass decision, per-layer hit counts and the budget arithmetic of Eq. 5-6, one workgroup per sequence.
-__global__ __launch_bounds__(kDecThreads) void rebalance_final_kernel(int n_seqs, int L, int layers_done, int w, int Hkv,
-                                                                      int mean_budget, int layer_max,
-                                                                      const int32_t* __restrict__ cu,
-                                                                      const int32_t* __restrict__ hist,
-                                                                      int32_t* __restrict__ state,
-                                                                      const int32_t* __restrict__ above,
-                                                                      int32_t* __restrict__ counts,
-                                                                      int32_t* __restrict__ budgets_out,
-                                                                      int32_t* __restrict__ hits_out) {
-  __shared__ int scratch[kDecWaves];
-  __shared__ int sh[3];
+// Last digit, per-layer hit counts and the budget arithmetic of Eq. 5-6, one workgroup per sequence.
+__global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
+    int n_seqs, int L, int layers_done, int interval, int w, int Hkv, int mean_budget, int layer_max, int total_tokens,
+    const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ tot0,
+    const int32_t* __restrict__ tot1, const int32_t* __restrict__ tot2, const int32_t* __restrict__ hist2,
+    const int32_t* __restrict__ above, int32_t* __restrict__ header, int32_t* __restrict__ counts,
+    int32_t* __restrict__ budgets_out, int32_t* __restrict__ hits_out) {
+  static_assert(DKV_MAX_LAYERS <= kFinalThreads, "one layer per thread");
+  __shared__ int scratch[kFinalThreads / 64];
+  __shared__ int sh[2];
   __shared__ int gt[DKV_MAX_LAYERS];
   __shared__ int eq[DKV_MAX_LAYERS];
+  __shared__ int wave_max[kFinalThreads / 64];
   const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  // digits of passes 0 and 1 were recorded by earlier kernels of this call
-  const int digit0 = state[seq * 8 + 2], digit1 = state[seq * 8 + 3];
-  decide_digit(2, seq, n_seqs, L, layers_done, w, Hkv, mean_budget, cu, hist, state, scratch, sh);
-  const int digit[3] = {digit0, digit1, sh[0]};
-  (void)digit0; (void)digit1;
-  const int need_eq = sh[1];   // elements equal to T that belong to the top-kg
-  const int kg = sh[2];
-  // per layer: elements above T = those counted by the scan kernels of passes 1 and 2 (higher digits larger)
-  // + the last-digit bins above the chosen one; equal to T = the chosen last-digit bin
-  for (int i = wv; i < layers_done; i += kDecWaves) {
-    int acc = 0;
-    const int32_t* __restrict__ g = hist + (((int64_t)2 * n_seqs + seq) * L + i) * kRadixBins;
-    for (int b = digit[2] + 1 + lane; b < 1024; b += 64) acc += g[b];     // the last digit has 10 bits
+  const int kg = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
+  // all histogram reads are requested together, before the first wait
+  const auto bins0 = load_bins<kFinalThreads, kRadixBins>(tot0 + (int64_t)seq * kRadixBins);
+  const auto bins1 = load_bins<kFinalThreads, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
+  const auto bins2 = load_bins<kFinalThreads, kLowBins>(tot2 + (int64_t)seq * kLowBins);
+  constexpr int kWaves = kFinalThreads / 64, kPerLane = kLowBins / 64;
+  // the first layer of this wavefront: lane l holds last-digit bins l, l + 64, ... (later layers are read in the loop)
+  int first[kPerLane];
+  {
+    const int32_t* __restrict__ g = hist2 + ((int64_t)seq * L + (wv < layers_done ? wv : 0)) * kLowBins;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) {
-      gt[i] = acc + above[seq * L + i];
-      eq[i] = g[digit[2]];
+    for (int r = 0; r < kPerLane; ++r) first[r] = g[lane + 64 * r];
+  }
+  const int above_mine = tid < layers_done ? above[seq * L + tid] : 0;
+  const int cur = tid < layers_done ? counts[seq * L + tid] : 0;
+  int rem = kg, d0, d1, d2;
+  pick_digit<kFinalThreads, kRadixBins>(bins0, rem, scratch, sh, d0, rem);
+  pick_digit<kFinalThreads, kRadixBins>(bins1, rem, scratch, sh, d1, rem);
+  pick_digit<kFinalThreads, kLowBins>(bins2, rem, scratch, sh, d2, rem);
+  const int need_eq = rem;   // elements equal to T that belong to the top-kg
+  (void)d0; (void)d1;
+  // per layer: elements above T = those counted by the scans (a higher digit is larger) + the last-digit bins
+  // above the chosen one; equal to T = the chosen last-digit bin
+  for (int i = wv; i < layers_done; i += kWaves) {
+    int acc = 0, at = 0;
+    const int32_t* __restrict__ g = hist2 + ((int64_t)seq * L + i) * kLowBins;
+#pragma unroll
+    for (int r = 0; r < kPerLane; ++r) {
+      const int b = lane + 64 * r;
+      const int v = i == wv ? first[r] : g[b];
+      acc += b > d2 ? v : 0;
+      at += b == d2 ? v : 0;
     }
-  }
-  __shared__ int cur[DKV_MAX_LAYERS];
-  for (int i = tid; i < layers_done; i += kDecThreads) cur[i] = counts[seq * L + i];
-  __syncthreads();
-  __shared__ long long red[2];   // max cnt, sum Z
-  if (tid == 0) {   // Phi: ties go to the lower flat index, i.e. earlier layers first (a serial prefix over L ints)
-    long long cmax = 0;
-    int left = need_eq;
-    for (int i = 0; i < layers_done; ++i) {
-      int take = 0;
-      if (kg > 0) { take = eq[i] < left ? eq[i] : left; left -= take; }
-      const int c = kg > 0 ? gt[i] + take : 0;
-      gt[i] = c;
-      cmax = c > cmax ? c : cmax;
-    }
-    red[0] = cmax;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { acc += __shfl_xor(acc, o); at += __shfl_xor(at, o); }
+    if (lane == 0) { gt[i] = acc; eq[i] = at; }
   }
   __syncthreads();
-  const long long cmax = red[0];
-  for (int i = tid; i < layers_done; i += kDecThreads)
-    eq[i] = cmax > 0 ? (int)(((long long)layer_max * gt[i]) / cmax) : 0;          // Eq. 5, exact floor
+  // Phi: ties go to the lower flat index, i.e. earlier layers first: layer i takes what the earlier layers left
+  const bool live = tid < layers_done;
+  const int my_eq = live ? eq[tid] : 0;
+  int eq_total;
+  const int eq_before = block_exclusive_scan_final(my_eq, scratch, eq_total);
+  int left = need_eq - eq_before;
+  left = left > 0 ? left : 0;
+  const int cnt = live && kg > 0 ? gt[tid] + above_mine + (my_eq < left ? my_eq : left) : 0;
+  int m = cnt;   // max over layers
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { const int t = __shfl_xor(m, o); m = t > m ? t : m; }
+  if (lane == 0) wave_max[wv] = m;
   __syncthreads();
-  if (tid == 0) {
-    long long zsum = 0;
-    for (int i = 0; i < layers_done; ++i) zsum += eq[i];
-    red[1] = zsum;
-  }
-  __syncthreads();
-  const long long zsum = red[1];
-  const long long B = (long long)mean_budget * L;                                 // Eq. 6: B = (wt - ws) * L
-  for (int i = tid; i < layers_done; i += kDecThreads) {
-    const long long zp = zsum > 0 ? ((long long)eq[i] * B) / zsum : 0;            // exact floor
+  int cmax = 0;
+  for (int i = 0; i < kFinalThreads / 64; ++i) cmax = wave_max[i] > cmax ? wave_max[i] : cmax;
+  const int z = cmax > 0 ? (int)(((long long)layer_max * cnt) / cmax) : 0;          // Eq. 5, exact floor
+  int zsum_i;
+  (void)block_exclusive_scan_final(z, scratch, zsum_i);                               // <= layer_max * layers: fits
+  const long long zsum = zsum_i;
+  const long long B = (long long)mean_budget * L;                                     // Eq. 6: B = (wt - ws) * L
+  if (live) {
+    const long long zp = zsum > 0 ? ((long long)z * B) / zsum : 0;                    // exact floor
     const int zpi = zp > 0x7fffffffLL ? 0x7fffffff : (int)zp;
-    if (budgets_out) budgets_out[seq * L + i] = zpi;
-    if (hits_out) hits_out[seq * L + i] = gt[i];
-    counts[seq * L + i] = cur[i] < zpi ? cur[i] : zpi;                            // truncation never grows a layer
+    if (budgets_out) budgets_out[seq * L + tid] = zpi;
+    if (hits_out) hits_out[seq * L + tid] = cnt;
+    counts[seq * L + tid] = cur < zpi ? cur : zpi;                                    // truncation never grows a layer
+  }
+  if (seq == 0 && tid == 0) {   // this call's layers are in the top-digit histogram now
+    const uint64_t ptr = reinterpret_cast<uint64_t>(scores_all);
+    header[0] = (int32_t)kHeaderMagic; header[1] = layers_done;
+    header[2] = (int32_t)(uint32_t)ptr; header[3] = (int32_t)(uint32_t)(ptr >> 32);
+    header[4] = interval; header[5] = n_seqs; header[6] = total_tokens;
   }
 }
 
 hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
                             int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
                             const WorkspaceLayout& wl, hipStream_t st) {
-  int32_t* hist = reinterpret_cast<int32_t*>(ws + wl.hist);
-  int32_t* state = reinterpret_cast<int32_t*>(ws + wl.state);
+  int32_t* header = reinterpret_cast<int32_t*>(ws + wl.header);
+  int32_t* tot0 = reinterpret_cast<int32_t*>(ws + wl.tot0);
+  int32_t* tot1 = reinterpret_cast<int32_t*>(ws + wl.tot1);
+  int32_t* tot2 = reinterpret_cast<int32_t*>(ws + wl.tot2);
+  int32_t* hist2 = reinterpret_cast<int32_t*>(ws + wl.hist2);
   int32_t* above = reinterpret_cast<int32_t*>(ws + wl.above);
-  hipError_t e = launch_fill_zero(ws + wl.hist, wl.total - wl.hist, st);
-  if (e != hipSuccess) return e;
-  const int chunks = p.total_tokens / kRebalanceChunk + p.n_seqs;
-  const dim3 grid(chunks, p.Hkv, layers_done);
-  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<0>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state, above);
-  launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 0, p.n_seqs, p.L, layers_done,
-                     p.w, p.Hkv, p.mean_budget, cu, hist, state);
-  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state, above);
-  launch(DKV_KERNEL_REBALANCE_DECIDE, rebalance_decide_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, 1, p.n_seqs, p.L, layers_done,
-                     p.w, p.Hkv, p.mean_budget, cu, hist, state);
-  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L, p.total_tokens,
-                     scores_all, cu, hist, state, above);
-  launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs), dim3(kDecThreads), 0, st, p.n_seqs, p.L, layers_done, p.w,
-                     p.Hkv, p.mean_budget, p.layer_max, cu, hist, state, above, counts, budgets_out, hits_out);
+  // tot1 .. above are contiguous: cleared on every call; tot0 only when the history does not match
+  const size_t always_words = (wl.total - wl.tot1) / 4, tot0_words = (wl.tot1 - wl.tot0) / 4;
+  size_t blocks = (always_words + 255) / 256;
+  blocks = blocks > 1024 ? 1024 : blocks;
+  launch(DKV_KERNEL_FILL, rebalance_clear_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+         reinterpret_cast<uint32_t*>(tot1), always_words, reinterpret_cast<uint32_t*>(tot0), tot0_words, header,
+         scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens);
+  const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, layers_done);
+  launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist0_kernel, grid0, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+         p.total_tokens, layers_done, p.interval, scores_all, cu, header, tot0);
+  const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, layers_done);
+  launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+         p.total_tokens, p.mean_budget, layers_done, scores_all, cu, tot0, tot1, tot2, hist2, above);
+  launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+         p.total_tokens, p.mean_budget, layers_done, scores_all, cu, tot0, tot1, tot2, hist2, above);
+  launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs), dim3(kFinalThreads), 0, st, p.n_seqs, p.L,
+         layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu, tot0, tot1,
+         tot2, hist2, above, header, counts, budgets_out, hits_out);
   return hipGetLastError();
 }
 

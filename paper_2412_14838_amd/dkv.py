@@ -121,7 +121,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
     return int(load().dkv_workspace_bytes(C.byref(desc)))
 
 
-KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_decide",
+KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
                 "rebalance_final", "fill", "select_order")
 
 

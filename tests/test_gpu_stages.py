@@ -320,3 +320,37 @@ def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
         pre = cfg.seqlens[s] - cfg.w
         ref = O.select_topk(A[2][:, cu[s]:cu[s] + pre], cfg.layer_max)
         assert np.array_equal(many.idx[2, s][:, :ref.shape[1]].cpu().numpy(), ref)
+
+
+def test_rebalance_history_is_only_used_when_it_matches(dkv):
+    """The update keeps a histogram of the layers it has scanned for the next call of the same prefill. Calls in
+    order (2, 4, 6) extend it; a repeated, an out-of-order or a restarted call (new scores in the same tensor,
+    layers_done == interval) must recount and still match the oracle."""
+    cfg = small_cfg("hist", L=6, interval=2, Hq=2, Hkv=2, seqlens=(1200, 640), layer_max=128, mean_budget=48)
+    cu = cfg.cu_seqlens
+    rng = np.random.default_rng(21)
+
+    def reference(A, l, s):
+        pre = cfg.seqlens[s] - cfg.w
+        cnt, Z, Zp = O.update_buffer_length([A[i][:, cu[s]:cu[s] + pre] for i in range(l)], cfg.layer_max,
+                                            cfg.mean_budget, cfg.L)
+        return cnt
+
+    def check(comp, A, l):
+        comp.rebalance(l)
+        torch.cuda.synchronize()
+        hits = comp.hits.cpu().numpy()
+        for s in range(cfg.n_seqs):
+            assert np.array_equal(hits[s, :l], reference(A, l, s)), (l, s)
+
+    comp = Compressor(cfg, keep_cache=False)
+    A = np.abs(rng.standard_normal((cfg.L, cfg.Hkv, cfg.total_tokens))).astype(np.float32)
+    comp.scores.copy_(torch.from_numpy(A))
+    for l in range(cfg.L):
+        comp.select(l)
+    for l in (2, 4, 6, 6, 4, 2, 6):          # in order, repeated, backwards, skipping
+        check(comp, A, l)
+    A2 = (A * np.float32(0.37) + np.float32(0.01)).astype(np.float32)[::-1].copy()
+    comp.scores.copy_(torch.from_numpy(A2))  # a new prefill in the same tensors
+    for l in (2, 4, 6):
+        check(comp, A2, l)
