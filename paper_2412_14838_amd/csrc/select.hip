@@ -8,7 +8,7 @@
 //   3. the k winners are written as 64-bit keys (~score bits, position), unordered, to the workspace.
 // A second kernel orders them by (score descending, position ascending) = ascending key, by counting: the rank
 // of a key is the number of smaller keys (keys are unique). That is k^2 comparisons, but they spread over the
-// whole GPU (k/64 workgroups per row) instead of a sorting network on the one CU that holds the row.
+// whole GPU (k/256 workgroups per row) instead of a sorting network on the one CU that holds the row.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -214,17 +214,18 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   for (int j = tid; j < k; j += kSelThreads) dst[j] = keys[j];
 }
 
-// Orders the winners of one (layer, sequence, KV head) by counting. grid = (ceil(layer_max / 64), Hkv, n_seqs * layers),
-// 256 threads:
-// lane l of every wavefront owns candidate blockIdx.x * 64 + l, wavefront g counts the smaller keys among
-// candidates [g * k/4, (g+1) * k/4) (all lanes read the same LDS word: a broadcast); the four partial counts add
-// up to the rank, which is the candidate's place in idx_out.
+// Orders the winners of one (layer, sequence, KV head) by counting. grid = (ceil(layer_max / 256), Hkv, n_seqs * layers),
+// 256 threads: the workgroup owns candidates [blockIdx.x * 256, + 256); lane l of every wavefront holds the four
+// candidates l, l + 64, l + 128, l + 192 of them in registers, and wavefront g counts, for each of the four, the
+// smaller keys among a quarter of all k keys. One LDS read of a key (the same word for all lanes: a broadcast)
+// thus serves 256 comparisons; the four partial counts add up to the rank = the candidate's place in idx_out.
+constexpr int kOrderCand = 256;
 __global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int layer_max, int n_seqs,
                                                            const int32_t* __restrict__ cu,
                                                            const u64* __restrict__ keys_in0,
                                                            int32_t* __restrict__ idx_out0, int64_t idx_stride_layer) {
-  __shared__ u64 keys[DKV_MAX_LAYER_MAX];
-  __shared__ int partial[4][64];
+  __shared__ __attribute__((aligned(16))) u64 keys[DKV_MAX_LAYER_MAX + 32];
+  __shared__ int partial[4][kOrderCand];
   const int seq = blockIdx.z % n_seqs, lz = blockIdx.z / n_seqs;
   const int head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
   const u64* __restrict__ keys_in = keys_in0 + (int64_t)lz * n_seqs * Hkv * DKV_MAX_LAYER_MAX;
@@ -233,29 +234,42 @@ __global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int l
   const int n = S > w ? S - w : 0;
   const int k = layer_max < n ? layer_max : n;
   int32_t* __restrict__ out = idx_out + ((int64_t)seq * Hkv + head) * layer_max;
-  const int e0 = blockIdx.x * 64;
+  const int e0 = blockIdx.x * kOrderCand;
   // slots past k hold -1 (each workgroup clears the ones in its own range)
-  if (tid < 64 && e0 + tid >= k && e0 + tid < layer_max) out[e0 + tid] = -1;
+  if (e0 + tid >= k && e0 + tid < layer_max) out[e0 + tid] = -1;
   if (e0 >= k) return;
   const u64* __restrict__ src = keys_in + ((int64_t)seq * Hkv + head) * DKV_MAX_LAYER_MAX;
-  for (int j = tid; j < k; j += 256) keys[j] = src[j];
+  // every wavefront scans `quarter` keys (a multiple of 8); the pad keys are the largest value: never "smaller"
+  const int quarter = ((k + 3) / 4 + 7) & ~7;
+  for (int j = tid; j < 4 * quarter; j += 256) keys[j] = j < k ? src[j] : ~0ull;
   __syncthreads();
-  const int e = e0 + lane;
-  const u64 mine = e < k ? keys[e] : ~0ull;
-  const int quarter = (k + 3) / 4;
-  const int j0 = g * quarter, j1 = (g + 1) * quarter < k ? (g + 1) * quarter : k;
-  int smaller = 0;
-  int j = j0;
-  for (; j + 8 <= j1; j += 8) {
+  u64 mine[4];
+  int smaller[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int u = 0; u < 8; ++u) smaller += keys[j + u] < mine ? 1 : 0;
+  for (int c = 0; c < 4; ++c) {
+    const int e = e0 + lane + 64 * c;
+    mine[c] = e < k ? keys[e] : ~0ull;
   }
-  for (; j < j1; ++j) smaller += keys[j] < mine ? 1 : 0;
-  partial[g][lane] = smaller;
+  const ulonglong2* __restrict__ kp = reinterpret_cast<const ulonglong2*>(keys + g * quarter);
+  for (int j = 0; j < quarter / 2; j += 4) {
+    ulonglong2 kk[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) kk[u] = kp[j + u];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        smaller[c] += kk[u].x < mine[c] ? 1 : 0;
+        smaller[c] += kk[u].y < mine[c] ? 1 : 0;
+      }
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) partial[g][lane + 64 * c] = smaller[c];
   __syncthreads();
-  if (g == 0 && e < k) {
-    const int rank = partial[0][lane] + partial[1][lane] + partial[2][lane] + partial[3][lane];
-    out[rank] = (int32_t)(uint32_t)mine;
+  const int e = e0 + tid;
+  if (e < k) {
+    const int rank = partial[0][tid] + partial[1][tid] + partial[2][tid] + partial[3][tid];
+    out[rank] = (int32_t)(uint32_t)keys[e];
   }
 }
 
@@ -274,7 +288,7 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
   launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st, p.Hkv, p.w,
          p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts,
          keys);
-  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + 63) / 64, p.Hkv, p.n_seqs * n_layers),
+  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + kOrderCand - 1) / kOrderCand, p.Hkv, p.n_seqs * n_layers),
          dim3(256), 0, st, p.Hkv, p.w, p.layer_max, p.n_seqs, cu, keys, idx_out, idx_stride_layer);
   return hipGetLastError();
 }
