@@ -281,6 +281,9 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 // Scores: a[s] = row_scale * sum_rows exp2(c * x[row, s] - lse2[row]) over the chunk's outputs plus the pooling
 // halo, max-pooled over the prefix. grid = (chunk upper bound over the S' prefix outputs, Hkv).
 // ------------------------------------------------------------------------------------------------------
+// Key tile that step `it` of the emit kernel works on (steps past the first tile repeat it: same values again).
+__device__ inline int emit_tile(int n_iter, int it) { return it < n_iter ? n_iter - 1 - it : 0; }
+
 template <int RS, int KS>
 __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int chunk, const uint16_t* __restrict__ q_win,
                                                                 const char* __restrict__ k, int64_t stride_token_b,
@@ -315,8 +318,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
       k + ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
   // All first loads are issued together (two key tiles, the Q block, the row statistics): one memory latency.
-  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
+  // Tiles are taken from the last to the first: the statistics kernel, which ran first to last over the same
+  // chunks on the same compute units, left its last tiles in the L2 of this compute die.
+  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
@@ -372,8 +377,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   // from `a`. Prefix keys are visible to every window row: no mask; columns past the computed range are
   // discarded below. Fixed summation order per column.
   auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
-    reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
-    const int wave_row0 = it * TL::kKeys + ks * 32;
+    reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, it + 2) * TL::kKeys, len - 1);
+    const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
     bf16x8 kf[8];
     read_k_frags(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, kf);
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
@@ -400,7 +405,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     step(it + 1, nxt, acc);
   }
   // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
-  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {   // steps past n_iter wrote beyond this range
+  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
     float a = part[i];
 #pragma unroll
     for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
