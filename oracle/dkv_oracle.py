@@ -101,6 +101,33 @@ def score_window(q_win: np.ndarray, k: np.ndarray, P: int, scale: Optional[float
     return max_pool_prefix(a, w, P)
 
 
+def row_lse(q_win: np.ndarray, k: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
+    """Natural-log normaliser of every window row: lse[g, i] = log sum_s exp(x[g, i, s]) over the visible keys.
+
+    This is the denominator of Eq. 1 in log form, the quantity a prefill attention kernel keeps per query row.
+    q_win [Hq, w, d], k [Hkv, S, d] -> [Hq, w] float64.
+    """
+    x = window_logits(q_win, k, scale)
+    m = x.max(axis=-1)
+    return m + np.log(np.exp(x - m[..., None]).sum(axis=-1))
+
+
+def score_window_from_lse(q_win: np.ndarray, k: np.ndarray, lse: np.ndarray, P: int,
+                          scale: Optional[float] = None, row_scale: float = 1.0) -> np.ndarray:
+    """Steps O1-O5 with the softmax of Eq. 1 taken from supplied row normalisers: p = exp(x - lse[row]).
+
+    With lse = row_lse(q_win, k) this is score_window; it lets the scoring run as ONE sweep over the keys when
+    the caller (the prefill attention) already holds the normalisers of its last w query rows.
+    lse [Hq, w] (natural log) -> A^l [Hkv, S'] float32.
+    """
+    Hq, w, _ = q_win.shape
+    Hkv = k.shape[0]
+    x = window_logits(q_win, k, scale)
+    p = np.exp(x - np.asarray(lse, dtype=np.float64)[..., None])
+    a = window_sum(p, Hkv, row_scale)
+    return max_pool_prefix(a, w, P)
+
+
 # --------------------------------------------------------------------------
 # Eq. 3 / Algorithm 1 "indices <- A^l.topk(B^l, dim=-1).indices"
 # --------------------------------------------------------------------------

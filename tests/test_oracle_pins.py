@@ -290,6 +290,48 @@ def test_scores_override_isolates_selection():
     assert r.n == r2.n and all(np.array_equal(a, b) for a, b in zip(r.idx, r2.idx))
 
 
+# ---------------------------------------------------------------- Eq. 1 with supplied row normalisers
+def test_row_lse_matches_library_logsumexp_and_closed_form():
+    """lse[g, i] = log of the denominator of Eq. 1 over the keys the row may see: torch.logsumexp on the masked
+    logits computed independently here, and the closed form log(S - w + i + 1) for zero queries."""
+    Hq, Hkv, w, d, S = 4, 2, 3, 8, 41
+    q, k = _rand((Hq, w, d), 31), _rand((Hkv, S, d), 32)
+    lse = O.row_lse(q, k)
+    G = Hq // Hkv
+    for g in range(Hq):
+        for i in range(w):
+            visible = S - w + i + 1
+            x = torch.tensor((q[g, i] @ k[g // G, :visible].T) / math.sqrt(d))
+            assert abs(lse[g, i] - torch.logsumexp(x, dim=0).item()) < 1e-12
+    zero = O.row_lse(np.zeros((Hq, w, d)), k)
+    assert np.allclose(zero, np.log(S - w + np.arange(w) + 1.0)[None, :], atol=1e-13)
+
+
+def test_scores_from_supplied_lse():
+    """With the true normalisers the single-sweep form equals the softmax form; shifting a row's lse by delta
+    scales that row's contribution by exp(-delta) (so a wrong sign or a missing row shows)."""
+    Hq, Hkv, w, d, S, P = 4, 2, 4, 16, 120, 5
+    q, k = _rand((Hq, w, d), 33), _rand((Hkv, S, d), 34)
+    lse = O.row_lse(q, k)
+    want = O.score_window(q, k, P)
+    got = O.score_window_from_lse(q, k, lse, P)
+    assert np.allclose(got, want, rtol=1e-6, atol=0)
+    # unpooled: a[h, s] = sum_rows exp(x - lse); shift all rows of KV head 0 by log 2, of head 1 by -log 3
+    shift = np.zeros((Hq, w))
+    shift[:2] = math.log(2.0)
+    shift[2:] = -math.log(3.0)
+    base = O.score_window_from_lse(q, k, lse, 1)
+    moved = O.score_window_from_lse(q, k, lse + shift, 1)
+    assert np.allclose(moved[0], base[0] / 2.0, rtol=1e-6) and np.allclose(moved[1], base[1] * 3.0, rtol=1e-6)
+    # brute force of one position
+    h, s = 1, 17
+    acc = 0.0
+    for g in (2, 3):
+        for i in range(w):
+            acc += math.exp(float(q[g, i] @ k[h, s]) / math.sqrt(d) - lse[g, i])
+    assert abs(base[h, s] - np.float32(acc)) <= 1e-6 * acc
+
+
 # ---------------------------------------------------------------- planted mistakes must be caught
 def test_pins_catch_planted_mistakes(monkeypatch):
     """Plant plausible mistakes in the oracle (on the CPU) and check that a pin fails."""
@@ -316,6 +358,17 @@ def test_pins_catch_planted_mistakes(monkeypatch):
     monkeypatch.setattr(O, "window_logits", lambda q, k, scale=None: -orig_logits(q, k, scale))
     assert fails(test_brute_force_scores_tiny)
     monkeypatch.setattr(O, "window_logits", orig_logits)
+
+    orig_lse = O.row_lse
+    monkeypatch.setattr(O, "row_lse", lambda q, k, scale=None: orig_logits(q, k, scale).max(axis=-1))   # max, not lse
+    assert fails(test_row_lse_matches_library_logsumexp_and_closed_form)
+    assert fails(test_scores_from_supplied_lse)
+    monkeypatch.setattr(O, "row_lse", orig_lse)
+    orig_from = O.score_window_from_lse
+    monkeypatch.setattr(O, "score_window_from_lse",
+                        lambda q, k, lse, P, scale=None, row_scale=1.0: orig_from(q, k, -np.asarray(lse), P, scale, row_scale))
+    assert fails(test_scores_from_supplied_lse)
+    monkeypatch.setattr(O, "score_window_from_lse", orig_from)
 
     orig_pool = O.max_pool_prefix
     monkeypatch.setattr(O, "max_pool_prefix", lambda a, w, P: orig_pool(a, 0, P)[:, :a.shape[1] - w])
