@@ -79,7 +79,8 @@ enum {
   DKV_KERNEL_REBALANCE_SCAN = 5,
   DKV_KERNEL_REBALANCE_FINAL = 6,
   DKV_KERNEL_FILL = 7,
-  DKV_KERNEL_SELECT_ORDER = 8
+  DKV_KERNEL_SELECT_ORDER = 8,
+  DKV_KERNEL_SCORE_LSE = 9        /* export of the row normalisers                    */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */
@@ -136,6 +137,28 @@ int dkv_score_window_stats(const dkv_desc* desc, const void* q_win, const void* 
 int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                           int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                           int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Eq. 1-2 in ONE sweep over K, for a caller that already holds the softmax normalisers of the window rows: the
+ * prefill attention of the same layer computes, for every query row, lse = log sum_s exp(scale * <q, k_s>) over
+ * the keys the row may see (causal); for the last ws rows that is exactly the denominator of Eq. 1. With it the
+ * probabilities are p = exp(scale * <q, k_s> - lse[row]) and the statistics sweep of dkv_score_window is not
+ * needed. Same arguments and output as dkv_score_window, plus
+ * lse   fp32 [n_seqs][Hq][ws], natural log, row (q, g, i) = window query i of query head g of sequence q.
+ * No workspace. The result equals dkv_score_window's up to the rounding of the supplied lse.
+ */
+int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                         int64_t k_stride_head, const int32_t* cu_seqlens, const float* lse, float* scores_out,
+                         int64_t scores_stride_head, void* stream);
+
+/*
+ * The normalisers themselves (the denominator of Eq. 1 in log form), from the row statistics that the last
+ * dkv_score_window_stats or dkv_score_window call left in `workspace`: lse_out fp32 [n_seqs][Hq][ws], natural log,
+ * in the layout dkv_score_window_lse takes. k_stride_token must be the value passed to that call (it selects the
+ * kernel family whose statistics are read). One small kernel.
+ */
+int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_seqlens, float* lse_out,
+                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Per-layer, per-KV-head top-k (Eq. 3; Algorithm 1, the A^l.topk(B^l).indices line) for layer index `layer`.

@@ -116,26 +116,35 @@ size_t dkv_workspace_bytes(const dkv_desc* desc) {
 static int score_window_phases(int phases, const dkv_desc* desc, const void* q_win, const void* k,
                                int64_t k_stride_token, int64_t k_stride_head, const int32_t* cu_seqlens,
                                float* scores_out, int64_t scores_stride_head, void* workspace, size_t workspace_bytes,
-                               void* stream) {
+                               const float* lse_in, float* lse_out, void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
-  if (!q_win || !k || !cu_seqlens || !scores_out) return DKV_ERR_INVALID_ARG;
-  if (!aligned16(q_win) || !aligned16(k)) return DKV_ERR_INVALID_ARG;
+  const bool sweeps = (phases & (kPhaseStats | kPhaseEmit)) != 0;       // reads Q and K
+  if (!cu_seqlens) return DKV_ERR_INVALID_ARG;
+  if (sweeps && (!q_win || !k || !aligned16(q_win) || !aligned16(k))) return DKV_ERR_INVALID_ARG;
+  if ((phases & kPhaseEmit) && !scores_out) return DKV_ERR_INVALID_ARG;
+  if ((phases & kPhaseLse) && !lse_out) return DKV_ERR_INVALID_ARG;
   st = check_kv_strides(*desc, k_stride_token, k_stride_head);
   if (st != DKV_OK) return st;
-  if (scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
-  WorkspaceLayout wl;
-  st = check_workspace(*desc, workspace, workspace_bytes, wl);
-  if (st != DKV_OK) return st;
+  if ((phases & kPhaseEmit) && scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl{};
+  const bool needs_workspace = phases != kPhaseEmit || lse_in == nullptr;   // everything but the single sweep
+  if (needs_workspace) {
+    st = check_workspace(*desc, workspace, workspace_bytes, wl);
+    if (st != DKV_OK) return st;
+  } else {
+    workspace = nullptr;
+  }
   if (desc->total_tokens == 0) return DKV_OK;
   const Params p = make_params(*desc);
   hipError_t e;
   if (score_mfma_supported(p, desc->dtype, k_stride_token)) {
     e = launch_score_mfma(p, phases, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
-                          static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+                          static_cast<char*>(workspace), wl, lse_in, lse_out, static_cast<hipStream_t>(stream));
   } else {
     e = launch_score_generic(p, phases, desc->dtype, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+                             scores_stride_head, static_cast<char*>(workspace), wl, lse_in, lse_out,
+                             static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
@@ -144,21 +153,37 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
                      int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                      int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
   return score_window_phases(kPhaseStats | kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens,
-                             scores_out, scores_stride_head, workspace, workspace_bytes, stream);
+                             scores_out, scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int dkv_score_window_stats(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                            int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                            int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
   return score_window_phases(kPhaseStats, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, workspace, workspace_bytes, stream);
+                             scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                           int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                           int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
   return score_window_phases(kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, workspace, workspace_bytes, stream);
+                             scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
+}
+
+int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                         int64_t k_stride_head, const int32_t* cu_seqlens, const float* lse, float* scores_out,
+                         int64_t scores_stride_head, void* stream) {
+  if (!lse) return DKV_ERR_INVALID_ARG;
+  return score_window_phases(kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, nullptr, 0, lse, nullptr, stream);
+}
+
+int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_seqlens, float* lse_out,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!desc) return DKV_ERR_INVALID_ARG;
+  return score_window_phases(kPhaseLse, desc, nullptr, nullptr, k_stride_token,
+                             (int64_t)desc->head_dim, cu_seqlens, nullptr, 0, workspace, workspace_bytes, nullptr,
+                             lse_out, stream);
 }
 
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,

@@ -98,14 +98,14 @@ Params make_params(const dkv_desc& d);
 
 // Stage launchers (defined next to their kernels). Each returns hipGetLastError() of its launches.
 // `phases` of the score launchers: bit 0 = row-statistics kernel, bit 1 = score kernel.
-constexpr int kPhaseStats = 1, kPhaseEmit = 2;
+constexpr int kPhaseStats = 1, kPhaseEmit = 2, kPhaseLse = 4;   // kPhaseLse: export the row normalisers
 hipError_t launch_score_generic(const Params& p, int phases, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                                char* ws, const WorkspaceLayout& wl, hipStream_t st);
+                                char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st);
 bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token);
 hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                              int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                             char* ws, const WorkspaceLayout& wl, hipStream_t st);
+                             char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st);
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
                          int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,
                          int32_t* counts, char* ws, const WorkspaceLayout& wl, hipStream_t st);

@@ -107,6 +107,7 @@ __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, con
                                                                    const T* __restrict__ k, int64_t k_stride_token,
                                                                    int64_t k_stride_head, const int32_t* __restrict__ cu,
                                                                    const float2* __restrict__ partials,
+                                                                   const float* __restrict__ lse_in,
                                                                    float* __restrict__ scores,
                                                                    int64_t scores_stride_head) {
   __shared__ float qs[kQRows * D];
@@ -123,7 +124,10 @@ __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, con
   float kreg[D];
   load_key_row<T, D>(k + (int64_t)(begin + s_ld) * k_stride_token + (int64_t)head * k_stride_head, kreg);
   const T* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * D;
-  {
+  if (lse_in != nullptr) {   // row normalisers supplied by the caller (natural log, one per window row)
+    for (int r = tid; r < p.rows; r += kGenericKeys)
+      lse_s[r] = lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + r];
+  } else {
     // chunks of the statistics kernel that belong to this sequence: [first, first + n_full), in linear order
     int first = 0;
     for (int q = 0; q < seq; ++q) first += chunks_of(cu[q + 1] - cu[q], 0, kGenericKeys);
@@ -165,11 +169,32 @@ __global__ __launch_bounds__(kGenericKeys) void score_emit_generic(Params p, con
     for (int j = tid; j < p.w; j += kGenericKeys) out[prefix + j] = -INFINITY;
 }
 
+// Natural-log row normalisers from the chunk partials: lse_out[(seq * Hq + head * G) * w + r]. grid = (n_seqs, Hkv).
+__global__ __launch_bounds__(256) void score_lse_generic(Params p, const int32_t* __restrict__ cu,
+                                                         const float2* __restrict__ partials,
+                                                         float* __restrict__ lse_out) {
+  const int seq = blockIdx.x, head = blockIdx.y;
+  int first = 0;
+  for (int q = 0; q < seq; ++q) first += chunks_of(cu[q + 1] - cu[q], 0, kGenericKeys);
+  const int n_full = chunks_of(cu[seq + 1] - cu[seq], 0, kGenericKeys);
+  for (int r = threadIdx.x; r < p.rows; r += 256) {
+    float m = -INFINITY;
+    for (int cc = 0; cc < n_full; ++cc) m = fmaxf(m, partials[(((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r].x);
+    float l = 0.0f;
+    for (int cc = 0; cc < n_full; ++cc) {
+      const float2 v = partials[(((int64_t)(first + cc)) * p.Hkv + head) * p.rows_pad + r];
+      if (v.x > -INFINITY) l += v.y * __expf(v.x - m);
+    }
+    lse_out[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + r] = m + __logf(l);
+  }
+}
+
 template <typename T, int D>
 static hipError_t launch_generic_t(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                                    int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                                   char* ws, const WorkspaceLayout& wl, hipStream_t st) {
-  float2* partials = reinterpret_cast<float2*>(ws + wl.partials);
+                                   char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out,
+                                   hipStream_t st) {
+  float2* partials = ws ? reinterpret_cast<float2*>(ws + wl.partials) : nullptr;   // no workspace: lse supplied
   const int chunks_stats = p.total_tokens / kGenericKeys + p.n_seqs;
   if (phases & kPhaseStats)
     launch(DKV_KERNEL_SCORE_STATS, (score_stats_generic<T, D>), dim3(chunks_stats, p.Hkv), dim3(kGenericKeys), 0, st, p,
@@ -180,19 +205,21 @@ static hipError_t launch_generic_t(const Params& p, int phases, const void* q_wi
   if (phases & kPhaseEmit)
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_generic<T, D>), dim3(chunks_emit, p.Hkv), dim3(kGenericKeys), 0, st, p,
                        static_cast<const T*>(q_win), static_cast<const T*>(k), k_stride_token, k_stride_head, cu,
-                       partials, scores, scores_stride_head);
+                       partials, lse_in, scores, scores_stride_head);
+  if (phases & kPhaseLse)
+    launch(DKV_KERNEL_SCORE_LSE, score_lse_generic, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, cu, partials, lse_out);
   return hipGetLastError();
 }
 
 hipError_t launch_score_generic(const Params& p, int phases, int dtype, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                                char* ws, const WorkspaceLayout& wl, hipStream_t st) {
+                                char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st) {
   if (dtype == DKV_F32) {
-    if (p.d == 64) return launch_generic_t<float, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-    return launch_generic_t<float, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+    if (p.d == 64) return launch_generic_t<float, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
+    return launch_generic_t<float, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
   }
-  if (p.d == 64) return launch_generic_t<uint16_t, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  return launch_generic_t<uint16_t, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+  if (p.d == 64) return launch_generic_t<uint16_t, 64>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
+  return launch_generic_t<uint16_t, 128>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
 }
 
 }  // namespace dkv

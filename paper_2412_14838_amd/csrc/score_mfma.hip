@@ -289,6 +289,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
                                                                 const char* __restrict__ k, int64_t stride_token_b,
                                                                 int64_t stride_head_b, const int32_t* __restrict__ cu,
                                                                 const float* __restrict__ partials,
+                                                                const float* __restrict__ lse_in,
                                                                 float* __restrict__ scores, int64_t scores_stride_head) {
   using TL = Tile<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -326,8 +327,15 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   bf16x8 qf[2][8];
   load_q_frags(q_head, rs, p.rows, qf);
 
-  // ---- lse2[row] of this (sequence, head) from the chunk partials of the statistics kernel
-  {
+  // ---- lse2[row] of this (sequence, head): supplied by the caller (natural log, one per window row), or merged
+  // from the chunk partials of the statistics kernel
+  if (lse_in != nullptr) {
+    store_tile<RS, KS>(tiles, reg);
+    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+    if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
+      lse_s[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
+    __syncthreads();                                         // the tiles are in place
+  } else {
     const int r = tid % kRows, q = tid / kRows;              // KS groups of kRows threads
     const float2* __restrict__ src =
         reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad + r;
@@ -426,6 +434,29 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     for (int j = tid; j < p.w; j += TL::kThreads) out[prefix + j] = -INFINITY;   // guard over the window slots
 }
 
+// Natural-log row normalisers from the chunk partials of the statistics kernel (log2 domain):
+// lse_out[(seq * Hq + head * G) * w + r]. grid = (n_seqs, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void score_lse_mfma(Params p, int chunk, const int32_t* __restrict__ cu,
+                                                      const float* __restrict__ partials, float* __restrict__ lse_out) {
+  const int seq = blockIdx.x, head = blockIdx.y;
+  int first_full = 0;
+  for (int q = 0; q < seq; ++q) first_full += (cu[q + 1] - cu[q] + chunk - 1) / chunk;
+  const int n_full = (cu[seq + 1] - cu[seq] + chunk - 1) / chunk;
+  for (int r = threadIdx.x; r < p.rows; r += 256) {
+    const float2* __restrict__ src =
+        reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad + r;
+    float M = -INFINITY, Lsum = 0.0f;
+    for (int cc = 0; cc < n_full; ++cc) {
+      const float2 v = src[(int64_t)cc * p.Hkv * p.rows_pad];
+      const float Mn = fmaxf(M, v.x);
+      const float Mu = Mn == -INFINITY ? 0.0f : Mn;
+      Lsum = Lsum * fast_exp2(M - Mu) + v.y * fast_exp2(v.x - Mu);
+      M = Mn;
+    }
+    lse_out[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + r] = (M + __log2f(Lsum)) * (1.0f / kLog2e);
+  }
+}
+
 bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token) {
   return dtype == DKV_BF16 && p.d == 128 && p.rows <= 256 && 2 * p.half <= kMaxHalo &&
          k_stride_token * 2 < (1 << 24);
@@ -447,10 +478,11 @@ static int pick_chunk(const Params& p, int keys_per_iter) {
 template <int RS, int KS>
 static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                                char* ws, const WorkspaceLayout& wl, hipStream_t st) {
+                                char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out,
+                                hipStream_t st) {
   using TL = Tile<RS, KS>;
   const int chunk = pick_chunk(p, TL::kKeys);
-  float* partials = reinterpret_cast<float*>(ws + wl.partials);
+  float* partials = ws ? reinterpret_cast<float*>(ws + wl.partials) : nullptr;   // no workspace: lse supplied
   const size_t lds_stats = 2 * TL::kTileBytes + (size_t)KS * RS * 64 * sizeof(float2);
   const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + 2 * TL::kKeys) * sizeof(float);
   static bool attr_set = false;
@@ -471,16 +503,18 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
   if (phases & kPhaseEmit)
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
                        static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
-                       k_stride_head * 2, cu, partials, scores, scores_stride_head);
+                       k_stride_head * 2, cu, partials, lse_in, scores, scores_stride_head);
+  if (phases & kPhaseLse)
+    launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, cu, partials, lse_out);
   return hipGetLastError();
 }
 
 hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
                              int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                             char* ws, const WorkspaceLayout& wl, hipStream_t st) {
-  if (p.rows <= 64) return launch_mfma_t<1, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  if (p.rows <= 128) return launch_mfma_t<2, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
-  return launch_mfma_t<4, 2>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, st);
+                             char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st) {
+  if (p.rows <= 64) return launch_mfma_t<1, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
+  if (p.rows <= 128) return launch_mfma_t<2, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
+  return launch_mfma_t<4, 2>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
 }
 
 }  // namespace dkv

@@ -18,7 +18,7 @@ DKV_MAX_SELECT_LAYERS = 8
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
-           "dkv_score_window_stats", "dkv_score_window_emit", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
+           "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
            "dkv_gather_kv", "dkv_gather_kv_layers")
 
 
@@ -62,6 +62,10 @@ def load() -> C.CDLL:
     for name in ("dkv_score_window", "dkv_score_window_stats", "dkv_score_window_emit"):
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [D, P, P, I64, I64, P, P, I64, P, SZ, P]
+    lib.dkv_score_window_lse.restype = C.c_int
+    lib.dkv_score_window_lse.argtypes = [D, P, P, I64, I64, P, P, P, I64, P]
+    lib.dkv_row_lse.restype = C.c_int
+    lib.dkv_row_lse.argtypes = [D, I64, P, P, P, SZ, P]
     lib.dkv_select_topk.restype = C.c_int
     lib.dkv_select_topk.argtypes = [D, I32, P, I64, P, P, P, P, SZ, P]
     lib.dkv_select_topk_layers.restype = C.c_int
@@ -122,7 +126,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "select_order")
+                "rebalance_final", "fill", "select_order", "score_lse")
 
 
 def dkv_profile_begin(capacity: int) -> None:
@@ -160,6 +164,18 @@ def dkv_score_window_emit(desc, q_win, k, k_stride_token, k_stride_head, cu_seql
                                         _ptr(cu_seqlens), _ptr(scores_out), scores_stride_head, _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)),
            "dkv_score_window_emit")
+
+
+def dkv_score_window_lse(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, lse, scores_out, scores_stride_head,
+                         stream=None) -> None:
+    _check(load().dkv_score_window_lse(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head,
+                                       _ptr(cu_seqlens), _ptr(lse), _ptr(scores_out), scores_stride_head,
+                                       _stream(stream)), "dkv_score_window_lse")
+
+
+def dkv_row_lse(desc, k_stride_token, cu_seqlens, lse_out, workspace, stream=None) -> None:
+    _check(load().dkv_row_lse(C.byref(desc), k_stride_token, _ptr(cu_seqlens), _ptr(lse_out), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_row_lse")
 
 
 def dkv_select_topk(desc, layer, scores, scores_stride_head, cu_seqlens, idx_out, counts, workspace,

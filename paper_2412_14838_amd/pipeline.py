@@ -50,6 +50,19 @@ class Compressor:
         dkv.dkv_score_window(self.desc, q_win, k, st, sh, self.cu, self.scores[layer], self.cfg.total_tokens, self.ws,
                              stream)
 
+    def score_from_lse(self, layer, q_win, k, lse, stride_token=None, stride_head=None, stream=None):
+        """One sweep over K with the caller's row normalisers lse [n_seqs][Hq][w] (natural log, fp32)."""
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_score_window_lse(self.desc, q_win, k, st, sh, self.cu, lse, self.scores[layer], self.cfg.total_tokens,
+                                 stream)
+
+    def row_lse(self, lse_out, stride_token=None, stream=None):
+        """The normalisers of the layer scored last: lse_out [n_seqs][Hq][w] fp32."""
+        st = self.cfg.d if stride_token is None else stride_token
+        dkv.dkv_row_lse(self.desc, st, self.cu, lse_out, self.ws, stream)
+
     def select(self, layer, stream=None):
         dkv.dkv_select_topk(self.desc, layer, self.scores[layer], self.cfg.total_tokens, self.cu, self.idx[layer],
                             self.counts, self.ws, stream)

@@ -143,6 +143,24 @@ def test_layer_batched_calls_reject_bad_ranges(lib):
                                     sq - 64, sq, sh, None) == inv
 
 
+def test_lse_calls_validate_their_arguments(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv, wsp = dkv.DKV_ERR_INVALID_ARG, dkv.DKV_ERR_WORKSPACE
+    assert lib.dkv_score_window_lse(C.byref(d), fake, fake, 64, 65536, fake, None, fake, 1024, None) == inv   # no lse
+    assert lib.dkv_score_window_lse(C.byref(d), None, fake, 64, 65536, fake, fake, fake, 1024, None) == inv
+    assert lib.dkv_score_window_lse(C.byref(d), fake, fake, 64, 65536, fake, fake, None, 1024, None) == inv
+    assert lib.dkv_score_window_lse(C.byref(d), fake, fake, 64, 65536, fake, fake, fake, 1000, None) == inv
+    assert lib.dkv_score_window_lse(C.byref(_good(pool_kernel=2)), fake, fake, 64, 65536, fake, fake, fake, 1024,
+                                    None) == inv
+    assert lib.dkv_row_lse(C.byref(d), 64, fake, None, fake, need, None) == inv
+    assert lib.dkv_row_lse(C.byref(d), 64, None, fake, fake, need, None) == inv
+    assert lib.dkv_row_lse(C.byref(d), 64, fake, fake, None, need, None) == wsp
+    assert lib.dkv_row_lse(C.byref(d), 64, fake, fake, fake, need - 1, None) == wsp
+    assert lib.dkv_row_lse(None, 64, fake, fake, fake, need, None) == inv
+
+
 def test_binding_raises_on_error():
     d = _good(pool_kernel=2)
     with pytest.raises(dkv.DkvError):

@@ -147,6 +147,32 @@ def test_full_ragged_batch8(dkv):
     check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7], group=4)
 
 
+@pytest.mark.parametrize("name", ["mistral_7b_32k", "ragged_batch8"])
+def test_full_single_sweep_scoring_from_row_lse(dkv, name):
+    """At full size: the exported normalisers match the oracle's log-sum-exp on sampled heads, and the single
+    sweep fed with them reproduces the two-sweep scores of the whole layer."""
+    cfg = W.standard_configs()[name]
+    comp = Compressor(cfg, keep_cache=False)
+    data = W.make_layer(cfg, 5, with_v=False)
+    dev = to_device(cfg, data)
+    comp.score(0, dev["q_win"], dev["k"])
+    lse = torch.empty((cfg.n_seqs, cfg.Hq, cfg.w), dtype=torch.float32, device="cuda")
+    comp.row_lse(lse)
+    comp.score_from_lse(1, dev["q_win"], dev["k"], lse)
+    torch.cuda.synchronize()
+    a, b = comp.scores[0].cpu().numpy(), comp.scores[1].cpu().numpy()
+    cu, G = cfg.cu_seqlens, cfg.G
+    for s in range(cfg.n_seqs):
+        n = cfg.seqlens[s] - cfg.w
+        x, y = a[:, cu[s]:cu[s] + n], b[:, cu[s]:cu[s] + n]
+        assert (np.abs(x - y) <= 1e-5 * np.abs(x)).all(), s
+        assert np.isneginf(b[:, cu[s] + n:cu[s + 1]]).all()
+    lse_h = lse.cpu().numpy()
+    for s, h in ((0, 1), (cfg.n_seqs - 1, cfg.Hkv - 1)):
+        ref = O.row_lse(data["q_win"][s][h * G:(h + 1) * G], data["k"][h:h + 1, cu[s]:cu[s + 1]])
+        assert np.abs(lse_h[s, h * G:(h + 1) * G] - ref).max() <= 1e-4
+
+
 def test_calibrated_planting_gives_layer_varying_budgets(dkv):
     """With the planted keys scaled so that they dominate (plant_normalize), the layers with many planted keys
     win the global selection: budgets vary by layer, and every check of the standard run still holds."""

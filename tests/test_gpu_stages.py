@@ -354,3 +354,45 @@ def test_rebalance_history_is_only_used_when_it_matches(dkv):
     comp.scores.copy_(torch.from_numpy(A2))  # a new prefill in the same tensors
     for l in (2, 4, 6):
         check(comp, A2, l)
+
+
+@pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_f32", "ragged_bf16"])
+def test_row_lse_and_single_sweep_scoring(dkv, case):
+    """dkv_row_lse exports the normalisers of Eq. 1 (checked against the oracle's log-sum-exp), and
+    dkv_score_window_lse, fed with the oracle's normalisers, reproduces the oracle's single-sweep scores and the
+    two-sweep scores, without touching a workspace."""
+    cfg = CASES[case]
+    comp = Compressor(cfg, keep_cache=False)
+    data = W.make_layer(cfg, 1)
+    dev = to_device(cfg, data)
+    cu = cfg.cu_seqlens
+    comp.score(0, dev["q_win"], dev["k"])
+    lse_gpu = torch.full((cfg.n_seqs, cfg.Hq, cfg.w), float("nan"), dtype=torch.float32, device="cuda")
+    comp.row_lse(lse_gpu)
+    torch.cuda.synchronize()
+    two_sweep = comp.scores[0].cpu().numpy().copy()
+    lse_ref = np.zeros((cfg.n_seqs, cfg.Hq, cfg.w), dtype=np.float64)
+    refs = []
+    for s in range(cfg.n_seqs):
+        if cfg.seqlens[s] < cfg.w:          # shorter than the window: the method does not define its rows
+            refs.append(None)
+            continue
+        k_s = data["k"][:, cu[s]:cu[s + 1]]
+        lse_ref[s] = O.row_lse(data["q_win"][s], k_s)
+        assert np.abs(lse_gpu[s].cpu().numpy() - lse_ref[s]).max() <= 1e-4, s      # absolute, in nats
+        refs.append(O.score_window_from_lse(data["q_win"][s], k_s, lse_ref[s].astype(np.float32), cfg.P))
+    comp.scores[0].fill_(7.0)
+    comp.ws.fill_(0xff)                     # the single sweep must not read the workspace
+    comp.score_from_lse(0, dev["q_win"], dev["k"], torch.from_numpy(lse_ref.astype(np.float32)).cuda())
+    torch.cuda.synchronize()
+    got = comp.scores[0].cpu().numpy()
+    for s in range(cfg.n_seqs):
+        n = cfg.seqlens[s] - cfg.w
+        if n <= 0 or refs[s] is None:
+            continue
+        g = got[:, cu[s]:cu[s] + n]
+        rel = np.abs(g - refs[s]) / np.maximum(refs[s], 1e-30)
+        assert rel.max() <= SCORE_RTOL, (s, rel.max())
+        t = two_sweep[:, cu[s]:cu[s] + n]
+        assert (np.abs(g - t) <= 1e-4 * np.abs(t)).all()      # same scores as the two-sweep call
+        assert np.isneginf(got[:, cu[s] + n:cu[s + 1]]).all()
