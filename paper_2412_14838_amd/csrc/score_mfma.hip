@@ -40,28 +40,60 @@ struct Tile {
   static constexpr int kTileBytes = kKeys * kLdsRow;
 };
 
-// Q fragments of this wavefront's 64 rows: qf[t][j] = 8 consecutive head-dim elements (16 j + 8 (lane / 32) ..)
-// of row rs * 64 + t * 32 + lane % 32; rows >= rows are zero.
-__device__ inline void load_q_frags(const uint16_t* __restrict__ q_head, int rs, int rows, bf16x8 (&qf)[2][8]) {
+// The Q block of one (sequence, KV head) - up to RS * 64 rows of 128 - goes through LDS once per workgroup
+// (every row is needed by KS wavefronts): load_q_pieces() fetches kQPieces 16-byte pieces per thread (rows past
+// `rows` are zero), store_q_pieces() puts them into `qbuf` in the padded row layout of the key tiles, and after a
+// barrier read_q_frags() gives each wavefront the fragments of its 64 rows in MFMA operand layout:
+// qf[t][j] = 8 consecutive head-dim elements (16 j + 8 (lane / 32) ..) of row rs * 64 + t * 32 + lane % 32.
+template <int N> struct PieceVec;
+template <> struct PieceVec<2> { typedef uint32_t type __attribute__((ext_vector_type(8))); };
+template <> struct PieceVec<4> { typedef uint32_t type __attribute__((ext_vector_type(16))); };
+template <> struct PieceVec<8> { typedef uint32_t type __attribute__((ext_vector_type(32))); };
+
+template <int RS, int KS>
+struct QStage {
+  static constexpr int kRows = RS * 64;
+  static constexpr int kPieces = kRows * 16 / (RS * KS * 64);     // 16 / KS
+  static constexpr int kBytes = kRows * kLdsRow;
+};
+
+template <int RS, int KS>
+__device__ inline typename PieceVec<QStage<RS, KS>::kPieces>::type load_q_pieces(const uint16_t* __restrict__ q_head,
+                                                                                  int rows) {
+  typename PieceVec<QStage<RS, KS>::kPieces>::type reg;
+#pragma unroll
+  for (int i = 0; i < QStage<RS, KS>::kPieces; ++i) {
+    const int pc = threadIdx.x + i * (RS * KS * 64);
+    const int row = pc >> 4;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < rows) v = *reinterpret_cast<const uint4*>(q_head + row * 128 + (pc & 15) * 8);
+    reg[4 * i] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
+  }
+  return reg;
+}
+
+template <int RS, int KS>
+__device__ inline void store_q_pieces(char* __restrict__ qbuf, typename PieceVec<QStage<RS, KS>::kPieces>::type reg) {
+#pragma unroll
+  for (int i = 0; i < QStage<RS, KS>::kPieces; ++i) {
+    const int pc = threadIdx.x + i * (RS * KS * 64);
+    *reinterpret_cast<uint4*>(qbuf + (pc >> 4) * kLdsRow + (pc & 15) * 16) =
+        make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
+  }
+}
+
+__device__ inline void read_q_frags(const char* __restrict__ qbuf, int rs, bf16x8 (&qf)[2][8]) {
   const int lane = threadIdx.x & 63;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const int r = rs * 64 + t * 32 + (lane & 31);
+    const char* row = qbuf + (rs * 64 + t * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < rows) v = *reinterpret_cast<const uint4*>(q_head + (int64_t)r * 128 + j * 16 + (lane >> 5) * 8);
-      qf[t][j] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int j = 0; j < 8; ++j) qf[t][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(row + j * 32));
   }
 }
 
 // One tile of keys in flight between global memory and LDS: kPieces 16-byte pieces per thread, held as ONE
 // vector value (a plain array would be demoted to scratch memory across the loop).
-template <int N> struct PieceVec;
-template <> struct PieceVec<2> { typedef uint32_t type __attribute__((ext_vector_type(8))); };
-template <> struct PieceVec<4> { typedef uint32_t type __attribute__((ext_vector_type(16))); };
-template <> struct PieceVec<8> { typedef uint32_t type __attribute__((ext_vector_type(32))); };
 
 // Fetches one tile of keys [row0, row0 + kKeys) (relative to the chunk start, clamped to its last row, so every
 // load stays inside the chunk and clamped rows are cache hits) into registers.
@@ -164,7 +196,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   using TL = Tile<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
-  float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes);         // [KS][RS * 64]
+  float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes);         // [KS][RS * 64], at the very end
+  char* qbuf = smem + 2 * TL::kTileBytes;                                      // Q staging, at the very start
 
   int seq, c, nc, begin, S, first_full, n_full;
   if (!find_chunk2(cu, p.n_seqs, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
@@ -184,8 +217,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
   typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  bf16x8 qf[2][8];
-  load_q_frags(q_head, rs, p.rows, qf);
+  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg = load_q_pieces<RS, KS>(q_head, p.rows);
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   int limit[2];                                     // last key (chunk-relative) visible to this lane's row
@@ -195,7 +227,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 
   store_tile<RS, KS>(tiles, reg);
   store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  store_q_pieces<RS, KS>(qbuf, qreg);
   __syncthreads();
+  bf16x8 qf[2][8];
+  read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<true>(tiles + lane_tile, qf, acc);
   __syncthreads();                                  // buffer 0 is rewritten by the first step
@@ -298,6 +333,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   constexpr int kPartStride = kMaxChunk + kMaxHalo + 2 * TL::kKeys;
   constexpr int kRows = RS * 64;
   float2* mstage = reinterpret_cast<float2*>(part);                            // [KS][kRows], before `part` is used
+  char* qbuf = smem + 2 * TL::kTileBytes + RS * kPartStride * sizeof(float);   // Q staging
   __shared__ __attribute__((aligned(16))) float lse_s[kRows];
 
   const int half = p.half;
@@ -324,14 +360,14 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
   typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  bf16x8 qf[2][8];
-  load_q_frags(q_head, rs, p.rows, qf);
+  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg = load_q_pieces<RS, KS>(q_head, p.rows);
 
   // ---- lse2[row] of this (sequence, head): supplied by the caller (natural log, one per window row), or merged
   // from the chunk partials of the statistics kernel
   if (lse_in != nullptr) {
     store_tile<RS, KS>(tiles, reg);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+    store_q_pieces<RS, KS>(qbuf, qreg);
     if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
       lse_s[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
     __syncthreads();                                         // the tiles are in place
@@ -351,6 +387,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     mstage[q * kRows + r] = make_float2(M, Lsum);
     store_tile<RS, KS>(tiles, reg);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+    store_q_pieces<RS, KS>(qbuf, qreg);
     __syncthreads();
     if (tid < kRows) {
       float Mx = -INFINITY;
@@ -368,6 +405,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
   }
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
+  bf16x8 qf[2][8];
+  read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<false>(tiles + lane_tile, qf, acc);
   __syncthreads();
@@ -483,8 +522,9 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
   using TL = Tile<RS, KS>;
   const int chunk = pick_chunk(p, TL::kKeys);
   float* partials = ws ? reinterpret_cast<float*>(ws + wl.partials) : nullptr;   // no workspace: lse supplied
-  const size_t lds_stats = 2 * TL::kTileBytes + (size_t)KS * RS * 64 * sizeof(float2);
-  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + 2 * TL::kKeys) * sizeof(float);
+  const size_t lds_stats = 2 * TL::kTileBytes + (size_t)QStage<RS, KS>::kBytes;     // Q staging >= the final [KS][RS * 64] float2
+  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + 2 * TL::kKeys) * sizeof(float) +
+                          (size_t)QStage<RS, KS>::kBytes;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_stats_mfma<RS, KS>),
