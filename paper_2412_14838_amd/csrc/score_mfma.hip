@@ -26,7 +26,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kLdsRow = 272;          // bytes per staged key row: 256 data + 16 pad (conflict-free 16-byte reads)
-constexpr int kMaxChunk = 2048;       // largest `chunk` the launcher picks
+constexpr int kLdsBudget = 156 * 1024; // dynamic LDS a workgroup may ask for (160 KB per compute unit, less the static part)
 constexpr int kMaxHalo = 64;          // >= 2 * half
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -52,6 +52,8 @@ template <> struct PieceVec<8> { typedef uint32_t type __attribute__((ext_vector
 
 template <int RS, int KS>
 struct QStage {
+  static constexpr bool kStatsViaLds = true;
+  static constexpr bool kEmitViaLds = KS >= 4;                    // else every wavefront loads its own fragments
   static constexpr int kRows = RS * 64;
   static constexpr int kPieces = kRows * 16 / (RS * KS * 64);     // 16 / KS
   static constexpr int kBytes = kRows * kLdsRow;
@@ -89,6 +91,22 @@ __device__ inline void read_q_frags(const char* __restrict__ qbuf, int rs, bf16x
     const char* row = qbuf + (rs * 64 + t * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 #pragma unroll
     for (int j = 0; j < 8; ++j) qf[t][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(row + j * 32));
+  }
+}
+
+// The same fragments straight from global memory, every wavefront for itself: used by the emit kernel where only
+// two wavefronts share a row slab (KS = 2), for which the detour through LDS measured slower there.
+__device__ inline void load_q_frags(const uint16_t* __restrict__ q_head, int rs, int rows, bf16x8 (&qf)[2][8]) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int r = rs * 64 + t * 32 + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (r < rows) v = *reinterpret_cast<const uint4*>(q_head + (int64_t)r * 128 + j * 16 + (lane >> 5) * 8);
+      qf[t][j] = __builtin_bit_cast(bf16x8, v);
+    }
   }
 }
 
@@ -217,7 +235,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
   typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg = load_q_pieces<RS, KS>(q_head, p.rows);
+  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
+  bf16x8 qf[2][8];
+  if (QStage<RS, KS>::kStatsViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
+  else load_q_frags(q_head, rs, p.rows, qf);
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   int limit[2];                                     // last key (chunk-relative) visible to this lane's row
@@ -227,10 +248,9 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 
   store_tile<RS, KS>(tiles, reg);
   store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
-  store_q_pieces<RS, KS>(qbuf, qreg);
+  if (QStage<RS, KS>::kStatsViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
   __syncthreads();
-  bf16x8 qf[2][8];
-  read_q_frags(qbuf, rs, qf);
+  if (QStage<RS, KS>::kStatsViaLds) read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<true>(tiles + lane_tile, qf, acc);
   __syncthreads();                                  // buffer 0 is rewritten by the first step
@@ -316,6 +336,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 // Scores: a[s] = row_scale * sum_rows exp2(c * x[row, s] - lse2[row]) over the chunk's outputs plus the pooling
 // halo, max-pooled over the prefix. grid = (chunk upper bound over the S' prefix outputs, Hkv).
 // ------------------------------------------------------------------------------------------------------
+// Column sums of one row slab in the emit kernel: the chunk's outputs, the pooling halo and two tiles of slack
+// (the last step computes a tile past the range).
+template <int RS, int KS>
+__host__ __device__ inline int emit_part_stride(int chunk) { return chunk + kMaxHalo + 2 * Tile<RS, KS>::kKeys; }
+
 // Key tile that step `it` of the emit kernel works on (steps past the first tile repeat it: same values again).
 __device__ inline int emit_tile(int n_iter, int it) { return it < n_iter ? n_iter - 1 - it : 0; }
 
@@ -330,7 +355,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
   float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kPartStride]
-  constexpr int kPartStride = kMaxChunk + kMaxHalo + 2 * TL::kKeys;
+  const int kPartStride = emit_part_stride<RS, KS>(chunk);
   constexpr int kRows = RS * 64;
   float2* mstage = reinterpret_cast<float2*>(part);                            // [KS][kRows], before `part` is used
   char* qbuf = smem + 2 * TL::kTileBytes + RS * kPartStride * sizeof(float);   // Q staging
@@ -360,14 +385,17 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
   typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg = load_q_pieces<RS, KS>(q_head, p.rows);
+  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
+  bf16x8 qf[2][8];
+  if (QStage<RS, KS>::kEmitViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
+  else load_q_frags(q_head, rs, p.rows, qf);
 
   // ---- lse2[row] of this (sequence, head): supplied by the caller (natural log, one per window row), or merged
   // from the chunk partials of the statistics kernel
   if (lse_in != nullptr) {
     store_tile<RS, KS>(tiles, reg);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
-    store_q_pieces<RS, KS>(qbuf, qreg);
+    if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
     if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
       lse_s[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
     __syncthreads();                                         // the tiles are in place
@@ -387,7 +415,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     mstage[q * kRows + r] = make_float2(M, Lsum);
     store_tile<RS, KS>(tiles, reg);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
-    store_q_pieces<RS, KS>(qbuf, qreg);
+    if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
     __syncthreads();
     if (tid < kRows) {
       float Mx = -INFINITY;
@@ -405,8 +433,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
   }
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-  bf16x8 qf[2][8];
-  read_q_frags(qbuf, rs, qf);
+  if (QStage<RS, KS>::kEmitViaLds) read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<false>(tiles + lane_tile, qf, acc);
   __syncthreads();
@@ -501,17 +528,39 @@ bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token) {
          k_stride_token * 2 < (1 << 24);
 }
 
-static int pick_chunk(const Params& p, int keys_per_iter) {
-  // aim at one workgroup per compute unit and round: enough keys per workgroup to amortise its Q load
-  const long long total = (long long)p.total_tokens * p.Hkv;
-  long long per_cu = total / 256;
-  long long rounds = (per_cu + 512) / 1024;
-  if (rounds < 1) rounds = 1;
-  long long chunk = (per_cu + rounds - 1) / rounds;
-  chunk = (chunk + keys_per_iter - 1) / keys_per_iter * keys_per_iter;
-  if (chunk < 256) chunk = 256;
-  if (chunk > kMaxChunk) chunk = kMaxChunk;
-  return (int)chunk;
+// Keys per workgroup. Every workgroup pays a fixed cost (locating its chunk, the first loads, the epilogue) and the
+// device holds one workgroup per compute unit, so the chunk is the multiple of the tile that minimises
+// rounds x (fixed + streaming): as few rounds of workgroups as possible, and within that the shortest chunk.
+// The number of chunks is exact for one sequence and an upper bound (one ragged tail per sequence) otherwise.
+template <int RS, int KS>
+static int pick_chunk(const Params& p, int cus) {
+  using TL = Tile<RS, KS>;
+  const long long lds_fixed = 2LL * TL::kTileBytes + QStage<RS, KS>::kBytes;
+  int max_chunk = (int)((kLdsBudget - lds_fixed) / (RS * (long long)sizeof(float))) - kMaxHalo - 2 * TL::kKeys;
+  max_chunk = max_chunk / TL::kKeys * TL::kKeys;
+  if (max_chunk > 4096) max_chunk = 4096;
+  const double fixed_us = 6.0, us_per_key = 0.0102;          // measured: 1.3 us per 128-key step of a full device
+  int best = 256;
+  double best_cost = 1e30;
+  for (int chunk = 256; chunk <= max_chunk; chunk += TL::kKeys) {
+    if (chunk % TL::kKeys) continue;
+    const long long chunks = p.n_seqs == 1 ? (p.total_tokens + chunk - 1) / chunk : p.total_tokens / chunk + p.n_seqs;
+    const long long rounds = (chunks * p.Hkv + cus - 1) / cus;
+    const double cost = rounds * (fixed_us + chunk * us_per_key);
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = chunk; }
+  }
+  return best;
+}
+
+static int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+      cus = 256;
+  }
+  return cus;
 }
 
 template <int RS, int KS>
@@ -520,18 +569,19 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
                                 char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out,
                                 hipStream_t st) {
   using TL = Tile<RS, KS>;
-  const int chunk = pick_chunk(p, TL::kKeys);
+  const int chunk = pick_chunk<RS, KS>(p, device_cus());
   float* partials = ws ? reinterpret_cast<float*>(ws + wl.partials) : nullptr;   // no workspace: lse supplied
-  const size_t lds_stats = 2 * TL::kTileBytes + (size_t)QStage<RS, KS>::kBytes;     // Q staging >= the final [KS][RS * 64] float2
-  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * (kMaxChunk + kMaxHalo + 2 * TL::kKeys) * sizeof(float) +
-                          (size_t)QStage<RS, KS>::kBytes;
+  const size_t stat_bytes = (size_t)KS * RS * 64 * sizeof(float2);               // the final [KS][RS * 64] partials
+  const size_t lds_stats = 2 * TL::kTileBytes + ((size_t)QStage<RS, KS>::kBytes > stat_bytes ? (size_t)QStage<RS, KS>::kBytes : stat_bytes);
+  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * emit_part_stride<RS, KS>(chunk) * sizeof(float) +
+                          (QStage<RS, KS>::kEmitViaLds ? (size_t)QStage<RS, KS>::kBytes : 0);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_stats_mfma<RS, KS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_stats);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_emit_mfma<RS, KS>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_emit);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
