@@ -80,7 +80,8 @@ enum {
   DKV_KERNEL_REBALANCE_FINAL = 6,
   DKV_KERNEL_FILL = 7,
   DKV_KERNEL_SELECT_ORDER = 8,
-  DKV_KERNEL_SCORE_LSE = 9        /* export of the row normalisers                    */
+  DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
+  DKV_KERNEL_PACK = 10            /* tight packing of the final cache                 */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */
@@ -242,6 +243,27 @@ int dkv_gather_kv_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_la
                          const int32_t* cu_seqlens, const int32_t* idx_all, const int32_t* counts, void* k_out_all,
                          void* v_out_all, int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head,
                          void* stream);
+
+/*
+ * The final compressed cache as one tight tensor (Algorithm 1, last line: K^c, V^c <- K^b, V^b after the
+ * truncations). The cache dkv_gather_kv builds is already usable in place (block (l, q, h) holds ws + counts[q][l]
+ * valid rows); this call copies the valid rows of every block next to each other for a consumer that wants no
+ * padding. For block i = q * L + l (sequence q, layer l), n = counts[q][l]:
+ *     row_offsets[i]            first packed row of the block (int64, [n_seqs * L + 1], written by the call;
+ *                               row_offsets[n_seqs * L] = total rows),
+ *     rows of head h            [row_offsets[i] + h * (w_q + n), + w_q + n): the n retained rows in selection
+ *                               order, then the w_q window rows in position order (the listing's cat order);
+ *                               w_q = min(ws, S_q).
+ * kb_all, vb_all   the buffers dkv_gather_kv wrote: element (l, q, h, slot, j) at
+ *                  kb[l * stride_layer + q * stride_seq + h * stride_head + slot * d + j] (elements).
+ * k_packed, v_packed  [capacity_rows][d]; a block that would end past capacity_rows is not written (its offsets
+ *                  still are). n_seqs * L * Hkv * (ws + layer_max) rows always suffice; after the last update
+ *                  of a model with L % interval == 0, n_seqs * Hkv * L * (ws + mean_budget) do.
+ * Two kernels (offsets by one workgroup, then the copy).
+ */
+int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_t* counts, const void* kb_all,
+                   const void* vb_all, int64_t stride_layer, int64_t stride_seq, int64_t stride_head, void* k_packed,
+                   void* v_packed, int64_t capacity_rows, int64_t* row_offsets, void* stream);
 
 #ifdef __cplusplus
 }

@@ -295,4 +295,25 @@ int dkv_gather_kv_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_la
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 
+int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_t* counts, const void* kb_all,
+                   const void* vb_all, int64_t stride_layer, int64_t stride_seq, int64_t stride_head, void* k_packed,
+                   void* v_packed, int64_t capacity_rows, int64_t* row_offsets, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!cu_seqlens || !counts || !kb_all || !vb_all || !k_packed || !v_packed || !row_offsets) return DKV_ERR_INVALID_ARG;
+  if (!aligned16(kb_all) || !aligned16(vb_all) || !aligned16(k_packed) || !aligned16(v_packed)) return DKV_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(row_offsets) % 8 != 0 || capacity_rows < 0) return DKV_ERR_INVALID_ARG;
+  const int64_t elt = desc->dtype == DKV_BF16 ? 2 : 4;
+  const int64_t block = (int64_t)(desc->window + desc->layer_max) * desc->head_dim;
+  if (stride_head < block || stride_seq < stride_head * desc->n_kv_heads || stride_layer < stride_seq * desc->n_seqs)
+    return DKV_ERR_INVALID_ARG;
+  if ((stride_head * elt) % 16 != 0 || (stride_seq * elt) % 16 != 0 || (stride_layer * elt) % 16 != 0)
+    return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_pack_cache(p, (int)elt, cu_seqlens, counts, kb_all, vb_all, stride_layer, stride_seq,
+                                         stride_head, k_packed, v_packed, capacity_rows, row_offsets,
+                                         static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -109,6 +109,10 @@ hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, con
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
                          int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,
                          int32_t* counts, char* ws, const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, const int32_t* counts, const void* kb,
+                             const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head,
+                             void* k_packed, void* v_packed, int64_t capacity_rows, int64_t* row_offsets,
+                             hipStream_t st);
 hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
                             int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
                             const WorkspaceLayout& wl, hipStream_t st);

@@ -19,7 +19,7 @@ DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAU
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
-           "dkv_gather_kv", "dkv_gather_kv_layers")
+           "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache")
 
 
 class dkv_desc(C.Structure):
@@ -72,6 +72,8 @@ def load() -> C.CDLL:
     lib.dkv_select_topk_layers.argtypes = [D, I32, I32, P, P, P, P, P, SZ, P]
     lib.dkv_gather_kv_layers.restype = C.c_int
     lib.dkv_gather_kv_layers.argtypes = [D, I32, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, I64, P]
+    lib.dkv_pack_cache.restype = C.c_int
+    lib.dkv_pack_cache.argtypes = [D, P, P, P, P, I64, I64, I64, P, P, I64, P, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
@@ -126,7 +128,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "select_order", "score_lse")
+                "rebalance_final", "fill", "select_order", "score_lse", "pack")
 
 
 def dkv_profile_begin(capacity: int) -> None:
@@ -217,6 +219,13 @@ def dkv_gather_kv(desc, layer, k, v, stride_token, stride_head, cu_seqlens, idx,
     _check(load().dkv_gather_kv(C.byref(desc), layer, _ptr(k), _ptr(v), stride_token, stride_head, _ptr(cu_seqlens),
                                 _ptr(idx), _ptr(counts), _ptr(k_out), _ptr(v_out), out_stride_seq, out_stride_head,
                                 _stream(stream)), "dkv_gather_kv")
+
+
+def dkv_pack_cache(desc, cu_seqlens, counts, kb_all, vb_all, stride_layer, stride_seq, stride_head, k_packed, v_packed,
+                   capacity_rows, row_offsets, stream=None) -> None:
+    _check(load().dkv_pack_cache(C.byref(desc), _ptr(cu_seqlens), _ptr(counts), _ptr(kb_all), _ptr(vb_all),
+                                 stride_layer, stride_seq, stride_head, _ptr(k_packed), _ptr(v_packed), capacity_rows,
+                                 _ptr(row_offsets), _stream(stream)), "dkv_pack_cache")
 
 
 def alloc_workspace(desc, device="cuda"):

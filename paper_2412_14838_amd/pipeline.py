@@ -86,6 +86,18 @@ class Compressor:
                                  self.vb, self.cfg.n_seqs * self.cfg.Hkv * self.slots * d,
                                  self.cfg.Hkv * self.slots * d, self.slots * d, stream)
 
+    def pack(self, capacity_rows=None, stream=None):
+        """Tight copy of the final cache: returns (k_packed [rows][d], v_packed, row_offsets int64 [n_seqs*L + 1])."""
+        cfg, d = self.cfg, self.cfg.d
+        if capacity_rows is None:
+            capacity_rows = cfg.n_seqs * cfg.L * cfg.Hkv * self.slots
+        kp = torch.zeros((capacity_rows, d), dtype=self.tdtype, device=self.device)
+        vp = torch.zeros_like(kp)
+        off = torch.zeros(cfg.n_seqs * cfg.L + 1, dtype=torch.int64, device=self.device)
+        dkv.dkv_pack_cache(self.desc, self.cu, self.counts, self.kb, self.vb, cfg.n_seqs * cfg.Hkv * self.slots * d,
+                           cfg.Hkv * self.slots * d, self.slots * d, kp, vp, capacity_rows, off, stream)
+        return kp, vp, off
+
     def rebalance(self, layers_done, stream=None):
         dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
                           stream)

@@ -161,6 +161,25 @@ def test_lse_calls_validate_their_arguments(lib):
     assert lib.dkv_row_lse(None, 64, fake, fake, fake, need, None) == inv
 
 
+def test_pack_cache_validates_its_arguments(lib):
+    d = _good()
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    sl, sq, sh = 2 * 272 * 64, 2 * 272 * 64, 272 * 64
+    ok_args = [fake, fake, fake, fake, sl, sq, sh, fake, fake, 1000, fake, None]
+    for i in (0, 1, 2, 3, 7, 8, 10):          # each required pointer in turn
+        a = list(ok_args)
+        a[i] = None
+        assert lib.dkv_pack_cache(C.byref(d), *a) == inv
+    a = list(ok_args); a[10] = C.c_void_p(0x1004)          # offsets not 8-byte aligned
+    assert lib.dkv_pack_cache(C.byref(d), *a) == inv
+    a = list(ok_args); a[6] = sh - 64                      # head stride smaller than a block
+    assert lib.dkv_pack_cache(C.byref(d), *a) == inv
+    a = list(ok_args); a[9] = -1
+    assert lib.dkv_pack_cache(C.byref(d), *a) == inv
+    assert lib.dkv_pack_cache(C.byref(_good(interval=0)), *ok_args) == inv
+
+
 def test_binding_raises_on_error():
     d = _good(pool_kernel=2)
     with pytest.raises(dkv.DkvError):

@@ -396,3 +396,62 @@ def test_row_lse_and_single_sweep_scoring(dkv, case):
         t = two_sweep[:, cu[s]:cu[s] + n]
         assert (np.abs(g - t) <= 1e-4 * np.abs(t)).all()      # same scores as the two-sweep call
         assert np.isneginf(got[:, cu[s] + n:cu[s + 1]]).all()
+
+
+@pytest.mark.parametrize("case", ["tiny_norm", "small_bf16", "ragged_bf16", "short_seqs"])
+def test_pack_cache_equals_the_oracles_final_cache(dkv, case):
+    """dkv_pack_cache lays the valid rows of every (sequence, layer, head) block next to each other: the oracle's
+    K^c, V^c (first n_l gathered rows, then the window rows), built from the GPU's own index lists and final
+    counts, bit for bit; offsets are the running sums of Hkv * (w_q + n); a capacity that is too small leaves
+    the blocks that do not fit unwritten."""
+    cfg = (small_cfg("short_seqs", seqlens=(32, 200, 20), L=2, interval=2, layer_max=64, mean_budget=16)
+           if case == "short_seqs" else CASES[case])
+    comp = Compressor(cfg)
+    host = []
+    for l in range(cfg.L):
+        data = W.make_layer(cfg, l)
+        host.append(data)
+        dev = to_device(cfg, data)
+        comp.step(l, dev["q_win"], dev["k"], dev["v"])
+    kp, vp, off = comp.pack()
+    torch.cuda.synchronize()
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    kp, vp, off = kp.float().cpu().numpy(), vp.float().cpu().numpy(), off.cpu().numpy()
+    cu, w = cfg.cu_seqlens, cfg.w
+    row = 0
+    for s in range(cfg.n_seqs):
+        S = cfg.seqlens[s]
+        wq = min(w, S)
+        for l in range(cfg.L):
+            n = int(counts[s, l])
+            assert off[s * cfg.L + l] == row
+            k_s, v_s = host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]]
+            for h in range(cfg.Hkv):
+                sel = idx[l, s][h, :n]
+                want_k = np.concatenate([k_s[h][sel], k_s[h][S - wq:]], axis=0)      # the listing's cat order
+                want_v = np.concatenate([v_s[h][sel], v_s[h][S - wq:]], axis=0)
+                assert np.array_equal(kp[row:row + wq + n], want_k), (s, l, h)
+                assert np.array_equal(vp[row:row + wq + n], want_v), (s, l, h)
+                row += wq + n
+    assert off[-1] == row and (kp[row:] == 0).all()
+    # the same selection through the oracle's own cache() for one sequence that is longer than the window
+    s = 1 if case in ("ragged_bf16", "short_seqs") else 0
+    if case == "short_seqs":
+        return
+    r = _oracle_on_gpu_scores(cfg, comp.scores.cpu().numpy())[s]
+    full = O.compress([(host[l]["q_win"][s], host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]])
+                       for l in range(cfg.L)], cfg.L, w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval,
+                      scores_override=r.A)
+    for l in range(cfg.L):
+        kc, vc = full.cache(l, w)
+        o = off[s * cfg.L + l]
+        rows = kc.shape[1]
+        for h in range(cfg.Hkv):
+            assert np.array_equal(kp[o + h * rows:o + (h + 1) * rows], kc[h])
+            assert np.array_equal(vp[o + h * rows:o + (h + 1) * rows], vc[h])
+    # too small a capacity: only the blocks that fit are written
+    cap = int(off[cfg.L])                       # exactly the blocks of sequence 0
+    kp2, vp2, off2 = comp.pack(capacity_rows=cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(off2.cpu().numpy(), off)
+    assert np.array_equal(kp2.float().cpu().numpy(), kp[:cap])
