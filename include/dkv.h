@@ -15,7 +15,8 @@
  *   - all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - arguments are validated on the host before anything is launched; on a negative status nothing
  *     was enqueued.
- *   - sequences are packed along the token axis: sequence s owns tokens [cu_seqlens[s], cu_seqlens[s+1]);
+ *   - sequences are packed along the token axis: sequence s owns tokens [cu_seqlens[s], cu_seqlens[s+1]),
+ *     cu_seqlens[0] = 0 and cu_seqlens[n_seqs] = total_tokens;
  *     its length S_s must be >= window for its scores to be meaningful; a sequence with S_s <= window
  *     has no candidate positions (count 0) and only its existing window rows are copied.
  *   - "prefix" of a sequence = its first S' = S - window positions: the candidates for retention.

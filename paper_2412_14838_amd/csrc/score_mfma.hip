@@ -178,9 +178,18 @@ __device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&q
 // Linear chunk index -> (sequence, chunk) for chunks of `chunk` items over (length - window_off) items per
 // sequence; also returns the number of chunks of (length) items in the earlier sequences (first_full) and in
 // this one (n_full): the statistics kernel cuts all S keys, the emit kernel the S' prefix outputs.
-__device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, int chunk, int window_off, int b,
-                                   int& seq, int& c, int& nc, int& seq_begin, int& seq_len, int& first_full,
-                                   int& n_full) {
+// A single sequence spans [0, total_tokens) (cu_seqlens[0] = 0, cu_seqlens[1] = total_tokens): nothing is read.
+__device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, int total_tokens, int chunk,
+                                   int window_off, int b, int& seq, int& c, int& nc, int& seq_begin, int& seq_len,
+                                   int& first_full, int& n_full) {
+  if (n_seqs == 1) {
+    int items = total_tokens - window_off;
+    items = items > 0 ? items : 0;
+    const int n = (items + chunk - 1) / chunk;
+    seq = 0; c = b; nc = n; seq_begin = 0; seq_len = total_tokens; first_full = 0;
+    n_full = (total_tokens + chunk - 1) / chunk;
+    return b < n;
+  }
   int begin = cu[0];
   int full = 0;
   for (int s = 0; s < n_seqs; ++s) {
@@ -218,7 +227,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   char* qbuf = smem + 2 * TL::kTileBytes;                                      // Q staging, at the very start
 
   int seq, c, nc, begin, S, first_full, n_full;
-  if (!find_chunk2(cu, p.n_seqs, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
+  if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rs = wave % RS, ks = wave / RS;
@@ -231,14 +240,15 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const char* __restrict__ k_chunk =
       k + ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
   const uint32_t stride_b = (uint32_t)stride_token_b;
-  // All first loads are issued together (two key tiles, then the Q block): one memory latency, not three.
+  // All first loads are issued together, in the order they are needed (loads return in order): key tile 0 and
+  // the Q block for the first MFMA tile, then key tile 1, whose arrival the first MFMA tile does not wait for.
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
   bf16x8 qf[2][8];
   if (QStage<RS, KS>::kStatsViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
   else load_q_frags(q_head, rs, p.rows, qf);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   int limit[2];                                     // last key (chunk-relative) visible to this lane's row
@@ -247,13 +257,13 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
 
   store_tile<RS, KS>(tiles, reg);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
   if (QStage<RS, KS>::kStatsViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
   __syncthreads();
   if (QStage<RS, KS>::kStatsViaLds) read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<true>(tiles + lane_tile, qf, acc);
-  __syncthreads();                                  // buffer 0 is rewritten by the first step
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  __syncthreads();                                  // tile 1 is in place; buffer 0 is rewritten by the first step
   const int lim_all = prefix_rel < len ? prefix_rel : len;
   // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
   // Tiles past the chunk are fully masked (they add exp2(-inf) = 0), so the step is branch-free but for the mask.
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
 
   const int half = p.half;
   int seq, c, nc, begin, S, first_full, n_full;
-  if (!find_chunk2(cu, p.n_seqs, chunk, p.w, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
+  if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, p.w, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   const int head = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rs = wave % RS, ks = wave / RS;
@@ -382,23 +392,24 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   // All first loads are issued together (two key tiles, the Q block, the row statistics): one memory latency.
   // Tiles are taken from the last to the first: the statistics kernel, which ran first to last over the same
   // chunks on the same compute units, left its last tiles in the L2 of this compute die.
+  // The first loads are issued in the order they are needed (loads return in order): the first key tile and the
+  // Q block, then the second key tile, whose arrival the first MFMA tile does not wait for.
   typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
   const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
   bf16x8 qf[2][8];
   if (QStage<RS, KS>::kEmitViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
   else load_q_frags(q_head, rs, p.rows, qf);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
 
   // ---- lse2[row] of this (sequence, head): supplied by the caller (natural log, one per window row), or merged
   // from the chunk partials of the statistics kernel
   if (lse_in != nullptr) {
     store_tile<RS, KS>(tiles, reg);
-    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
     if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
     if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
       lse_s[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
-    __syncthreads();                                         // the tiles are in place
+    __syncthreads();                                         // the first tile is in place
   } else {
     const int r = tid % kRows, q = tid / kRows;              // KS groups of kRows threads
     const float2* __restrict__ src =
@@ -414,7 +425,6 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     }
     mstage[q * kRows + r] = make_float2(M, Lsum);
     store_tile<RS, KS>(tiles, reg);
-    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
     if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
     __syncthreads();
     if (tid < kRows) {
@@ -436,7 +446,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   if (QStage<RS, KS>::kEmitViaLds) read_q_frags(qbuf, rs, qf);
   floatx16 acc[2], nxt[2];
   mfma_tile<false>(tiles + lane_tile, qf, acc);
-  __syncthreads();
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  __syncthreads();                                           // the second tile is in place; lse_s is complete
   // lse2 of the rows this lane accumulates: register j of tile t is row rs*64 + t*32 + 8*(j/4) + 4*(lane/32) + j%4
   float lse_r[2][16];
 #pragma unroll
