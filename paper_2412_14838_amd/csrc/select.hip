@@ -97,26 +97,35 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
     const int hshift = pass == 0 ? 32 : (pass == 1 ? 21 : 10);   // bits above this digit
-    for (int b = tid; b < kRadixBins * kHistCopies; b += kSelThreads) hist[b] = 0;
+    // pass 0 sees every element (lanes that share a digit spread over 8 copies of the histogram); the later
+    // passes only the elements that share the digits found so far: 2 copies, less to clear and to add up
+    const int copies = pass == 0 ? kHistCopies : 2;
+    for (int b = tid; b < kRadixBins * copies; b += kSelThreads) hist[b] = 0;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kSelPerThread; ++j) {
       const uint32_t u = v[j];
       const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
       if (j * kSelThreads + tid < n_res && match)
-        atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * kHistCopies + (lane & (kHistCopies - 1))], 1);
+        atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
     }
     for (int i = kSelResident + tid; i < n; i += kSelThreads) {
       const uint32_t u = row[i];
       const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
-      if (match) atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * kHistCopies + (lane & (kHistCopies - 1))], 1);
+      if (match) atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
     }
     __syncthreads();
     // thread t owns digits 2047 - 2t and 2046 - 2t (scanned from the top)
     const int hi = kRadixBins - 1 - 2 * tid, lo = hi - 1;
     int c_hi = 0, c_lo = 0;
+    if (pass == 0) {
 #pragma unroll
-    for (int c = 0; c < kHistCopies; ++c) { c_hi += hist[hi * kHistCopies + c]; c_lo += hist[lo * kHistCopies + c]; }
+      for (int c = 0; c < kHistCopies; ++c) { c_hi += hist[hi * kHistCopies + c]; c_lo += hist[lo * kHistCopies + c]; }
+    } else {   // lo and hi are adjacent: 4 consecutive words
+      const int4 q = *reinterpret_cast<const int4*>(&hist[lo * 2]);
+      c_lo = q.x + q.y;
+      c_hi = q.z + q.w;
+    }
     const int above = block_exclusive_scan(c_hi + c_lo, scratch);
     if (above < rem && rem <= above + c_hi) { picked[0] = hi; picked[1] = above; }
     else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { picked[0] = lo; picked[1] = above + c_hi; }
@@ -135,20 +144,24 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   if (tid == 0) n_greater_slots = 0;
   for (int j = k + tid; j < 2048; j += kSelThreads) keys[j] = ~0ull;      // pads sort to the end
   __syncthreads();
+  // elements above T: every thread counts its own, one scan over the threads gives it a contiguous range of
+  // slots (any order will do); elements equal to T: counted per (j, wavefront) for the position-ordered pick below
+  int my_gt = 0;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
     const int i = j * kSelThreads + tid;
     const uint32_t u = v[j];
-    const bool gt = i < n_res && u > T;
-    const bool eq = i < n_res && u == T;
-    const unsigned long long gmask = __ballot(gt), emask = __ballot(eq);
+    my_gt += i < n_res && u > T ? 1 : 0;
+    const unsigned long long emask = __ballot(i < n_res && u == T);
     if (lane == 0) eq_base[j * kSelWaves + wv] = __popcll(emask);
-    if (gmask) {
-      int base = 0;
-      if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
-      base = __shfl(base, 0);
-      if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
-    }
+  }
+  int slot = block_exclusive_scan(my_gt, scratch);
+  if (tid == kSelThreads - 1) n_greater_slots = slot + my_gt;     // the tail of a long row continues from here
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    const int i = j * kSelThreads + tid;
+    const uint32_t u = v[j];
+    if (i < n_res && u > T) keys[slot++] = ((u64)(~u) << 32) | (uint32_t)i;
   }
   __syncthreads();
   {
