@@ -164,6 +164,38 @@ def gather_kv(k: np.ndarray, v: np.ndarray, idx: np.ndarray, w: int) -> Tuple[np
 
 
 # --------------------------------------------------------------------------
+# Decoding over the compressed cache (Section 4.3: the decoding phase is unchanged - ordinary attention of the
+# new token over whatever keys and values the cache holds)
+# --------------------------------------------------------------------------
+def decode_attention(q_new: np.ndarray, kc: np.ndarray, vc: np.ndarray,
+                     scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Attention of one new token over one layer's compressed cache.
+
+    q_new [Hq, d]; kc, vc [Hkv, R, d] (R = retained + window rows, any order: the result does not depend on it).
+    out[g] = sum_r softmax_r(scale * <q_new[g], kc[g // G, r]>) * vc[g // G, r]  -> [Hq, d] float64,
+    lse[g] = log sum_r exp(scale * <q_new[g], kc[g // G, r]>)                    -> [Hq]    float64.
+    """
+    q = np.asarray(q_new, dtype=np.float64)
+    k = np.asarray(kc, dtype=np.float64)
+    v = np.asarray(vc, dtype=np.float64)
+    Hq, d = q.shape
+    Hkv, R, _ = k.shape
+    assert Hq % Hkv == 0 and R >= 1
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((Hq, d), dtype=np.float64)
+    lse = np.empty(Hq, dtype=np.float64)
+    for g in range(Hq):
+        x = scale * (k[g // G] @ q[g])
+        m = x.max()
+        e = np.exp(x - m)
+        out[g] = (e / e.sum()) @ v[g // G]
+        lse[g] = m + np.log(e.sum())
+    return out, lse
+
+
+# --------------------------------------------------------------------------
 # Eq. 4-6 / Algorithm 1 "Update_Buffer_Length"
 # --------------------------------------------------------------------------
 def layer_hit_counts(A_list: Sequence[np.ndarray], mean_budget: int) -> np.ndarray:

@@ -332,6 +332,35 @@ def test_scores_from_supplied_lse():
     assert abs(base[h, s] - np.float32(acc)) <= 1e-6 * acc
 
 
+# ---------------------------------------------------------------- decoding over the compressed cache
+def test_decode_attention_against_library_and_special_cases():
+    """Ordinary softmax attention of one query per head (Section 4.3): equals torch's scaled_dot_product_attention
+    with the KV heads repeated G times; does not depend on the order of the cached rows; one row returns that row
+    of V; a zero query returns the mean of V and lse = log R."""
+    Hq, Hkv, d, R = 6, 2, 16, 37
+    G = Hq // Hkv
+    q, k, v = _rand((Hq, d), 41), _rand((Hkv, R, d), 42), _rand((Hkv, R, d), 43)
+    out, lse = O.decode_attention(q, k, v)
+    tq = torch.tensor(q)[:, None, :]                                 # [Hq, 1, d]
+    tk = torch.tensor(np.repeat(k, G, axis=0))                       # [Hq, R, d]
+    tv = torch.tensor(np.repeat(v, G, axis=0))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[:, 0, :].numpy()
+    assert np.allclose(out, ref, rtol=1e-10, atol=1e-12)
+    x = torch.einsum("gd,grd->gr", torch.tensor(q), tk) / math.sqrt(d)
+    assert np.allclose(lse, torch.logsumexp(x, dim=1).numpy(), atol=1e-12)
+    perm = np.random.default_rng(5).permutation(R)
+    out_p, lse_p = O.decode_attention(q, k[:, perm], v[:, perm])
+    assert np.allclose(out_p, out, atol=1e-12) and np.allclose(lse_p, lse, atol=1e-12)
+    one, _ = O.decode_attention(q, k[:, 3:4], v[:, 3:4])
+    assert np.allclose(one, np.repeat(v[:, 3], G, axis=0), atol=1e-13)
+    zero, lse0 = O.decode_attention(np.zeros((Hq, d)), k, v)
+    assert np.allclose(zero, np.repeat(v.mean(axis=1), G, axis=0), atol=1e-12) and np.allclose(lse0, math.log(R))
+    # the scale: doubling q equals doubling the scale
+    a, _ = O.decode_attention(2 * q, k, v)
+    b, _ = O.decode_attention(q, k, v, scale=2.0 / math.sqrt(d))
+    assert np.allclose(a, b, atol=1e-12)
+
+
 # ---------------------------------------------------------------- planted mistakes must be caught
 def test_pins_catch_planted_mistakes(monkeypatch):
     """Plant plausible mistakes in the oracle (on the CPU) and check that a pin fails."""
@@ -369,6 +398,19 @@ def test_pins_catch_planted_mistakes(monkeypatch):
                         lambda q, k, lse, P, scale=None, row_scale=1.0: orig_from(q, k, -np.asarray(lse), P, scale, row_scale))
     assert fails(test_scores_from_supplied_lse)
     monkeypatch.setattr(O, "score_window_from_lse", orig_from)
+
+    orig_dec = O.decode_attention
+
+    def wrong_head(q, k, v, scale=None):      # KV head by g % Hkv instead of g // G
+        Hq, Hkv = np.asarray(q).shape[0], np.asarray(k).shape[0]
+        order = [g % Hkv for g in range(Hq)]
+        return orig_dec(q, np.asarray(k)[order], np.asarray(v)[order], scale)
+
+    monkeypatch.setattr(O, "decode_attention", wrong_head)
+    assert fails(test_decode_attention_against_library_and_special_cases)
+    monkeypatch.setattr(O, "decode_attention", lambda q, k, v, scale=None: orig_dec(q, k, v, 1.0 if scale is None else scale))
+    assert fails(test_decode_attention_against_library_and_special_cases)
+    monkeypatch.setattr(O, "decode_attention", orig_dec)
 
     orig_pool = O.max_pool_prefix
     monkeypatch.setattr(O, "max_pool_prefix", lambda a, w, P: orig_pool(a, 0, P)[:, :a.shape[1] - w])
