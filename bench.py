@@ -173,6 +173,26 @@ def main():
     roofline["single_sweep_lse"] = {"us_per_layer": single_us,
                                     "hbm_frac": (k_bytes + q_bytes + a_bytes) / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
+    # ---- decode attention of one new token per sequence over the final compressed cache, all layers (reported
+    # beside the main figure, not part of `value`)
+    q_new = torch.randn((cfg.n_seqs, cfg.Hq, d), device="cuda").to(comp.tdtype)
+    dec_out = torch.empty((cfg.n_seqs, cfg.Hq, d), dtype=torch.float32, device="cuda")
+    for l in range(cfg.L):
+        comp.decode_attention(l, q_new, dec_out)
+    torch.cuda.synchronize()
+    dkv.dkv_profile_begin(2 * cfg.L * args.steps + 16)
+    for _ in range(args.steps):
+        for l in range(cfg.L):
+            comp.decode_attention(l, q_new, dec_out)
+    torch.cuda.synchronize()
+    rec = [us for name, us in dkv.dkv_profile_end(2 * cfg.L * args.steps + 16) if name == "decode"]
+    dec_us = sum(rec) / max(args.steps * cfg.L, 1)                       # both kernels of a layer
+    counts_h = comp.counts.cpu().numpy()
+    rows = sum(min(cfg.w, S) * cfg.L + int(counts_h[q].sum()) for q, S in enumerate(cfg.seqlens))
+    dec_bytes = rows * cfg.Hkv * d * elt * 2 / cfg.L                      # K and V rows read per layer
+    roofline["decode_attention"] = {"us_per_layer": dec_us, "cache_bytes_per_layer": dec_bytes,
+                                    "hbm_frac": dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
     out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

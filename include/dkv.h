@@ -49,6 +49,7 @@ enum {
 #define DKV_MAX_ROWS 256       /* G * window: score rows per KV head         */
 #define DKV_MAX_SEQS 4096
 #define DKV_MAX_LAYERS 512
+#define DKV_MAX_DECODE_GROUP 16   /* query heads per KV head dkv_decode_attention handles */
 #define DKV_MAX_SELECT_LAYERS 8   /* layers one dkv_select_topk_layers call may cover */
 
 /* Problem descriptor (host memory, read during the call only). Symbols as in Algorithm 1. */
@@ -82,7 +83,8 @@ enum {
   DKV_KERNEL_FILL = 7,
   DKV_KERNEL_SELECT_ORDER = 8,
   DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
-  DKV_KERNEL_PACK = 10            /* tight packing of the final cache                 */
+  DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
+  DKV_KERNEL_DECODE = 11          /* decode attention over the compressed cache       */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */
@@ -265,6 +267,25 @@ int dkv_gather_kv_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_la
 int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_t* counts, const void* kb_all,
                    const void* vb_all, int64_t stride_layer, int64_t stride_seq, int64_t stride_head, void* k_packed,
                    void* v_packed, int64_t capacity_rows, int64_t* row_offsets, void* stream);
+
+/*
+ * Decode-phase attention of one new token per sequence over the compressed cache of layer `layer` (Section 4.3:
+ * the decoding phase is unchanged, i.e. ordinary softmax attention over the keys and values the prefill
+ * retained). For sequence q and query head g (KV head h = g / G):
+ *     out[q][g][:] = sum_r softmax_r(softmax_scale * <q_new[q][g], K_r>) * V_r
+ * over the valid rows r of cache block (layer, q, h): its w_q = min(ws, S_q) window rows and its counts[q][layer]
+ * retained rows (the new token's own key and value are the caller's to append; they are not part of this sum).
+ * q_new    [n_seqs][Hq][d], element type of the descriptor.
+ * kb, vb   the layer's block of the cache dkv_gather_kv wrote: element (q, h, slot, j) at
+ *          kb[q * stride_seq + h * stride_head + slot * d + j] (elements).
+ * out      fp32 [n_seqs][Hq][d]; lse_out fp32 [n_seqs][Hq] (natural log of the softmax denominator) or NULL.
+ *          A sequence without any cached row gets zeros and lse = -inf.
+ * Hq / Hkv must not exceed DKV_MAX_DECODE_GROUP. fp32 arithmetic. Two kernels (the cache rows are split over
+ * workgroups, then merged); the split results live in the workspace.
+ */
+int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new, const void* kb, const void* vb,
+                         int64_t stride_seq, int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts,
+                         float* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

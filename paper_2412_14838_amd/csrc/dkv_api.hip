@@ -316,4 +316,26 @@ int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 
+int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new, const void* kb, const void* vb,
+                         int64_t stride_seq, int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts,
+                         float* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!q_new || !kb || !vb || !cu_seqlens || !counts || !out) return DKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= desc->n_layers) return DKV_ERR_INVALID_ARG;
+  if (!aligned16(kb) || !aligned16(vb)) return DKV_ERR_INVALID_ARG;
+  if (desc->n_q_heads / desc->n_kv_heads > DKV_MAX_DECODE_GROUP) return DKV_ERR_UNSUPPORTED;
+  const int64_t elt = desc->dtype == DKV_BF16 ? 2 : 4;
+  const int64_t block = (int64_t)(desc->window + desc->layer_max) * desc->head_dim;
+  if (stride_head < block || stride_seq < stride_head * desc->n_kv_heads) return DKV_ERR_INVALID_ARG;
+  if ((stride_head * elt) % 16 != 0 || (stride_seq * elt) % 16 != 0) return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_decode(p, desc->dtype, layer, q_new, kb, vb, stride_seq, stride_head, cu_seqlens, counts,
+                                     out, lse_out, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
 }  // extern "C"

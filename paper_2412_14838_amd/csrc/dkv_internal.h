@@ -18,6 +18,11 @@ constexpr int kRadixBins = 2048;       // 11-bit digits; 3 passes cover bits 31.
 // ----------------------------------------------------------------------------------------------
 // Workspace layout (byte offsets, all 256-byte aligned)
 // ----------------------------------------------------------------------------------------------
+constexpr int kDecodeMaxGroup = 16;    // query heads per KV head the decode kernel handles
+constexpr int kDecodeMaxSlabs = (DKV_MAX_LAYER_MAX + DKV_MAX_ROWS + 31) / 32;   // slabs of one cache block at most
+// cache rows per workgroup of the decode kernel, by element size
+constexpr int decode_slab_rows(size_t elt_bytes) { return elt_bytes == 2 ? 64 : 32; }
+
 struct WorkspaceLayout {
   size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
@@ -28,6 +33,7 @@ struct WorkspaceLayout {
   size_t tot2;         // int32 [n_seqs][1024]           last digit, elements sharing the two digits above
   size_t hist2;        // int32 [n_seqs][L][1024]        the same per layer
   size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
+  size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
   size_t total;
   int rows_pad;        // G*w rounded up to 64
   int chunks_max;      // upper bound on statistics chunks over all sequences
@@ -45,6 +51,8 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   size_t off = 0;
   w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
   w.select_keys = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
+  w.decode_partials = off;
+  off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
   w.header = off;   off += align256(8 * sizeof(int32_t));
   w.tot0 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
   w.tot1 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));   // tot1 .. above: cleared per call
@@ -113,6 +121,9 @@ hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, 
                              const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head,
                              void* k_packed, void* v_packed, int64_t capacity_rows, int64_t* row_offsets,
                              hipStream_t st);
+hipError_t launch_decode(const Params& p, int dtype, int layer, const void* q_new, const void* kb, const void* vb,
+                         int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts, float* out,
+                         float* lse_out, char* ws, const WorkspaceLayout& wl, hipStream_t st);
 hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
                             int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
                             const WorkspaceLayout& wl, hipStream_t st);

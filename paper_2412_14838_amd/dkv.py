@@ -19,7 +19,7 @@ DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAU
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
-           "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache")
+           "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention")
 
 
 class dkv_desc(C.Structure):
@@ -74,6 +74,8 @@ def load() -> C.CDLL:
     lib.dkv_gather_kv_layers.argtypes = [D, I32, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, I64, P]
     lib.dkv_pack_cache.restype = C.c_int
     lib.dkv_pack_cache.argtypes = [D, P, P, P, P, I64, I64, I64, P, P, I64, P, P]
+    lib.dkv_decode_attention.restype = C.c_int
+    lib.dkv_decode_attention.argtypes = [D, I32, P, P, P, I64, I64, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
@@ -128,7 +130,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "select_order", "score_lse", "pack")
+                "rebalance_final", "fill", "select_order", "score_lse", "pack", "decode")
 
 
 def dkv_profile_begin(capacity: int) -> None:
@@ -226,6 +228,14 @@ def dkv_pack_cache(desc, cu_seqlens, counts, kb_all, vb_all, stride_layer, strid
     _check(load().dkv_pack_cache(C.byref(desc), _ptr(cu_seqlens), _ptr(counts), _ptr(kb_all), _ptr(vb_all),
                                  stride_layer, stride_seq, stride_head, _ptr(k_packed), _ptr(v_packed), capacity_rows,
                                  _ptr(row_offsets), _stream(stream)), "dkv_pack_cache")
+
+
+def dkv_decode_attention(desc, layer, q_new, kb, vb, stride_seq, stride_head, cu_seqlens, counts, out, lse_out, workspace,
+                         stream=None) -> None:
+    _check(load().dkv_decode_attention(C.byref(desc), layer, _ptr(q_new), _ptr(kb), _ptr(vb), stride_seq, stride_head,
+                                       _ptr(cu_seqlens), _ptr(counts), _ptr(out), _ptr(lse_out), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_decode_attention")
 
 
 def alloc_workspace(desc, device="cuda"):

@@ -98,6 +98,12 @@ class Compressor:
                            cfg.Hkv * self.slots * d, self.slots * d, kp, vp, capacity_rows, off, stream)
         return kp, vp, off
 
+    def decode_attention(self, layer, q_new, out, lse_out=None, stream=None):
+        """Attention of one new token per sequence (q_new [n_seqs][Hq][d]) over layer `layer` of the compressed cache."""
+        d = self.cfg.d
+        dkv.dkv_decode_attention(self.desc, layer, q_new, self.kb[layer], self.vb[layer], self.cfg.Hkv * self.slots * d,
+                                 self.slots * d, self.cu, self.counts, out, lse_out, self.ws, stream)
+
     def rebalance(self, layers_done, stream=None):
         dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
                           stream)

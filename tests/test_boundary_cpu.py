@@ -180,6 +180,30 @@ def test_pack_cache_validates_its_arguments(lib):
     assert lib.dkv_pack_cache(C.byref(_good(interval=0)), *ok_args) == inv
 
 
+def test_decode_attention_validates_its_arguments(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv, wsp = dkv.DKV_ERR_INVALID_ARG, dkv.DKV_ERR_WORKSPACE
+    sq, sh = 2 * 272 * 64, 272 * 64
+    ok = [0, fake, fake, fake, sq, sh, fake, fake, fake, None, fake, need, None]
+    for i in (1, 2, 3, 6, 7, 8):                 # each required pointer in turn (lse_out may be null)
+        a = list(ok)
+        a[i] = None
+        assert lib.dkv_decode_attention(C.byref(d), *a) == inv
+    for layer in (-1, 4):
+        a = list(ok); a[0] = layer
+        assert lib.dkv_decode_attention(C.byref(d), *a) == inv
+    a = list(ok); a[5] = sh - 64                 # head stride smaller than a block
+    assert lib.dkv_decode_attention(C.byref(d), *a) == inv
+    a = list(ok); a[10] = None
+    assert lib.dkv_decode_attention(C.byref(d), *a) == wsp
+    a = list(ok); a[11] = need - 1
+    assert lib.dkv_decode_attention(C.byref(d), *a) == wsp
+    wide = _good(n_q_heads=34, n_kv_heads=2, window=4)        # 17 query heads per KV head
+    assert lib.dkv_decode_attention(C.byref(wide), *ok[:11], dkv.dkv_workspace_bytes(wide), None) == dkv.DKV_ERR_UNSUPPORTED
+
+
 def test_binding_raises_on_error():
     d = _good(pool_kernel=2)
     with pytest.raises(dkv.DkvError):

@@ -173,6 +173,29 @@ def test_full_single_sweep_scoring_from_row_lse(dkv, name):
         assert np.abs(lse_h[s, h * G:(h + 1) * G] - ref).max() <= 1e-4
 
 
+def test_full_decode_attention_over_final_cache(dkv):
+    """Config 2 at full size: after the whole compression, decode attention over sampled layers of the final cache
+    against the oracle's attention over the rows the GPU's lists and final counts name."""
+    cfg = W.standard_configs()["llama3_8b_8k"].with_(L=8)
+    comp, host, snaps = run_config(cfg, list(range(cfg.L)), group=4)
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    q_new = W.round_to_bf16(np.random.default_rng(3).standard_normal((cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32))
+    q_dev = torch.from_numpy(q_new).to(device="cuda", dtype=comp.tdtype)
+    out = torch.empty((cfg.n_seqs, cfg.Hq, cfg.d), dtype=torch.float32, device="cuda")
+    lse = torch.empty((cfg.n_seqs, cfg.Hq), dtype=torch.float32, device="cuda")
+    S, w = cfg.seqlens[0], cfg.w
+    for l in (0, 3, 7):
+        comp.decode_attention(l, q_dev, out, lse)
+        torch.cuda.synchronize()
+        n = int(counts[0, l])
+        k_s, v_s = host[l]["k"], host[l]["v"]
+        kc = np.stack([np.concatenate([k_s[h][idx[l, 0][h, :n]], k_s[h][S - w:]]) for h in range(cfg.Hkv)])
+        vc = np.stack([np.concatenate([v_s[h][idx[l, 0][h, :n]], v_s[h][S - w:]]) for h in range(cfg.Hkv)])
+        ref, ref_lse = O.decode_attention(q_new[0], kc, vc)
+        assert np.abs(out[0].cpu().numpy() - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), l
+        assert np.abs(lse[0].cpu().numpy() - ref_lse).max() <= 2e-5 * np.abs(ref_lse).max(), l
+
+
 def test_calibrated_planting_gives_layer_varying_budgets(dkv):
     """With the planted keys scaled so that they dominate (plant_normalize), the layers with many planted keys
     win the global selection: budgets vary by layer, and every check of the standard run still holds."""

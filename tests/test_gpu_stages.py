@@ -455,3 +455,45 @@ def test_pack_cache_equals_the_oracles_final_cache(dkv, case):
     torch.cuda.synchronize()
     assert np.array_equal(off2.cpu().numpy(), off)
     assert np.array_equal(kp2.float().cpu().numpy(), kp[:cap])
+
+
+@pytest.mark.parametrize("case", ["tiny_norm", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_bf16",
+                                  "ragged_f32", "short_seqs"])
+def test_decode_attention_over_the_compressed_cache(dkv, case):
+    """After a whole prefill compression, attention of one new token per sequence over every layer's compressed
+    cache equals the oracle's softmax attention over the same rows (the rows the GPU's index lists and final
+    counts name, taken from the host tensors), outputs and log-sum-exp, to fp32 accuracy."""
+    cfg = (small_cfg("short_seqs", seqlens=(32, 200, 20), L=2, interval=2, layer_max=64, mean_budget=16)
+           if case == "short_seqs" else CASES[case])
+    comp = Compressor(cfg)
+    host = []
+    for l in range(cfg.L):
+        data = W.make_layer(cfg, l)
+        host.append(data)
+        dev = to_device(cfg, data)
+        comp.step(l, dev["q_win"], dev["k"], dev["v"])
+    rng = np.random.default_rng(17)
+    q_new = rng.standard_normal((cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        q_new = W.round_to_bf16(q_new)
+    q_dev = torch.from_numpy(q_new).to(device="cuda", dtype=comp.tdtype)
+    out = torch.full((cfg.n_seqs, cfg.Hq, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((cfg.n_seqs, cfg.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    cu, w = cfg.cu_seqlens, cfg.w
+    for l in range(cfg.L):
+        comp.decode_attention(l, q_dev, out, lse)
+        torch.cuda.synchronize()
+        got, got_lse = out.cpu().numpy(), lse.cpu().numpy()
+        for s in range(cfg.n_seqs):
+            S = cfg.seqlens[s]
+            wq, n = min(w, S), int(counts[s, l])
+            k_s, v_s = host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]]
+            kc = np.stack([np.concatenate([k_s[h][idx[l, s][h, :n]], k_s[h][S - wq:]]) for h in range(cfg.Hkv)])
+            vc = np.stack([np.concatenate([v_s[h][idx[l, s][h, :n]], v_s[h][S - wq:]]) for h in range(cfg.Hkv)])
+            ref, ref_lse = O.decode_attention(q_new[s], kc, vc)
+            assert np.abs(got[s] - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), (l, s)
+            assert np.abs(got_lse[s] - ref_lse).max() <= 2e-5 * max(1.0, np.abs(ref_lse).max()), (l, s)
+    # without the optional output
+    comp.decode_attention(0, q_dev, out, None)
+    torch.cuda.synchronize()
