@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--workload", default="mistral_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--group", type=int, default=0,
-                    help="layers whose selection and compaction are issued together (0: one update interval, "
+                    help="layers whose scoring, selection and compaction are issued together (0: one update interval, "
                          "1: layer by layer as in Algorithm 1)")
     ap.add_argument("--overlap", action="store_true",
                     help="select/gather/rebalance of layer l on a second stream, next to the scoring of layer l+1")
@@ -134,8 +134,13 @@ def main():
     k_bytes = cfg.Hkv * T * d * elt                 # every key row read once per sweep
     q_bytes = cfg.n_seqs * cfg.Hq * cfg.w * d * elt
     a_bytes = cfg.Hkv * T * 4                       # pooled fp32 scores written
-    alg = {"score_stats": k_bytes + q_bytes, "score_emit": k_bytes + q_bytes + a_bytes}
-    dom = max(alg, key=lambda n: stage_us_per_launch[n])
+    # a score launch covers `group` layers (fewer at the end of an interval): bytes per launch = bytes per layer
+    # x the average number of layers per launch
+    layers_per_launch = {n: cfg.L * args.steps / kernel_n[n] for n in ("score_stats", "score_emit")}
+    alg_layer = {"score_stats": k_bytes + q_bytes, "score_emit": k_bytes + q_bytes + a_bytes}
+    alg = {n: alg_layer[n] * layers_per_launch[n] for n in alg_layer}
+    us_per_layer = {n: stage_us_per_launch[n] / layers_per_launch[n] for n in alg_layer}
+    dom = max(alg, key=lambda n: us_per_layer[n])
     achieved = alg[dom] / (stage_us_per_launch[dom] * 1e-6) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -144,11 +149,12 @@ def main():
             traffic = json.load(open(tpath)).get(cfg.name, {}).get(dom, {}).get("total_bytes")
         except Exception:
             traffic = None
-    score_us = stage_us_per_launch["score_stats"] + stage_us_per_launch["score_emit"]
+    score_us = us_per_layer["score_stats"] + us_per_layer["score_emit"]
     flops_per_sweep = 2.0 * cfg.Hq * cfg.w * T * d
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": alg[dom], "us_per_launch": stage_us_per_launch[dom],
+                "layers_per_launch": layers_per_launch[dom], "bytes_per_layer": alg_layer[dom],
                 # the whole score step (K counted ONCE although both sweeps read it) and its MFMA rate
                 "score_step": {"us_per_layer": score_us,
                                "hbm_frac_k_once": (k_bytes + q_bytes + a_bytes) / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
@@ -196,7 +202,7 @@ def main():
     out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": cfg.dtype, "data": "synthetic", "streams": 2 if args.overlap else 1, "layers_per_select_call": group,
+           "dtype": cfg.dtype, "data": "synthetic", "streams": 2 if args.overlap else 1, "layers_per_call": group,
            "config": {"workload": cfg.name, "layers": cfg.L, "q_heads": cfg.Hq, "kv_heads": cfg.Hkv, "head_dim": d,
                       "context": list(cfg.seqlens), "window": cfg.w, "pool": cfg.P, "mean_budget": cfg.mean_budget,
                       "layer_max": cfg.layer_max, "interval": cfg.interval},

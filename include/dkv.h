@@ -129,6 +129,23 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
                      int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dkv_score_window (Eq. 1-2) for the n_layers consecutive layers [layer_begin, layer_begin + n_layers) in one call,
+ * for a caller that holds the window queries and the keys of a few layers (see dkv_select_topk_layers): a layer's
+ * scores depend on that layer's Q and K only. One launch per sweep covers all the layers; a workgroup takes its
+ * chunk of keys through the layers one after the other and fetches the next layer's first tiles while it finishes
+ * the current one, so the start-up cost of a launch is paid once per call instead of once per layer. Results are
+ * identical to n_layers dkv_score_window calls.
+ * h_q_layers, h_k_layers  HOST arrays of n_layers DEVICE pointers (Q_win and K of layer layer_begin + i), all with the
+ *                         strides given; read during the call only.
+ * scores_all              fp32 [L][Hkv][total_tokens] contiguous; the blocks of the layers of the call are written.
+ * n_layers                1 .. DKV_MAX_SELECT_LAYERS, layer_begin + n_layers <= L.
+ */
+int dkv_score_window_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* const* h_q_layers,
+                            const void* const* h_k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                            const int32_t* cu_seqlens, float* scores_all, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
  * The two kernels of dkv_score_window as separate calls with the same arguments (Eq. 1-2): first the per-row
  * softmax normalisers (log-sum-exp of every window row over all keys, kept in the workspace), then the scores.
  * dkv_score_window(...) is exactly dkv_score_window_stats(...) followed by dkv_score_window_emit(...) on the same

@@ -113,15 +113,22 @@ size_t dkv_workspace_bytes(const dkv_desc* desc) {
   return workspace_layout(*desc).total;
 }
 
-static int score_window_phases(int phases, const dkv_desc* desc, const void* q_win, const void* k,
-                               int64_t k_stride_token, int64_t k_stride_head, const int32_t* cu_seqlens,
-                               float* scores_out, int64_t scores_stride_head, void* workspace, size_t workspace_bytes,
+// Common body of the score entry points: n_layers layers (q_layers / k_layers: host arrays of device pointers),
+// scores of layer i at scores_out + i * scores_stride_layer.
+static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, const void* const* q_layers,
+                               const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                               const int32_t* cu_seqlens, float* scores_out, int64_t scores_stride_head,
+                               int64_t scores_stride_layer, void* workspace, size_t workspace_bytes,
                                const float* lse_in, float* lse_out, void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   const bool sweeps = (phases & (kPhaseStats | kPhaseEmit)) != 0;       // reads Q and K
   if (!cu_seqlens) return DKV_ERR_INVALID_ARG;
-  if (sweeps && (!q_win || !k || !aligned16(q_win) || !aligned16(k))) return DKV_ERR_INVALID_ARG;
+  if (sweeps) {
+    if (!q_layers || !k_layers) return DKV_ERR_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i)
+      if (!q_layers[i] || !k_layers[i] || !aligned16(q_layers[i]) || !aligned16(k_layers[i])) return DKV_ERR_INVALID_ARG;
+  }
   if ((phases & kPhaseEmit) && !scores_out) return DKV_ERR_INVALID_ARG;
   if ((phases & kPhaseLse) && !lse_out) return DKV_ERR_INVALID_ARG;
   st = check_kv_strides(*desc, k_stride_token, k_stride_head);
@@ -137,14 +144,18 @@ static int score_window_phases(int phases, const dkv_desc* desc, const void* q_w
   }
   if (desc->total_tokens == 0) return DKV_OK;
   const Params p = make_params(*desc);
-  hipError_t e;
+  const hipStream_t hs = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
   if (score_mfma_supported(p, desc->dtype, k_stride_token)) {
-    e = launch_score_mfma(p, phases, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
-                          static_cast<char*>(workspace), wl, lse_in, lse_out, static_cast<hipStream_t>(stream));
+    e = launch_score_mfma(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                          scores_stride_head, scores_stride_layer, static_cast<char*>(workspace), wl, lse_in, lse_out, hs);
   } else {
-    e = launch_score_generic(p, phases, desc->dtype, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, static_cast<char*>(workspace), wl, lse_in, lse_out,
-                             static_cast<hipStream_t>(stream));
+    // the vector-ALU kernels take one layer at a time (both sweeps of a layer before the next layer's)
+    for (int i = 0; i < (sweeps ? n_layers : 1) && e == hipSuccess; ++i)
+      e = launch_score_generic(p, phases, desc->dtype, sweeps ? q_layers[i] : nullptr, sweeps ? k_layers[i] : nullptr,
+                               k_stride_token, k_stride_head, cu_seqlens,
+                               scores_out ? scores_out + i * scores_stride_layer : nullptr, scores_stride_head,
+                               static_cast<char*>(workspace), wl, lse_in, lse_out, hs);
   }
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
@@ -152,38 +163,52 @@ static int score_window_phases(int phases, const dkv_desc* desc, const void* q_w
 int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                      int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                      int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
-  return score_window_phases(kPhaseStats | kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens,
-                             scores_out, scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
+  return score_window_phases(kPhaseStats | kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens,
+                             scores_out, scores_stride_head, 0, workspace, workspace_bytes, nullptr, nullptr, stream);
+}
+
+int dkv_score_window_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* const* h_q_layers,
+                            const void* const* h_k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                            const int32_t* cu_seqlens, float* scores_all, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  const int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!scores_all) return DKV_ERR_INVALID_ARG;
+  if (n_layers < 1 || n_layers > DKV_MAX_SELECT_LAYERS) return DKV_ERR_INVALID_ARG;
+  if (layer_begin < 0 || layer_begin + n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  const int64_t stride_layer = (int64_t)desc->n_kv_heads * desc->total_tokens;
+  return score_window_phases(kPhaseStats | kPhaseEmit, desc, n_layers, h_q_layers, h_k_layers, k_stride_token,
+                             k_stride_head, cu_seqlens, scores_all + layer_begin * stride_layer, desc->total_tokens,
+                             stride_layer, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int dkv_score_window_stats(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                            int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                            int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
-  return score_window_phases(kPhaseStats, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
+  return score_window_phases(kPhaseStats, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, 0, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                           int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
                           int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream) {
-  return score_window_phases(kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, workspace, workspace_bytes, nullptr, nullptr, stream);
+  return score_window_phases(kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, 0, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                          int64_t k_stride_head, const int32_t* cu_seqlens, const float* lse, float* scores_out,
                          int64_t scores_stride_head, void* stream) {
   if (!lse) return DKV_ERR_INVALID_ARG;
-  return score_window_phases(kPhaseEmit, desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                             scores_stride_head, nullptr, 0, lse, nullptr, stream);
+  return score_window_phases(kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
+                             scores_stride_head, 0, nullptr, 0, lse, nullptr, stream);
 }
 
 int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_seqlens, float* lse_out,
                 void* workspace, size_t workspace_bytes, void* stream) {
   if (!desc) return DKV_ERR_INVALID_ARG;
-  return score_window_phases(kPhaseLse, desc, nullptr, nullptr, k_stride_token,
-                             (int64_t)desc->head_dim, cu_seqlens, nullptr, 0, workspace, workspace_bytes, nullptr,
-                             lse_out, stream);
+  return score_window_phases(kPhaseLse, desc, 1, nullptr, nullptr, k_stride_token, (int64_t)desc->head_dim, cu_seqlens,
+                             nullptr, 0, 0, workspace, workspace_bytes, nullptr, lse_out, stream);
 }
 
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,

@@ -24,7 +24,8 @@ constexpr int kDecodeMaxSlabs = (DKV_MAX_LAYER_MAX + DKV_MAX_ROWS + 31) / 32;   
 constexpr int decode_slab_rows(size_t elt_bytes) { return elt_bytes == 2 ? 64 : 32; }
 
 struct WorkspaceLayout {
-  size_t partials;     // float2 [chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
+  size_t partials;     // float2 [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
+  size_t partials_layer_bytes;   // one layer's share of it
   size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
   size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
@@ -49,7 +50,9 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.rows_pad = (rows + 63) / 64 * 64;
   w.chunks_max = d.total_tokens / min_stats_keys() + d.n_seqs;
   size_t off = 0;
-  w.partials = off; off += align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
+  w.partials = off;
+  w.partials_layer_bytes = align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
+  off += w.partials_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.select_keys = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
@@ -111,8 +114,9 @@ hipError_t launch_score_generic(const Params& p, int phases, int dtype, const vo
                                 int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
                                 char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st);
 bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token);
-hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
-                             int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
+hipError_t launch_score_mfma(const Params& p, int phases, int n_layers, const void* const* q_layers,
+                             const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                             const int32_t* cu, float* scores, int64_t scores_stride_head, int64_t scores_stride_layer,
                              char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st);
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
                          int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,

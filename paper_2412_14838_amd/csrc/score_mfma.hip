@@ -20,13 +20,15 @@
 // bit-identical sums whichever workgroup or lane computes them (fixed summation order per column).
 #include "dkv_internal.h"
 
+#include <type_traits>
+
 namespace dkv {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kLdsRow = 272;          // bytes per staged key row: 256 data + 16 pad (conflict-free 16-byte reads)
-constexpr int kLdsBudget = 156 * 1024; // dynamic LDS a workgroup may ask for (160 KB per compute unit, less the static part)
+constexpr int kLdsBudget = 152 * 1024; // dynamic LDS a workgroup may ask for (160 KB per compute unit, less the static part)
 constexpr int kMaxHalo = 64;          // >= 2 * half
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -175,6 +177,13 @@ __device__ inline void mfma_tile(const char* __restrict__ tile, const bf16x8 (&q
   for (int j = 0; j < 8; ++j) mfma_slice<KEYS_AS_M>(j, kf, qf, acc);
 }
 
+// lse2 of the four rows that accumulator registers 4 * (j & 3) .. + 3 of tile j / 4 hold (slice j of the emit
+// kernel's exponentials): rows rs * 64 + t * 32 + 8 * (j & 3) + 4 * (lane / 32) + 0..3.
+__device__ inline float4 rows_of_slice(const float* __restrict__ row_val, int rs, int j) {
+  const int lane = threadIdx.x & 63;
+  return *reinterpret_cast<const float4*>(&row_val[rs * 64 + (j >> 2) * 32 + 8 * (j & 3) + 4 * (lane >> 5)]);
+}
+
 // Linear chunk index -> (sequence, chunk) for chunks of `chunk` items over (length - window_off) items per
 // sequence; also returns the number of chunks of (length) items in the earlier sequences (first_full) and in
 // this one (n_full): the statistics kernel cuts all S keys, the emit kernel the S' prefix outputs.
@@ -210,21 +219,32 @@ __device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, i
   return false;
 }
 
+// Q and K of the layers one launch covers (kernel argument, indexed by the layer's place in the launch).
+struct ScoreLayers {
+  const uint16_t* q[DKV_MAX_SELECT_LAYERS];
+  const char* k[DKV_MAX_SELECT_LAYERS];
+};
+
 // ------------------------------------------------------------------------------------------------------
-// Row statistics: one partial (max, sum of exp2) per chunk and row, in the log2 domain:
+// Row statistics: one partial (max, sum of exp2) per layer, chunk and row, in the log2 domain:
 // y = c * x with c = softmax_scale * log2(e); partial = (max y, sum exp2(y - max y)).
-// grid = (chunk upper bound over all S keys, Hkv).
+// grid = (chunk upper bound over all S keys, Hkv). A workgroup owns one chunk of one (sequence, KV head) and
+// takes it through all n_layers layers of the launch: the geometry is the same for every layer, and while the
+// last two steps of a layer run, the first two key tiles and the Q block of the next layer are already being
+// fetched, so that only the first layer pays for a cold start.
 // ------------------------------------------------------------------------------------------------------
 template <int RS, int KS>
-__global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int chunk, const uint16_t* __restrict__ q_win,
-                                                                 const char* __restrict__ k, int64_t stride_token_b,
-                                                                 int64_t stride_head_b, const int32_t* __restrict__ cu,
-                                                                 float* __restrict__ partials) {
+__global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int chunk, int n_layers, ScoreLayers src,
+                                                                 int64_t stride_token_b, int64_t stride_head_b,
+                                                                 const int32_t* __restrict__ cu,
+                                                                 float* __restrict__ partials,
+                                                                 int64_t partials_stride_layer) {
   using TL = Tile<RS, KS>;
+  using QS = QStage<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
-  float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes);         // [KS][RS * 64], at the very end
-  char* qbuf = smem + 2 * TL::kTileBytes;                                      // Q staging, at the very start
+  char* qbuf = smem + 2 * TL::kTileBytes;                                      // Q staging
+  float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes + QS::kBytes);   // [KS][RS * 64]
 
   int seq, c, nc, begin, S, first_full, n_full;
   if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
@@ -234,111 +254,141 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int c0 = c * chunk;
   const int len = (c0 + chunk < S ? c0 + chunk : S) - c0;
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
+  const int n_steps = n_iter > 2 ? n_iter : 2;      // a layer's last two steps fetch the next layer's first two tiles
   const int prefix_rel = S - p.w - c0;              // first window key, relative to the chunk (may be <= 0)
   const float cexp = p.scale * kLog2e;
-
-  const char* __restrict__ k_chunk =
-      k + ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
+  const int64_t k_off = ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
+  const int64_t q_off = ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   const uint32_t stride_b = (uint32_t)stride_token_b;
-  // All first loads are issued together, in the order they are needed (loads return in order): key tile 0 and
-  // the Q block for the first MFMA tile, then key tile 1, whose arrival the first MFMA tile does not wait for.
-  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, 0, len - 1);
-  const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
-  bf16x8 qf[2][8];
-  if (QStage<RS, KS>::kStatsViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
-  else load_q_frags(q_head, rs, p.rows, qf);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, TL::kKeys, len - 1);
-
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   int limit[2];                                     // last key (chunk-relative) visible to this lane's row
 #pragma unroll
   for (int t = 0; t < 2; ++t) limit[t] = prefix_rel + (rs * 64 + t * 32 + (lane & 31)) % p.w;
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-
-  store_tile<RS, KS>(tiles, reg);
-  if (QStage<RS, KS>::kStatsViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
-  __syncthreads();
-  if (QStage<RS, KS>::kStatsViaLds) read_q_frags(qbuf, rs, qf);
-  floatx16 acc[2], nxt[2];
-  mfma_tile<true>(tiles + lane_tile, qf, acc);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
-  __syncthreads();                                  // tile 1 is in place; buffer 0 is rewritten by the first step
   const int lim_all = prefix_rel < len ? prefix_rel : len;
-  // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
-  // Tiles past the chunk are fully masked (they add exp2(-inf) = 0), so the step is branch-free but for the mask.
-  auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
-    reg = load_tile<RS, KS>(k_chunk, stride_b, (it + 2) * TL::kKeys, len - 1);
-    const int wave_row0 = it * TL::kKeys + ks * 32;
-    if (wave_row0 + 32 > lim_all) {                      // touches the window or runs past the chunk
-      const int kb = wave_row0 + 4 * (lane >> 5);        // + 8 * (j / 4) + j % 4
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int s = kb + 8 * (j >> 2) + (j & 3);
-          if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
-        }
-    }
-    // 8 slices: two MFMAs of tile it + 1 each, interleaved with one eighth of the exponentials of tile it, so
-    // that the matrix pipe and the vector ALU are busy together within one wavefront
-    bf16x8 kf[8];
-    read_k_frags(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, kf);
-    float m_use[2], s0, s1, s2, s3;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_slice<true>(j, kf, qf, b);
-      const int t = j >> 2, e = (j & 3) * 4;
-      if ((j & 3) == 0) {   // row maximum of tile t, new running maximum
-        float mx = fmaxf(a[t][0], a[t][1]);
-#pragma unroll
-        for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(a[t][i], a[t][i + 1]));
-        const float m_new = fmaxf(m_run[t], mx * cexp);
-        m_use[t] = m_new == -INFINITY ? 0.0f : m_new;
-        l_run[t] *= fast_exp2(m_run[t] - m_use[t]);
-        m_run[t] = m_new;
-        s0 = s1 = s2 = s3 = 0.0f;
-      }
-      s0 += fast_exp2(fmaf(a[t][e], cexp, -m_use[t]));
-      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -m_use[t]));
-      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -m_use[t]));
-      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -m_use[t]));
-      if ((j & 3) == 3) l_run[t] += (s0 + s1) + (s2 + s3);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // buffer it & 1 held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
-    store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
+
+  // First layer: all first loads are issued together (one memory latency, not three).
+  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(src.k[0] + k_off, stride_b, 0, len - 1);
+  typename PieceVec<QS::kPieces>::type qreg = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, TL::kKeys, len - 1);
+  store_tile<RS, KS>(tiles, reg);
+  store_q_pieces<RS, KS>(qbuf, qreg);
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+
+  int par = 0;                                      // LDS buffer that holds tile 0 of the current layer
+  for (int li = 0; li < n_layers; ++li) {
+    const char* __restrict__ k_chunk = src.k[li] + k_off;
+    const bool has_next = li + 1 < n_layers;
+    const char* __restrict__ k_next = src.k[has_next ? li + 1 : li] + k_off;
+    // here key tiles 0 and 1 and the Q block of this layer are on their way into LDS
     __syncthreads();
-  };
-  for (int it = 0; it < n_iter; it += 2) {
-    step(it, acc, nxt);
-    step(it + 1, nxt, acc);
-  }
-  // ---- merge the two half-wavefronts (same row, other keys), then the KS key tiles, then publish
+    bf16x8 qf[2][8];
+    read_q_frags(qbuf, rs, qf);
+    floatx16 acc[2], nxt[2];
+    mfma_tile<true>(tiles + par * TL::kTileBytes + lane_tile, qf, acc);
+    __syncthreads();                                // the buffer of tile 0 is rewritten by the first step
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+
+    // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
+    // Tiles past the chunk are fully masked (they add exp2(-inf) = 0). Tiles n_steps and n_steps + 1 are tiles 0
+    // and 1 of the next layer; the last step of a layer multiplies nothing (the MFMAs of the next layer's tile 0
+    // wait for that layer's Q, top of the loop) and fetches the next layer's Q block instead.
+    auto step = [&](auto is_last, int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
+      constexpr bool kLast = decltype(is_last)::value;
+      const int ahead = it + 2;
+      if (ahead >= n_steps && has_next) reg = load_tile<RS, KS>(k_next, stride_b, (ahead - n_steps) * TL::kKeys, len - 1);
+      else reg = load_tile<RS, KS>(k_chunk, stride_b, ahead * TL::kKeys, len - 1);
+      if (kLast && has_next) qreg = load_q_pieces<RS, KS>(src.q[li + 1] + q_off, p.rows);
+      const int wave_row0 = it * TL::kKeys + ks * 32;
+      if (wave_row0 + 32 > lim_all) {                      // touches the window or runs past the chunk
+        const int kb = wave_row0 + 4 * (lane >> 5);        // + 8 * (j / 4) + j % 4
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const float m2 = __shfl_xor(m_run[t], 32), l2 = __shfl_xor(l_run[t], 32);
-    const float M = fmaxf(m_run[t], m2);
-    const float Mu = M == -INFINITY ? 0.0f : M;
-    const float Lsum = l_run[t] * fast_exp2(m_run[t] - Mu) + l2 * fast_exp2(m2 - Mu);
-    if (lane < 32) stat[ks * (RS * 64) + rs * 64 + t * 32 + lane] = make_float2(M, Lsum);
-  }
-  __syncthreads();
-  float2* __restrict__ part =
-      reinterpret_cast<float2*>(partials) + (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad;
-  for (int r = tid; r < RS * 64; r += TL::kThreads) {
-    float M = -INFINITY;
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int q = 0; q < KS; ++q) M = fmaxf(M, stat[q * (RS * 64) + r].x);
-    const float Mu = M == -INFINITY ? 0.0f : M;
-    float Lsum = 0.0f;
+          for (int j = 0; j < 16; ++j) {
+            const int s = kb + 8 * (j >> 2) + (j & 3);
+            if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
+          }
+      }
+      float m_use[2], s0, s1, s2, s3;
+      auto exps = [&](int j) {   // one eighth of the exponentials of tile it
+        const int t = j >> 2, e = (j & 3) * 4;
+        if ((j & 3) == 0) {      // row maximum of tile t, new running maximum
+          float mx = fmaxf(a[t][0], a[t][1]);
 #pragma unroll
-    for (int q = 0; q < KS; ++q) {
-      const float2 v = stat[q * (RS * 64) + r];
-      Lsum += v.y * fast_exp2(v.x - Mu);
+          for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(a[t][i], a[t][i + 1]));
+          const float m_new = fmaxf(m_run[t], mx * cexp);
+          m_use[t] = m_new == -INFINITY ? 0.0f : m_new;
+          l_run[t] *= fast_exp2(m_run[t] - m_use[t]);
+          m_run[t] = m_new;
+          s0 = s1 = s2 = s3 = 0.0f;
+        }
+        s0 += fast_exp2(fmaf(a[t][e], cexp, -m_use[t]));
+        s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -m_use[t]));
+        s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -m_use[t]));
+        s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -m_use[t]));
+        if ((j & 3) == 3) l_run[t] += (s0 + s1) + (s2 + s3);
+      };
+      if (!kLast) {
+        // 8 slices: two MFMAs of tile it + 1 each, interleaved with one eighth of the exponentials of tile it,
+        // so that the matrix pipe and the vector ALU are busy together within one wavefront
+        bf16x8 kf[8];
+        read_k_frags(tiles + ((it + 1 + par) & 1) * TL::kTileBytes + lane_tile, kf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          __builtin_amdgcn_sched_barrier(0);
+          mfma_slice<true>(j, kf, qf, b);
+          exps(j);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) exps(j);
+      }
+      // the buffer held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
+      store_tile<RS, KS>(tiles + ((it + par) & 1) * TL::kTileBytes, reg);
+      if (kLast && has_next) store_q_pieces<RS, KS>(qbuf, qreg);   // this layer's Q is in registers
+      __syncthreads();
+    };
+    // the steps alternate between the two accumulator sets
+    constexpr std::false_type kInner{};
+    constexpr std::true_type kFinal{};
+    int it = 0;
+    for (; it + 2 < n_steps; it += 2) {
+      step(kInner, it, acc, nxt);
+      step(kInner, it + 1, nxt, acc);
     }
-    part[r] = make_float2(M, Lsum);
+    if (it + 2 == n_steps) {
+      step(kInner, it, acc, nxt);
+      step(kFinal, it + 1, nxt, acc);
+    } else {
+      step(kFinal, it, acc, nxt);
+    }
+    par ^= n_steps & 1;
+    // ---- merge the two half-wavefronts (same row, other keys), then the KS key tiles, then publish
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const float m2 = __shfl_xor(m_run[t], 32), l2 = __shfl_xor(l_run[t], 32);
+      const float M = fmaxf(m_run[t], m2);
+      const float Mu = M == -INFINITY ? 0.0f : M;
+      const float Lsum = l_run[t] * fast_exp2(m_run[t] - Mu) + l2 * fast_exp2(m2 - Mu);
+      if (lane < 32) stat[ks * (RS * 64) + rs * 64 + t * 32 + lane] = make_float2(M, Lsum);
+    }
+    __syncthreads();
+    float2* __restrict__ part = reinterpret_cast<float2*>(partials + li * partials_stride_layer) +
+                                (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad;
+    for (int r = tid; r < RS * 64; r += TL::kThreads) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < KS; ++q) M = fmaxf(M, stat[q * (RS * 64) + r].x);
+      const float Mu = M == -INFINITY ? 0.0f : M;
+      float Lsum = 0.0f;
+#pragma unroll
+      for (int q = 0; q < KS; ++q) {
+        const float2 v = stat[q * (RS * 64) + r];
+        Lsum += v.y * fast_exp2(v.x - Mu);
+      }
+      part[r] = make_float2(M, Lsum);
+    }
   }
 }
 
@@ -354,22 +404,32 @@ __host__ __device__ inline int emit_part_stride(int chunk) { return chunk + kMax
 // Key tile that step `it` of the emit kernel works on (steps past the first tile repeat it: same values again).
 __device__ inline int emit_tile(int n_iter, int it) { return it < n_iter ? n_iter - 1 - it : 0; }
 
+// As in the statistics kernel, a workgroup takes its chunk through all n_layers layers of the launch and fetches
+// the first two key tiles and the Q block of the next layer during the last two steps of the current one. The
+// next layer's row normalisers are merged from its chunk partials in the same last step (at most kEmitPrefetch
+// partials per thread wait in registers while the step's exponentials run; longer sequences merge them at the
+// top of the layer instead). lse_in (row normalisers supplied by the caller) is for single-layer launches.
+constexpr int kEmitPrefetch = 8;
+
 template <int RS, int KS>
-__global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int chunk, const uint16_t* __restrict__ q_win,
-                                                                const char* __restrict__ k, int64_t stride_token_b,
-                                                                int64_t stride_head_b, const int32_t* __restrict__ cu,
+__global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int chunk, int n_layers, ScoreLayers src,
+                                                                int64_t stride_token_b, int64_t stride_head_b,
+                                                                const int32_t* __restrict__ cu,
                                                                 const float* __restrict__ partials,
+                                                                int64_t partials_stride_layer,
                                                                 const float* __restrict__ lse_in,
-                                                                float* __restrict__ scores, int64_t scores_stride_head) {
+                                                                float* __restrict__ scores, int64_t scores_stride_head,
+                                                                int64_t scores_stride_layer) {
   using TL = Tile<RS, KS>;
+  using QS = QStage<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
   float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kPartStride]
   const int kPartStride = emit_part_stride<RS, KS>(chunk);
   constexpr int kRows = RS * 64;
-  float2* mstage = reinterpret_cast<float2*>(part);                            // [KS][kRows], before `part` is used
   char* qbuf = smem + 2 * TL::kTileBytes + RS * kPartStride * sizeof(float);   // Q staging
-  __shared__ __attribute__((aligned(16))) float lse_s[kRows];
+  __shared__ float2 mstage[KS * kRows];                                        // partial merges of KS thread groups
+  __shared__ __attribute__((aligned(16))) float lse_s[2][kRows];               // lse2 per row, by layer parity
 
   const int half = p.half;
   int seq, c, nc, begin, S, first_full, n_full;
@@ -384,131 +444,188 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const int kend = o1 + half < prefix ? o1 + half : prefix;
   const int len = kend - kbeg;                               // <= chunk + 2 * half
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
+  const int n_steps = n_iter > 2 ? n_iter : 2;               // a layer's last two steps fetch the next layer's first two tiles
   const float cexp = p.scale * kLog2e;
-
-  const char* __restrict__ k_chunk =
-      k + ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
+  const int64_t k_off = ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
+  const int64_t q_off = ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   const uint32_t stride_b = (uint32_t)stride_token_b;
-  // All first loads are issued together (two key tiles, the Q block, the row statistics): one memory latency.
-  // Tiles are taken from the last to the first: the statistics kernel, which ran first to last over the same
-  // chunks on the same compute units, left its last tiles in the L2 of this compute die.
-  // The first loads are issued in the order they are needed (loads return in order): the first key tile and the
-  // Q block, then the second key tile, whose arrival the first MFMA tile does not wait for.
-  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
-  const uint16_t* __restrict__ q_head = q_win + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
-  typename PieceVec<QStage<RS, KS>::kPieces>::type qreg;
-  bf16x8 qf[2][8];
-  if (QStage<RS, KS>::kEmitViaLds) qreg = load_q_pieces<RS, KS>(q_head, p.rows);
-  else load_q_frags(q_head, rs, p.rows, qf);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
-
-  // ---- lse2[row] of this (sequence, head): supplied by the caller (natural log, one per window row), or merged
-  // from the chunk partials of the statistics kernel
-  if (lse_in != nullptr) {
-    store_tile<RS, KS>(tiles, reg);
-    if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
-    if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
-      lse_s[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
-    __syncthreads();                                         // the first tile is in place
-  } else {
-    const int r = tid % kRows, q = tid / kRows;              // KS groups of kRows threads
-    const float2* __restrict__ src =
-        reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad + r;
-    float M = -INFINITY, Lsum = 0.0f;
-#pragma unroll 4
-    for (int cc = q; cc < n_full; cc += KS) {
-      const float2 v = src[(int64_t)cc * p.Hkv * p.rows_pad];
-      const float Mn = fmaxf(M, v.x);
-      const float Mu = Mn == -INFINITY ? 0.0f : Mn;
-      Lsum = Lsum * fast_exp2(M - Mu) + v.y * fast_exp2(v.x - Mu);
-      M = Mn;
-    }
-    mstage[q * kRows + r] = make_float2(M, Lsum);
-    store_tile<RS, KS>(tiles, reg);
-    if (QStage<RS, KS>::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
-    __syncthreads();
-    if (tid < kRows) {
-      float Mx = -INFINITY;
-#pragma unroll
-      for (int g = 0; g < KS; ++g) Mx = fmaxf(Mx, mstage[g * kRows + tid].x);
-      const float Mu = Mx == -INFINITY ? 0.0f : Mx;
-      float L = 0.0f;
-#pragma unroll
-      for (int g = 0; g < KS; ++g) {
-        const float2 v = mstage[g * kRows + tid];
-        L += v.y * fast_exp2(v.x - Mu);
-      }
-      // padding rows get +inf: exp2(x - inf) = 0
-      lse_s[tid] = tid < p.rows ? Mx + __log2f(L) : INFINITY;
-    }
-  }
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-  if (QStage<RS, KS>::kEmitViaLds) read_q_frags(qbuf, rs, qf);
-  floatx16 acc[2], nxt[2];
-  mfma_tile<false>(tiles + lane_tile, qf, acc);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
-  __syncthreads();                                           // the second tile is in place; lse_s is complete
-  // lse2 of the rows this lane accumulates: register j of tile t is row rs*64 + t*32 + 8*(j/4) + 4*(lane/32) + j%4
-  float lse_r[2][16];
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int j4 = 0; j4 < 4; ++j4) {
-      const float4 v = *reinterpret_cast<const float4*>(&lse_s[rs * 64 + t * 32 + 8 * j4 + 4 * (lane >> 5)]);
-      lse_r[t][4 * j4] = v.x; lse_r[t][4 * j4 + 1] = v.y; lse_r[t][4 * j4 + 2] = v.z; lse_r[t][4 * j4 + 3] = v.w;
-    }
+  const int mrow = tid % kRows, mgrp = tid / kRows;          // partial merge: KS groups of kRows threads
+  const int64_t part_off = ((int64_t)first_full * p.Hkv + head) * p.rows_pad + mrow;     // in float2
+  const int64_t part_step = (int64_t)p.Hkv * p.rows_pad;                                  // from chunk to chunk
+  const bool prefetch_lse = n_full <= kEmitPrefetch * KS;
 
-  // One step: prefetch tile it + 2, MFMAs of tile it + 1 into `b`, exponentials and column sums of tile it
-  // from `a`. Prefix keys are visible to every window row: no mask; columns past the computed range are
-  // discarded below. Fixed summation order per column.
-  auto step = [&](int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
-    reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, it + 2) * TL::kKeys, len - 1);
-    const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
-    bf16x8 kf[8];
-    read_k_frags(tiles + ((it + 1) & 1) * TL::kTileBytes + lane_tile, kf);
-    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {   // two MFMAs of tile it + 1, then one eighth of the exponentials of tile it
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_slice<false>(j, kf, qf, b);
-      const int t = j >> 2, e = (j & 3) * 4;
-      s0 += fast_exp2(fmaf(a[t][e], cexp, -lse_r[t][e]));
-      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -lse_r[t][e + 1]));
-      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -lse_r[t][e + 2]));
-      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -lse_r[t][e + 3]));
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    float col = (s0 + s1) + (s2 + s3);
-    const float other = __shfl_xor(col, 32);
-    col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
-    if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
-    store_tile<RS, KS>(tiles + (it & 1) * TL::kTileBytes, reg);
-    __syncthreads();
+  // (max, sum) of row `mrow` over the chunks mgrp, mgrp + KS, ...: online merge in chunk order
+  auto merge_pair = [&](float& M, float& Lsum, const float2 v) {
+    const float Mn = fmaxf(M, v.x);
+    const float Mu = Mn == -INFINITY ? 0.0f : Mn;
+    Lsum = fmaf(Lsum, fast_exp2(M - Mu), v.y * fast_exp2(v.x - Mu));   // spelled out: every call site rounds alike
+    M = Mn;
   };
-  for (int it = 0; it < n_iter; it += 2) {
-    step(it, acc, nxt);
-    step(it + 1, nxt, acc);
-  }
-  // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
-  for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
-    float a = part[i];
+  // lse2 of row tid from the KS staged merges; padding rows get +inf: exp2(x - inf) = 0
+  auto finish_lse = [&](float* __restrict__ dst) {
+    float Mx = -INFINITY;
 #pragma unroll
-    for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
-    part[i] = i < len ? a * p.row_scale : -INFINITY;
-  }
-  __syncthreads();
-  float* __restrict__ out = scores + (int64_t)head * scores_stride_head + begin;
-  for (int s = o0 + tid; s < o1; s += TL::kThreads) {
-    const int i = s - kbeg;
-    float m = part[i];
-    for (int o = 1; o <= half; ++o) {
-      if (i - o >= 0) m = fmaxf(m, part[i - o]);           // i - o < 0 only at the start of the sequence
-      if (i + o < len) m = fmaxf(m, part[i + o]);          // i + o >= len only at the end of the prefix
+    for (int g = 0; g < KS; ++g) Mx = fmaxf(Mx, mstage[g * kRows + tid].x);
+    const float Mu = Mx == -INFINITY ? 0.0f : Mx;
+    float L = 0.0f;
+#pragma unroll
+    for (int g = 0; g < KS; ++g) {
+      const float2 v = mstage[g * kRows + tid];
+      L = fmaf(v.y, fast_exp2(v.x - Mu), L);
     }
-    out[s] = m;
+    dst[tid] = tid < p.rows ? Mx + __log2f(L) : INFINITY;
+  };
+
+  // Tiles are taken from the last to the first: the statistics kernel, which ran first to last over the same
+  // chunks on the same compute units, left its last tiles as the most recently used lines.
+  // First layer: all first loads are issued together (one memory latency, not three).
+  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
+  typename PieceVec<QS::kPieces>::type qreg;
+  if (QS::kEmitViaLds) qreg = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
+  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
+  store_tile<RS, KS>(tiles, reg);
+  if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
+  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+
+  int par = 0;                                               // LDS buffer that holds the current layer's first tile
+  for (int li = 0; li < n_layers; ++li) {
+    const char* __restrict__ k_chunk = src.k[li] + k_off;
+    const bool has_next = li + 1 < n_layers;
+    const char* __restrict__ k_next = src.k[has_next ? li + 1 : li] + k_off;
+    float* __restrict__ lse_cur = lse_s[li & 1];
+    bf16x8 qf[2][8];
+    if (!QS::kEmitViaLds) load_q_frags(src.q[li] + q_off, rs, p.rows, qf);
+
+    // ---- lse2[row] of this (layer, sequence, head): from the caller's lse (natural log, one per window
+    // row), from the previous layer's last step, or merged here from the chunk partials of the statistics kernel
+    if (lse_in != nullptr) {
+      if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
+        lse_cur[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
+    } else if (li == 0 || !prefetch_lse) {
+      const float2* __restrict__ psrc = reinterpret_cast<const float2*>(partials + li * partials_stride_layer) + part_off;
+      float M = -INFINITY, Lsum = 0.0f;
+#pragma unroll 4
+      for (int cc = mgrp; cc < n_full; cc += KS) merge_pair(M, Lsum, psrc[cc * part_step]);
+      mstage[mgrp * kRows + mrow] = make_float2(M, Lsum);
+      __syncthreads();
+      if (tid < kRows) finish_lse(lse_cur);
+    }
+    floatx16 acc[2], nxt[2];
+    __syncthreads();                                           // lse_cur is complete, the first tile and Q are in place
+    if (QS::kEmitViaLds) read_q_frags(qbuf, rs, qf);
+    mfma_tile<false>(tiles + par * TL::kTileBytes + lane_tile, qf, acc);
+    __syncthreads();                                           // the buffer of the first tile is rewritten by the first step
+
+    // One step: prefetch the tile of step it + 2, MFMAs of the tile of step it + 1 into `b`, exponentials and
+    // column sums of the tile of step it from `a`. Steps n_steps and n_steps + 1 belong to the next layer; the
+    // last step of a layer multiplies nothing and fetches the next layer's Q block and chunk partials instead.
+    // Prefix keys are visible to every window row: no mask; columns past the computed range are discarded
+    // below. Fixed summation order per column.
+    auto step = [&](auto is_last, int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
+      constexpr bool kLast = decltype(is_last)::value;
+      const int ahead = it + 2;
+      if (ahead >= n_steps && has_next)
+        reg = load_tile<RS, KS>(k_next, stride_b, emit_tile(n_iter, ahead - n_steps) * TL::kKeys, len - 1);
+      else
+        reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, ahead) * TL::kKeys, len - 1);
+      float2 pf[kEmitPrefetch];
+      if (kLast && has_next) {
+        if (QS::kEmitViaLds) qreg = load_q_pieces<RS, KS>(src.q[li + 1] + q_off, p.rows);
+        if (prefetch_lse) {
+          const float2* __restrict__ psrc = reinterpret_cast<const float2*>(partials + (li + 1) * partials_stride_layer) + part_off;
+#pragma unroll
+          for (int i = 0; i < kEmitPrefetch; ++i) {
+            const int cc = mgrp + i * KS;
+            pf[i] = cc < n_full ? psrc[cc * part_step] : make_float2(-INFINITY, 0.0f);   // (-inf, 0) merges as nothing
+          }
+        }
+      }
+      const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
+      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+      // one eighth of the exponentials of this step's tile; lz = lse2 of its four rows, read from LDS one slice
+      // ahead (the per-row constants of all 32 accumulator registers would not fit beside the rest)
+      auto exps = [&](int j, const float4 lz) {
+        const int t = j >> 2, e = (j & 3) * 4;
+        s0 += fast_exp2(fmaf(a[t][e], cexp, -lz.x));
+        s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -lz.y));
+        s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -lz.z));
+        s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -lz.w));
+      };
+      float4 lz = rows_of_slice(lse_cur, rs, 0);
+      if (!kLast) {
+        bf16x8 kf[8];
+        read_k_frags(tiles + ((it + 1 + par) & 1) * TL::kTileBytes + lane_tile, kf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {   // two MFMAs of the next tile, then one eighth of the exponentials of this one
+          __builtin_amdgcn_sched_barrier(0);
+          const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
+          mfma_slice<false>(j, kf, qf, b);
+          exps(j, lz);
+          lz = lz_next;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          exps(j, lz);
+          lz = rows_of_slice(lse_cur, rs, (j + 1) & 7);
+        }
+      }
+      float col = (s0 + s1) + (s2 + s3);
+      const float other = __shfl_xor(col, 32);
+      col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
+      if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
+      store_tile<RS, KS>(tiles + ((it + par) & 1) * TL::kTileBytes, reg);
+      if (kLast && has_next) {
+        if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
+        if (prefetch_lse) {            // same merge order as at the top of a layer
+          float M = -INFINITY, Lsum = 0.0f;
+#pragma unroll
+          for (int i = 0; i < kEmitPrefetch; ++i) merge_pair(M, Lsum, pf[i]);
+          mstage[mgrp * kRows + mrow] = make_float2(M, Lsum);
+        }
+      }
+      __syncthreads();
+    };
+    // the steps alternate between the two accumulator sets
+    constexpr std::false_type kInner{};
+    constexpr std::true_type kFinal{};
+    int it = 0;
+    for (; it + 2 < n_steps; it += 2) {
+      step(kInner, it, acc, nxt);
+      step(kInner, it + 1, nxt, acc);
+    }
+    if (it + 2 == n_steps) {
+      step(kInner, it, acc, nxt);
+      step(kFinal, it + 1, nxt, acc);
+    } else {
+      step(kFinal, it, acc, nxt);
+    }
+    par ^= n_steps & 1;
+    // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
+    for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
+      float a = part[i];
+#pragma unroll
+      for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
+      part[i] = i < len ? a * p.row_scale : -INFINITY;
+    }
+    if (has_next && prefetch_lse && tid < kRows) finish_lse(lse_s[(li + 1) & 1]);
+    __syncthreads();
+    float* __restrict__ out = scores + li * scores_stride_layer + (int64_t)head * scores_stride_head + begin;
+    for (int s = o0 + tid; s < o1; s += TL::kThreads) {
+      const int i = s - kbeg;
+      float m = part[i];
+      for (int o = 1; o <= half; ++o) {
+        if (i - o >= 0) m = fmaxf(m, part[i - o]);           // i - o < 0 only at the start of the sequence
+        if (i + o < len) m = fmaxf(m, part[i + o]);          // i + o >= len only at the end of the prefix
+      }
+      out[s] = m;
+    }
+    if (c == nc - 1)
+      for (int j = tid; j < p.w; j += TL::kThreads) out[prefix + j] = -INFINITY;   // guard over the window slots
+    if (has_next) __syncthreads();                             // `part` is reused by the next layer
   }
-  if (c == nc - 1)
-    for (int j = tid; j < p.w; j += TL::kThreads) out[prefix + j] = -INFINITY;   // guard over the window slots
 }
 
 // Natural-log row normalisers from the chunk partials of the statistics kernel (log2 domain):
@@ -575,15 +692,17 @@ static int device_cus() {
 }
 
 template <int RS, int KS>
-static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
-                                int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
-                                char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out,
-                                hipStream_t st) {
+static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const void* const* q_layers,
+                                const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                                const int32_t* cu, float* scores, int64_t scores_stride_head,
+                                int64_t scores_stride_layer, char* ws, const WorkspaceLayout& wl, const float* lse_in,
+                                float* lse_out, hipStream_t st) {
   using TL = Tile<RS, KS>;
   const int chunk = pick_chunk<RS, KS>(p, device_cus());
   float* partials = ws ? reinterpret_cast<float*>(ws + wl.partials) : nullptr;   // no workspace: lse supplied
+  const int64_t partials_stride_layer = (int64_t)wl.partials_layer_bytes / (int64_t)sizeof(float);
   const size_t stat_bytes = (size_t)KS * RS * 64 * sizeof(float2);               // the final [KS][RS * 64] partials
-  const size_t lds_stats = 2 * TL::kTileBytes + ((size_t)QStage<RS, KS>::kBytes > stat_bytes ? (size_t)QStage<RS, KS>::kBytes : stat_bytes);
+  const size_t lds_stats = 2 * TL::kTileBytes + (size_t)QStage<RS, KS>::kBytes + stat_bytes;
   const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * emit_part_stride<RS, KS>(chunk) * sizeof(float) +
                           (QStage<RS, KS>::kEmitViaLds ? (size_t)QStage<RS, KS>::kBytes : 0);
   static bool attr_set = false;
@@ -596,26 +715,36 @@ static hipError_t launch_mfma_t(const Params& p, int phases, const void* q_win, 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
+  ScoreLayers src{};
+  for (int i = 0; i < n_layers && (phases & (kPhaseStats | kPhaseEmit)); ++i) {
+    src.q[i] = static_cast<const uint16_t*>(q_layers[i]);
+    src.k[i] = static_cast<const char*>(k_layers[i]);
+  }
   const int grid_x = p.total_tokens / chunk + p.n_seqs;      // upper bound on chunks over all sequences
   if (phases & kPhaseStats)
     launch(DKV_KERNEL_SCORE_STATS, (score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
-                       static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
-                       k_stride_head * 2, cu, partials);
+           n_layers, src, k_stride_token * 2, k_stride_head * 2, cu, partials, partials_stride_layer);
   if (phases & kPhaseEmit)
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
-                       static_cast<const uint16_t*>(q_win), static_cast<const char*>(k), k_stride_token * 2,
-                       k_stride_head * 2, cu, partials, lse_in, scores, scores_stride_head);
+           n_layers, src, k_stride_token * 2, k_stride_head * 2, cu, static_cast<const float*>(partials),
+           partials_stride_layer, lse_in, scores, scores_stride_head, scores_stride_layer);
   if (phases & kPhaseLse)
     launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, cu, partials, lse_out);
   return hipGetLastError();
 }
 
-hipError_t launch_score_mfma(const Params& p, int phases, const void* q_win, const void* k, int64_t k_stride_token,
-                             int64_t k_stride_head, const int32_t* cu, float* scores, int64_t scores_stride_head,
+hipError_t launch_score_mfma(const Params& p, int phases, int n_layers, const void* const* q_layers,
+                             const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
+                             const int32_t* cu, float* scores, int64_t scores_stride_head, int64_t scores_stride_layer,
                              char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st) {
-  if (p.rows <= 64) return launch_mfma_t<1, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
-  if (p.rows <= 128) return launch_mfma_t<2, 4>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
-  return launch_mfma_t<4, 2>(p, phases, q_win, k, k_stride_token, k_stride_head, cu, scores, scores_stride_head, ws, wl, lse_in, lse_out, st);
+  if (p.rows <= 64)
+    return launch_mfma_t<1, 4>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
+                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
+  if (p.rows <= 128)
+    return launch_mfma_t<2, 4>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
+                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
+  return launch_mfma_t<4, 2>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
+                             scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
 }
 
 }  // namespace dkv

@@ -9,9 +9,9 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
              layer i of sequence q holds w + counts[q][i] valid rows per head.
 
 Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
-grouped (`group` > 1): a layer is scored when it arrives, and the selection and compaction of up to `group`
-layers are issued together when the group is full, at an update boundary, or at the last layer; the caller then
-holds the K and V of a group's layers until that point.
+grouped (`group` > 1): the scoring, the selection and the compaction of up to `group` layers are issued together
+when the group is full, at an update boundary, or at the last layer; the caller then holds the window queries, K
+and V of a group's layers until that point.
 """
 from __future__ import annotations
 
@@ -118,12 +118,18 @@ class Compressor:
         if (layer + 1) % self.cfg.interval == 0:
             self.rebalance(layer + 1)
 
+    def score_layers(self, layer_begin, qs, ks, stride_token=None, stride_head=None, stream=None):
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_score_window_layers(self.desc, layer_begin, qs, ks, st, sh, self.cu, self.scores, self.ws, stream)
+
     def _step_grouped(self, layer, q_win, k, v, **strides):
-        self.score(layer, q_win, k, **strides)
-        self._pending.append((layer, k, v))
+        self._pending.append((layer, k, v, q_win))
         boundary = (layer + 1) % self.cfg.interval == 0
         if len(self._pending) == self.group or boundary or layer == self.cfg.L - 1:
             first, n = self._pending[0][0], len(self._pending)
+            self.score_layers(first, [e[3] for e in self._pending], [e[1] for e in self._pending], **strides)
             self.select_layers(first, n)
             if self.keep_cache:
                 self.gather_layers(first, [e[1] for e in self._pending], [e[2] for e in self._pending], **strides)

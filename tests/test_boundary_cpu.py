@@ -143,6 +143,29 @@ def test_layer_batched_calls_reject_bad_ranges(lib):
                                     sq - 64, sq, sh, None) == inv
 
 
+def test_layer_batched_scoring_rejects_bad_ranges_and_pointers(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    ptrs = (C.c_void_p * 9)(*([0x1000] * 9))
+    bad = (C.c_void_p * 2)(0x1000, 0)          # a null layer pointer
+    odd = (C.c_void_p * 2)(0x1000, 0x1008)     # a misaligned layer pointer
+    call = lib.dkv_score_window_layers
+    for begin, n in ((0, 0), (0, 9), (3, 2), (-1, 1), (4, 1)):
+        assert call(C.byref(d), begin, n, ptrs, ptrs, 64, 65536, fake, fake, fake, need, None) == inv
+    for arr in (bad, odd):
+        assert call(C.byref(d), 0, 2, arr, ptrs, 64, 65536, fake, fake, fake, need, None) == inv
+        assert call(C.byref(d), 0, 2, ptrs, arr, 64, 65536, fake, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, None, ptrs, 64, 65536, fake, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, None, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, None, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, fake, None, need, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, fake, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 63, 65536, fake, fake, fake, need, None) == inv     # rows overlap
+    assert call(None, 0, 2, ptrs, ptrs, 64, 65536, fake, fake, fake, need, None) == inv
+
+
 def test_lse_calls_validate_their_arguments(lib):
     d = _good()
     need = dkv.dkv_workspace_bytes(d)

@@ -322,6 +322,32 @@ def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
         assert np.array_equal(many.idx[2, s][:, :ref.shape[1]].cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_bf16", "ragged_f32",
+                                  "long_ragged"])
+def test_layer_batched_scoring_equals_per_layer_calls(dkv, case):
+    """dkv_score_window_layers over layers [1, 1 + n) writes, bit for bit, what dkv_score_window writes layer by
+    layer (which the tests above check against the oracle), and leaves the other layers' scores alone."""
+    if case == "long_ragged":     # several chunks per sequence, odd and even numbers of key tiles per chunk
+        cfg = small_cfg("long_ragged", L=5, Hq=8, Hkv=2, seqlens=(5000, 33, 9000, 32, 1300, 2177), interval=5)
+    else:
+        cfg = CASES[case].with_(L=max(CASES[case].L, 4))
+    n = cfg.L - 1
+    one, many = Compressor(cfg), Compressor(cfg)
+    data = [to_device(cfg, W.make_layer(cfg, l)) for l in range(cfg.L)]
+    for comp in (one, many):
+        comp.scores.fill_(123.0)
+    for l in range(1, 1 + n):
+        one.score(l, data[l]["q_win"], data[l]["k"])
+    many.score_layers(1, [data[l]["q_win"] for l in range(1, 1 + n)], [data[l]["k"] for l in range(1, 1 + n)])
+    torch.cuda.synchronize()
+    assert torch.equal(one.scores.view(torch.int32), many.scores.view(torch.int32))
+    assert (many.scores[0] == 123.0).all()
+    # layers differ from each other (a stale tile or Q block of the previous layer would show here)
+    assert not torch.equal(many.scores[1], many.scores[2])
+    ref = oracle_scores(cfg, W.make_layer(cfg, n))
+    assert_scores_close(cfg, many.scores[n].cpu().numpy(), ref)
+
+
 def test_rebalance_history_is_only_used_when_it_matches(dkv):
     """The update keeps a histogram of the layers it has scanned for the next call of the same prefill. Calls in
     order (2, 4, 6) extend it; a repeated, an out-of-order or a restarted call (new scores in the same tensor,
