@@ -176,7 +176,8 @@ int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k,
  * The normalisers themselves (the denominator of Eq. 1 in log form), from the row statistics that the last
  * dkv_score_window_stats or dkv_score_window call left in `workspace`: lse_out fp32 [n_seqs][Hq][ws], natural log,
  * in the layout dkv_score_window_lse takes. k_stride_token must be the value passed to that call (it selects the
- * kernel family whose statistics are read). One small kernel.
+ * kernel family whose statistics are read). After dkv_score_window_layers it is that call's FIRST layer whose
+ * normalisers are exported. One small kernel.
  */
 int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_seqlens, float* lse_out,
                 void* workspace, size_t workspace_bytes, void* stream);

@@ -724,10 +724,20 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
   if (phases & kPhaseStats)
     launch(DKV_KERNEL_SCORE_STATS, (score_stats_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_stats, st, p, chunk,
            n_layers, src, k_stride_token * 2, k_stride_head * 2, cu, partials, partials_stride_layer);
-  if (phases & kPhaseEmit)
+  if (phases & kPhaseEmit) {
+    // The emit kernel takes the layers of the call from the last to the first: the statistics kernel has just
+    // streamed them first to last, so the last layers are the ones the memory-side cache still holds.
+    ScoreLayers rev{};
+    for (int i = 0; i < n_layers; ++i) {
+      rev.q[i] = src.q[n_layers - 1 - i];
+      rev.k[i] = src.k[n_layers - 1 - i];
+    }
+    const int last = n_layers - 1;
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
-           n_layers, src, k_stride_token * 2, k_stride_head * 2, cu, static_cast<const float*>(partials),
-           partials_stride_layer, lse_in, scores, scores_stride_head, scores_stride_layer);
+           n_layers, rev, k_stride_token * 2, k_stride_head * 2, cu,
+           partials ? static_cast<const float*>(partials) + last * partials_stride_layer : nullptr, -partials_stride_layer,
+           lse_in, scores + last * scores_stride_layer, scores_stride_head, -scores_stride_layer);
+  }
   if (phases & kPhaseLse)
     launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, cu, partials, lse_out);
   return hipGetLastError();

@@ -9,9 +9,10 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
              layer i of sequence q holds w + counts[q][i] valid rows per head.
 
 Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
-grouped (`group` > 1): the scoring, the selection and the compaction of up to `group` layers are issued together
-when the group is full, at an update boundary, or at the last layer; the caller then holds the window queries, K
-and V of a group's layers until that point.
+grouped (`group` > 1): the scoring of up to `group` layers is issued in one call when the group is full or at
+the last layer, followed by the selection and the compaction of its layers (one call each per stretch of layers
+between two update boundaries) and the updates that fall inside the group; the caller then holds the window
+queries, K and V of a group's layers until that point.
 """
 from __future__ import annotations
 
@@ -25,6 +26,7 @@ class Compressor:
         self.cfg = cfg
         self.group = max(1, min(int(group), dkv.DKV_MAX_SELECT_LAYERS))
         self._pending = []
+        self.on_update = None       # optional host callback(layers_done), called after each update has been issued
         self.device = device
         self.desc = dkv.desc_from_workload(cfg, **(desc_override or {}))
         self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -116,7 +118,12 @@ class Compressor:
         if self.keep_cache:
             self.gather(layer, k, v, **strides)
         if (layer + 1) % self.cfg.interval == 0:
-            self.rebalance(layer + 1)
+            self._update(layer + 1)
+
+    def _update(self, layers_done):
+        self.rebalance(layers_done)
+        if self.on_update is not None:
+            self.on_update(layers_done)
 
     def score_layers(self, layer_begin, qs, ks, stride_token=None, stride_head=None, stream=None):
         d = self.cfg.d
@@ -126,16 +133,21 @@ class Compressor:
 
     def _step_grouped(self, layer, q_win, k, v, **strides):
         self._pending.append((layer, k, v, q_win))
-        boundary = (layer + 1) % self.cfg.interval == 0
-        if len(self._pending) == self.group or boundary or layer == self.cfg.L - 1:
-            first, n = self._pending[0][0], len(self._pending)
-            self.score_layers(first, [e[3] for e in self._pending], [e[1] for e in self._pending], **strides)
-            self.select_layers(first, n)
-            if self.keep_cache:
-                self.gather_layers(first, [e[1] for e in self._pending], [e[2] for e in self._pending], **strides)
-            self._pending = []      # the caller may release K and V of these layers now
-        if boundary:
-            self.rebalance(layer + 1)
+        if len(self._pending) < self.group and layer != self.cfg.L - 1:
+            return
+        pending, self._pending = self._pending, []      # the caller may release K and V of these layers afterwards
+        self.score_layers(pending[0][0], [e[3] for e in pending], [e[1] for e in pending], **strides)
+        stretch = []
+        for e in pending:
+            stretch.append(e)
+            boundary = (e[0] + 1) % self.cfg.interval == 0
+            if boundary or e is pending[-1]:
+                self.select_layers(stretch[0][0], len(stretch))
+                if self.keep_cache:
+                    self.gather_layers(stretch[0][0], [x[1] for x in stretch], [x[2] for x in stretch], **strides)
+                stretch = []
+            if boundary:
+                self._update(e[0] + 1)
 
     def run(self, layers, overlap=False):
         """layers: sequence of (q_win, k, v) device tensors, one per layer.
