@@ -84,7 +84,8 @@ enum {
   DKV_KERNEL_SELECT_ORDER = 8,
   DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
   DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
-  DKV_KERNEL_DECODE = 11          /* decode attention over the compressed cache       */
+  DKV_KERNEL_DECODE = 11,         /* decode attention over the compressed cache       */
+  DKV_KERNEL_SCORE_MERGE = 12     /* row normalisers of a multi-layer scoring call    */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */

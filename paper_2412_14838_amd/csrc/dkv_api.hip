@@ -31,7 +31,7 @@ Params make_params(const dkv_desc& d) {
   p.d = d.head_dim; p.w = d.window; p.P = d.pool_kernel; p.half = (d.pool_kernel - 1) / 2;
   p.layer_max = d.layer_max; p.mean_budget = d.mean_budget; p.interval = d.interval;
   p.n_seqs = d.n_seqs; p.total_tokens = d.total_tokens; p.max_seq_len = d.max_seq_len;
-  p.rows = p.G * p.w; p.rows_pad = (p.rows + 63) / 64 * 64;
+  p.rows = p.G * p.w; p.rows_pad = padded_rows(p.rows);
   p.scale = d.softmax_scale > 0.0f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
   p.row_scale = d.row_scale > 0.0f ? d.row_scale : 1.0f;
   return p;

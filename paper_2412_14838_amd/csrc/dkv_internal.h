@@ -26,6 +26,7 @@ constexpr int decode_slab_rows(size_t elt_bytes) { return elt_bytes == 2 ? 64 : 
 struct WorkspaceLayout {
   size_t partials;     // float2 [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t partials_layer_bytes;   // one layer's share of it
+  size_t lse_rows;     // float [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][rows_pad] merged row normalisers (log2) of a multi-layer scoring call
   size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
   size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
@@ -36,23 +37,28 @@ struct WorkspaceLayout {
   size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
   size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
   size_t total;
-  int rows_pad;        // G*w rounded up to 64
+  int rows_pad;        // padded_rows(G*w)
   int chunks_max;      // upper bound on statistics chunks over all sequences
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Rows of the per-(chunk, head) statistics blocks: G*w rounded up to what the widest kernel writes (the MFMA
+// kernels work on 64, 128 or 256 rows), so that a block never reaches into its neighbour's.
+inline int padded_rows(int rows) { return rows <= 64 ? 64 : rows <= 128 ? 128 : (rows + 255) / 256 * 256; }
 
 inline int min_stats_keys() { return kGenericKeys < kMfmaMinChunk ? kGenericKeys : kMfmaMinChunk; }
 
 inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   WorkspaceLayout w{};
   const int rows = (d.n_q_heads / d.n_kv_heads) * d.window;
-  w.rows_pad = (rows + 63) / 64 * 64;
+  w.rows_pad = padded_rows(rows);
   w.chunks_max = d.total_tokens / min_stats_keys() + d.n_seqs;
   size_t off = 0;
   w.partials = off;
   w.partials_layer_bytes = align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
   off += w.partials_layer_bytes * DKV_MAX_SELECT_LAYERS;
+  w.lse_rows = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * w.rows_pad * sizeof(float));
   w.select_keys = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * DKV_MAX_LAYER_MAX * sizeof(uint64_t));
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));

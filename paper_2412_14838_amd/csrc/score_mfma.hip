@@ -55,22 +55,25 @@ template <> struct PieceVec<8> { typedef uint32_t type __attribute__((ext_vector
 template <int RS, int KS>
 struct QStage {
   static constexpr bool kStatsViaLds = true;
-  static constexpr bool kEmitViaLds = KS >= 4;                    // else every wavefront loads its own fragments
+  static constexpr bool kEmitViaLds = KS >= 4;                    // else every wavefront loads its own fragments (first layer of a launch)
   static constexpr int kRows = RS * 64;
   static constexpr int kPieces = kRows * 16 / (RS * KS * 64);     // 16 / KS
   static constexpr int kBytes = kRows * kLdsRow;
+  static constexpr int kParts = kPieces > 4 ? kPieces / 4 : 1;    // steps over which the next layer's block is fetched
+  static constexpr int kPartPieces = kPieces / kParts;
 };
 
 template <int RS, int KS>
 __device__ inline typename PieceVec<QStage<RS, KS>::kPieces>::type load_q_pieces(const uint16_t* __restrict__ q_head,
                                                                                   int rows) {
   typename PieceVec<QStage<RS, KS>::kPieces>::type reg;
+  uint32_t t = threadIdx.x;
+  asm volatile("" : "+v"(t));   // the addresses are rebuilt here: kept across the caller's loop they cost registers
 #pragma unroll
   for (int i = 0; i < QStage<RS, KS>::kPieces; ++i) {
-    const int pc = threadIdx.x + i * (RS * KS * 64);
-    const int row = pc >> 4;
+    const uint32_t pc = t + i * (RS * KS * 64);                // piece pc of the block: row pc / 16, 16 bytes at pc * 16
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < rows) v = *reinterpret_cast<const uint4*>(q_head + row * 128 + (pc & 15) * 8);
+    if ((int)(pc >> 4) < rows) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q_head) + pc * 16u);
     reg[4 * i] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
   }
   return reg;
@@ -81,6 +84,34 @@ __device__ inline void store_q_pieces(char* __restrict__ qbuf, typename PieceVec
 #pragma unroll
   for (int i = 0; i < QStage<RS, KS>::kPieces; ++i) {
     const int pc = threadIdx.x + i * (RS * KS * 64);
+    *reinterpret_cast<uint4*>(qbuf + (pc >> 4) * kLdsRow + (pc & 15) * 16) =
+        make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
+  }
+}
+
+// The same for one part of the block: pieces [part * kPartPieces, (part + 1) * kPartPieces) of every thread. The
+// kernels fetch the next layer's Q in QStage::kParts steps, at most 4 pieces (16 registers) at a time.
+template <int RS, int KS>
+__device__ inline typename PieceVec<QStage<RS, KS>::kPartPieces>::type load_q_part(const uint16_t* __restrict__ q_head,
+                                                                                    int rows, int part) {
+  typename PieceVec<QStage<RS, KS>::kPartPieces>::type reg;
+  uint32_t t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+#pragma unroll
+  for (int i = 0; i < QStage<RS, KS>::kPartPieces; ++i) {
+    const uint32_t pc = t + (uint32_t)(part * QStage<RS, KS>::kPartPieces + i) * (RS * KS * 64);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if ((int)(pc >> 4) < rows) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q_head) + pc * 16u);
+    reg[4 * i] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
+  }
+  return reg;
+}
+
+template <int RS, int KS>
+__device__ inline void store_q_part(char* __restrict__ qbuf, typename PieceVec<QStage<RS, KS>::kPartPieces>::type reg, int part) {
+#pragma unroll
+  for (int i = 0; i < QStage<RS, KS>::kPartPieces; ++i) {
+    const int pc = threadIdx.x + (part * QStage<RS, KS>::kPartPieces + i) * (RS * KS * 64);
     *reinterpret_cast<uint4*>(qbuf + (pc >> 4) * kLdsRow + (pc & 15) * 16) =
         make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
   }
@@ -151,7 +182,30 @@ __device__ inline void read_k_frags(const char* __restrict__ tile, bf16x8 (&kf)[
   for (int j = 0; j < 8; ++j) kf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
 }
 
+// Fragment j of them alone (the steps of the kernels read one slice ahead instead of a whole tile at once: fewer
+// registers, same latency hiding).
+__device__ inline bf16x8 read_k_frag(const char* __restrict__ tile, int j) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
+}
+
 // Slice j of the two accumulators: acc[t] (+)= (KEYS_AS_M ? K_tile . Q_t^T : Q_t . K_tile^T) over head dims 16j..16j+15.
+template <bool KEYS_AS_M>
+__device__ inline void mfma_slice(int j, const bf16x8 kfj, const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
+  if (j == 0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+  }
+  if (KEYS_AS_M) {
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfj, qf[0][j], acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfj, qf[1][j], acc[1], 0, 0, 0);
+  } else {
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][j], kfj, acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[1][j], kfj, acc[1], 0, 0, 0);
+  }
+}
+
 template <bool KEYS_AS_M>
 __device__ inline void mfma_slice(int j, const bf16x8 (&kf)[8], const bf16x8 (&qf)[2][8], floatx16 (&acc)[2]) {
   if (j == 0) {
@@ -219,11 +273,32 @@ __device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, i
   return false;
 }
 
+// Workgroup barrier that orders LDS traffic only. __syncthreads() also waits for every global load the wavefront
+// has in flight (its release fence covers global memory), which would cut the prefetch of the key tiles down to
+// what fits between two barriers; the wavefronts of a score kernel talk to each other through LDS alone.
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Q and K of the layers one launch covers (kernel argument, indexed by the layer's place in the launch).
 struct ScoreLayers {
   const uint16_t* q[DKV_MAX_SELECT_LAYERS];
   const char* k[DKV_MAX_SELECT_LAYERS];
 };
+
+// The tile `ahead` steps after the start of layer `li` in the stream of n_steps tiles per layer: its layer and
+// its step within that layer. Past the end of the call it is the last layer's last step again (loaded, not used).
+__device__ inline void stream_tile(int li, int ahead, int n_steps, int n_layers, int& layer, int& step) {
+  layer = li;
+  step = ahead;
+  while (step >= n_steps && layer + 1 < n_layers) {   // at most twice (ahead <= n_steps + 2, n_steps >= 2)
+    step -= n_steps;
+    ++layer;
+  }
+  if (step >= n_steps) step = n_steps - 1;
+}
 
 // ------------------------------------------------------------------------------------------------------
 // Row statistics: one partial (max, sum of exp2) per layer, chunk and row, in the log2 domain:
@@ -254,7 +329,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int c0 = c * chunk;
   const int len = (c0 + chunk < S ? c0 + chunk : S) - c0;
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
-  const int n_steps = n_iter > 2 ? n_iter : 2;      // a layer's last two steps fetch the next layer's first two tiles
+  const int n_steps = n_iter > QS::kParts + 1 ? n_iter : QS::kParts + 1;   // the steps before a layer's last one fetch the next layer's Q
   const int prefix_rel = S - p.w - c0;              // first window key, relative to the chunk (may be <= 0)
   const float cexp = p.scale * kLog2e;
   const int64_t k_off = ((int64_t)begin + c0) * stride_token_b + (int64_t)head * stride_head_b;
@@ -266,117 +341,121 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
   const int lim_all = prefix_rel < len ? prefix_rel : len;
 
-  // First layer: all first loads are issued together (one memory latency, not three).
-  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(src.k[0] + k_off, stride_b, 0, len - 1);
-  typename PieceVec<QS::kPieces>::type qreg = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, TL::kKeys, len - 1);
-  store_tile<RS, KS>(tiles, reg);
-  store_q_pieces<RS, KS>(qbuf, qreg);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  // First layer: all first loads are issued together (one memory latency, not three). Tile loads stay in flight
+  // for two steps (one step is shorter than the memory latency under load), so there are two register sets:
+  // the set of tile u is ld[u & 1].
+  typename PieceVec<TL::kPieces>::type ld[2];
+  {
+    const typename PieceVec<TL::kPieces>::type reg0 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, 0, len - 1);
+    const typename PieceVec<QS::kPieces>::type q0 = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
+    const typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, TL::kKeys, len - 1);
+    int l2, t2;
+    stream_tile(0, 2, n_steps, n_layers, l2, t2);
+    ld[0] = load_tile<RS, KS>(src.k[l2] + k_off, stride_b, t2 * TL::kKeys, len - 1);   // stored by the first step
+    store_tile<RS, KS>(tiles, reg0);
+    store_q_pieces<RS, KS>(qbuf, q0);
+    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  }
+  lds_barrier();                                  // key tiles 0 and 1 and the Q block of the first layer are in LDS
+  bf16x8 qf[2][8];
+  read_q_frags(qbuf, rs, qf);
+  floatx16 acc[2], nxt[2];
+  mfma_tile<true>(tiles + lane_tile, qf, acc);
+  lds_barrier();                                  // buffer 0 is rewritten by the first step
 
-  int par = 0;                                      // LDS buffer that holds tile 0 of the current layer
-  for (int li = 0; li < n_layers; ++li) {
-    const char* __restrict__ k_chunk = src.k[li] + k_off;
+  // The key tiles of all layers form one stream: n_steps tiles per layer, layer after layer; tile v of the stream
+  // lives in LDS buffer v & 1. One step: issue the loads of tile v + 3, MFMAs of tile v + 1 into `b`,
+  // exponentials of tile v from `a`, tile v + 2 from registers to LDS. Tiles past the chunk are fully masked (they add exp2(-inf) = 0). The step
+  // before a layer's last one fetches the next layer's Q block into LDS; the last step, which has nothing of its
+  // own layer left to multiply, takes that Q as its operand for the next layer's tile 0, and is followed by the
+  // layer's epilogue - so the matrix pipe, the vector ALU and the loads never pause between layers.
+  int li = 0, it = 0;                               // layer of the call and step within it (uniform over the workgroup)
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+  auto step = [&](auto buffer, floatx16 (&a)[2], floatx16 (&b)[2]) {
+    constexpr int kBuf = decltype(buffer)::value;   // buffer of this step's tile
+    if (li >= n_layers) return;                     // the padding step of an odd stream
     const bool has_next = li + 1 < n_layers;
-    const char* __restrict__ k_next = src.k[has_next ? li + 1 : li] + k_off;
-    // here key tiles 0 and 1 and the Q block of this layer are on their way into LDS
-    __syncthreads();
-    bf16x8 qf[2][8];
-    read_q_frags(qbuf, rs, qf);
-    floatx16 acc[2], nxt[2];
-    mfma_tile<true>(tiles + par * TL::kTileBytes + lane_tile, qf, acc);
-    __syncthreads();                                // the buffer of tile 0 is rewritten by the first step
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
-
-    // One step: prefetch tile it + 2 (registers), MFMAs of tile it + 1 into `b`, exponentials of tile it from `a`.
-    // Tiles past the chunk are fully masked (they add exp2(-inf) = 0). Tiles n_steps and n_steps + 1 are tiles 0
-    // and 1 of the next layer; the last step of a layer multiplies nothing (the MFMAs of the next layer's tile 0
-    // wait for that layer's Q, top of the loop) and fetches the next layer's Q block instead.
-    auto step = [&](auto is_last, int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
-      constexpr bool kLast = decltype(is_last)::value;
-      const int ahead = it + 2;
-      if (ahead >= n_steps && has_next) reg = load_tile<RS, KS>(k_next, stride_b, (ahead - n_steps) * TL::kKeys, len - 1);
-      else reg = load_tile<RS, KS>(k_chunk, stride_b, ahead * TL::kKeys, len - 1);
-      if (kLast && has_next) qreg = load_q_pieces<RS, KS>(src.q[li + 1] + q_off, p.rows);
-      const int wave_row0 = it * TL::kKeys + ks * 32;
-      if (wave_row0 + 32 > lim_all) {                      // touches the window or runs past the chunk
-        const int kb = wave_row0 + 4 * (lane >> 5);        // + 8 * (j / 4) + j % 4
+    const int q_part = it + 1 + QS::kParts - n_steps;         // part of the next layer's Q block this step fetches
+    const bool fetch_q = q_part >= 0 && q_part < QS::kParts && has_next;
+    const bool last = it + 1 == n_steps;
+    typename PieceVec<QS::kPartPieces>::type qnext;  // local: no value is carried from step to step
+    // issued before the tile's loads, which stay in flight past the end of the step (loads return in order)
+    if (fetch_q) qnext = load_q_part<RS, KS>(src.q[li + 1] + q_off, p.rows, q_part);
+    int la, ta;                                     // tile v + 3: issued now, stored to LDS at the end of the next step
+    stream_tile(li, it + 3, n_steps, n_layers, la, ta);
+    ld[kBuf ^ 1] = load_tile<RS, KS>(src.k[la] + k_off, stride_b, ta * TL::kKeys, len - 1);
+    const int wave_row0 = it * TL::kKeys + ks * 32;
+    if (wave_row0 + 32 > lim_all) {                        // touches the window or runs past the chunk
+      const int kb = wave_row0 + 4 * (lane >> 5);          // + 8 * (j / 4) + j % 4
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const int s = kb + 8 * (j >> 2) + (j & 3);
-            if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
-          }
-      }
-      float m_use[2], s0, s1, s2, s3;
-      auto exps = [&](int j) {   // one eighth of the exponentials of tile it
-        const int t = j >> 2, e = (j & 3) * 4;
-        if ((j & 3) == 0) {      // row maximum of tile t, new running maximum
-          float mx = fmaxf(a[t][0], a[t][1]);
-#pragma unroll
-          for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(a[t][i], a[t][i + 1]));
-          const float m_new = fmaxf(m_run[t], mx * cexp);
-          m_use[t] = m_new == -INFINITY ? 0.0f : m_new;
-          l_run[t] *= fast_exp2(m_run[t] - m_use[t]);
-          m_run[t] = m_new;
-          s0 = s1 = s2 = s3 = 0.0f;
+        for (int j = 0; j < 16; ++j) {
+          const int s = kb + 8 * (j >> 2) + (j & 3);
+          if (s > limit[t] || s >= len) a[t][j] = -INFINITY;
         }
-        s0 += fast_exp2(fmaf(a[t][e], cexp, -m_use[t]));
-        s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -m_use[t]));
-        s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -m_use[t]));
-        s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -m_use[t]));
-        if ((j & 3) == 3) l_run[t] += (s0 + s1) + (s2 + s3);
-      };
-      if (!kLast) {
-        // 8 slices: two MFMAs of tile it + 1 each, interleaved with one eighth of the exponentials of tile it,
-        // so that the matrix pipe and the vector ALU are busy together within one wavefront
-        bf16x8 kf[8];
-        read_k_frags(tiles + ((it + 1 + par) & 1) * TL::kTileBytes + lane_tile, kf);
+    }
+    float m_use[2], s0, s1, s2, s3;
+    auto exps = [&](int j) {   // one eighth of the exponentials of this step's tile
+      const int t = j >> 2, e = (j & 3) * 4;
+      if ((j & 3) == 0) {      // row maximum of tile t, new running maximum
+        float mx = fmaxf(a[t][0], a[t][1]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          __builtin_amdgcn_sched_barrier(0);
-          mfma_slice<true>(j, kf, qf, b);
-          exps(j);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) exps(j);
+        for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(a[t][i], a[t][i + 1]));
+        const float m_new = fmaxf(m_run[t], mx * cexp);
+        m_use[t] = m_new == -INFINITY ? 0.0f : m_new;
+        l_run[t] *= fast_exp2(m_run[t] - m_use[t]);
+        m_run[t] = m_new;
+        s0 = s1 = s2 = s3 = 0.0f;
       }
-      // the buffer held tile it, whose MFMAs ran before the previous barrier: it is free for tile it + 2
-      store_tile<RS, KS>(tiles + ((it + par) & 1) * TL::kTileBytes, reg);
-      if (kLast && has_next) store_q_pieces<RS, KS>(qbuf, qreg);   // this layer's Q is in registers
-      __syncthreads();
+      s0 += fast_exp2(fmaf(a[t][e], cexp, -m_use[t]));
+      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -m_use[t]));
+      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -m_use[t]));
+      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -m_use[t]));
+      if ((j & 3) == 3) l_run[t] += (s0 + s1) + (s2 + s3);
     };
-    // the steps alternate between the two accumulator sets
-    constexpr std::false_type kInner{};
-    constexpr std::true_type kFinal{};
-    int it = 0;
-    for (; it + 2 < n_steps; it += 2) {
-      step(kInner, it, acc, nxt);
-      step(kInner, it + 1, nxt, acc);
+    // 8 slices: two MFMAs of the next tile each, interleaved with one eighth of the exponentials of this tile, so
+    // that the matrix pipe and the vector ALU are busy together within one wavefront. After the last layer the
+    // product of the last step is of stale operands and unused (cheaper than a second variant of the step).
+    if (last) read_q_frags(qbuf, rs, qf);                  // the next layer's Q, stored before the previous barrier
+    {
+      const char* __restrict__ next_tile = tiles + (kBuf ^ 1) * TL::kTileBytes + lane_tile;
+      bf16x8 kfj = read_k_frag(next_tile, 0);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
+        mfma_slice<true>(j, kfj, qf, b);
+        exps(j);
+        kfj = kf_ahead;
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (it + 2 == n_steps) {
-      step(kInner, it, acc, nxt);
-      step(kFinal, it + 1, nxt, acc);
-    } else {
-      step(kFinal, it, acc, nxt);
+    // this buffer held this step's tile, whose MFMAs ran before the previous barrier: it is free for tile v + 2,
+    // whose load was issued one step ago
+    store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);
+    if (fetch_q) store_q_part<RS, KS>(qbuf, qnext, q_part);   // every wavefront has this layer's Q in registers
+    lds_barrier();
+    if (!last) {
+      ++it;
+      return;
     }
-    par ^= n_steps & 1;
-    // ---- merge the two half-wavefronts (same row, other keys), then the KS key tiles, then publish
+    // ---- end of a layer: merge the two half-wavefronts (same row, other keys), then the KS key tiles, publish
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const float m2 = __shfl_xor(m_run[t], 32), l2 = __shfl_xor(l_run[t], 32);
       const float M = fmaxf(m_run[t], m2);
       const float Mu = M == -INFINITY ? 0.0f : M;
-      const float Lsum = l_run[t] * fast_exp2(m_run[t] - Mu) + l2 * fast_exp2(m2 - Mu);
+      const float Lsum = fmaf(l_run[t], fast_exp2(m_run[t] - Mu), l2 * fast_exp2(m2 - Mu));   // spelled out: both copies of this code round alike
       if (lane < 32) stat[ks * (RS * 64) + rs * 64 + t * 32 + lane] = make_float2(M, Lsum);
+      m_run[t] = -INFINITY;
+      l_run[t] = 0.0f;
     }
-    __syncthreads();
+    lds_barrier();
     float2* __restrict__ part = reinterpret_cast<float2*>(partials + li * partials_stride_layer) +
                                 (((int64_t)blockIdx.x) * p.Hkv + head) * p.rows_pad;
-    for (int r = tid; r < RS * 64; r += TL::kThreads) {
+    if (tid < RS * 64) {                            // no loop around memory instructions: key tiles are in flight
+      const int r = tid;
       float M = -INFINITY;
 #pragma unroll
       for (int q = 0; q < KS; ++q) M = fmaxf(M, stat[q * (RS * 64) + r].x);
@@ -385,10 +464,16 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 #pragma unroll
       for (int q = 0; q < KS; ++q) {
         const float2 v = stat[q * (RS * 64) + r];
-        Lsum += v.y * fast_exp2(v.x - Mu);
+        Lsum = fmaf(v.y, fast_exp2(v.x - Mu), Lsum);
       }
       part[r] = make_float2(M, Lsum);
     }
+    ++li;
+    it = 0;
+  };
+  while (li < n_layers) {                           // the steps alternate between the two accumulator sets
+    step(std::integral_constant<int, 0>{}, acc, nxt);
+    step(std::integral_constant<int, 1>{}, nxt, acc);
   }
 }
 
@@ -404,19 +489,85 @@ __host__ __device__ inline int emit_part_stride(int chunk) { return chunk + kMax
 // Key tile that step `it` of the emit kernel works on (steps past the first tile repeat it: same values again).
 __device__ inline int emit_tile(int n_iter, int it) { return it < n_iter ? n_iter - 1 - it : 0; }
 
-// As in the statistics kernel, a workgroup takes its chunk through all n_layers layers of the launch and fetches
-// the first two key tiles and the Q block of the next layer during the last two steps of the current one. The
-// next layer's row normalisers are merged from its chunk partials in the same last step (at most kEmitPrefetch
-// partials per thread wait in registers while the step's exponentials run; longer sequences merge them at the
-// top of the layer instead). lse_in (row normalisers supplied by the caller) is for single-layer launches.
-constexpr int kEmitPrefetch = 8;
+// ---- Row normalisers lse2[row] = log2 sum_keys exp2(c * x[row, key]) from the chunk partials of the statistics
+// kernel, by the RS * KS * 64 threads of a workgroup: thread (row mrow, group mgrp) merges the chunks mgrp,
+// mgrp + KS, ... online in chunk order into `mstage`; after a barrier thread `row` combines the KS groups.
+// Written once and used both inside the emit kernel (single-layer launches) and by the merge kernel below, so
+// that both give the same bits.
+__device__ inline void merge_pair(float& M, float& Lsum, const float2 v) {
+  const float Mn = fmaxf(M, v.x);
+  const float Mu = Mn == -INFINITY ? 0.0f : Mn;
+  Lsum = fmaf(Lsum, fast_exp2(M - Mu), v.y * fast_exp2(v.x - Mu));   // spelled out: every call site rounds alike
+  M = Mn;
+}
 
+// psrc: partials of chunk 0 of this (layer, sequence, head), float2 [chunk][Hkv][rows_pad]
+template <int RS, int KS>
+__device__ inline void merge_chunks(const float2* __restrict__ psrc, int n_full, uint32_t chunk_step, float2* __restrict__ mstage) {
+  constexpr int kRows = RS * 64;
+  const int mrow = threadIdx.x % kRows, mgrp = threadIdx.x / kRows;
+  const uint32_t t0 = (uint32_t)mrow + (uint32_t)mgrp * chunk_step;   // 32-bit element offsets from a shared base
+  float M = -INFINITY, Lsum = 0.0f;
+#pragma unroll 8
+  for (int cc = mgrp; cc < n_full; cc += KS, psrc += KS * chunk_step) merge_pair(M, Lsum, psrc[t0]);
+  mstage[mgrp * kRows + mrow] = make_float2(M, Lsum);
+}
+
+// lse2 of row `row` (< RS * 64) from the KS staged merges; padding rows get +inf: exp2(x - inf) = 0
+template <int RS, int KS>
+__device__ inline float combine_groups(const float2* __restrict__ mstage, int row, int rows) {
+  constexpr int kRows = RS * 64;
+  float Mx = -INFINITY;
+#pragma unroll
+  for (int g = 0; g < KS; ++g) Mx = fmaxf(Mx, mstage[g * kRows + row].x);
+  const float Mu = Mx == -INFINITY ? 0.0f : Mx;
+  float L = 0.0f;
+#pragma unroll
+  for (int g = 0; g < KS; ++g) {
+    const float2 v = mstage[g * kRows + row];
+    L = fmaf(v.y, fast_exp2(v.x - Mu), L);
+  }
+  return row < rows ? Mx + __log2f(L) : INFINITY;
+}
+
+// Merge kernel of multi-layer launches: lse_rows[layer][seq][head][rows_pad] (log2 domain), between the two
+// sweeps. grid = (n_seqs, Hkv, n_layers), RS * KS * 64 threads. Inside the emit kernel this merge would sit on
+// the critical path of every layer (a chain of dependent loads per thread, 32 deep for 64 chunks).
+template <int RS, int KS>
+__global__ __launch_bounds__(RS * KS * 64) void score_merge_mfma(Params p, int chunk, const int32_t* __restrict__ cu,
+                                                                 const float* __restrict__ partials,
+                                                                 int64_t partials_stride_layer,
+                                                                 float* __restrict__ lse_rows) {
+  constexpr int kRows = RS * 64;
+  __shared__ float2 mstage[KS * kRows];
+  const int seq = blockIdx.x, head = blockIdx.y, layer = blockIdx.z;
+  int first_full = 0;
+  for (int q = 0; q < seq; ++q) first_full += (cu[q + 1] - cu[q] + chunk - 1) / chunk;
+  const int n_full = (cu[seq + 1] - cu[seq] + chunk - 1) / chunk;
+  const float2* __restrict__ psrc = reinterpret_cast<const float2*>(partials + layer * partials_stride_layer) +
+                                    ((int64_t)first_full * p.Hkv + head) * p.rows_pad;
+  merge_chunks<RS, KS>(psrc, n_full, (uint32_t)(p.Hkv * p.rows_pad), mstage);
+  __syncthreads();
+  if (threadIdx.x < kRows)
+    lse_rows[(((int64_t)layer * p.n_seqs + seq) * p.Hkv + head) * p.rows_pad + threadIdx.x] =
+        combine_groups<RS, KS>(mstage, threadIdx.x, p.rows);
+}
+
+// Outputs per thread of the emit kernel's epilogue (the chunk is at most kMaxChunk outputs).
+constexpr int kMaxChunk = 4096;
+
+// As in the statistics kernel, a workgroup takes its chunk through all n_layers layers of the launch: the key tiles
+// form one stream, the next layer's Q block and row normalisers are fetched while the current layer's last steps
+// run. The row normalisers come from lse_rows (multi-layer launches, written by the merge kernel), from lse_in
+// (supplied by the caller, natural log, single-layer launches) or are merged here from the chunk partials
+// (single-layer launches).
 template <int RS, int KS>
 __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int chunk, int n_layers, ScoreLayers src,
                                                                 int64_t stride_token_b, int64_t stride_head_b,
                                                                 const int32_t* __restrict__ cu,
                                                                 const float* __restrict__ partials,
-                                                                int64_t partials_stride_layer,
+                                                                const float* __restrict__ lse_rows,
+                                                                int64_t lse_rows_stride_layer,
                                                                 const float* __restrict__ lse_in,
                                                                 float* __restrict__ scores, int64_t scores_stride_head,
                                                                 int64_t scores_stride_layer) {
@@ -444,187 +595,151 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const int kend = o1 + half < prefix ? o1 + half : prefix;
   const int len = kend - kbeg;                               // <= chunk + 2 * half
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
-  const int n_steps = n_iter > 2 ? n_iter : 2;               // a layer's last two steps fetch the next layer's first two tiles
+  const int n_steps = n_iter > QS::kParts + 1 ? n_iter : QS::kParts + 1;   // the steps before a layer's last one fetch the next layer's Q
   const float cexp = p.scale * kLog2e;
   const int64_t k_off = ((int64_t)begin + kbeg) * stride_token_b + (int64_t)head * stride_head_b;
   const int64_t q_off = ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w * 128;
   const uint32_t stride_b = (uint32_t)stride_token_b;
   const int lane_tile = (ks * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-  const int mrow = tid % kRows, mgrp = tid / kRows;          // partial merge: KS groups of kRows threads
-  const int64_t part_off = ((int64_t)first_full * p.Hkv + head) * p.rows_pad + mrow;     // in float2
-  const int64_t part_step = (int64_t)p.Hkv * p.rows_pad;                                  // from chunk to chunk
-  const bool prefetch_lse = n_full <= kEmitPrefetch * KS;
-
-  // (max, sum) of row `mrow` over the chunks mgrp, mgrp + KS, ...: online merge in chunk order
-  auto merge_pair = [&](float& M, float& Lsum, const float2 v) {
-    const float Mn = fmaxf(M, v.x);
-    const float Mu = Mn == -INFINITY ? 0.0f : Mn;
-    Lsum = fmaf(Lsum, fast_exp2(M - Mu), v.y * fast_exp2(v.x - Mu));   // spelled out: every call site rounds alike
-    M = Mn;
-  };
-  // lse2 of row tid from the KS staged merges; padding rows get +inf: exp2(x - inf) = 0
-  auto finish_lse = [&](float* __restrict__ dst) {
-    float Mx = -INFINITY;
-#pragma unroll
-    for (int g = 0; g < KS; ++g) Mx = fmaxf(Mx, mstage[g * kRows + tid].x);
-    const float Mu = Mx == -INFINITY ? 0.0f : Mx;
-    float L = 0.0f;
-#pragma unroll
-    for (int g = 0; g < KS; ++g) {
-      const float2 v = mstage[g * kRows + tid];
-      L = fmaf(v.y, fast_exp2(v.x - Mu), L);
-    }
-    dst[tid] = tid < p.rows ? Mx + __log2f(L) : INFINITY;
-  };
+  // lse2 of row tid of this (sequence, head) in lse_rows, per layer of the launch
+  const float* __restrict__ lse_row = lse_rows + ((int64_t)seq * p.Hkv + head) * p.rows_pad + (tid < kRows ? tid : 0);
 
   // Tiles are taken from the last to the first: the statistics kernel, which ran first to last over the same
   // chunks on the same compute units, left its last tiles as the most recently used lines.
-  // First layer: all first loads are issued together (one memory latency, not three).
-  typename PieceVec<TL::kPieces>::type reg = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
-  typename PieceVec<QS::kPieces>::type qreg;
-  if (QS::kEmitViaLds) qreg = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
-  typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
-  store_tile<RS, KS>(tiles, reg);
-  if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
-  store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  // First layer: all first loads are issued together (one memory latency, not three). Tile loads stay in flight
+  // for two steps (one step is shorter than the memory latency under load), so there are two register sets:
+  // the set of the tile of step u is ld[u & 1].
+  typename PieceVec<TL::kPieces>::type ld[2];
+  bf16x8 qf[2][8];
+  {
+    const typename PieceVec<TL::kPieces>::type reg0 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
+    typename PieceVec<QS::kPieces>::type q0;
+    if (QS::kEmitViaLds) q0 = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
+    else load_q_frags(src.q[0] + q_off, rs, p.rows, qf);
+    const typename PieceVec<TL::kPieces>::type reg1 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 1) * TL::kKeys, len - 1);
+    int l2, t2;
+    stream_tile(0, 2, n_steps, n_layers, l2, t2);
+    ld[0] = load_tile<RS, KS>(src.k[l2] + k_off, stride_b, emit_tile(n_iter, t2) * TL::kKeys, len - 1);   // stored by the first step
+    store_tile<RS, KS>(tiles, reg0);
+    if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, q0);
+    store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
+  }
+  // ---- lse2[row] of the first layer
+  if (lse_rows != nullptr) {
+    if (tid < kRows) lse_s[0][tid] = lse_row[0];
+  } else if (lse_in != nullptr) {
+    if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
+      lse_s[0][tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
+  } else {
+    merge_chunks<RS, KS>(reinterpret_cast<const float2*>(partials) + ((int64_t)first_full * p.Hkv + head) * p.rows_pad, n_full,
+                         (uint32_t)(p.Hkv * p.rows_pad), mstage);
+    lds_barrier();
+    if (tid < kRows) lse_s[0][tid] = combine_groups<RS, KS>(mstage, tid, p.rows);
+  }
+  floatx16 acc[2], nxt[2];
+  lds_barrier();                                             // lse2 is complete, the first tile and Q are in place
+  if (QS::kEmitViaLds) read_q_frags(qbuf, rs, qf);
+  mfma_tile<false>(tiles + lane_tile, qf, acc);
+  lds_barrier();                                             // buffer 0 is rewritten by the first step
 
-  int par = 0;                                               // LDS buffer that holds the current layer's first tile
-  for (int li = 0; li < n_layers; ++li) {
-    const char* __restrict__ k_chunk = src.k[li] + k_off;
+  // The key tiles of all layers form one stream: n_steps tiles per layer, layer after layer; tile v of the stream
+  // lives in LDS buffer v & 1. One step: issue the loads of tile v + 3, MFMAs of tile v + 1 into `b`, exponentials
+  // and column sums of tile v from `a`, tile v + 2 from registers to LDS. The step before a layer's last one
+  // fetches the next layer's Q block into LDS; the last step, which has nothing of its own layer left to multiply,
+  // takes that Q as its operand for the next layer's first tile, fetches the next layer's lse2, and is followed
+  // by the layer's epilogue. Loads that a step consumes itself are issued before the tile's, which stay in flight
+  // past the end of the step (loads return in order). Prefix keys are visible to every window row: no mask;
+  // columns past the computed range are discarded in the epilogue. Fixed summation order per column.
+  int li = 0, it = 0;                                          // layer of the call and step within it (uniform over the workgroup)
+  auto step = [&](auto buffer, floatx16 (&a)[2], floatx16 (&b)[2]) {
+    constexpr int kBuf = decltype(buffer)::value;              // buffer of this step's tile
+    if (li >= n_layers) return;                                // the padding step of an odd stream
     const bool has_next = li + 1 < n_layers;
-    const char* __restrict__ k_next = src.k[has_next ? li + 1 : li] + k_off;
-    float* __restrict__ lse_cur = lse_s[li & 1];
-    bf16x8 qf[2][8];
-    if (!QS::kEmitViaLds) load_q_frags(src.q[li] + q_off, rs, p.rows, qf);
-
-    // ---- lse2[row] of this (layer, sequence, head): from the caller's lse (natural log, one per window
-    // row), from the previous layer's last step, or merged here from the chunk partials of the statistics kernel
-    if (lse_in != nullptr) {
-      if (tid < kRows)   // padding rows get +inf: exp2(x - inf) = 0
-        lse_cur[tid] = tid < p.rows ? lse_in[((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w + tid] * kLog2e : INFINITY;
-    } else if (li == 0 || !prefetch_lse) {
-      const float2* __restrict__ psrc = reinterpret_cast<const float2*>(partials + li * partials_stride_layer) + part_off;
-      float M = -INFINITY, Lsum = 0.0f;
-#pragma unroll 4
-      for (int cc = mgrp; cc < n_full; cc += KS) merge_pair(M, Lsum, psrc[cc * part_step]);
-      mstage[mgrp * kRows + mrow] = make_float2(M, Lsum);
-      __syncthreads();
-      if (tid < kRows) finish_lse(lse_cur);
-    }
-    floatx16 acc[2], nxt[2];
-    __syncthreads();                                           // lse_cur is complete, the first tile and Q are in place
-    if (QS::kEmitViaLds) read_q_frags(qbuf, rs, qf);
-    mfma_tile<false>(tiles + par * TL::kTileBytes + lane_tile, qf, acc);
-    __syncthreads();                                           // the buffer of the first tile is rewritten by the first step
-
-    // One step: prefetch the tile of step it + 2, MFMAs of the tile of step it + 1 into `b`, exponentials and
-    // column sums of the tile of step it from `a`. Steps n_steps and n_steps + 1 belong to the next layer; the
-    // last step of a layer multiplies nothing and fetches the next layer's Q block and chunk partials instead.
-    // Prefix keys are visible to every window row: no mask; columns past the computed range are discarded
-    // below. Fixed summation order per column.
-    auto step = [&](auto is_last, int it, floatx16 (&a)[2], floatx16 (&b)[2]) {
-      constexpr bool kLast = decltype(is_last)::value;
-      const int ahead = it + 2;
-      if (ahead >= n_steps && has_next)
-        reg = load_tile<RS, KS>(k_next, stride_b, emit_tile(n_iter, ahead - n_steps) * TL::kKeys, len - 1);
-      else
-        reg = load_tile<RS, KS>(k_chunk, stride_b, emit_tile(n_iter, ahead) * TL::kKeys, len - 1);
-      float2 pf[kEmitPrefetch];
-      if (kLast && has_next) {
-        if (QS::kEmitViaLds) qreg = load_q_pieces<RS, KS>(src.q[li + 1] + q_off, p.rows);
-        if (prefetch_lse) {
-          const float2* __restrict__ psrc = reinterpret_cast<const float2*>(partials + (li + 1) * partials_stride_layer) + part_off;
-#pragma unroll
-          for (int i = 0; i < kEmitPrefetch; ++i) {
-            const int cc = mgrp + i * KS;
-            pf[i] = cc < n_full ? psrc[cc * part_step] : make_float2(-INFINITY, 0.0f);   // (-inf, 0) merges as nothing
-          }
-        }
-      }
-      const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
-      float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-      // one eighth of the exponentials of this step's tile; lz = lse2 of its four rows, read from LDS one slice
-      // ahead (the per-row constants of all 32 accumulator registers would not fit beside the rest)
-      auto exps = [&](int j, const float4 lz) {
-        const int t = j >> 2, e = (j & 3) * 4;
-        s0 += fast_exp2(fmaf(a[t][e], cexp, -lz.x));
-        s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -lz.y));
-        s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -lz.z));
-        s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -lz.w));
-      };
-      float4 lz = rows_of_slice(lse_cur, rs, 0);
-      if (!kLast) {
-        bf16x8 kf[8];
-        read_k_frags(tiles + ((it + 1 + par) & 1) * TL::kTileBytes + lane_tile, kf);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {   // two MFMAs of the next tile, then one eighth of the exponentials of this one
-          __builtin_amdgcn_sched_barrier(0);
-          const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
-          mfma_slice<false>(j, kf, qf, b);
-          exps(j, lz);
-          lz = lz_next;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          exps(j, lz);
-          lz = rows_of_slice(lse_cur, rs, (j + 1) & 7);
-        }
-      }
-      float col = (s0 + s1) + (s2 + s3);
-      const float other = __shfl_xor(col, 32);
-      col = lane < 32 ? col + other : other + col;         // rows 0-3 mod 8 first, in both half-wavefronts
-      if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
-      store_tile<RS, KS>(tiles + ((it + par) & 1) * TL::kTileBytes, reg);
-      if (kLast && has_next) {
-        if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, qreg);
-        if (prefetch_lse) {            // same merge order as at the top of a layer
-          float M = -INFINITY, Lsum = 0.0f;
-#pragma unroll
-          for (int i = 0; i < kEmitPrefetch; ++i) merge_pair(M, Lsum, pf[i]);
-          mstage[mgrp * kRows + mrow] = make_float2(M, Lsum);
-        }
-      }
-      __syncthreads();
+    const int q_part = it + 1 + QS::kParts - n_steps;          // part of the next layer's Q block this step fetches
+    const bool fetch_q = q_part >= 0 && q_part < QS::kParts && has_next;
+    const bool last = it + 1 == n_steps;
+    const bool fetch_lse = last && has_next && tid < kRows;    // multi-layer launches come with lse_rows
+    typename PieceVec<QS::kPartPieces>::type qnext;            // local: no value is carried from step to step
+    float lse_next;
+    if (fetch_q) qnext = load_q_part<RS, KS>(src.q[li + 1] + q_off, p.rows, q_part);
+    if (fetch_lse) lse_next = lse_row[(li + 1) * lse_rows_stride_layer];
+    int la, ta;                                                // tile v + 3: issued now, stored to LDS at the end of the next step
+    stream_tile(li, it + 3, n_steps, n_layers, la, ta);
+    ld[kBuf ^ 1] = load_tile<RS, KS>(src.k[la] + k_off, stride_b, emit_tile(n_iter, ta) * TL::kKeys, len - 1);
+    const float* __restrict__ lse_cur = lse_s[li & 1];
+    const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    // one eighth of the exponentials of this step's tile; lz = lse2 of its four rows, read from LDS one slice
+    // ahead (the per-row constants of all 32 accumulator registers would not fit beside the rest)
+    auto exps = [&](int j, const float4 lz) {
+      const int t = j >> 2, e = (j & 3) * 4;
+      s0 += fast_exp2(fmaf(a[t][e], cexp, -lz.x));
+      s1 += fast_exp2(fmaf(a[t][e + 1], cexp, -lz.y));
+      s2 += fast_exp2(fmaf(a[t][e + 2], cexp, -lz.z));
+      s3 += fast_exp2(fmaf(a[t][e + 3], cexp, -lz.w));
     };
-    // the steps alternate between the two accumulator sets
-    constexpr std::false_type kInner{};
-    constexpr std::true_type kFinal{};
-    int it = 0;
-    for (; it + 2 < n_steps; it += 2) {
-      step(kInner, it, acc, nxt);
-      step(kInner, it + 1, nxt, acc);
-    }
-    if (it + 2 == n_steps) {
-      step(kInner, it, acc, nxt);
-      step(kFinal, it + 1, nxt, acc);
-    } else {
-      step(kFinal, it, acc, nxt);
-    }
-    par ^= n_steps & 1;
-    // ---- sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling
-    for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
-      float a = part[i];
+    float4 lz = rows_of_slice(lse_cur, rs, 0);
+    // After the last layer the product of the last step is of stale operands and unused (cheaper than a second
+    // variant of the step).
+    if (last) read_q_frags(qbuf, rs, qf);                      // the next layer's Q, stored before the previous barrier
+    {
+      const char* __restrict__ next_tile = tiles + (kBuf ^ 1) * TL::kTileBytes + lane_tile;
+      bf16x8 kfj = read_k_frag(next_tile, 0);
 #pragma unroll
-      for (int q = 1; q < RS; ++q) a += part[q * kPartStride + i];
-      part[i] = i < len ? a * p.row_scale : -INFINITY;
-    }
-    if (has_next && prefetch_lse && tid < kRows) finish_lse(lse_s[(li + 1) & 1]);
-    __syncthreads();
-    float* __restrict__ out = scores + li * scores_stride_layer + (int64_t)head * scores_stride_head + begin;
-    for (int s = o0 + tid; s < o1; s += TL::kThreads) {
-      const int i = s - kbeg;
-      float m = part[i];
-      for (int o = 1; o <= half; ++o) {
-        if (i - o >= 0) m = fmaxf(m, part[i - o]);           // i - o < 0 only at the start of the sequence
-        if (i + o < len) m = fmaxf(m, part[i + o]);          // i + o >= len only at the end of the prefix
+      for (int j = 0; j < 8; ++j) {   // two MFMAs of the next tile, then one eighth of the exponentials of this one
+        __builtin_amdgcn_sched_barrier(0);
+        const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
+        const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
+        mfma_slice<false>(j, kfj, qf, b);
+        exps(j, lz);
+        lz = lz_next;
+        kfj = kf_ahead;
       }
-      out[s] = m;
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (c == nc - 1)
-      for (int j = tid; j < p.w; j += TL::kThreads) out[prefix + j] = -INFINITY;   // guard over the window slots
-    if (has_next) __syncthreads();                             // `part` is reused by the next layer
+    float col = (s0 + s1) + (s2 + s3);
+    const float other = __shfl_xor(col, 32);
+    col = lane < 32 ? col + other : other + col;           // rows 0-3 mod 8 first, in both half-wavefronts
+    if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
+    store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2, issued one step ago
+    if (fetch_q) store_q_part<RS, KS>(qbuf, qnext, q_part);    // every wavefront has this layer's Q in registers
+    if (fetch_lse) lse_s[(li + 1) & 1][tid] = lse_next;
+    lds_barrier();
+    if (!last) {
+      ++it;
+      return;
+    }
+    // ---- end of a layer (no loops around memory instructions here: the key tiles of the next layer are in
+    // flight). Sum the row slabs in a fixed order; positions past the computed range are ignored by the pooling.
+    for (int i = tid; i < n_iter * TL::kKeys; i += TL::kThreads) {
+      float x = part[i];
+#pragma unroll
+      for (int q = 1; q < RS; ++q) x += part[q * kPartStride + i];
+      part[i] = i < len ? x * p.row_scale : -INFINITY;
+    }
+    lds_barrier();
+    float* __restrict__ out = scores + li * scores_stride_layer + (int64_t)head * scores_stride_head + begin;
+#pragma unroll
+    for (int u = 0; u < kMaxChunk / TL::kThreads; ++u) {
+      const int s = o0 + tid + u * TL::kThreads;
+      if (s < o1) {
+        const int i = s - kbeg;
+        float m = part[i];
+        for (int o = 1; o <= half; ++o) {
+          if (i - o >= 0) m = fmaxf(m, part[i - o]);         // i - o < 0 only at the start of the sequence
+          if (i + o < len) m = fmaxf(m, part[i + o]);        // i + o >= len only at the end of the prefix
+        }
+        out[s] = m;
+      }
+    }
+    if (c == nc - 1 && tid < p.w) out[prefix + tid] = -INFINITY;   // guard over the window slots (w <= 256 <= threads)
+    if (has_next) lds_barrier();                               // `part` is reused by the next layer
+    ++li;
+    it = 0;
+  };
+  while (li < n_layers) {                                      // the steps alternate between the two accumulator sets
+    step(std::integral_constant<int, 0>{}, acc, nxt);
+    step(std::integral_constant<int, 1>{}, nxt, acc);
   }
 }
 
@@ -666,7 +781,7 @@ static int pick_chunk(const Params& p, int cus) {
   const long long lds_fixed = 2LL * TL::kTileBytes + QStage<RS, KS>::kBytes;
   int max_chunk = (int)((kLdsBudget - lds_fixed) / (RS * (long long)sizeof(float))) - kMaxHalo - 2 * TL::kKeys;
   max_chunk = max_chunk / TL::kKeys * TL::kKeys;
-  if (max_chunk > 4096) max_chunk = 4096;
+  if (max_chunk > kMaxChunk) max_chunk = kMaxChunk;
   const double fixed_us = 6.0, us_per_key = 0.0102;          // measured: 1.3 us per 128-key step of a full device
   int best = 256;
   double best_cost = 1e30;
@@ -704,7 +819,7 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
   const size_t stat_bytes = (size_t)KS * RS * 64 * sizeof(float2);               // the final [KS][RS * 64] partials
   const size_t lds_stats = 2 * TL::kTileBytes + (size_t)QStage<RS, KS>::kBytes + stat_bytes;
   const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * emit_part_stride<RS, KS>(chunk) * sizeof(float) +
-                          (QStage<RS, KS>::kEmitViaLds ? (size_t)QStage<RS, KS>::kBytes : 0);
+                          (size_t)QStage<RS, KS>::kBytes;   // the Q staging area serves the next layer in every variant
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_stats_mfma<RS, KS>),
@@ -733,9 +848,17 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
       rev.k[i] = src.k[n_layers - 1 - i];
     }
     const int last = n_layers - 1;
+    // several layers: their row normalisers are merged from the chunk partials by a small kernel of its own
+    float* lse_rows = nullptr;
+    const int64_t lse_rows_stride_layer = (int64_t)p.n_seqs * p.Hkv * p.rows_pad;
+    if (n_layers > 1) {
+      lse_rows = reinterpret_cast<float*>(ws + wl.lse_rows);
+      launch(DKV_KERNEL_SCORE_MERGE, (score_merge_mfma<RS, KS>), dim3(p.n_seqs, p.Hkv, n_layers), dim3(TL::kThreads), 0, st, p,
+             chunk, cu, static_cast<const float*>(partials), partials_stride_layer, lse_rows);
+    }
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
-           n_layers, rev, k_stride_token * 2, k_stride_head * 2, cu,
-           partials ? static_cast<const float*>(partials) + last * partials_stride_layer : nullptr, -partials_stride_layer,
+           n_layers, rev, k_stride_token * 2, k_stride_head * 2, cu, static_cast<const float*>(partials),
+           lse_rows ? static_cast<const float*>(lse_rows) + last * lse_rows_stride_layer : nullptr, -lse_rows_stride_layer,
            lse_in, scores + last * scores_stride_layer, scores_stride_head, -scores_stride_layer);
   }
   if (phases & kPhaseLse)

@@ -132,7 +132,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "select_order", "score_lse", "pack", "decode")
+                "rebalance_final", "fill", "select_order", "score_lse", "pack", "decode", "score_merge")
 
 
 def dkv_profile_begin(capacity: int) -> None:

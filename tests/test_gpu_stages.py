@@ -30,6 +30,7 @@ CASES = {
     "tiny_norm": W.standard_configs()["tiny"].with_(plant_normalize=True),
     "small_bf16": small_cfg(),
     "small_bf16_gqa7": small_cfg("gqa7", Hq=14, Hkv=2, seqlens=(1111,)),
+    "small_bf16_gqa5": small_cfg("gqa5", Hq=10, Hkv=2, seqlens=(1800,)),     # 160 rows: between two kernel widths
     "small_bf16_d64": small_cfg("d64", d=64, seqlens=(700,)),
     "ragged_f32": small_cfg("ragged_f32", dtype="f32", d=64, Hq=4, Hkv=2, w=16, seqlens=(300, 17, 16, 1000, 259), L=2,
                             interval=2, layer_max=100, mean_budget=30),
@@ -322,8 +323,8 @@ def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
         assert np.array_equal(many.idx[2, s][:, :ref.shape[1]].cpu().numpy(), ref)
 
 
-@pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_bf16", "ragged_f32",
-                                  "long_ragged"])
+@pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_gqa5", "small_bf16_d64",
+                                  "ragged_bf16", "ragged_f32", "long_ragged"])
 def test_layer_batched_scoring_equals_per_layer_calls(dkv, case):
     """dkv_score_window_layers over layers [1, 1 + n) writes, bit for bit, what dkv_score_window writes layer by
     layer (which the tests above check against the oracle), and leaves the other layers' scores alone."""
