@@ -9,10 +9,9 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
              layer i of sequence q holds w + counts[q][i] valid rows per head.
 
 Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
-grouped (`group` > 1): the scoring of up to `group` layers is issued in one call when the group is full or at
-the last layer, followed by the selection and the compaction of its layers (one call each per stretch of layers
-between two update boundaries) and the updates that fall inside the group; the caller then holds the window
-queries, K and V of a group's layers until that point.
+grouped (`group` > 1): the scoring, the selection and the compaction of up to `group` layers are issued in one
+call each when the group is full or at the last layer, followed by the updates that fall inside the group; the
+caller then holds the window queries, K and V of a group's layers until that point.
 """
 from __future__ import annotations
 
@@ -136,17 +135,15 @@ class Compressor:
         if len(self._pending) < self.group and layer != self.cfg.L - 1:
             return
         pending, self._pending = self._pending, []      # the caller may release K and V of these layers afterwards
-        self.score_layers(pending[0][0], [e[3] for e in pending], [e[1] for e in pending], **strides)
-        stretch = []
+        first, n = pending[0][0], len(pending)
+        # a layer's selection and compaction need that layer's scores only, and an update touches the layers before
+        # its boundary only: one call each for the whole group, then the updates that fall inside it, in order
+        self.score_layers(first, [e[3] for e in pending], [e[1] for e in pending], **strides)
+        self.select_layers(first, n)
+        if self.keep_cache:
+            self.gather_layers(first, [e[1] for e in pending], [e[2] for e in pending], **strides)
         for e in pending:
-            stretch.append(e)
-            boundary = (e[0] + 1) % self.cfg.interval == 0
-            if boundary or e is pending[-1]:
-                self.select_layers(stretch[0][0], len(stretch))
-                if self.keep_cache:
-                    self.gather_layers(stretch[0][0], [x[1] for x in stretch], [x[2] for x in stretch], **strides)
-                stretch = []
-            if boundary:
+            if (e[0] + 1) % self.cfg.interval == 0:
                 self._update(e[0] + 1)
 
     def run(self, layers, overlap=False):
