@@ -65,6 +65,9 @@ def main():
                          "1: layer by layer as in Algorithm 1)")
     ap.add_argument("--overlap", action="store_true",
                     help="select/gather/rebalance of layer l on a second stream, next to the scoring of layer l+1")
+    ap.add_argument("--main-only", action="store_true",
+                    help="skip the side measurements (single-sweep scoring, decode attention): under a profiler the "
+                         "per-kernel averages then cover the timed loop alone")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale profiler counters)")
     args = ap.parse_args()
@@ -162,43 +165,44 @@ def main():
                                "mfma_tflops": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12,
                                "mfma_frac": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
 
-    # ---- the single-sweep variant (row normalisers supplied, as a prefill attention kernel would): reported
-    # beside the main figure, never part of `value`. The normalisers come from the library's own statistics.
-    lse_all = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq, cfg.w), dtype=torch.float32, device="cuda")
-    scratch_scores = torch.empty_like(comp.scores[0])
-    for l, (q, k, v) in enumerate(layers):
-        dkv.dkv_score_window_stats(comp.desc, q, k, d, T * d, comp.cu, scratch_scores, T, comp.ws)
-        comp.row_lse(lse_all[l])
-    torch.cuda.synchronize()
-    dkv.dkv_profile_begin(cfg.L * args.steps + 16)
-    for _ in range(args.steps):
+    if not args.main_only:
+        # ---- the single-sweep variant (row normalisers supplied, as a prefill attention kernel would): reported
+        # beside the main figure, never part of `value`. The normalisers come from the library's own statistics.
+        lse_all = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq, cfg.w), dtype=torch.float32, device="cuda")
+        scratch_scores = torch.empty_like(comp.scores[0])
         for l, (q, k, v) in enumerate(layers):
-            dkv.dkv_score_window_lse(comp.desc, q, k, d, T * d, comp.cu, lse_all[l], scratch_scores, T)
-    torch.cuda.synchronize()
-    rec = [us for name, us in dkv.dkv_profile_end(cfg.L * args.steps + 16) if name == "score_emit"]
-    single_us = sum(rec) / max(len(rec), 1)
-    roofline["single_sweep_lse"] = {"us_per_layer": single_us,
-                                    "hbm_frac": (k_bytes + q_bytes + a_bytes) / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+            dkv.dkv_score_window_stats(comp.desc, q, k, d, T * d, comp.cu, scratch_scores, T, comp.ws)
+            comp.row_lse(lse_all[l])
+        torch.cuda.synchronize()
+        dkv.dkv_profile_begin(cfg.L * args.steps + 16)
+        for _ in range(args.steps):
+            for l, (q, k, v) in enumerate(layers):
+                dkv.dkv_score_window_lse(comp.desc, q, k, d, T * d, comp.cu, lse_all[l], scratch_scores, T)
+        torch.cuda.synchronize()
+        rec = [us for name, us in dkv.dkv_profile_end(cfg.L * args.steps + 16) if name == "score_emit"]
+        single_us = sum(rec) / max(len(rec), 1)
+        roofline["single_sweep_lse"] = {"us_per_layer": single_us,
+                                        "hbm_frac": (k_bytes + q_bytes + a_bytes) / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
-    # ---- decode attention of one new token per sequence over the final compressed cache, all layers (reported
-    # beside the main figure, not part of `value`)
-    q_new = torch.randn((cfg.n_seqs, cfg.Hq, d), device="cuda").to(comp.tdtype)
-    dec_out = torch.empty((cfg.n_seqs, cfg.Hq, d), dtype=torch.float32, device="cuda")
-    for l in range(cfg.L):
-        comp.decode_attention(l, q_new, dec_out)
-    torch.cuda.synchronize()
-    dkv.dkv_profile_begin(2 * cfg.L * args.steps + 16)
-    for _ in range(args.steps):
+        # ---- decode attention of one new token per sequence over the final compressed cache, all layers (reported
+        # beside the main figure, not part of `value`)
+        q_new = torch.randn((cfg.n_seqs, cfg.Hq, d), device="cuda").to(comp.tdtype)
+        dec_out = torch.empty((cfg.n_seqs, cfg.Hq, d), dtype=torch.float32, device="cuda")
         for l in range(cfg.L):
             comp.decode_attention(l, q_new, dec_out)
-    torch.cuda.synchronize()
-    rec = [us for name, us in dkv.dkv_profile_end(2 * cfg.L * args.steps + 16) if name == "decode"]
-    dec_us = sum(rec) / max(args.steps * cfg.L, 1)                       # both kernels of a layer
-    counts_h = comp.counts.cpu().numpy()
-    rows = sum(min(cfg.w, S) * cfg.L + int(counts_h[q].sum()) for q, S in enumerate(cfg.seqlens))
-    dec_bytes = rows * cfg.Hkv * d * elt * 2 / cfg.L                      # K and V rows read per layer
-    roofline["decode_attention"] = {"us_per_layer": dec_us, "cache_bytes_per_layer": dec_bytes,
-                                    "hbm_frac": dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        torch.cuda.synchronize()
+        dkv.dkv_profile_begin(2 * cfg.L * args.steps + 16)
+        for _ in range(args.steps):
+            for l in range(cfg.L):
+                comp.decode_attention(l, q_new, dec_out)
+        torch.cuda.synchronize()
+        rec = [us for name, us in dkv.dkv_profile_end(2 * cfg.L * args.steps + 16) if name == "decode"]
+        dec_us = sum(rec) / max(args.steps * cfg.L, 1)                       # both kernels of a layer
+        counts_h = comp.counts.cpu().numpy()
+        rows = sum(min(cfg.w, S) * cfg.L + int(counts_h[q].sum()) for q, S in enumerate(cfg.seqlens))
+        dec_bytes = rows * cfg.Hkv * d * elt * 2 / cfg.L                      # K and V rows read per layer
+        roofline["decode_attention"] = {"us_per_layer": dec_us, "cache_bytes_per_layer": dec_bytes,
+                                        "hbm_frac": dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
     out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

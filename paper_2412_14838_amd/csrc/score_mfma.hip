@@ -685,13 +685,16 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     {
       const char* __restrict__ next_tile = tiles + (kBuf ^ 1) * TL::kTileBytes + lane_tile;
       bf16x8 kfj = read_k_frag(next_tile, 0);
+      // a wavefront whose 32 keys of this tile all lie past the computed range (the ragged tile of the pooling
+      // halo) has no exponentials to take: its column sums are never read
+      const bool live = wave_row0 < len;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {   // two MFMAs of the next tile, then one eighth of the exponentials of this one
         __builtin_amdgcn_sched_barrier(0);
         const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
         const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
         mfma_slice<false>(j, kfj, qf, b);
-        exps(j, lz);
+        if (live) exps(j, lz);
         lz = lz_next;
         kfj = kf_ahead;
       }
@@ -723,11 +726,24 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     for (int u = 0; u < kMaxChunk / TL::kThreads; ++u) {
       const int s = o0 + tid + u * TL::kThreads;
       if (s < o1) {
+        // window [i - half, i + half] cut to [0, len): an index clamped to the range stays inside the window, and
+        // taking an element twice does not change a maximum (the cuts happen only at the two ends of the prefix)
         const int i = s - kbeg;
         float m = part[i];
-        for (int o = 1; o <= half; ++o) {
-          if (i - o >= 0) m = fmaxf(m, part[i - o]);         // i - o < 0 only at the start of the sequence
-          if (i + o < len) m = fmaxf(m, part[i + o]);        // i + o >= len only at the end of the prefix
+        if (half == 3) {                                     // the kernel size the method uses: all reads at once
+          float v[6];
+#pragma unroll
+          for (int o = 1; o <= 3; ++o) {
+            v[2 * o - 2] = part[i - o > 0 ? i - o : 0];
+            v[2 * o - 1] = part[i + o < len ? i + o : len - 1];
+          }
+#pragma unroll
+          for (int q = 0; q < 6; ++q) m = fmaxf(m, v[q]);
+        } else {
+          for (int o = 1; o <= half; ++o) {
+            m = fmaxf(m, part[i - o > 0 ? i - o : 0]);
+            m = fmaxf(m, part[i + o < len ? i + o : len - 1]);
+          }
         }
         out[s] = m;
       }
