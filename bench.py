@@ -81,7 +81,7 @@ def main():
     dkv.load()
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    cfg = W.standard_configs()[args.workload]
+    cfg = W.all_configs()[args.workload]
     workers = min(16, len(os.sched_getaffinity(0)))
     dev, host_sample = [], []
     with cf.ThreadPoolExecutor(max_workers=workers) as ex:

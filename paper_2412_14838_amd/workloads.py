@@ -119,6 +119,18 @@ def standard_configs() -> Dict[str, Workload]:
     return {c.name: c for c in cfgs}
 
 
+def extended_configs() -> Dict[str, Workload]:
+    """Beyond the five benchmark configurations: config 3's shape at four times the context."""
+    base = standard_configs()["mistral_7b_32k"]
+    return {"mistral_7b_128k": base.with_(name="mistral_7b_128k", seqlens=(131072,), seed=1005)}
+
+
+def all_configs() -> Dict[str, Workload]:
+    cfgs = standard_configs()
+    cfgs.update(extended_configs())
+    return cfgs
+
+
 def planted_count(cfg: Workload, layer: int) -> int:
     """Number of planted heavy-key positions of one layer (same for every sequence)."""
     r = _rng(cfg.seed, layer, _TENSOR_PLANT)

@@ -150,6 +150,14 @@ def test_full_ragged_batch8(dkv):
     check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7], group=4)
 
 
+def test_long_context_128k(dkv):
+    """Config 3's shape at a context of 131072 tokens, 8 layers (two updates), the grouped schedule: rows four
+    times longer than the selection keeps in registers, 32 chunks of 4096 keys per head in the score kernels,
+    134 MB of scores under the second update. Same checks as the benchmark configurations."""
+    cfg = W.extended_configs()["mistral_7b_128k"].with_(L=8)
+    check_config(cfg, [0, cfg.L - 1], [2], [0], group=8)
+
+
 @pytest.mark.parametrize("name", ["mistral_7b_32k", "ragged_batch8"])
 def test_full_single_sweep_scoring_from_row_lse(dkv, name):
     """At full size: the exported normalisers match the oracle's log-sum-exp on sampled heads, and the single
