@@ -175,13 +175,15 @@ def main():
             comp.row_lse(lse_all[l])
         torch.cuda.synchronize()
         dkv.dkv_profile_begin(cfg.L * args.steps + 16)
-        for _ in range(args.steps):
-            for l, (q, k, v) in enumerate(layers):
-                dkv.dkv_score_window_lse(comp.desc, q, k, d, T * d, comp.cu, lse_all[l], scratch_scores, T)
+        for _ in range(args.steps):                      # `group` layers per call, as in the timed loop
+            for l0 in range(0, cfg.L, group):
+                part = layers[l0:l0 + group]
+                comp.score_layers_from_lse(l0, [x[0] for x in part], [x[1] for x in part],
+                                           [lse_all[l0 + i] for i in range(len(part))])
         torch.cuda.synchronize()
-        rec = [us for name, us in dkv.dkv_profile_end(cfg.L * args.steps + 16) if name == "score_emit"]
-        single_us = sum(rec) / max(len(rec), 1)
-        roofline["single_sweep_lse"] = {"us_per_layer": single_us,
+        rec = [us for name, us in dkv.dkv_profile_end(cfg.L * args.steps + 16) if name in ("score_emit", "score_merge")]
+        single_us = sum(rec) / max(args.steps * cfg.L, 1)
+        roofline["single_sweep_lse"] = {"us_per_layer": single_us, "layers_per_call": group,
                                         "hbm_frac": (k_bytes + q_bytes + a_bytes) / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
         # ---- decode attention of one new token per sequence over the final compressed cache, all layers (reported

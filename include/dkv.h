@@ -122,7 +122,8 @@ int dkv_profile_end(int32_t* kernel_ids_out /* host */, float* microseconds_out 
  * k          element (seq s, token t, head h, j) at k[(cu_seqlens[s] + t) * k_stride_token + h * k_stride_head + j];
  *            strides in elements, rows 16-byte aligned.
  * scores_out fp32; A[h,s] of sequence q is written to scores_out[h * scores_stride_head + cu_seqlens[q] + s]
- *            for s < S'; the window slots [S', S) of each sequence receive -inf. Candidate scores are >= 0.
+ *            for s < S'; the window slots [S', S) of each sequence longer than the window receive -inf (a
+ *            sequence without a prefix has no candidates and its slots are left alone). Candidate scores are >= 0.
  * Accumulation is fp32 (bf16 products are exact in fp32). Two kernels are enqueued (row statistics, then scores).
  */
 int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
@@ -172,6 +173,17 @@ int dkv_score_window_emit(const dkv_desc* desc, const void* q_win, const void* k
 int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
                          int64_t k_stride_head, const int32_t* cu_seqlens, const float* lse, float* scores_out,
                          int64_t scores_stride_head, void* stream);
+
+/*
+ * dkv_score_window_lse for the n_layers consecutive layers [layer_begin, layer_begin + n_layers) in one call (see
+ * dkv_score_window_layers): h_lse_layers is a HOST array of n_layers device pointers, one lse tensor per layer in
+ * the layout above. Writes the layers' blocks of scores_all. Unlike the single-layer call this one uses the
+ * workspace (the normalisers of all layers are first brought into the kernels' own layout by a small kernel).
+ */
+int dkv_score_window_lse_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers,
+                                const void* const* h_q_layers, const void* const* h_k_layers, int64_t k_stride_token,
+                                int64_t k_stride_head, const int32_t* cu_seqlens, const float* const* h_lse_layers,
+                                float* scores_all, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The normalisers themselves (the denominator of Eq. 1 in log form), from the row statistics that the last

@@ -119,7 +119,8 @@ static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, c
                                const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
                                const int32_t* cu_seqlens, float* scores_out, int64_t scores_stride_head,
                                int64_t scores_stride_layer, void* workspace, size_t workspace_bytes,
-                               const float* lse_in, float* lse_out, void* stream) {
+                               const float* lse_in, float* lse_out, void* stream,
+                               const float* const* lse_layers = nullptr) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   const bool sweeps = (phases & (kPhaseStats | kPhaseEmit)) != 0;       // reads Q and K
@@ -135,7 +136,10 @@ static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, c
   if (st != DKV_OK) return st;
   if ((phases & kPhaseEmit) && scores_stride_head < desc->total_tokens) return DKV_ERR_INVALID_ARG;
   WorkspaceLayout wl{};
-  const bool needs_workspace = phases != kPhaseEmit || lse_in == nullptr;   // everything but the single sweep
+  if (lse_layers)
+    for (int i = 0; i < n_layers; ++i)
+      if (!lse_layers[i]) return DKV_ERR_INVALID_ARG;
+  const bool needs_workspace = phases != kPhaseEmit || lse_in == nullptr;   // everything but the single-layer single sweep
   if (needs_workspace) {
     st = check_workspace(*desc, workspace, workspace_bytes, wl);
     if (st != DKV_OK) return st;
@@ -148,14 +152,15 @@ static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, c
   hipError_t e = hipSuccess;
   if (score_mfma_supported(p, desc->dtype, k_stride_token)) {
     e = launch_score_mfma(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu_seqlens, scores_out,
-                          scores_stride_head, scores_stride_layer, static_cast<char*>(workspace), wl, lse_in, lse_out, hs);
+                          scores_stride_head, scores_stride_layer, static_cast<char*>(workspace), wl, lse_in, lse_layers,
+                          lse_out, hs);
   } else {
     // the vector-ALU kernels take one layer at a time (both sweeps of a layer before the next layer's)
     for (int i = 0; i < (sweeps ? n_layers : 1) && e == hipSuccess; ++i)
       e = launch_score_generic(p, phases, desc->dtype, sweeps ? q_layers[i] : nullptr, sweeps ? k_layers[i] : nullptr,
                                k_stride_token, k_stride_head, cu_seqlens,
                                scores_out ? scores_out + i * scores_stride_layer : nullptr, scores_stride_head,
-                               static_cast<char*>(workspace), wl, lse_in, lse_out, hs);
+                               static_cast<char*>(workspace), wl, lse_layers ? lse_layers[i] : lse_in, lse_out, hs);
   }
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
@@ -202,6 +207,21 @@ int dkv_score_window_lse(const dkv_desc* desc, const void* q_win, const void* k,
   if (!lse) return DKV_ERR_INVALID_ARG;
   return score_window_phases(kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens, scores_out,
                              scores_stride_head, 0, nullptr, 0, lse, nullptr, stream);
+}
+
+int dkv_score_window_lse_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers,
+                                const void* const* h_q_layers, const void* const* h_k_layers, int64_t k_stride_token,
+                                int64_t k_stride_head, const int32_t* cu_seqlens, const float* const* h_lse_layers,
+                                float* scores_all, void* workspace, size_t workspace_bytes, void* stream) {
+  const int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!scores_all || !h_lse_layers) return DKV_ERR_INVALID_ARG;
+  if (n_layers < 1 || n_layers > DKV_MAX_SELECT_LAYERS) return DKV_ERR_INVALID_ARG;
+  if (layer_begin < 0 || layer_begin + n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  const int64_t stride_layer = (int64_t)desc->n_kv_heads * desc->total_tokens;
+  return score_window_phases(kPhaseEmit, desc, n_layers, h_q_layers, h_k_layers, k_stride_token, k_stride_head,
+                             cu_seqlens, scores_all + layer_begin * stride_layer, desc->total_tokens, stride_layer,
+                             workspace, workspace_bytes, nullptr, nullptr, stream, h_lse_layers);
 }
 
 int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_seqlens, float* lse_out,

@@ -123,7 +123,8 @@ bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token);
 hipError_t launch_score_mfma(const Params& p, int phases, int n_layers, const void* const* q_layers,
                              const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
                              const int32_t* cu, float* scores, int64_t scores_stride_head, int64_t scores_stride_layer,
-                             char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st);
+                             char* ws, const WorkspaceLayout& wl, const float* lse_in, const float* const* lse_layers,
+                             float* lse_out, hipStream_t st);
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
                          int64_t scores_stride_layer, const int32_t* cu, int32_t* idx_out, int64_t idx_stride_layer,
                          int32_t* counts, char* ws, const WorkspaceLayout& wl, hipStream_t st);

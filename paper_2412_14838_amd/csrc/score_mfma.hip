@@ -553,6 +553,20 @@ __global__ __launch_bounds__(RS * KS * 64) void score_merge_mfma(Params p, int c
         combine_groups<RS, KS>(mstage, threadIdx.x, p.rows);
 }
 
+// Row normalisers supplied by the caller for every layer of a multi-layer call (natural log, [n_seqs][Hq][w] per
+// layer) into the layout and the log2 domain the emit kernel reads. grid = (n_seqs, Hkv, n_layers), 256 threads.
+struct LseLayers {
+  const float* lse[DKV_MAX_SELECT_LAYERS];
+};
+
+__global__ __launch_bounds__(256) void score_import_lse(Params p, LseLayers src, float* __restrict__ lse_rows) {
+  const int seq = blockIdx.x, head = blockIdx.y, layer = blockIdx.z;
+  const float* __restrict__ in = src.lse[layer] + ((int64_t)seq * p.Hq + (int64_t)head * p.G) * p.w;
+  float* __restrict__ out = lse_rows + (((int64_t)layer * p.n_seqs + seq) * p.Hkv + head) * p.rows_pad;
+  for (int r = threadIdx.x; r < p.rows_pad; r += 256)   // padding rows get +inf: exp2(x - inf) = 0
+    out[r] = r < p.rows ? in[r] * kLog2e : INFINITY;
+}
+
 // Outputs per thread of the emit kernel's epilogue (the chunk is at most kMaxChunk outputs).
 constexpr int kMaxChunk = 4096;
 
@@ -827,6 +841,7 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
                                 const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
                                 const int32_t* cu, float* scores, int64_t scores_stride_head,
                                 int64_t scores_stride_layer, char* ws, const WorkspaceLayout& wl, const float* lse_in,
+                                const float* const* lse_layers,
                                 float* lse_out, hipStream_t st) {
   using TL = Tile<RS, KS>;
   const int chunk = pick_chunk<RS, KS>(p, device_cus());
@@ -869,8 +884,16 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
     const int64_t lse_rows_stride_layer = (int64_t)p.n_seqs * p.Hkv * p.rows_pad;
     if (n_layers > 1) {
       lse_rows = reinterpret_cast<float*>(ws + wl.lse_rows);
-      launch(DKV_KERNEL_SCORE_MERGE, (score_merge_mfma<RS, KS>), dim3(p.n_seqs, p.Hkv, n_layers), dim3(TL::kThreads), 0, st, p,
-             chunk, cu, static_cast<const float*>(partials), partials_stride_layer, lse_rows);
+      if (lse_layers != nullptr) {       // single sweep: the caller's normalisers, no statistics
+        LseLayers in{};
+        for (int i = 0; i < n_layers; ++i) in.lse[i] = lse_layers[i];
+        launch(DKV_KERNEL_SCORE_MERGE, score_import_lse, dim3(p.n_seqs, p.Hkv, n_layers), dim3(256), 0, st, p, in, lse_rows);
+      } else {
+        launch(DKV_KERNEL_SCORE_MERGE, (score_merge_mfma<RS, KS>), dim3(p.n_seqs, p.Hkv, n_layers), dim3(TL::kThreads), 0, st,
+               p, chunk, cu, static_cast<const float*>(partials), partials_stride_layer, lse_rows);
+      }
+    } else if (lse_layers != nullptr) {
+      lse_in = lse_layers[0];
     }
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
            n_layers, rev, k_stride_token * 2, k_stride_head * 2, cu, static_cast<const float*>(partials),
@@ -885,15 +908,16 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
 hipError_t launch_score_mfma(const Params& p, int phases, int n_layers, const void* const* q_layers,
                              const void* const* k_layers, int64_t k_stride_token, int64_t k_stride_head,
                              const int32_t* cu, float* scores, int64_t scores_stride_head, int64_t scores_stride_layer,
-                             char* ws, const WorkspaceLayout& wl, const float* lse_in, float* lse_out, hipStream_t st) {
+                             char* ws, const WorkspaceLayout& wl, const float* lse_in, const float* const* lse_layers,
+                             float* lse_out, hipStream_t st) {
   if (p.rows <= 64)
     return launch_mfma_t<1, 4>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
-                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
+                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_layers, lse_out, st);
   if (p.rows <= 128)
     return launch_mfma_t<2, 4>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
-                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
+                               scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_layers, lse_out, st);
   return launch_mfma_t<4, 2>(p, phases, n_layers, q_layers, k_layers, k_stride_token, k_stride_head, cu, scores,
-                             scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_out, st);
+                             scores_stride_head, scores_stride_layer, ws, wl, lse_in, lse_layers, lse_out, st);
 }
 
 }  // namespace dkv

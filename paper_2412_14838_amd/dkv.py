@@ -18,7 +18,7 @@ DKV_MAX_SELECT_LAYERS = 8
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
-           "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
+           "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
            "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention")
 
 
@@ -66,6 +66,8 @@ def load() -> C.CDLL:
     lib.dkv_score_window_layers.argtypes = [D, I32, I32, P, P, I64, I64, P, P, P, SZ, P]
     lib.dkv_score_window_lse.restype = C.c_int
     lib.dkv_score_window_lse.argtypes = [D, P, P, I64, I64, P, P, P, I64, P]
+    lib.dkv_score_window_lse_layers.restype = C.c_int
+    lib.dkv_score_window_lse_layers.argtypes = [D, I32, I32, P, P, I64, I64, P, P, P, P, SZ, P]
     lib.dkv_row_lse.restype = C.c_int
     lib.dkv_row_lse.argtypes = [D, I64, P, P, P, SZ, P]
     lib.dkv_select_topk.restype = C.c_int
@@ -166,6 +168,19 @@ def dkv_score_window_layers(desc, layer_begin, q_layers, k_layers, k_stride_toke
                                           _ptr(cu_seqlens), _ptr(scores_all), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream(stream)),
            "dkv_score_window_layers")
+
+
+def dkv_score_window_lse_layers(desc, layer_begin, q_layers, k_layers, k_stride_token, k_stride_head, cu_seqlens,
+                                lse_layers, scores_all, workspace, stream=None) -> None:
+    """q_layers, k_layers, lse_layers: sequences of device tensors, one per layer of the call."""
+    n = len(k_layers)
+    qs = (C.c_void_p * n)(*[t.data_ptr() for t in q_layers])
+    ks = (C.c_void_p * n)(*[t.data_ptr() for t in k_layers])
+    ls = (C.c_void_p * n)(*[t.data_ptr() for t in lse_layers])
+    _check(load().dkv_score_window_lse_layers(C.byref(desc), layer_begin, n, qs, ks, k_stride_token, k_stride_head,
+                                              _ptr(cu_seqlens), ls, _ptr(scores_all), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_score_window_lse_layers")
 
 
 def dkv_score_window_stats(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,

@@ -130,6 +130,15 @@ class Compressor:
         sh = self.cfg.total_tokens * d if stride_head is None else stride_head
         dkv.dkv_score_window_layers(self.desc, layer_begin, qs, ks, st, sh, self.cu, self.scores, self.ws, stream)
 
+    def score_layers_from_lse(self, layer_begin, qs, ks, lses, stride_token=None, stride_head=None, stream=None):
+        """One sweep over K per layer, several layers per call, with the caller's row normalisers (one tensor
+        [n_seqs][Hq][w], natural log, per layer)."""
+        d = self.cfg.d
+        st = d if stride_token is None else stride_token
+        sh = self.cfg.total_tokens * d if stride_head is None else stride_head
+        dkv.dkv_score_window_lse_layers(self.desc, layer_begin, qs, ks, st, sh, self.cu, lses, self.scores, self.ws,
+                                        stream)
+
     def _step_grouped(self, layer, q_win, k, v, **strides):
         self._pending.append((layer, k, v, q_win))
         if len(self._pending) < self.group and layer != self.cfg.L - 1:

@@ -166,6 +166,24 @@ def test_layer_batched_scoring_rejects_bad_ranges_and_pointers(lib):
     assert call(None, 0, 2, ptrs, ptrs, 64, 65536, fake, fake, fake, need, None) == inv
 
 
+def test_layer_batched_single_sweep_validates_its_arguments(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    ptrs = (C.c_void_p * 9)(*([0x1000] * 9))
+    bad = (C.c_void_p * 2)(0x1000, 0)          # a null layer pointer
+    call = lib.dkv_score_window_lse_layers
+    for begin, n in ((0, 0), (0, 9), (3, 2), (-1, 1), (4, 1)):
+        assert call(C.byref(d), begin, n, ptrs, ptrs, 64, 65536, fake, ptrs, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, bad, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, None, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, bad, ptrs, 64, 65536, fake, ptrs, fake, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, ptrs, None, fake, need, None) == inv
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, ptrs, fake, None, need, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), 0, 2, ptrs, ptrs, 64, 65536, fake, ptrs, fake, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
+
+
 def test_lse_calls_validate_their_arguments(lib):
     d = _good()
     need = dkv.dkv_workspace_bytes(d)

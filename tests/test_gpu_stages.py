@@ -425,6 +425,41 @@ def test_row_lse_and_single_sweep_scoring(dkv, case):
         assert np.isneginf(got[:, cu[s] + n:cu[s + 1]]).all()
 
 
+@pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "ragged_bf16", "ragged_f32"])
+def test_layer_batched_single_sweep_equals_per_layer_calls(dkv, case):
+    """dkv_score_window_lse_layers over three layers with the library's own exported normalisers writes, bit for
+    bit, what dkv_score_window_lse writes layer by layer, and (like that call, checked against the oracle
+    above) reproduces the two-sweep scores."""
+    cfg = CASES[case].with_(L=max(CASES[case].L, 4))
+    one, many = Compressor(cfg, keep_cache=False), Compressor(cfg, keep_cache=False)
+    data = [to_device(cfg, W.make_layer(cfg, l)) for l in range(cfg.L)]
+    lses = []
+    for l in range(cfg.L):
+        one.score(l, data[l]["q_win"], data[l]["k"])
+        lse = torch.full((cfg.n_seqs, cfg.Hq, cfg.w), float("nan"), dtype=torch.float32, device="cuda")
+        one.row_lse(lse)
+        lses.append(lse)
+    torch.cuda.synchronize()
+    two_sweep = one.scores.clone()
+    one.scores.fill_(55.0)          # slots of sequences without a prefix are written by no call
+    many.scores.fill_(55.0)
+    for l in (1, 2, 3):
+        one.score_from_lse(l, data[l]["q_win"], data[l]["k"], lses[l])
+    many.score_layers_from_lse(1, [data[l]["q_win"] for l in (1, 2, 3)], [data[l]["k"] for l in (1, 2, 3)],
+                               [lses[l] for l in (1, 2, 3)])
+    torch.cuda.synchronize()
+    assert torch.equal(one.scores[1:4].view(torch.int32), many.scores[1:4].view(torch.int32))
+    assert (many.scores[0] == 55.0).all()
+    a, b = two_sweep[1:4].cpu().numpy(), many.scores[1:4].cpu().numpy()
+    cu = cfg.cu_seqlens
+    for s in range(cfg.n_seqs):
+        n = cfg.seqlens[s] - cfg.w
+        if n > 0:
+            x, y = a[:, :, cu[s]:cu[s] + n], b[:, :, cu[s]:cu[s] + n]
+            assert (np.abs(x - y) <= 1e-5 * np.abs(x)).all()
+            assert np.isneginf(b[:, :, cu[s] + n:cu[s + 1]]).all()
+
+
 @pytest.mark.parametrize("case", ["tiny_norm", "small_bf16", "ragged_bf16", "short_seqs"])
 def test_pack_cache_equals_the_oracles_final_cache(dkv, case):
     """dkv_pack_cache lays the valid rows of every (sequence, layer, head) block next to each other: the oracle's
