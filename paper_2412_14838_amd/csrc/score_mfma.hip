@@ -486,6 +486,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 template <int RS, int KS>
 __host__ __device__ inline int emit_part_stride(int chunk) { return chunk + kMaxHalo + 2 * Tile<RS, KS>::kKeys; }
 
+// Slabs of that size in LDS: one per row slab, and at least two (the second also holds the pooled outputs).
+template <int RS>
+__host__ __device__ constexpr int emit_slabs() { return RS > 1 ? RS : 2; }
+
 // Key tile that step `it` of the emit kernel works on (steps past the first tile repeat it: same values again).
 __device__ inline int emit_tile(int n_iter, int it) { return it < n_iter ? n_iter - 1 - it : 0; }
 
@@ -589,10 +593,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   using QS = QStage<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
-  float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [RS][kPartStride]
+  float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [emit_slabs][kPartStride]
   const int kPartStride = emit_part_stride<RS, KS>(chunk);
   constexpr int kRows = RS * 64;
-  char* qbuf = smem + 2 * TL::kTileBytes + RS * kPartStride * sizeof(float);   // Q staging
+  char* qbuf = smem + 2 * TL::kTileBytes + emit_slabs<RS>() * kPartStride * sizeof(float);   // Q staging
   __shared__ float2 mstage[KS * kRows];                                        // partial merges of KS thread groups
   __shared__ __attribute__((aligned(16))) float lse_s[2][kRows];               // lse2 per row, by layer parity
 
@@ -735,32 +739,24 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
       part[i] = i < len ? x * p.row_scale : -INFINITY;
     }
     lds_barrier();
+    // max-pool into the second slab (its column sums are summed up by now; every thread reads back only what it
+    // wrote itself), window [i - half, i + half] cut to [0, len): an index clamped to the range stays inside the
+    // window, and taking an element twice does not change a maximum
+    float* __restrict__ pooled = part + kPartStride;
+    for (int s = o0 + tid; s < o1; s += TL::kThreads) {
+      const int i = s - kbeg;
+      float m = part[i];
+      for (int o = 1; o <= half; ++o) {
+        const float lo = part[i - o > 0 ? i - o : 0], hi = part[i + o < len ? i + o : len - 1];
+        m = fmaxf(m, fmaxf(lo, hi));
+      }
+      pooled[s - o0] = m;
+    }
     float* __restrict__ out = scores + li * scores_stride_layer + (int64_t)head * scores_stride_head + begin;
 #pragma unroll
-    for (int u = 0; u < kMaxChunk / TL::kThreads; ++u) {
+    for (int u = 0; u < kMaxChunk / TL::kThreads; ++u) {      // straight-line stores
       const int s = o0 + tid + u * TL::kThreads;
-      if (s < o1) {
-        // window [i - half, i + half] cut to [0, len): an index clamped to the range stays inside the window, and
-        // taking an element twice does not change a maximum (the cuts happen only at the two ends of the prefix)
-        const int i = s - kbeg;
-        float m = part[i];
-        if (half == 3) {                                     // the kernel size the method uses: all reads at once
-          float v[6];
-#pragma unroll
-          for (int o = 1; o <= 3; ++o) {
-            v[2 * o - 2] = part[i - o > 0 ? i - o : 0];
-            v[2 * o - 1] = part[i + o < len ? i + o : len - 1];
-          }
-#pragma unroll
-          for (int q = 0; q < 6; ++q) m = fmaxf(m, v[q]);
-        } else {
-          for (int o = 1; o <= half; ++o) {
-            m = fmaxf(m, part[i - o > 0 ? i - o : 0]);
-            m = fmaxf(m, part[i + o < len ? i + o : len - 1]);
-          }
-        }
-        out[s] = m;
-      }
+      if (s < o1) out[s] = pooled[s - o0];
     }
     if (c == nc - 1 && tid < p.w) out[prefix + tid] = -INFINITY;   // guard over the window slots (w <= 256 <= threads)
     if (has_next) lds_barrier();                               // `part` is reused by the next layer
@@ -809,7 +805,7 @@ template <int RS, int KS>
 static int pick_chunk(const Params& p, int cus) {
   using TL = Tile<RS, KS>;
   const long long lds_fixed = 2LL * TL::kTileBytes + QStage<RS, KS>::kBytes;
-  int max_chunk = (int)((kLdsBudget - lds_fixed) / (RS * (long long)sizeof(float))) - kMaxHalo - 2 * TL::kKeys;
+  int max_chunk = (int)((kLdsBudget - lds_fixed) / (emit_slabs<RS>() * (long long)sizeof(float))) - kMaxHalo - 2 * TL::kKeys;
   max_chunk = max_chunk / TL::kKeys * TL::kKeys;
   if (max_chunk > kMaxChunk) max_chunk = kMaxChunk;
   const double fixed_us = 6.0, us_per_key = 0.0102;          // measured: 1.3 us per 128-key step of a full device
@@ -849,7 +845,7 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
   const int64_t partials_stride_layer = (int64_t)wl.partials_layer_bytes / (int64_t)sizeof(float);
   const size_t stat_bytes = (size_t)KS * RS * 64 * sizeof(float2);               // the final [KS][RS * 64] partials
   const size_t lds_stats = 2 * TL::kTileBytes + (size_t)QStage<RS, KS>::kBytes + stat_bytes;
-  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)RS * emit_part_stride<RS, KS>(chunk) * sizeof(float) +
+  const size_t lds_emit = 2 * TL::kTileBytes + (size_t)emit_slabs<RS>() * emit_part_stride<RS, KS>(chunk) * sizeof(float) +
                           (size_t)QStage<RS, KS>::kBytes;   // the Q staging area serves the next layer in every variant
   static bool attr_set = false;
   if (!attr_set) {
