@@ -6,18 +6,24 @@
 //   stats kernel: S_tile = K_tile . Q^T  (keys as the MFMA M index, rows as N: a lane holds ONE row and 16
 //                 keys, so the running row maximum / sum of exponentials is an in-lane reduction); every
 //                 workgroup writes one partial (max, sum) per row for its chunk of keys;
-//   emit kernel:  merges the chunk partials of its (sequence, head) into lse2[row] (kernel boundaries are the
-//                 only synchronisation between workgroups), then S_tile = Q . K_tile^T (rows as M, keys as N:
-//                 a lane holds ONE key and 16 rows, so the sum over the rows is an in-lane reduction),
-//                 p = exp2(S * c - lse2[row]), window/group sum, max-pool, write.
+//   merge:        the chunk partials of a (sequence, head) become lse2[row] (kernel boundaries are the only
+//                 synchronisation between workgroups): in the emit kernel's prologue for a single layer, in a
+//                 small kernel of its own when a call covers several layers;
+//   emit kernel:  S_tile = Q . K_tile^T (rows as M, keys as N: a lane holds ONE key and 16 rows, so the sum over
+//                 the rows is an in-lane reduction), p = exp2(S * c - lse2[row]), window/group sum, max-pool,
+//                 write.
 // Both use v_mfma_f32_32x32x16_bf16 with the whole Q block of the wavefront resident in registers and K tiles
 // staged through LDS (coalesced 16-byte global loads, padded rows, 16-byte LDS reads in MFMA operand layout).
-// The MFMAs of tile i+1 are issued in the same loop body as the exponentials of tile i (two accumulator sets).
+// The MFMAs of one tile are issued in the same step as the exponentials of the tile before it (two accumulator
+// sets), while the loads of the tile three steps on are issued and the tile two steps on goes to LDS.
 //
 // Workgroup = RS x KS wavefronts: RS row slabs of 64 rows (2 MFMA tiles) x KS key tiles of 32 keys.
-// Every workgroup owns a contiguous chunk of one (sequence, KV head). The emit kernel computes (P-1)/2 extra
-// keys on each side of its output chunk, so pooling never needs another workgroup's sums; identical keys give
-// bit-identical sums whichever workgroup or lane computes them (fixed summation order per column).
+// Every workgroup owns a contiguous chunk of one (sequence, KV head) and takes it through all layers of the call
+// (up to DKV_MAX_SELECT_LAYERS): the key tiles of the layers form one stream of steps, the next layer's Q and
+// normalisers arrive while the current layer's last steps run. The emit kernel computes (P-1)/2 extra keys on
+// each side of its output chunk, so pooling never needs another workgroup's sums; identical keys give
+// bit-identical sums whichever workgroup or lane computes them (fixed summation order per column), and a layer
+// gets the same bits whether it is scored alone or as part of a multi-layer call.
 #include "dkv_internal.h"
 
 #include <type_traits>
