@@ -50,7 +50,8 @@ enum {
 #define DKV_MAX_SEQS 4096
 #define DKV_MAX_LAYERS 512
 #define DKV_MAX_DECODE_GROUP 16   /* query heads per KV head dkv_decode_attention handles */
-#define DKV_MAX_SELECT_LAYERS 8   /* layers one dkv_select_topk_layers call may cover */
+#define DKV_MAX_SELECT_LAYERS 8   /* layers one dkv_*_layers call may cover */
+#define DKV_MAX_UPDATES 4         /* progressive updates per dkv_rebalance_batch call */
 
 /* Problem descriptor (host memory, read during the call only). Symbols as in Algorithm 1. */
 typedef struct dkv_desc {
@@ -245,6 +246,21 @@ int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_
 int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
                   int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
                   size_t workspace_bytes, void* stream);
+
+/*
+ * The n_updates consecutive updates after layers_done, layers_done + interval, ... layers in one call (Section 4.2
+ * as above, once per update): for a caller that has scored and selected the layers of several update intervals
+ * before it updates (see dkv_score_window_layers). The updates read the scores only and meet in
+ * counts[q][i] <- min(counts[q][i], Z'_i), which commutes, so the result equals n_updates dkv_rebalance calls in
+ * order; every kernel of the update takes the updates side by side.
+ * n_updates          1 .. DKV_MAX_UPDATES; layers_done + (n_updates - 1) * interval <= L.
+ * budgets_out, hits_out   as for dkv_rebalance, one [n_seqs][L] block per update: update u writes at
+ *                    out + u * out_stride_update (ints; >= n_seqs * L when n_updates > 1). May be NULL.
+ * The history rule of dkv_rebalance applies with the last update's layers_done.
+ */
+int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, const float* scores_all,
+                        const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
+                        int64_t out_stride_update, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Compaction of the retained K/V rows of layer index `layer` (Algorithm 1, the two cat(gather(...), window) lines).

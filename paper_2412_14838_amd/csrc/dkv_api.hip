@@ -269,20 +269,32 @@ int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 
-int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
-                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
-                  size_t workspace_bytes, void* stream) {
+int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, const float* scores_all,
+                        const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
+                        int64_t out_stride_update, void* workspace, size_t workspace_bytes, void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   if (!scores_all || !cu_seqlens || !counts || !aligned16(scores_all)) return DKV_ERR_INVALID_ARG;
-  if (layers_done < 1 || layers_done > desc->n_layers || layers_done % desc->interval != 0) return DKV_ERR_INVALID_ARG;
+  if (n_updates < 1 || n_updates > DKV_MAX_UPDATES) return DKV_ERR_INVALID_ARG;
+  if (layers_done < 1 || layers_done % desc->interval != 0) return DKV_ERR_INVALID_ARG;
+  if ((int64_t)layers_done + (int64_t)(n_updates - 1) * desc->interval > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  if (n_updates > 1 && (budgets_out || hits_out) && out_stride_update < (int64_t)desc->n_seqs * desc->n_layers)
+    return DKV_ERR_INVALID_ARG;
   WorkspaceLayout wl;
   st = check_workspace(*desc, workspace, workspace_bytes, wl);
   if (st != DKV_OK) return st;
   const Params p = make_params(*desc);
-  const hipError_t e = launch_rebalance(p, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out,
-                                        static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_rebalance(p, layers_done, n_updates, scores_all, cu_seqlens, counts, budgets_out, hits_out,
+                                        out_stride_update, static_cast<char*>(workspace), wl,
+                                        static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
+                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  return dkv_rebalance_batch(desc, layers_done, 1, scores_all, cu_seqlens, counts, budgets_out, hits_out, 0, workspace,
+                             workspace_bytes, stream);
 }
 
 int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void* v, int64_t stride_token,

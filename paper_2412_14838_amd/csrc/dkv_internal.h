@@ -30,11 +30,13 @@ struct WorkspaceLayout {
   size_t select_keys;  // uint64 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][DKV_MAX_LAYER_MAX] unordered winners of the selection
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
   size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
-  size_t tot0;         // int32 [n_seqs][kRadixBins]     top digit
+  size_t tot0;         // int32 [DKV_MAX_UPDATES][n_seqs][kRadixBins]  top digit: slot 0 kept from call to call, slot u the layers new to update u
   size_t tot1;         // int32 [n_seqs][kRadixBins]     middle digit, elements sharing the threshold's top digit
   size_t tot2;         // int32 [n_seqs][1024]           last digit, elements sharing the two digits above
   size_t hist2;        // int32 [n_seqs][L][1024]        the same per layer
   size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
+  size_t tot0_slot_bytes;      // one of the DKV_MAX_UPDATES slots of the top-digit histogram
+  size_t update_block_bytes;   // tot1 .. above of one update; DKV_MAX_UPDATES such blocks follow each other
   size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
   size_t total;
   int rows_pad;        // padded_rows(G*w)
@@ -63,11 +65,15 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
   w.header = off;   off += align256(8 * sizeof(int32_t));
-  w.tot0 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
-  w.tot1 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));   // tot1 .. above: cleared per call
+  w.tot0_slot_bytes = align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
+  w.tot0 = off;     off += w.tot0_slot_bytes * DKV_MAX_UPDATES;
+  const size_t block = off;                                                             // tot1 .. above: one update's block
+  w.tot1 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
   w.tot2 = off;     off += align256(size_t(d.n_seqs) * 1024 * sizeof(int32_t));
   w.hist2 = off;    off += align256(size_t(d.n_seqs) * d.n_layers * 1024 * sizeof(int32_t));
   w.above = off;    off += align256(size_t(d.n_seqs) * d.n_layers * sizeof(int32_t));
+  w.update_block_bytes = off - block;
+  off = block + w.update_block_bytes * DKV_MAX_UPDATES;                                 // one block per update of a call
   w.total = off;
   return w;
 }
@@ -135,9 +141,9 @@ hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, 
 hipError_t launch_decode(const Params& p, int dtype, int layer, const void* q_new, const void* kb, const void* vb,
                          int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts, float* out,
                          float* lse_out, char* ws, const WorkspaceLayout& wl, hipStream_t st);
-hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
-                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
-                            const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, const float* scores_all, const int32_t* cu,
+                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, int64_t out_stride_update,
+                            char* ws, const WorkspaceLayout& wl, hipStream_t st);
 hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers, const void* const* k_layers,
                          const void* const* v_layers, int64_t stride_token, int64_t stride_head, const int32_t* cu,
                          const int32_t* idx, int64_t idx_stride_layer, const int32_t* counts, void* k_out, void* v_out,

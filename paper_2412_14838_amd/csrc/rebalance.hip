@@ -16,6 +16,12 @@
 //   final   one workgroup per sequence: digit 2, then cnt_i = #{> T in layer i} + the share of the elements
 //           equal to T that the tie rule (lower layer first) gives to layer i, then Z, Z' and counts.
 // The scans read the scores as 16-byte vectors, all loads of a workgroup's chunk in flight together.
+//
+// Several consecutive updates (layers_done, layers_done + interval, ...) can be asked for in one call: they are
+// independent of each other except for the final min into `counts`, which commutes. Update u then owns slot u
+// of every histogram: T[u] holds the top-digit histogram of the layers that are new to update u (T[0]
+// additionally the kept history), so update u's top-digit histogram is T[0] + ... + T[u]; every kernel takes
+// the update as one more grid dimension. The next call folds T[1..] into T[0] before it starts.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -38,6 +44,9 @@ __device__ inline int layers_already_counted(const int32_t* __restrict__ header,
   return same && layers_done > interval ? layers_done - interval : 0;
 }
 
+// always: the per-update histograms of this call (n_updates slots, contiguous); tot0: the kMaxUpdates slots T[v] of
+// the top-digit histogram, tot0_words each. With a matching history the slots the previous call used (header[7])
+// are folded into T[0]; without, T[0] starts from zero. The other slots are zeroed either way.
 __global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restrict__ always, size_t always_words,
                                                               uint32_t* __restrict__ tot0, size_t tot0_words,
                                                               const int32_t* __restrict__ header,
@@ -45,8 +54,16 @@ __global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restri
                                                               int n_seqs, int total_tokens) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < always_words; i += stride) always[i] = 0u;
-  if (layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens) == 0)
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < tot0_words; i += stride) tot0[i] = 0u;
+  const bool keep = layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens) != 0;
+  int used = keep ? header[7] : 0;
+  used = used < 1 ? 1 : (used > DKV_MAX_UPDATES ? DKV_MAX_UPDATES : used);
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < tot0_words; i += stride) {
+    uint32_t v = 0u;
+    if (keep)
+      for (int u = 0; u < used; ++u) v += tot0[(size_t)u * tot0_words + i];
+    tot0[i] = v;
+    for (int u = 1; u < DKV_MAX_UPDATES; ++u) tot0[(size_t)u * tot0_words + i] = 0u;
+  }
 }
 
 // A workgroup's chunk of one (layer, head, sequence) score row as 16-byte vectors: element e of the score tensor
@@ -122,6 +139,18 @@ __device__ inline Bins<NT, NB> load_bins(const int32_t* __restrict__ tot) {
   return b;
 }
 
+// The same, summed over the first n_slots histograms (slot stride in ints).
+template <int NT, int NB>
+__device__ inline Bins<NT, NB> load_bins_sum(const int32_t* __restrict__ tot, int n_slots, int64_t slot_stride) {
+  Bins<NT, NB> b = load_bins<NT, NB>(tot);
+  for (int u = 1; u < n_slots; ++u) {
+    const Bins<NT, NB> x = load_bins<NT, NB>(tot + u * slot_stride);
+#pragma unroll
+    for (int i = 0; i < NB / NT; ++i) b.c[i] += x.c[i];
+  }
+  return b;
+}
+
 // The digit that holds the rem-th largest element of the histogram, and the rank that remains inside it (both 0
 // when rem <= 0). scratch: NT / 64 ints, sh: 2 ints (LDS). Starts and ends with a barrier.
 template <int NT, int NB>
@@ -162,15 +191,17 @@ __device__ inline int global_k(const int32_t* __restrict__ cu, int seq, int w, i
 }
 
 // Top-digit histogram of the layers not yet counted. grid = (chunk upper bound, Hkv, layers_done), 256 threads.
+// layers_done: of the call's first update; layers at or past it belong to the later updates' slots.
 __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
                                                               int layers_done, int interval,
                                                               const float* __restrict__ scores_all,
                                                               const int32_t* __restrict__ cu,
                                                               const int32_t* __restrict__ header,
-                                                              int32_t* __restrict__ tot0) {
+                                                              int32_t* __restrict__ tot0, int64_t tot0_words) {
   __shared__ int h[kRadixBins * kHist0Copies];
   const int head = blockIdx.y, layer = blockIdx.z;
   if (layer < layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens)) return;
+  const int slot = layer < layers_done ? 0 : 1 + (layer - layers_done) / interval;
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kHist0Chunk, w, blockIdx.x, seq, c, begin, len)) return;
   const int n = len - w;
@@ -197,7 +228,7 @@ __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hk
     }
   }
   __syncthreads();
-  int32_t* __restrict__ g = tot0 + (int64_t)seq * kRadixBins;
+  int32_t* __restrict__ g = tot0 + slot * tot0_words + (int64_t)seq * kRadixBins;
   for (int b = threadIdx.x; b < kRadixBins; b += 256) {
     int v = 0;
 #pragma unroll
@@ -210,14 +241,17 @@ __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hk
 //   PASS 1: histogram of the middle digit over elements with digit 0 == d0 -> tot1; above[layer] += #{digit 0 > d0}
 //   PASS 2: histogram of the last digit over elements with digits (0, 1) == (d0, d1) -> tot2 and hist2[layer];
 //           above[layer] += #{digit 0 == d0, digit 1 > d1}
+// blockIdx.z runs over the (update, layer) pairs of the call: update u covers layers [0, layers_done + u * interval).
+// tot1 .. above point at update 0's histograms; update u's lie u * always_words ints further.
 template <int PASS>
 __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
-                                                             int mean_budget, int layers_done,
+                                                             int mean_budget, int layers_done, int interval,
                                                              const float* __restrict__ scores_all,
                                                              const int32_t* __restrict__ cu,
-                                                             const int32_t* __restrict__ tot0,
+                                                             const int32_t* __restrict__ tot0, int64_t tot0_words,
                                                              int32_t* __restrict__ tot1, int32_t* __restrict__ tot2,
-                                                             int32_t* __restrict__ hist2, int32_t* __restrict__ above) {
+                                                             int32_t* __restrict__ hist2, int32_t* __restrict__ above,
+                                                             int64_t always_words) {
   constexpr int BINS = PASS == 1 ? kRadixBins : kLowBins;
   __shared__ int h[BINS];
   __shared__ int scratch[4];
@@ -225,7 +259,15 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
   __shared__ int n_above;
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kScanChunk, w, blockIdx.x, seq, c, begin, len)) return;
-  const int head = blockIdx.y, layer = blockIdx.z;
+  int update = 0, layer = blockIdx.z;
+  while (layer >= layers_done) {           // the grid holds exactly the pairs of the call
+    layer -= layers_done;
+    layers_done += interval;
+    ++update;
+  }
+  tot1 += update * always_words; tot2 += update * always_words;
+  hist2 += update * always_words; above += update * always_words;
+  const int head = blockIdx.y;
   const int n = len - w;
   const int i0 = c * kScanChunk;
   const int i1 = i0 + kScanChunk < n ? i0 + kScanChunk : n;
@@ -233,7 +275,7 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
   ChunkVectors<NV> cv;
   const int64_t e_lo = ((int64_t)layer * Hkv + head) * total_tokens + begin + i0;
   // everything this workgroup reads from memory is requested here, before the first wait
-  const Bins<256, kRadixBins> bins0 = load_bins<256, kRadixBins>(tot0 + (int64_t)seq * kRadixBins);
+  const Bins<256, kRadixBins> bins0 = load_bins_sum<256, kRadixBins>(tot0 + (int64_t)seq * kRadixBins, update + 1, tot0_words);
   Bins<256, kRadixBins> bins1;
   if (PASS == 2) bins1 = load_bins<256, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
   load_chunk<NV>(scores_all, (int64_t)L * Hkv * total_tokens, e_lo, e_lo + (i1 - i0), cv);
@@ -308,12 +350,19 @@ __device__ inline int block_exclusive_scan_final(int v, int* scratch, int& total
 }
 
 // Last digit, per-layer hit counts and the budget arithmetic of Eq. 5-6, one workgroup per sequence.
+// grid = (n_seqs, n_updates): blockIdx.y is the update, layers_done comes in as the first update's.
 __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     int n_seqs, int L, int layers_done, int interval, int w, int Hkv, int mean_budget, int layer_max, int total_tokens,
-    const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ tot0,
+    const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ tot0, int64_t tot0_words,
     const int32_t* __restrict__ tot1, const int32_t* __restrict__ tot2, const int32_t* __restrict__ hist2,
-    const int32_t* __restrict__ above, int32_t* __restrict__ header, int32_t* __restrict__ counts,
-    int32_t* __restrict__ budgets_out, int32_t* __restrict__ hits_out) {
+    const int32_t* __restrict__ above, int64_t always_words, int32_t* __restrict__ header, int32_t* __restrict__ counts,
+    int32_t* __restrict__ budgets_out, int32_t* __restrict__ hits_out, int64_t out_stride_update) {
+  const int update = blockIdx.y, n_updates = gridDim.y;
+  layers_done += update * interval;
+  tot1 += update * always_words; tot2 += update * always_words;
+  hist2 += update * always_words; above += update * always_words;
+  if (budgets_out) budgets_out += update * out_stride_update;
+  if (hits_out) hits_out += update * out_stride_update;
   static_assert(DKV_MAX_LAYERS <= kFinalThreads, "one layer per thread");
   __shared__ int scratch[kFinalThreads / 64];
   __shared__ int sh[2];
@@ -323,7 +372,7 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
   const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int kg = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
   // all histogram reads are requested together, before the first wait
-  const auto bins0 = load_bins<kFinalThreads, kRadixBins>(tot0 + (int64_t)seq * kRadixBins);
+  const auto bins0 = load_bins_sum<kFinalThreads, kRadixBins>(tot0 + (int64_t)seq * kRadixBins, update + 1, tot0_words);
   const auto bins1 = load_bins<kFinalThreads, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
   const auto bins2 = load_bins<kFinalThreads, kLowBins>(tot2 + (int64_t)seq * kLowBins);
   constexpr int kWaves = kFinalThreads / 64, kPerLane = kLowBins / 64;
@@ -335,7 +384,6 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     for (int r = 0; r < kPerLane; ++r) first[r] = g[lane + 64 * r];
   }
   const int above_mine = tid < layers_done ? above[seq * L + tid] : 0;
-  const int cur = tid < layers_done ? counts[seq * L + tid] : 0;
   int rem = kg, d0, d1, d2;
   pick_digit<kFinalThreads, kRadixBins>(bins0, rem, scratch, sh, d0, rem);
   pick_digit<kFinalThreads, kRadixBins>(bins1, rem, scratch, sh, d1, rem);
@@ -384,43 +432,53 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     const int zpi = zp > 0x7fffffffLL ? 0x7fffffff : (int)zp;
     if (budgets_out) budgets_out[seq * L + tid] = zpi;
     if (hits_out) hits_out[seq * L + tid] = cnt;
-    counts[seq * L + tid] = cur < zpi ? cur : zpi;                                    // truncation never grows a layer
+    atomicMin(&counts[seq * L + tid], zpi);       // truncation never grows a layer; the updates of a call commute
   }
-  if (seq == 0 && tid == 0) {   // this call's layers are in the top-digit histogram now
+  if (seq == 0 && tid == 0 && update == n_updates - 1) {   // this call's layers are in the top-digit histograms now
     const uint64_t ptr = reinterpret_cast<uint64_t>(scores_all);
     header[0] = (int32_t)kHeaderMagic; header[1] = layers_done;
     header[2] = (int32_t)(uint32_t)ptr; header[3] = (int32_t)(uint32_t)(ptr >> 32);
-    header[4] = interval; header[5] = n_seqs; header[6] = total_tokens;
+    header[4] = interval; header[5] = n_seqs; header[6] = total_tokens; header[7] = n_updates;
   }
 }
 
-hipError_t launch_rebalance(const Params& p, int layers_done, const float* scores_all, const int32_t* cu,
-                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, char* ws,
-                            const WorkspaceLayout& wl, hipStream_t st) {
+// layers_done: of the first update; update u of the n_updates covers layers [0, layers_done + u * interval).
+// budgets_out / hits_out (may be null): update u writes its block out_stride_update ints after update u - 1's.
+hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, const float* scores_all, const int32_t* cu,
+                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, int64_t out_stride_update,
+                            char* ws, const WorkspaceLayout& wl, hipStream_t st) {
   int32_t* header = reinterpret_cast<int32_t*>(ws + wl.header);
   int32_t* tot0 = reinterpret_cast<int32_t*>(ws + wl.tot0);
   int32_t* tot1 = reinterpret_cast<int32_t*>(ws + wl.tot1);
   int32_t* tot2 = reinterpret_cast<int32_t*>(ws + wl.tot2);
   int32_t* hist2 = reinterpret_cast<int32_t*>(ws + wl.hist2);
   int32_t* above = reinterpret_cast<int32_t*>(ws + wl.above);
-  // tot1 .. above are contiguous: cleared on every call; tot0 only when the history does not match
-  const size_t always_words = (wl.total - wl.tot1) / 4, tot0_words = (wl.tot1 - wl.tot0) / 4;
-  size_t blocks = (always_words + 255) / 256;
+  // tot1 .. above of an update are one contiguous block, the blocks of the updates follow each other: those of
+  // this call are cleared; the top-digit slots are folded or cleared according to the history
+  const int64_t always_words = (int64_t)(wl.update_block_bytes / 4), tot0_words = (int64_t)(wl.tot0_slot_bytes / 4);
+  const size_t clear_words = (size_t)always_words * n_updates;
+  size_t blocks = (clear_words + 255) / 256;
   blocks = blocks > 1024 ? 1024 : blocks;
   launch(DKV_KERNEL_FILL, rebalance_clear_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-         reinterpret_cast<uint32_t*>(tot1), always_words, reinterpret_cast<uint32_t*>(tot0), tot0_words, header,
+         reinterpret_cast<uint32_t*>(tot1), clear_words, reinterpret_cast<uint32_t*>(tot0), (size_t)tot0_words, header,
          scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens);
-  const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, layers_done);
+  const int last_done = layers_done + (n_updates - 1) * p.interval;
+  int pairs = 0;                                                 // (update, layer) pairs of the call
+  for (int u = 0; u < n_updates; ++u) pairs += layers_done + u * p.interval;
+  const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, last_done);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist0_kernel, grid0, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, layers_done, p.interval, scores_all, cu, header, tot0);
-  const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, layers_done);
+         p.total_tokens, layers_done, p.interval, scores_all, cu, header, tot0, tot0_words);
+  const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, pairs);
   launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, p.mean_budget, layers_done, scores_all, cu, tot0, tot1, tot2, hist2, above);
+         p.total_tokens, p.mean_budget, layers_done, p.interval, scores_all, cu, tot0, tot0_words, tot1, tot2, hist2, above,
+         always_words);
   launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, p.mean_budget, layers_done, scores_all, cu, tot0, tot1, tot2, hist2, above);
-  launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs), dim3(kFinalThreads), 0, st, p.n_seqs, p.L,
-         layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu, tot0, tot1,
-         tot2, hist2, above, header, counts, budgets_out, hits_out);
+         p.total_tokens, p.mean_budget, layers_done, p.interval, scores_all, cu, tot0, tot0_words, tot1, tot2, hist2, above,
+         always_words);
+  launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs, n_updates), dim3(kFinalThreads), 0, st,
+         p.n_seqs, p.L, layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu,
+         tot0, tot0_words, tot1, tot2, hist2, above, always_words, header, counts, budgets_out, hits_out,
+         out_stride_update);
   return hipGetLastError();
 }
 

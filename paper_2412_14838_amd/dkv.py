@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libdkv.so")
 
 DKV_F32, DKV_BF16 = 0, 1
 DKV_MAX_SELECT_LAYERS = 8
+DKV_MAX_UPDATES = 4
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
-           "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance",
+           "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance", "dkv_rebalance_batch",
            "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention")
 
 
@@ -82,6 +83,8 @@ def load() -> C.CDLL:
     lib.dkv_decode_attention.argtypes = [D, I32, P, P, P, I64, I64, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
+    lib.dkv_rebalance_batch.restype = C.c_int
+    lib.dkv_rebalance_batch.argtypes = [D, I32, I32, P, P, P, P, P, I64, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
     lib.dkv_gather_kv.argtypes = [D, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, P]
     _lib = lib
@@ -243,6 +246,14 @@ def dkv_rebalance(desc, layers_done, scores_all, cu_seqlens, counts, budgets_out
     _check(load().dkv_rebalance(C.byref(desc), layers_done, _ptr(scores_all), _ptr(cu_seqlens), _ptr(counts),
                                 _ptr(budgets_out), _ptr(hits_out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_rebalance")
+
+
+def dkv_rebalance_batch(desc, layers_done, n_updates, scores_all, cu_seqlens, counts, budgets_out, hits_out,
+                        out_stride_update, workspace, stream=None) -> None:
+    _check(load().dkv_rebalance_batch(C.byref(desc), layers_done, n_updates, _ptr(scores_all), _ptr(cu_seqlens),
+                                      _ptr(counts), _ptr(budgets_out), _ptr(hits_out), out_stride_update,
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "dkv_rebalance_batch")
 
 
 def dkv_gather_kv(desc, layer, k, v, stride_token, stride_head, cu_seqlens, idx, counts, k_out, v_out, out_stride_seq,

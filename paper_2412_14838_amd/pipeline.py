@@ -4,13 +4,14 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
     scores   fp32  [L][Hkv][T]                 A^b, pooled scores of every processed layer
     idx      int32 [L][n_seqs][Hkv][layer_max] ordered candidates of every layer
     counts   int32 [n_seqs][L]                 retained prefix rows per KV head
-    budgets  int32 [n_seqs][L]                 Z' of the latest update;  hits: cnt of the latest update
+    budgets_all, hits_all  int32 [L / m][n_seqs][L]   Z' and cnt of every update; `budgets`, `hits`: the latest one's
     kb, vb   [L][n_seqs][Hkv][w + layer_max][d] compressed cache: window rows first, then retained rows;
              layer i of sequence q holds w + counts[q][i] valid rows per head.
 
 Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
 grouped (`group` > 1): the scoring, the selection and the compaction of up to `group` layers are issued in one
-call each when the group is full or at the last layer, followed by the updates that fall inside the group; the
+call each when the group is full or at the last layer, followed by one call for the updates that fall inside the
+group; the
 caller then holds the window queries, K and V of a group's layers until that point.
 """
 from __future__ import annotations
@@ -35,13 +36,23 @@ class Compressor:
         self.scores = torch.zeros((L, Hkv, T), dtype=torch.float32, device=device)
         self.idx = torch.full((L, cfg.n_seqs, Hkv, cfg.layer_max), -1, dtype=torch.int32, device=device)
         self.counts = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
-        self.budgets = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
-        self.hits = torch.zeros((cfg.n_seqs, L), dtype=torch.int32, device=device)
+        n_updates = max(1, L // cfg.interval)
+        self.budgets_all = torch.zeros((n_updates, cfg.n_seqs, L), dtype=torch.int32, device=device)
+        self.hits_all = torch.zeros((n_updates, cfg.n_seqs, L), dtype=torch.int32, device=device)
+        self._last_update = 0
         self.keep_cache = keep_cache
         if keep_cache:
             self.kb = torch.zeros((L, cfg.n_seqs, Hkv, self.slots, d), dtype=self.tdtype, device=device)
             self.vb = torch.zeros_like(self.kb)
         self.ws = dkv.alloc_workspace(self.desc, device)
+
+    @property
+    def budgets(self):
+        return self.budgets_all[self._last_update]
+
+    @property
+    def hits(self):
+        return self.hits_all[self._last_update]
 
     # one layer of Algorithm 1's loop: score, select, gather, and the update every `interval` layers
     def score(self, layer, q_win, k, stride_token=None, stride_head=None, stream=None):
@@ -105,9 +116,20 @@ class Compressor:
         dkv.dkv_decode_attention(self.desc, layer, q_new, self.kb[layer], self.vb[layer], self.cfg.Hkv * self.slots * d,
                                  self.slots * d, self.cu, self.counts, out, lse_out, self.ws, stream)
 
+    def _update_slot(self, layers_done):
+        return min(max(layers_done // self.cfg.interval - 1, 0), self.budgets_all.shape[0] - 1)
+
     def rebalance(self, layers_done, stream=None):
+        self._last_update = self._update_slot(layers_done)
         dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
                           stream)
+
+    def rebalance_batch(self, layers_done, n_updates, stream=None):
+        """The updates after layers_done, layers_done + interval, ... layers in one call."""
+        u0 = self._update_slot(layers_done)
+        self._last_update = u0 + n_updates - 1
+        dkv.dkv_rebalance_batch(self.desc, layers_done, n_updates, self.scores, self.cu, self.counts,
+                                self.budgets_all[u0], self.hits_all[u0], self.cfg.n_seqs * self.cfg.L, self.ws, stream)
 
     def step(self, layer, q_win, k, v, **strides):
         if self.group > 1:
@@ -151,9 +173,14 @@ class Compressor:
         self.select_layers(first, n)
         if self.keep_cache:
             self.gather_layers(first, [e[1] for e in pending], [e[2] for e in pending], **strides)
-        for e in pending:
-            if (e[0] + 1) % self.cfg.interval == 0:
-                self._update(e[0] + 1)
+        done = [e[0] + 1 for e in pending if (e[0] + 1) % self.cfg.interval == 0]
+        for i in range(0, len(done), dkv.DKV_MAX_UPDATES):      # consecutive boundaries: one call takes several
+            part = done[i:i + dkv.DKV_MAX_UPDATES]
+            self.rebalance_batch(part[0], len(part))
+            if self.on_update is not None:
+                for l in part:
+                    self._last_update = self._update_slot(l)
+                    self.on_update(l)
 
     def run(self, layers, overlap=False):
         """layers: sequence of (q_win, k, v) device tensors, one per layer.

@@ -143,6 +143,28 @@ def test_layer_batched_calls_reject_bad_ranges(lib):
                                     sq - 64, sq, sh, None) == inv
 
 
+def test_batched_updates_validate_their_arguments(lib):
+    d = _good()
+    need = dkv.dkv_workspace_bytes(d)
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    call = lib.dkv_rebalance_batch
+    big = d.n_seqs * d.n_layers
+    assert call(C.byref(d), d.interval, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, dkv.DKV_MAX_UPDATES + 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval + 1, 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv      # not a boundary
+    assert call(C.byref(d), 0, 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    last = d.n_layers // d.interval * d.interval
+    assert call(C.byref(d), last, 2, fake, fake, fake, fake, fake, big, fake, need, None) == inv                # runs past L
+    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big - 1, fake, need, None) == inv      # outputs overlap
+    assert call(C.byref(d), d.interval, 2, None, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, fake, None, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, fake, fake, None, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, C.c_void_p(0x1004), fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big, None, need, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
+
+
 def test_layer_batched_scoring_rejects_bad_ranges_and_pointers(lib):
     d = _good()
     need = dkv.dkv_workspace_bytes(d)

@@ -383,6 +383,55 @@ def test_rebalance_history_is_only_used_when_it_matches(dkv):
         check(comp, A2, l)
 
 
+def test_batched_updates_equal_updates_in_order(dkv):
+    """dkv_rebalance_batch over several consecutive updates gives, for every update, the oracle's hit counts and
+    budgets, and leaves the counts that the same updates give one call after the other; with every kind of
+    history before it (none, a single call, another batch, a foreign one) and tie-heavy scores."""
+    cfg = small_cfg("batch", L=8, interval=2, Hq=2, Hkv=2, seqlens=(1200, 640, 40), layer_max=128, mean_budget=48)
+    cu = cfg.cu_seqlens
+    rng = np.random.default_rng(33)
+    smooth = np.abs(rng.standard_normal((cfg.L, cfg.Hkv, cfg.total_tokens))).astype(np.float32)
+    tied = (rng.integers(0, 4, size=(cfg.L, cfg.Hkv, cfg.total_tokens)) / 4).astype(np.float32)
+    # values that share the two upper radix digits of the threshold, so that the last digit decides
+    bits = (0x1e6 << 21) | (0xd7 << 10) | rng.integers(0, 1024, size=(cfg.L, cfg.Hkv, cfg.total_tokens))
+    low = bits.astype(np.uint32).view(np.float32)
+
+    def reference(A, l, s):
+        pre = cfg.seqlens[s] - cfg.w
+        return O.update_buffer_length([A[i][:, cu[s]:cu[s] + pre] for i in range(l)], cfg.layer_max, cfg.mean_budget,
+                                      cfg.L)
+
+    def fresh(A):
+        comp = Compressor(cfg, keep_cache=False)
+        comp.scores.copy_(torch.from_numpy(A))
+        comp.select_layers(0, cfg.L)
+        return comp
+
+    for A in (smooth, tied, low):
+        # the plan: (first layers_done, number of updates) per call; 1 = the single-update entry point
+        for plan in ([(2, 4)], [(2, 1), (4, 3)], [(2, 2), (6, 2)], [(2, 3), (8, 1)], [(4, 2), (2, 4)], [(2, 4), (2, 4)]):
+            comp, seq = fresh(A), fresh(A)
+            for first, n in plan:
+                if n == 1:
+                    comp.rebalance(first)
+                else:
+                    comp.rebalance_batch(first, n)
+                for u in range(n):
+                    seq.rebalance(first + u * cfg.interval)
+                torch.cuda.synchronize()
+                hits, budgets = comp.hits_all.cpu().numpy(), comp.budgets_all.cpu().numpy()
+                for u in range(n):
+                    l = first + u * cfg.interval
+                    for s in range(cfg.n_seqs):
+                        if cfg.seqlens[s] <= cfg.w:
+                            continue
+                        cnt, Z, Zp = reference(A, l, s)
+                        slot = l // cfg.interval - 1
+                        assert np.array_equal(hits[slot, s, :l], cnt), (plan, l, s)
+                        assert np.array_equal(budgets[slot, s, :l], np.minimum(Zp, 2**31 - 1)), (plan, l, s)
+                assert torch.equal(comp.counts, seq.counts), plan
+
+
 @pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_f32", "ragged_bf16"])
 def test_row_lse_and_single_sweep_scoring(dkv, case):
     """dkv_row_lse exports the normalisers of Eq. 1 (checked against the oracle's log-sum-exp), and
