@@ -10,8 +10,8 @@ No arithmetic of the method happens here; every step is a dkv_* call.  Buffers (
 
 Two schedules give identical results: layer by layer (score, select, gather per layer, the paper's order), or
 grouped (`group` > 1): the scoring, the selection and the compaction of up to `group` layers are issued in one
-call each when the group is full or at the last layer, followed by one call for the updates that fall inside the
-group; the
+call each when the group is full or at the last layer, with one call for the updates that fall inside the group
+between selection and compaction (so that only rows the updates keep are copied); the
 caller then holds the window queries, K and V of a group's layers until that point.
 """
 from __future__ import annotations
@@ -167,12 +167,12 @@ class Compressor:
             return
         pending, self._pending = self._pending, []      # the caller may release K and V of these layers afterwards
         first, n = pending[0][0], len(pending)
-        # a layer's selection and compaction need that layer's scores only, and an update touches the layers before
-        # its boundary only: one call each for the whole group, then the updates that fall inside it, in order
+        # a layer's selection needs that layer's scores only, and an update touches the layers before its boundary
+        # only: one scoring and one selection call for the whole group, one call for the updates that fall inside
+        # it, and then the compaction, which copies only the rows those updates have left (a row an update drops
+        # never comes back: the later updates only lower the counts)
         self.score_layers(first, [e[3] for e in pending], [e[1] for e in pending], **strides)
         self.select_layers(first, n)
-        if self.keep_cache:
-            self.gather_layers(first, [e[1] for e in pending], [e[2] for e in pending], **strides)
         done = [e[0] + 1 for e in pending if (e[0] + 1) % self.cfg.interval == 0]
         for i in range(0, len(done), dkv.DKV_MAX_UPDATES):      # consecutive boundaries: one call takes several
             part = done[i:i + dkv.DKV_MAX_UPDATES]
@@ -181,6 +181,8 @@ class Compressor:
                 for l in part:
                     self._last_update = self._update_slot(l)
                     self.on_update(l)
+        if self.keep_cache:
+            self.gather_layers(first, [e[1] for e in pending], [e[2] for e in pending], **strides)
 
     def run(self, layers, overlap=False):
         """layers: sequence of (q_win, k, v) device tensors, one per layer.
