@@ -37,6 +37,8 @@ CASES = {
     "ragged_bf16": small_cfg("ragged_bf16", seqlens=(700, 33, 32, 2049, 517), L=2, interval=1),
     "pool1": small_cfg("pool1", P=1, seqlens=(600,)),
     "pool15": small_cfg("pool15", P=15, seqlens=(900,)),
+    "pool63": small_cfg("pool63", P=63, seqlens=(2300, 70)),                     # the widest pooling window
+    "rows256": small_cfg("rows256", Hq=16, Hkv=2, seqlens=(1300, 300)),         # G * w = 256: the most score rows
 }
 
 
@@ -324,7 +326,7 @@ def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
 
 
 @pytest.mark.parametrize("case", ["tiny", "small_bf16", "small_bf16_gqa7", "small_bf16_gqa5", "small_bf16_d64",
-                                  "ragged_bf16", "ragged_f32", "long_ragged"])
+                                  "ragged_bf16", "ragged_f32", "long_ragged", "pool1", "pool63", "rows256"])
 def test_layer_batched_scoring_equals_per_layer_calls(dkv, case):
     """dkv_score_window_layers over layers [1, 1 + n) writes, bit for bit, what dkv_score_window writes layer by
     layer (which the tests above check against the oracle), and leaves the other layers' scores alone."""
