@@ -188,8 +188,8 @@ __device__ inline void read_k_frags(const char* __restrict__ tile, bf16x8 (&kf)[
   for (int j = 0; j < 8; ++j) kf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
 }
 
-// Fragment j of them alone (the steps of the kernels read one slice ahead instead of a whole tile at once: fewer
-// registers, same latency hiding).
+// Fragment j of them alone (the emit kernel, short of registers, reads one slice ahead instead of a whole tile
+// at once).
 __device__ inline bf16x8 read_k_frag(const char* __restrict__ tile, int j) {
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + j * 32));
 }
@@ -426,14 +426,16 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
     if (last) read_q_frags(qbuf, rs, qf);                  // the next layer's Q, stored before the previous barrier
     {
       const char* __restrict__ next_tile = tiles + (kBuf ^ 1) * TL::kTileBytes + lane_tile;
-      bf16x8 kfj = read_k_frag(next_tile, 0);
+      bf16x8 kf[8];                                        // all eight at once: there are registers to spare here
+      read_k_frags(next_tile, kf);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         __builtin_amdgcn_sched_barrier(0);
-        const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
-        mfma_slice<true>(j, kfj, qf, b);
+        mfma_slice<true>(j, kf[j], qf, b);
         exps(j);
-        kfj = kf_ahead;
+        // the sums are pinned here: without an anchor the compiler sinks the exponentials of all eight slices past
+        // the matrix instructions (the scheduling barrier alone only holds what is already in its region)
+        asm volatile("" : "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3), "+v"(l_run[0]), "+v"(l_run[1]));
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -719,6 +721,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
         const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
         mfma_slice<false>(j, kfj, qf, b);
         if (live) exps(j, lz);
+        // pinned here (see the statistics kernel)
+        asm volatile("" : "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3));
         lz = lz_next;
         kfj = kf_ahead;
       }
