@@ -82,7 +82,7 @@ enum {
   DKV_KERNEL_REBALANCE_SCAN = 5,
   DKV_KERNEL_REBALANCE_FINAL = 6,
   DKV_KERNEL_FILL = 7,
-  DKV_KERNEL_SELECT_ORDER = 8,
+  DKV_KERNEL_SELECT_ORDER = 8,     /* (not launched any more: the selection kernel orders its winners itself) */
   DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
   DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
   DKV_KERNEL_DECODE = 11,         /* decode attention over the compressed cache       */
@@ -204,7 +204,8 @@ int dkv_row_lse(const dkv_desc* desc, int64_t k_stride_token, const int32_t* cu_
  * scores     as written by dkv_score_window for this layer.
  * idx_out    int32 [n_seqs][Hkv][layer_max], sequence-local positions; entries >= k are set to -1.
  * counts     int32 [n_seqs][L]; counts[q][layer] = k is written.
- * Two kernels are enqueued (selection of the winners, then their ordering).
+ * One kernel (selection of the winners and their ordering, one workgroup per sequence and KV head); the workspace
+ * arguments are validated like those of the other calls but the kernel needs no scratch memory.
  */
 int dkv_select_topk(const dkv_desc* desc, int32_t layer, const float* scores, int64_t scores_stride_head,
                     const int32_t* cu_seqlens, int32_t* idx_out, int32_t* counts, void* workspace,

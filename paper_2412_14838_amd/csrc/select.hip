@@ -1,14 +1,12 @@
 // Per-layer, per-KV-head top-k (Eq. 3; Algorithm 1: indices <- A^l.topk(B^l, dim=-1).indices).
-// One workgroup per (sequence, KV head):
+// One workgroup per (layer, sequence, KV head):
 //   1. LDS radix-select (3 digits of 11/11/10 bits of the fp32 pattern; scores are >= 0 so patterns order like
 //      values) finds the k-th largest score T. The digit histogram is kept in 8 interleaved copies so that
 //      lanes whose scores share a digit do not serialise on one LDS word.
-//   2. wavefront-ballot compaction collects the winners: everything above T, and the first (k - #above)
-//      elements equal to T in position order (ties go to the lower position).
-//   3. the k winners are written as 64-bit keys (~score bits, position), unordered, to the workspace.
-// A second kernel orders them by (score descending, position ascending) = ascending key, by counting: the rank
-// of a key is the number of smaller keys (keys are unique). That is k^2 comparisons, but they spread over the
-// whole GPU (k/256 workgroups per row) instead of a sorting network on the one CU that holds the row.
+//   2. wavefront-ballot compaction collects the winners as 64-bit keys (~score bits, position) in LDS: everything
+//      above T, and the first (k - #above) elements equal to T in position order (ties go to the lower position).
+//   3. the k winners are ordered by (score descending, position ascending) = ascending key: bucketed by the
+//      leading bits of their scores, the buckets laid out by a scan, the few keys of a bucket ranked by counting.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -52,8 +50,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
                                                                   const int32_t* __restrict__ cu,
                                                                   int32_t* __restrict__ idx_out0,
                                                                   int64_t idx_stride_layer,
-                                                                  int32_t* __restrict__ counts,
-                                                                  u64* __restrict__ keys_out0) {
+                                                                  int32_t* __restrict__ counts) {
   extern __shared__ __attribute__((aligned(16))) char sel_smem[];
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
@@ -66,7 +63,6 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   const int layer = layer0 + blockIdx.z;
   const float* __restrict__ scores = scores0 + (int64_t)blockIdx.z * scores_stride_layer;
   int32_t* __restrict__ idx_out = idx_out0 + (int64_t)blockIdx.z * idx_stride_layer;
-  u64* __restrict__ keys_out = keys_out0 + (int64_t)blockIdx.z * gridDim.y * Hkv * DKV_MAX_LAYER_MAX;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int begin = cu[seq];
   const int S = cu[seq + 1] - begin;
@@ -222,68 +218,74 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   }
   __syncthreads();
 
-  // ---- hand the k winners to the ordering kernel
-  u64* __restrict__ dst = keys_out + ((int64_t)seq * Hkv + head) * DKV_MAX_LAYER_MAX;
-  for (int j = tid; j < k; j += kSelThreads) dst[j] = keys[j];
-}
-
-// Orders the winners of one (layer, sequence, KV head) by counting. grid = (ceil(layer_max / 256), Hkv, n_seqs * layers),
-// 256 threads: the workgroup owns candidates [blockIdx.x * 256, + 256); lane l of every wavefront holds the four
-// candidates l, l + 64, l + 128, l + 192 of them in registers, and wavefront g counts, for each of the four, the
-// smaller keys among a quarter of all k keys. One LDS read of a key (the same word for all lanes: a broadcast)
-// thus serves 256 comparisons; the four partial counts add up to the rank = the candidate's place in idx_out.
-constexpr int kOrderCand = 256;
-__global__ __launch_bounds__(256) void select_order_kernel(int Hkv, int w, int layer_max, int n_seqs,
-                                                           const int32_t* __restrict__ cu,
-                                                           const u64* __restrict__ keys_in0,
-                                                           int32_t* __restrict__ idx_out0, int64_t idx_stride_layer) {
-  __shared__ __attribute__((aligned(16))) u64 keys[DKV_MAX_LAYER_MAX + 32];
-  __shared__ int partial[4][kOrderCand];
-  const int seq = blockIdx.z % n_seqs, lz = blockIdx.z / n_seqs;
-  const int head = blockIdx.y, tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
-  const u64* __restrict__ keys_in = keys_in0 + (int64_t)lz * n_seqs * Hkv * DKV_MAX_LAYER_MAX;
-  int32_t* __restrict__ idx_out = idx_out0 + (int64_t)lz * idx_stride_layer;
-  const int S = cu[seq + 1] - cu[seq];
-  const int n = S > w ? S - w : 0;
-  const int k = layer_max < n ? layer_max : n;
-  int32_t* __restrict__ out = idx_out + ((int64_t)seq * Hkv + head) * layer_max;
-  const int e0 = blockIdx.x * kOrderCand;
-  // slots past k hold -1 (each workgroup clears the ones in its own range)
-  if (e0 + tid >= k && e0 + tid < layer_max) out[e0 + tid] = -1;
-  if (e0 >= k) return;
-  const u64* __restrict__ src = keys_in + ((int64_t)seq * Hkv + head) * DKV_MAX_LAYER_MAX;
-  // every wavefront scans `quarter` keys (a multiple of 8); the pad keys are the largest value: never "smaller"
-  const int quarter = ((k + 3) / 4 + 7) & ~7;
-  for (int j = tid; j < 4 * quarter; j += 256) keys[j] = j < k ? src[j] : ~0ull;
+  // ---- order the k winners by (score descending, position ascending) = ascending 64-bit key, here in LDS:
+  // buckets by the leading bits of the keys' score halves (2048 linear bins between the smallest and the largest
+  // one), a scan over the buckets, and a rank inside the bucket by counting. The winners are the upper tail of the
+  // row, a few keys per bucket; k keys that all share one bucket (all scores equal) cost k^2 comparisons.
+  int* bcount = hist;                                          // [kRadixBins] keys per bucket
+  int* bstart = hist + kRadixBins;                             // [kRadixBins] first place of the bucket
+  u64* sorted = reinterpret_cast<u64*>(hist + 2 * kRadixBins); // [2048] keys in bucket order
+  u64 mine[2];
+  uint32_t lo = 0xffffffffu, hi = 0u;
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int j = tid + c * kSelThreads;
+    mine[c] = j < k ? keys[j] : ~0ull;
+    if (j < k) {
+      const uint32_t h = (uint32_t)(mine[c] >> 32);
+      lo = h < lo ? h : lo;
+      hi = h > hi ? h : hi;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
+    lo = l2 < lo ? l2 : lo;
+    hi = h2 > hi ? h2 : hi;
+  }
+  __shared__ uint32_t wave_lo[kSelWaves], wave_hi[kSelWaves];
+  if (lane == 0) { wave_lo[wv] = lo; wave_hi[wv] = hi; }
+  for (int bI = tid; bI < kRadixBins; bI += kSelThreads) bcount[bI] = 0;
   __syncthreads();
-  u64 mine[4];
-  int smaller[4] = {0, 0, 0, 0};
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const int e = e0 + lane + 64 * c;
-    mine[c] = e < k ? keys[e] : ~0ull;
+  for (int i = 0; i < kSelWaves; ++i) {
+    lo = wave_lo[i] < lo ? wave_lo[i] : lo;
+    hi = wave_hi[i] > hi ? wave_hi[i] : hi;
   }
-  const ulonglong2* __restrict__ kp = reinterpret_cast<const ulonglong2*>(keys + g * quarter);
-  for (int j = 0; j < quarter / 2; j += 4) {
-    ulonglong2 kk[4];
+  const uint32_t range = hi - lo;                              // k >= 1 here: lo <= hi
+  const int shift = range < (uint32_t)kRadixBins ? 0 : (32 - __builtin_clz(range)) - 11;   // (range >> shift) < 2048
+  int bin[2], place[2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) kk[u] = kp[j + u];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        smaller[c] += kk[u].x < mine[c] ? 1 : 0;
-        smaller[c] += kk[u].y < mine[c] ? 1 : 0;
-      }
+  for (int c = 0; c < 2; ++c) {
+    const int j = tid + c * kSelThreads;
+    bin[c] = (int)((((uint32_t)(mine[c] >> 32)) - lo) >> shift);
+    place[c] = j < k ? atomicAdd(&bcount[bin[c]], 1) : 0;       // order of arrival inside the bucket: any order will do
   }
-#pragma unroll
-  for (int c = 0; c < 4; ++c) partial[g][lane + 64 * c] = smaller[c];
   __syncthreads();
-  const int e = e0 + tid;
-  if (e < k) {
-    const int rank = partial[0][tid] + partial[1][tid] + partial[2][tid] + partial[3][tid];
-    out[rank] = (int32_t)(uint32_t)keys[e];
+  {
+    const int c0 = bcount[2 * tid], c1 = bcount[2 * tid + 1];  // thread t owns buckets 2t and 2t + 1
+    const int ex = block_exclusive_scan(c0 + c1, scratch);
+    bstart[2 * tid] = ex;
+    bstart[2 * tid + 1] = ex + c0;
   }
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int j = tid + c * kSelThreads;
+    if (j < k) sorted[bstart[bin[c]] + place[c]] = mine[c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int j = tid + c * kSelThreads;
+    if (j < k) {
+      const int first = bstart[bin[c]], n_in = bcount[bin[c]];
+      int rank = first;
+      for (int i = 0; i < n_in; ++i) rank += sorted[first + i] < mine[c] ? 1 : 0;
+      out[rank] = (int32_t)(uint32_t)mine[c];
+    }
+  }
+  for (int j = k + tid; j < layer_max; j += kSelThreads) out[j] = -1;
 }
 
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
@@ -297,12 +299,9 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  u64* keys = reinterpret_cast<u64*>(ws + wl.select_keys);
+  (void)ws; (void)wl;   // the selection needs no scratch memory any more
   launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st, p.Hkv, p.w,
-         p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts,
-         keys);
-  launch(DKV_KERNEL_SELECT_ORDER, select_order_kernel, dim3((p.layer_max + kOrderCand - 1) / kOrderCand, p.Hkv, p.n_seqs * n_layers),
-         dim3(256), 0, st, p.Hkv, p.w, p.layer_max, p.n_seqs, cu, keys, idx_out, idx_stride_layer);
+         p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts);
   return hipGetLastError();
 }
 
