@@ -105,10 +105,21 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       if (j * kSelThreads + tid < n_res && match)
         atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
     }
-    for (int i = kSelResident + tid; i < n; i += kSelThreads) {
-      const uint32_t u = row[i];
-      const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
-      if (match) atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
+    // the tail of a long row, eight loads in flight per thread
+    for (int i0 = kSelResident + tid; i0 < n; i0 += 8 * kSelThreads) {
+      uint32_t u8[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int i = i0 + q * kSelThreads;
+        u8[q] = i < n ? row[i] : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t u = u8[q];
+        const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
+        if (i0 + q * kSelThreads < n && match)
+          atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
+      }
     }
     __syncthreads();
     // thread t owns digits 2047 - 2t and 2046 - 2t (scanned from the top)
@@ -187,18 +198,27 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     const int seg_begin = kSelResident + wv * seg;
     const int seg_end = seg_begin + seg < n ? seg_begin + seg : n;
     int eq_count = 0;
-    for (int i0 = seg_begin; i0 < seg_end; i0 += 64) {
-      const int i = i0 + lane;
-      const uint32_t u = i < seg_end ? row[i] : 0u;
-      const bool gt = i < seg_end && u > T;
-      const bool eq = i < seg_end && u == T;
-      const unsigned long long gmask = __ballot(gt);
-      eq_count += __popcll(__ballot(eq));
-      if (gmask) {
-        int base = 0;
-        if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
-        base = __shfl(base, 0);
-        if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
+    for (int i00 = seg_begin; i00 < seg_end; i00 += 4 * 64) {   // four loads in flight per lane
+      uint32_t u4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i00 + q * 64 + lane;
+        u4[q] = i < seg_end ? row[i] : 0u;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i00 + q * 64 + lane;
+        const uint32_t u = u4[q];
+        const bool gt = i < seg_end && u > T;
+        const bool eq = i < seg_end && u == T;
+        const unsigned long long gmask = __ballot(gt);
+        eq_count += __popcll(__ballot(eq));
+        if (gmask) {
+          int base = 0;
+          if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
+          base = __shfl(base, 0);
+          if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
+        }
       }
     }
     if (lane == 0) wave_eq[wv] = eq_count;
