@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--workload", default="mistral_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--group", type=int, default=0,
-                    help="layers whose scoring, selection and compaction are issued together (0: whole update intervals, "
+                    help="layers whose scoring, selection and compaction are issued together (0: as many whole update intervals as one call takes, "
                          "1: layer by layer as in Algorithm 1)")
     ap.add_argument("--overlap", action="store_true",
                     help="select/gather/rebalance of layer l on a second stream, next to the scoring of layer l+1")
@@ -91,8 +91,9 @@ def main():
                 host_sample.append(data)
     torch.cuda.synchronize()
 
-    # default: as many whole update intervals as one scoring call takes (8 layers at most)
-    group = args.group if args.group > 0 else (8 // cfg.interval * cfg.interval if cfg.interval <= 8 else 8)
+    # default: as many whole update intervals as one call takes (all layers, for the configurations at hand)
+    most = min(cfg.L, dkv.DKV_MAX_SELECT_LAYERS, dkv.DKV_MAX_UPDATES * cfg.interval)
+    group = args.group if args.group > 0 else max(most // cfg.interval * cfg.interval, 1)
     comp = Compressor(cfg, group=group)
     d, T = cfg.d, cfg.total_tokens
     st, sh = d, T * d

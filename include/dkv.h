@@ -50,8 +50,8 @@ enum {
 #define DKV_MAX_SEQS 4096
 #define DKV_MAX_LAYERS 512
 #define DKV_MAX_DECODE_GROUP 16   /* query heads per KV head dkv_decode_attention handles */
-#define DKV_MAX_SELECT_LAYERS 8   /* layers one dkv_*_layers call may cover */
-#define DKV_MAX_UPDATES 4         /* progressive updates per dkv_rebalance_batch call */
+#define DKV_MAX_SELECT_LAYERS 32  /* layers one dkv_*_layers call may cover */
+#define DKV_MAX_UPDATES 8         /* progressive updates per dkv_rebalance_batch call */
 
 /* Problem descriptor (host memory, read during the call only). Symbols as in Algorithm 1. */
 typedef struct dkv_desc {
@@ -82,7 +82,7 @@ enum {
   DKV_KERNEL_REBALANCE_SCAN = 5,
   DKV_KERNEL_REBALANCE_FINAL = 6,
   DKV_KERNEL_FILL = 7,
-  DKV_KERNEL_SELECT_ORDER = 8,     /* (not launched any more: the selection kernel orders its winners itself) */
+  DKV_KERNEL_SCORE_BORDERS = 8,   /* pooled scores next to the chunk borders of a multi-layer scoring call */
   DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
   DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
   DKV_KERNEL_DECODE = 11,         /* decode attention over the compressed cache       */

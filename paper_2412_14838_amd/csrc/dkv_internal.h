@@ -27,6 +27,8 @@ struct WorkspaceLayout {
   size_t partials;     // float2 [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
   size_t partials_layer_bytes;   // one layer's share of it
   size_t lse_rows;     // float [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][rows_pad] merged row normalisers (log2) of a multi-layer scoring call
+  size_t edges;        // float [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][64] column sums next to the chunk borders of a multi-layer emit launch
+  size_t edges_layer_bytes;      // one layer's share of it
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
   size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
   size_t tot0;         // int32 [DKV_MAX_UPDATES][n_seqs][kRadixBins]  top digit: slot 0 kept from call to call, slot u the layers new to update u
@@ -60,6 +62,9 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.partials_layer_bytes = align256(size_t(w.chunks_max) * d.n_kv_heads * w.rows_pad * 2 * sizeof(float));
   off += w.partials_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.lse_rows = off; off += align256(size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * w.rows_pad * sizeof(float));
+  w.edges = off;
+  w.edges_layer_bytes = align256(size_t(w.chunks_max) * d.n_kv_heads * 64 * sizeof(float));
+  off += w.edges_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
   w.header = off;   off += align256(8 * sizeof(int32_t));

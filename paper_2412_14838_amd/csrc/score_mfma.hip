@@ -596,7 +596,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
                                                                 int64_t lse_rows_stride_layer,
                                                                 const float* __restrict__ lse_in,
                                                                 float* __restrict__ scores, int64_t scores_stride_head,
-                                                                int64_t scores_stride_layer) {
+                                                                int64_t scores_stride_layer, float* __restrict__ edges,
+                                                                int64_t edges_stride_layer) {
   using TL = Tile<RS, KS>;
   using QS = QStage<RS, KS>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -617,8 +618,12 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   const int prefix = S - p.w;                                // > 0 here
   const int o0 = c * chunk;                                  // outputs [o0, o1)
   const int o1 = o0 + chunk < prefix ? o0 + chunk : prefix;
-  const int kbeg = o0 - half > 0 ? o0 - half : 0;            // keys [kbeg, kend): outputs plus halo, inside the prefix
-  const int kend = o1 + half < prefix ? o1 + half : prefix;
+  // keys [kbeg, kend): the outputs plus the pooling halo, inside the prefix - or, with `edges`, the outputs alone:
+  // then the pooled values next to a chunk border lack the neighbour's keys, the column sums of the first and the
+  // last `half` keys go to `edges`, and score_fix_borders completes those outputs afterwards
+  const int halo = edges != nullptr ? 0 : half;
+  const int kbeg = o0 - halo > 0 ? o0 - halo : 0;
+  const int kend = o1 + halo < prefix ? o1 + halo : prefix;
   const int len = kend - kbeg;                               // <= chunk + 2 * half
   const int n_iter = (len + TL::kKeys - 1) / TL::kKeys;
   const int n_steps = n_iter > QS::kParts + 1 ? n_iter : QS::kParts + 1;   // the steps before a layer's last one fetch the next layer's Q
@@ -753,6 +758,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     // wrote itself), window [i - half, i + half] cut to [0, len): an index clamped to the range stays inside the
     // window, and taking an element twice does not change a maximum
     float* __restrict__ pooled = part + kPartStride;
+    if (edges != nullptr && tid < 2 * half) {                  // [0, half): the first column sums, [half, 2 half): the last
+      const int i = tid < half ? tid : len - 2 * half + tid;
+      edges[li * edges_stride_layer + ((int64_t)blockIdx.x * p.Hkv + head) * kMaxHalo + tid] =
+          i >= 0 && i < len ? part[i] : -INFINITY;
+    }
     for (int s = o0 + tid; s < o1; s += TL::kThreads) {
       const int i = s - kbeg;
       float m = part[i];
@@ -777,6 +787,40 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     step(std::integral_constant<int, 0>{}, acc, nxt);
     step(std::integral_constant<int, 1>{}, nxt, acc);
   }
+}
+
+// Completes the outputs next to the chunk borders of an emit launch that left the pooling halo out: output s of
+// chunk c within `half` of the border to chunk c + 1 takes the maximum with the neighbour's column sums that its
+// pooling window reaches (a maximum is exact, so the result is the one the halo variant computes).
+// grid = (chunk upper bound, Hkv, layers), 64 threads: one workgroup per border, thread t < half the output
+// half - t before it, thread half + u the output u after it.
+__global__ __launch_bounds__(64) void score_fix_borders(Params p, int chunk, const int32_t* __restrict__ cu,
+                                                        const float* __restrict__ edges, int64_t edges_stride_layer,
+                                                        float* __restrict__ scores, int64_t scores_stride_head,
+                                                        int64_t scores_stride_layer) {
+  int seq, c, nc, begin, S, first_full, n_full;
+  if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, p.w, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
+  if (c == nc - 1) return;                                     // no chunk behind the last one
+  const int head = blockIdx.y, layer = blockIdx.z, half = p.half, t = threadIdx.x;
+  if (t >= 2 * half) return;
+  const int prefix = S - p.w;
+  const int o1 = (c + 1) * chunk;                              // first output of the next chunk (< prefix)
+  const int next_len = o1 + chunk < prefix ? chunk : prefix - o1;
+  const float* __restrict__ mine = edges + layer * edges_stride_layer + ((int64_t)blockIdx.x * p.Hkv + head) * kMaxHalo + half;
+  const float* __restrict__ next = edges + layer * edges_stride_layer + ((int64_t)(blockIdx.x + 1) * p.Hkv + head) * kMaxHalo;
+  float* __restrict__ out = scores + layer * scores_stride_layer + (int64_t)head * scores_stride_head + begin;
+  float m = -INFINITY;
+  int s;
+  if (t < half) {            // output o1 - half + t: its window ends at o1 + t, the next chunk's first t + 1 keys
+    s = o1 - half + t;
+    for (int e = 0; e <= t; ++e) m = fmaxf(m, next[e]);        // -inf past the end of a short last chunk
+  } else {                   // output o1 + u: its window starts at o1 + u - half, this chunk's last half - u keys
+    const int u = t - half;
+    if (u >= next_len) return;
+    s = o1 + u;
+    for (int e = u; e < half; ++e) m = fmaxf(m, mine[e]);
+  }
+  out[s] = fmaxf(out[s], m);
 }
 
 // Natural-log row normalisers from the chunk partials of the statistics kernel (log2 domain):
@@ -901,10 +945,18 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
     } else if (lse_layers != nullptr) {
       lse_in = lse_layers[0];
     }
+    // A call over several layers leaves the pooling halo to a small kernel behind the emit kernel (one launch for
+    // all layers); a single layer recomputes the halo keys inside the emit kernel, which is cheaper than a launch.
+    float* edges = n_layers > 1 && p.half > 0 ? reinterpret_cast<float*>(ws + wl.edges) : nullptr;
+    const int64_t edges_stride_layer = (int64_t)wl.edges_layer_bytes / (int64_t)sizeof(float);
     launch(DKV_KERNEL_SCORE_EMIT, (score_emit_mfma<RS, KS>), dim3(grid_x, p.Hkv), dim3(TL::kThreads), lds_emit, st, p, chunk,
            n_layers, rev, k_stride_token * 2, k_stride_head * 2, cu, static_cast<const float*>(partials),
            lse_rows ? static_cast<const float*>(lse_rows) + last * lse_rows_stride_layer : nullptr, -lse_rows_stride_layer,
-           lse_in, scores + last * scores_stride_layer, scores_stride_head, -scores_stride_layer);
+           lse_in, scores + last * scores_stride_layer, scores_stride_head, -scores_stride_layer, edges, edges_stride_layer);
+    if (edges != nullptr)
+      launch(DKV_KERNEL_SCORE_BORDERS, score_fix_borders, dim3(grid_x, p.Hkv, n_layers), dim3(64), 0, st, p, chunk, cu,
+             static_cast<const float*>(edges), edges_stride_layer, scores + last * scores_stride_layer, scores_stride_head,
+             -scores_stride_layer);
   }
   if (phases & kPhaseLse)
     launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, cu, partials, lse_out);

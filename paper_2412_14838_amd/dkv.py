@@ -14,8 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdkv.so")
 
 DKV_F32, DKV_BF16 = 0, 1
-DKV_MAX_SELECT_LAYERS = 8
-DKV_MAX_UPDATES = 4
+DKV_MAX_SELECT_LAYERS = 32
+DKV_MAX_UPDATES = 8
 DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
@@ -137,7 +137,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "select_order", "score_lse", "pack", "decode", "score_merge")
+                "rebalance_final", "fill", "score_borders", "score_lse", "pack", "decode", "score_merge")
 
 
 def dkv_profile_begin(capacity: int) -> None:

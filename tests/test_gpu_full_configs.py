@@ -133,12 +133,12 @@ def test_full_tiny_chained_end_to_end(dkv):
 
 def test_full_llama3_8b_8k(dkv):
     cfg = W.standard_configs()["llama3_8b_8k"]
-    check_config(cfg, [0, 13, cfg.L - 1], [0, 5], [0])
+    check_config(cfg, [0, 13, cfg.L - 1], [0, 5], [0], group=16)    # two calls of four updates each
 
 
 def test_full_mistral_7b_32k(dkv):
     cfg = W.standard_configs()["mistral_7b_32k"]
-    check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=8)     # the schedule bench.py times: two updates per group
+    check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=32)    # the schedule bench.py times: all layers, eight updates per call
 
 
 def test_full_qwen2_7b_32k_extreme(dkv):

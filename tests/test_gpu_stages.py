@@ -385,11 +385,20 @@ def test_rebalance_history_is_only_used_when_it_matches(dkv):
         check(comp, A2, l)
 
 
-def test_batched_updates_equal_updates_in_order(dkv):
+BATCH_PLANS = {
+    # layers -> plans; a plan: (first layers_done, number of updates) per call; 1 = the single-update entry point
+    8: ([(2, 4)], [(2, 1), (4, 3)], [(2, 2), (6, 2)], [(2, 3), (8, 1)], [(4, 2), (2, 4)], [(2, 4), (2, 4)]),
+    16: ([(2, 8)], [(2, 3), (8, 5)], [(2, 8), (2, 8)], [(4, 1), (6, 6)]),
+}
+
+
+@pytest.mark.parametrize("layers", [8, 16])
+def test_batched_updates_equal_updates_in_order(dkv, layers):
     """dkv_rebalance_batch over several consecutive updates gives, for every update, the oracle's hit counts and
     budgets, and leaves the counts that the same updates give one call after the other; with every kind of
-    history before it (none, a single call, another batch, a foreign one) and tie-heavy scores."""
-    cfg = small_cfg("batch", L=8, interval=2, Hq=2, Hkv=2, seqlens=(1200, 640, 40), layer_max=128, mean_budget=48)
+    history before it (none, a single call, another batch, a foreign one), tie-heavy scores, and up to the most
+    updates a call takes."""
+    cfg = small_cfg("batch", L=layers, interval=2, Hq=2, Hkv=2, seqlens=(1200, 640, 40), layer_max=128, mean_budget=48)
     cu = cfg.cu_seqlens
     rng = np.random.default_rng(33)
     smooth = np.abs(rng.standard_normal((cfg.L, cfg.Hkv, cfg.total_tokens))).astype(np.float32)
@@ -410,8 +419,7 @@ def test_batched_updates_equal_updates_in_order(dkv):
         return comp
 
     for A in (smooth, tied, low):
-        # the plan: (first layers_done, number of updates) per call; 1 = the single-update entry point
-        for plan in ([(2, 4)], [(2, 1), (4, 3)], [(2, 2), (6, 2)], [(2, 3), (8, 1)], [(4, 2), (2, 4)], [(2, 4), (2, 4)]):
+        for plan in BATCH_PLANS[layers]:
             comp, seq = fresh(A), fresh(A)
             for first, n in plan:
                 if n == 1:
