@@ -86,7 +86,8 @@ enum {
   DKV_KERNEL_SCORE_LSE = 9,       /* export of the row normalisers                    */
   DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
   DKV_KERNEL_DECODE = 11,         /* decode attention over the compressed cache       */
-  DKV_KERNEL_SCORE_MERGE = 12     /* row normalisers of a multi-layer scoring call    */
+  DKV_KERNEL_SCORE_MERGE = 12,    /* row normalisers of a multi-layer scoring call    */
+  DKV_KERNEL_REBALANCE_PICK = 13  /* digits of the updates' thresholds, between the scans */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */

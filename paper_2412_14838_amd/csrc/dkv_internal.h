@@ -32,12 +32,15 @@ struct WorkspaceLayout {
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
   size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
   size_t tot0;         // int32 [DKV_MAX_UPDATES][n_seqs][kRadixBins]  top digit: slot 0 kept from call to call, slot u the layers new to update u
-  size_t tot1;         // int32 [n_seqs][kRadixBins]     middle digit, elements sharing the threshold's top digit
-  size_t tot2;         // int32 [n_seqs][1024]           last digit, elements sharing the two digits above
+  // per class of updates of a call (updates whose thresholds share the digits found so far see the same elements;
+  // a class is named by its first update), DKV_MAX_UPDATES blocks of:
+  size_t tot1;         // int32 [n_seqs][DKV_MAX_UPDATES][kRadixBins]  middle digit of the elements sharing the threshold's top digit, summed over the layers new to update f (slot f)
+  size_t tot2;         // int32 [n_seqs][DKV_MAX_UPDATES][1024]        last digit of the elements sharing the two digits above, same slots
   size_t hist2;        // int32 [n_seqs][L][1024]        the same per layer
-  size_t above;        // int32 [n_seqs][L]              per-layer counts of elements known to be above the threshold
+  size_t above;        // int32 [2][n_seqs][L]           per-layer counts of elements known to be above the threshold (by the top digit; by the middle digit)
   size_t tot0_slot_bytes;      // one of the DKV_MAX_UPDATES slots of the top-digit histogram
-  size_t update_block_bytes;   // tot1 .. above of one update; DKV_MAX_UPDATES such blocks follow each other
+  size_t update_block_bytes;   // tot1 .. above of one class; DKV_MAX_UPDATES such blocks follow each other
+  size_t picks;        // int32 [DKV_MAX_UPDATES][n_seqs][4]  per update: digit 0 of its threshold, rank left inside it, digit 1, rank left inside that
   size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
   size_t total;
   int rows_pad;        // padded_rows(G*w)
@@ -70,13 +73,14 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.header = off;   off += align256(8 * sizeof(int32_t));
   w.tot0_slot_bytes = align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
   w.tot0 = off;     off += w.tot0_slot_bytes * DKV_MAX_UPDATES;
-  const size_t block = off;                                                             // tot1 .. above: one update's block
-  w.tot1 = off;     off += align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
-  w.tot2 = off;     off += align256(size_t(d.n_seqs) * 1024 * sizeof(int32_t));
+  const size_t block = off;                                                             // tot1 .. above: one class's block
+  w.tot1 = off;     off += align256(size_t(d.n_seqs) * DKV_MAX_UPDATES * kRadixBins * sizeof(int32_t));
+  w.tot2 = off;     off += align256(size_t(d.n_seqs) * DKV_MAX_UPDATES * 1024 * sizeof(int32_t));
   w.hist2 = off;    off += align256(size_t(d.n_seqs) * d.n_layers * 1024 * sizeof(int32_t));
-  w.above = off;    off += align256(size_t(d.n_seqs) * d.n_layers * sizeof(int32_t));
+  w.above = off;    off += align256(size_t(2) * d.n_seqs * d.n_layers * sizeof(int32_t));
   w.update_block_bytes = off - block;
-  off = block + w.update_block_bytes * DKV_MAX_UPDATES;                                 // one block per update of a call
+  off = block + w.update_block_bytes * DKV_MAX_UPDATES;                                 // at most one class per update of a call
+  w.picks = off;    off += align256(size_t(DKV_MAX_UPDATES) * d.n_seqs * 4 * sizeof(int32_t));
   w.total = off;
   return w;
 }

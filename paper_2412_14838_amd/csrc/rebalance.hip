@@ -8,20 +8,23 @@
 //   hist0   histogram of the top digit. A layer's scores never change once written, so the histogram is kept in
 //           the workspace and a call only adds the layers that the previous call (layers_done - interval, same
 //           score tensor, recorded in a small header) had not seen; any other history means a full recount.
-//   scan1   every workgroup first derives digit 0 of T from the top-digit histogram (a 2048-bin scan, cheaper
-//           than a kernel of its own), then histograms the middle digit of the elements that share digit 0 and
-//           counts, per layer, the elements whose digit 0 is larger (they are above T).
-//   scan2   the same one digit down: derives digits 0 and 1, histograms the last digit (per layer and in
-//           total), counts per layer the elements that share digit 0 and have a larger middle digit.
+//   pick0   digit 0 of T from the top-digit histogram (one workgroup per sequence and update).
+//   scan1   histograms the middle digit of the elements that share digit 0 and counts, per layer, the elements
+//           whose digit 0 is larger (they are above T).
+//   pick1   digit 1 of T from that histogram.
+//   scan2   the same one digit down: histograms the last digit (per layer and in total), counts per layer the
+//           elements that share digit 0 and have a larger middle digit.
 //   final   one workgroup per sequence: digit 2, then cnt_i = #{> T in layer i} + the share of the elements
 //           equal to T that the tie rule (lower layer first) gives to layer i, then Z, Z' and counts.
 // The scans read the scores as 16-byte vectors, all loads of a workgroup's chunk in flight together.
 //
 // Several consecutive updates (layers_done, layers_done + interval, ...) can be asked for in one call: they are
 // independent of each other except for the final min into `counts`, which commutes. Update u then owns slot u
-// of every histogram: T[u] holds the top-digit histogram of the layers that are new to update u (T[0]
-// additionally the kept history), so update u's top-digit histogram is T[0] + ... + T[u]; every kernel takes
-// the update as one more grid dimension. The next call folds T[1..] into T[0] before it starts.
+// of the top-digit histogram: T[u] holds the layers that are new to update u (T[0] additionally the kept
+// history), so update u's top-digit histogram is T[0] + ... + T[u]; the next call folds T[1..] into T[0] before
+// it starts. The scans read every layer once per call, however many updates cover it: the updates whose
+// thresholds agree in the digits found so far form a class (see class_of below), a workgroup keeps its chunk of
+// scores in registers, takes it through the classes (usually one) and stores what it finds once per class.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -29,7 +32,7 @@ namespace dkv {
 constexpr int kFinalThreads = 1024;
 constexpr int kHist0Copies = 4;      // interleaved LDS copies of the top-digit histogram (every element lands there)
 constexpr int kHist0Chunk = 8192;    // prefix positions per workgroup, top-digit histogram
-constexpr int kScanChunk = 16384;    // prefix positions per workgroup, scans 1 and 2
+constexpr int kScanChunk = 8192;     // prefix positions per workgroup, scans 1 and 2
 constexpr int kLowBins = 1024;       // the last digit has 10 bits
 constexpr uint32_t kHeaderMagic = 0x646b7631u;
 
@@ -237,98 +240,156 @@ __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hk
   }
 }
 
-// Scans 1 and 2. grid = (chunk upper bound, Hkv, layers_done), 256 threads.
-//   PASS 1: histogram of the middle digit over elements with digit 0 == d0 -> tot1; above[layer] += #{digit 0 > d0}
-//   PASS 2: histogram of the last digit over elements with digits (0, 1) == (d0, d1) -> tot2 and hist2[layer];
-//           above[layer] += #{digit 0 == d0, digit 1 > d1}
-// blockIdx.z runs over the (update, layer) pairs of the call: update u covers layers [0, layers_done + u * interval).
-// tot1 .. above point at update 0's histograms; update u's lie u * always_words ints further.
+// Classes. Update u of a call covers the layers [0, layers_done + u * interval); a layer is new to update
+// f = first_update(layer) and is covered by the updates f .. n_updates - 1. Among those, the updates whose
+// thresholds agree in the digits found so far (`key`) see exactly the same elements of the layer: they form a
+// class, named by its first member, class_of(key, f, u) = min {v in [f, u] : key[v] == key[u]}. What a scan
+// finds for a class is stored once, under the class's name (block `class * always_words`) and the slot f (sums
+// over layers) or the layer itself; whoever needs update u's figures asks for class_of(.., f, u) again.
+__device__ inline int class_of(const uint32_t* key, int f, int u) {
+  const uint32_t k = key[u];
+  for (int v = f; v < u; ++v)
+    if (key[v] == k) return v;
+  return u;
+}
+
+__device__ inline int first_update_of(int layer, int layers_done, int interval) {
+  return layer < layers_done ? 0 : (layer - layers_done) / interval + 1;
+}
+
+// picks[(update * n_seqs + seq) * 4 + ..]: digit 0 of the update's threshold, rank left inside it, digit 1, rank
+// left inside that. grid = (n_seqs, n_updates), kFinalThreads threads; layers_done comes in as the first update's.
+//   LEVEL 0 (after hist0): from the top-digit histograms; LEVEL 1 (after scan 1): from the classes' tot1 slots.
+template <int LEVEL>
+__global__ __launch_bounds__(kFinalThreads) void rebalance_pick_kernel(int n_seqs, int w, int Hkv, int mean_budget,
+                                                                       int layers_done, int interval,
+                                                                       const int32_t* __restrict__ cu,
+                                                                       const int32_t* __restrict__ tot0, int64_t tot0_words,
+                                                                       const int32_t* __restrict__ tot1, int64_t always_words,
+                                                                       int32_t* __restrict__ picks) {
+  __shared__ int scratch[kFinalThreads / 64];
+  __shared__ int sh[2];
+  __shared__ uint32_t key[DKV_MAX_UPDATES];
+  const int seq = blockIdx.x, update = blockIdx.y, n_updates = gridDim.y;
+  int32_t* __restrict__ mine = picks + ((int64_t)update * n_seqs + seq) * 4;
+  Bins<kFinalThreads, kRadixBins> bins;
+  int rem;
+  if (LEVEL == 0) {
+    bins = load_bins_sum<kFinalThreads, kRadixBins>(tot0 + (int64_t)seq * kRadixBins, update + 1, tot0_words);
+    rem = global_k(cu, seq, w, Hkv, mean_budget, layers_done + update * interval);
+  } else {
+    if (threadIdx.x < n_updates) key[threadIdx.x] = (uint32_t)picks[((int64_t)threadIdx.x * n_seqs + seq) * 4];
+    __syncthreads();
+    // the layers new to update f, as the class of this update saw them; all slots are requested before the first wait
+    Bins<kFinalThreads, kRadixBins> x[DKV_MAX_UPDATES];
+#pragma unroll
+    for (int f = 0; f < DKV_MAX_UPDATES; ++f)
+      if (f <= update)
+        x[f] = load_bins<kFinalThreads, kRadixBins>(tot1 + class_of(key, f, update) * always_words +
+                                                    ((int64_t)seq * DKV_MAX_UPDATES + f) * kRadixBins);
+    rem = mine[1];
+#pragma unroll
+    for (int i = 0; i < kRadixBins / kFinalThreads; ++i) bins.c[i] = 0;
+#pragma unroll
+    for (int f = 0; f < DKV_MAX_UPDATES; ++f)
+      if (f <= update)
+#pragma unroll
+        for (int i = 0; i < kRadixBins / kFinalThreads; ++i) bins.c[i] += x[f].c[i];
+  }
+  int digit, left;
+  pick_digit<kFinalThreads, kRadixBins>(bins, rem, scratch, sh, digit, left);
+  if (threadIdx.x == 0) { mine[2 * LEVEL] = digit; mine[2 * LEVEL + 1] = left; }
+}
+
+// Scans 1 and 2. grid = (chunk upper bound, Hkv, layers of the call's last update), 256 threads. A workgroup reads
+// its chunk of one layer's scores once and takes it through the classes of the updates that cover the layer
+// (usually one: T moves little from one update to the next):
+//   PASS 1: histogram of the middle digit over elements with digit 0 == d0 -> tot1 (slot of the layer);
+//           above[0][layer] += #{digit 0 > d0}
+//   PASS 2: histogram of the last digit over elements with digits (0, 1) == (d0, d1) -> tot2 (slot of the layer) and
+//           hist2[layer]; above[1][layer] += #{digit 0 == d0, digit 1 > d1}
+// with (d0, d1) of the updates from `picks`. tot1 .. above point at class 0's block.
 template <int PASS>
 __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
-                                                             int mean_budget, int layers_done, int interval,
+                                                             int layers_done, int interval, int n_updates,
                                                              const float* __restrict__ scores_all,
                                                              const int32_t* __restrict__ cu,
-                                                             const int32_t* __restrict__ tot0, int64_t tot0_words,
+                                                             const int32_t* __restrict__ picks,
                                                              int32_t* __restrict__ tot1, int32_t* __restrict__ tot2,
                                                              int32_t* __restrict__ hist2, int32_t* __restrict__ above,
                                                              int64_t always_words) {
   constexpr int BINS = PASS == 1 ? kRadixBins : kLowBins;
   __shared__ int h[BINS];
-  __shared__ int scratch[4];
-  __shared__ int sh[2];
+  __shared__ uint32_t key_of[DKV_MAX_UPDATES];        // the digits of the updates' thresholds found so far
   __shared__ int n_above;
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kScanChunk, w, blockIdx.x, seq, c, begin, len)) return;
-  int update = 0, layer = blockIdx.z;
-  while (layer >= layers_done) {           // the grid holds exactly the pairs of the call
-    layer -= layers_done;
-    layers_done += interval;
-    ++update;
-  }
-  tot1 += update * always_words; tot2 += update * always_words;
-  hist2 += update * always_words; above += update * always_words;
-  const int head = blockIdx.y;
+  const int head = blockIdx.y, layer = blockIdx.z;
+  const int first_update = first_update_of(layer, layers_done, interval);   // < n_updates by the grid
   const int n = len - w;
   const int i0 = c * kScanChunk;
   const int i1 = i0 + kScanChunk < n ? i0 + kScanChunk : n;
   constexpr int NV = kScanChunk / 4 / 256 + 1;
   ChunkVectors<NV> cv;
   const int64_t e_lo = ((int64_t)layer * Hkv + head) * total_tokens + begin + i0;
-  // everything this workgroup reads from memory is requested here, before the first wait
-  const Bins<256, kRadixBins> bins0 = load_bins_sum<256, kRadixBins>(tot0 + (int64_t)seq * kRadixBins, update + 1, tot0_words);
-  Bins<256, kRadixBins> bins1;
-  if (PASS == 2) bins1 = load_bins<256, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
   load_chunk<NV>(scores_all, (int64_t)L * Hkv * total_tokens, e_lo, e_lo + (i1 - i0), cv);
-  for (int b = threadIdx.x; b < BINS; b += 256) h[b] = 0;
-  if (threadIdx.x == 0) n_above = 0;
-  int rem = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
-  int d0, d1 = 0;
-  pick_digit<256, kRadixBins>(bins0, rem, scratch, sh, d0, rem);
-  if (PASS == 2) pick_digit<256, kRadixBins>(bins1, rem, scratch, sh, d1, rem);
-  // (pick_digit ends with a barrier: h and n_above are cleared for everyone)
+  if (threadIdx.x < n_updates) {
+    const int32_t* __restrict__ pk = picks + ((int64_t)threadIdx.x * n_seqs + seq) * 4;
+    key_of[threadIdx.x] = PASS == 1 ? (uint32_t)pk[0] : (((uint32_t)pk[0] << 11) | (uint32_t)pk[2]);
+  }
+  __syncthreads();
   // PASS 1 looks at the top digit p = u >> 21, PASS 2 at the top two p = u >> 10; an element is "above" when
   // p lies in (key, end): PASS 1 any larger top digit, PASS 2 a larger middle digit under the same top digit.
   constexpr int SH = PASS == 1 ? 21 : 10;
-  const uint32_t key = PASS == 1 ? (uint32_t)d0 : (((uint32_t)d0 << 11) | (uint32_t)d1);
-  const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((uint32_t)d0 + 1u) << 11);
-  const uint32_t span = end - key - 1u;   // p in (key, end)  <=>  p - key - 1 < span (unsigned)
   auto bin_of = [](uint32_t u) { return PASS == 1 ? ((u >> 10) & (uint32_t)(kRadixBins - 1)) : (u & (uint32_t)(kLowBins - 1)); };
-  int mine = 0;
+  for (int update = first_update; update < n_updates; ++update) {
+    if (class_of(key_of, first_update, update) != update) continue;       // an earlier update did this class's work
+    for (int b = threadIdx.x; b < BINS; b += 256) h[b] = 0;
+    if (threadIdx.x == 0) n_above = 0;
+    __syncthreads();
+    const uint32_t key = key_of[update];
+    const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((key >> 11) + 1u) << 11);
+    const uint32_t span = end - key - 1u;   // p in (key, end)  <=>  p - key - 1 < span (unsigned)
+    int mine = 0;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    if (cv.ok[j] == 0xf) {
-      const uint32_t p0 = cv.v[j].x >> SH, p1 = cv.v[j].y >> SH, p2 = cv.v[j].z >> SH, p3 = cv.v[j].w >> SH;
-      mine += (p0 - key - 1u < span) + (p1 - key - 1u < span) + (p2 - key - 1u < span) + (p3 - key - 1u < span);
-      if (p0 == key || p1 == key || p2 == key || p3 == key) {       // rare: a few elements in a thousand
-        if (p0 == key) atomicAdd(&h[bin_of(cv.v[j].x)], 1);
-        if (p1 == key) atomicAdd(&h[bin_of(cv.v[j].y)], 1);
-        if (p2 == key) atomicAdd(&h[bin_of(cv.v[j].z)], 1);
-        if (p3 == key) atomicAdd(&h[bin_of(cv.v[j].w)], 1);
-      }
-    } else if (cv.ok[j]) {
+    for (int j = 0; j < NV; ++j) {
+      if (cv.ok[j] == 0xf) {
+        const uint32_t p0 = cv.v[j].x >> SH, p1 = cv.v[j].y >> SH, p2 = cv.v[j].z >> SH, p3 = cv.v[j].w >> SH;
+        mine += (p0 - key - 1u < span) + (p1 - key - 1u < span) + (p2 - key - 1u < span) + (p3 - key - 1u < span);
+        if (p0 == key || p1 == key || p2 == key || p3 == key) {       // one branch per vector
+          if (p0 == key) atomicAdd(&h[bin_of(cv.v[j].x)], 1);
+          if (p1 == key) atomicAdd(&h[bin_of(cv.v[j].y)], 1);
+          if (p2 == key) atomicAdd(&h[bin_of(cv.v[j].z)], 1);
+          if (p3 == key) atomicAdd(&h[bin_of(cv.v[j].w)], 1);
+        }
+      } else if (cv.ok[j]) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (!(cv.ok[j] >> q & 1)) continue;
-        const uint32_t u = lane_of(cv.v[j], q), pq = u >> SH;
-        mine += pq - key - 1u < span;
-        if (pq == key) atomicAdd(&h[bin_of(u)], 1);
+        for (int q = 0; q < 4; ++q) {
+          if (!(cv.ok[j] >> q & 1)) continue;
+          const uint32_t u = lane_of(cv.v[j], q), pq = u >> SH;
+          mine += pq - key - 1u < span;
+          if (pq == key) atomicAdd(&h[bin_of(u)], 1);
+        }
       }
     }
-  }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
-  __syncthreads();
-  if (threadIdx.x == 0 && n_above) atomicAdd(&above[seq * L + layer], n_above);
-  for (int b = threadIdx.x; b < BINS; b += 256) {
-    const int v = h[b];
-    if (!v) continue;
-    if (PASS == 1) {
-      atomicAdd(&tot1[(int64_t)seq * kRadixBins + b], v);
-    } else {
-      atomicAdd(&tot2[(int64_t)seq * kLowBins + b], v);
-      atomicAdd(&hist2[((int64_t)seq * L + layer) * kLowBins + b], v);
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
+    __syncthreads();
+    const int64_t cls = (int64_t)update * always_words;                 // the class's block
+    if (threadIdx.x == 0 && n_above) atomicAdd(&above[cls + ((int64_t)(PASS - 1) * n_seqs + seq) * L + layer], n_above);
+    const int64_t slot = (int64_t)seq * DKV_MAX_UPDATES + first_update;
+    for (int b = threadIdx.x; b < BINS; b += 256) {
+      const int v = h[b];
+      if (!v) continue;
+      if (PASS == 1) {
+        atomicAdd(&tot1[cls + slot * kRadixBins + b], v);
+      } else {
+        atomicAdd(&tot2[cls + slot * kLowBins + b], v);
+        atomicAdd(&hist2[cls + ((int64_t)seq * L + layer) * kLowBins + b], v);
+      }
     }
+    __syncthreads();                                                    // h and n_above are reused by the next class
   }
 }
 
@@ -353,14 +414,13 @@ __device__ inline int block_exclusive_scan_final(int v, int* scratch, int& total
 // grid = (n_seqs, n_updates): blockIdx.y is the update, layers_done comes in as the first update's.
 __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     int n_seqs, int L, int layers_done, int interval, int w, int Hkv, int mean_budget, int layer_max, int total_tokens,
-    const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ tot0, int64_t tot0_words,
-    const int32_t* __restrict__ tot1, const int32_t* __restrict__ tot2, const int32_t* __restrict__ hist2,
-    const int32_t* __restrict__ above, int64_t always_words, int32_t* __restrict__ header, int32_t* __restrict__ counts,
+    const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ picks,
+    const int32_t* __restrict__ tot2, const int32_t* __restrict__ hist2, const int32_t* __restrict__ above,
+    int64_t always_words, int32_t* __restrict__ header, int32_t* __restrict__ counts,
     int32_t* __restrict__ budgets_out, int32_t* __restrict__ hits_out, int64_t out_stride_update) {
   const int update = blockIdx.y, n_updates = gridDim.y;
+  const int first_done = layers_done;                  // of the call's first update: it fixes the slots of the layers
   layers_done += update * interval;
-  tot1 += update * always_words; tot2 += update * always_words;
-  hist2 += update * always_words; above += update * always_words;
   if (budgets_out) budgets_out += update * out_stride_update;
   if (hits_out) hits_out += update * out_stride_update;
   static_assert(DKV_MAX_LAYERS <= kFinalThreads, "one layer per thread");
@@ -369,32 +429,57 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
   __shared__ int gt[DKV_MAX_LAYERS];
   __shared__ int eq[DKV_MAX_LAYERS];
   __shared__ int wave_max[kFinalThreads / 64];
+  __shared__ uint32_t key1[DKV_MAX_UPDATES], key2[DKV_MAX_UPDATES];   // digit 0, digits (0, 1) of the updates' thresholds
   const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int kg = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
-  // all histogram reads are requested together, before the first wait
-  const auto bins0 = load_bins_sum<kFinalThreads, kRadixBins>(tot0 + (int64_t)seq * kRadixBins, update + 1, tot0_words);
-  const auto bins1 = load_bins<kFinalThreads, kRadixBins>(tot1 + (int64_t)seq * kRadixBins);
-  const auto bins2 = load_bins<kFinalThreads, kLowBins>(tot2 + (int64_t)seq * kLowBins);
+  if (tid < n_updates) {
+    const int32_t* __restrict__ pk = picks + ((int64_t)tid * n_seqs + seq) * 4;
+    key1[tid] = (uint32_t)pk[0];
+    key2[tid] = ((uint32_t)pk[0] << 11) | (uint32_t)pk[2];
+  }
+  __syncthreads();
+  // last-digit histogram of this update: the slots of the layers it covers, each from the class this update is in
+  // (all reads are requested before the first wait)
+  Bins<kFinalThreads, kLowBins> slot2[DKV_MAX_UPDATES];
+#pragma unroll
+  for (int f = 0; f < DKV_MAX_UPDATES; ++f)
+    if (f <= update)
+      slot2[f] = load_bins<kFinalThreads, kLowBins>(tot2 + class_of(key2, f, update) * always_words +
+                                                    ((int64_t)seq * DKV_MAX_UPDATES + f) * kLowBins);
   constexpr int kWaves = kFinalThreads / 64, kPerLane = kLowBins / 64;
-  // the first layer of this wavefront: lane l holds last-digit bins l, l + 64, ... (later layers are read in the loop)
+  // the first layer of this wavefront, requested before the first wait: lane l holds last-digit bins l, l + 64, ...
+  // (later layers are read in the loop)
   int first[kPerLane];
   {
-    const int32_t* __restrict__ g = hist2 + ((int64_t)seq * L + (wv < layers_done ? wv : 0)) * kLowBins;
+    const int i = wv < layers_done ? wv : 0;
+    const int cls = class_of(key2, first_update_of(i, first_done, interval), update);
+    const int32_t* __restrict__ g = hist2 + cls * always_words + ((int64_t)seq * L + i) * kLowBins;
 #pragma unroll
     for (int r = 0; r < kPerLane; ++r) first[r] = g[lane + 64 * r];
   }
-  const int above_mine = tid < layers_done ? above[seq * L + tid] : 0;
-  int rem = kg, d0, d1, d2;
-  pick_digit<kFinalThreads, kRadixBins>(bins0, rem, scratch, sh, d0, rem);
-  pick_digit<kFinalThreads, kRadixBins>(bins1, rem, scratch, sh, d1, rem);
+  int above_mine = 0;
+  if (tid < layers_done) {
+    const int f = first_update_of(tid, first_done, interval);
+    above_mine = above[class_of(key1, f, update) * always_words + ((int64_t)0 * n_seqs + seq) * L + tid] +
+                 above[class_of(key2, f, update) * always_words + ((int64_t)1 * n_seqs + seq) * L + tid];
+  }
+  int rem = picks[((int64_t)update * n_seqs + seq) * 4 + 3], d2;      // rank left inside the digits (0, 1)
+  Bins<kFinalThreads, kLowBins> bins2;
+#pragma unroll
+  for (int i = 0; i < kLowBins / kFinalThreads; ++i) bins2.c[i] = 0;
+#pragma unroll
+  for (int f = 0; f < DKV_MAX_UPDATES; ++f)
+    if (f <= update)
+#pragma unroll
+      for (int i = 0; i < kLowBins / kFinalThreads; ++i) bins2.c[i] += slot2[f].c[i];
   pick_digit<kFinalThreads, kLowBins>(bins2, rem, scratch, sh, d2, rem);
   const int need_eq = rem;   // elements equal to T that belong to the top-kg
-  (void)d0; (void)d1;
   // per layer: elements above T = those counted by the scans (a higher digit is larger) + the last-digit bins
   // above the chosen one; equal to T = the chosen last-digit bin
   for (int i = wv; i < layers_done; i += kWaves) {
     int acc = 0, at = 0;
-    const int32_t* __restrict__ g = hist2 + ((int64_t)seq * L + i) * kLowBins;
+    const int cls = class_of(key2, first_update_of(i, first_done, interval), update);
+    const int32_t* __restrict__ g = hist2 + cls * always_words + ((int64_t)seq * L + i) * kLowBins;
 #pragma unroll
     for (int r = 0; r < kPerLane; ++r) {
       const int b = lane + 64 * r;
@@ -453,6 +538,7 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, con
   int32_t* tot2 = reinterpret_cast<int32_t*>(ws + wl.tot2);
   int32_t* hist2 = reinterpret_cast<int32_t*>(ws + wl.hist2);
   int32_t* above = reinterpret_cast<int32_t*>(ws + wl.above);
+  int32_t* picks = reinterpret_cast<int32_t*>(ws + wl.picks);
   // tot1 .. above of an update are one contiguous block, the blocks of the updates follow each other: those of
   // this call are cleared; the top-digit slots are folded or cleared according to the history
   const int64_t always_words = (int64_t)(wl.update_block_bytes / 4), tot0_words = (int64_t)(wl.tot0_slot_bytes / 4);
@@ -463,22 +549,22 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, con
          reinterpret_cast<uint32_t*>(tot1), clear_words, reinterpret_cast<uint32_t*>(tot0), (size_t)tot0_words, header,
          scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens);
   const int last_done = layers_done + (n_updates - 1) * p.interval;
-  int pairs = 0;                                                 // (update, layer) pairs of the call
-  for (int u = 0; u < n_updates; ++u) pairs += layers_done + u * p.interval;
   const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, last_done);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist0_kernel, grid0, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
          p.total_tokens, layers_done, p.interval, scores_all, cu, header, tot0, tot0_words);
-  const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, pairs);
+  const dim3 grid_pick(p.n_seqs, n_updates);
+  launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<0>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
+         p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
+  const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, last_done);
   launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, p.mean_budget, layers_done, p.interval, scores_all, cu, tot0, tot0_words, tot1, tot2, hist2, above,
-         always_words);
+         p.total_tokens, layers_done, p.interval, n_updates, scores_all, cu, picks, tot1, tot2, hist2, above, always_words);
+  launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<1>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
+         p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
   launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, p.mean_budget, layers_done, p.interval, scores_all, cu, tot0, tot0_words, tot1, tot2, hist2, above,
-         always_words);
+         p.total_tokens, layers_done, p.interval, n_updates, scores_all, cu, picks, tot1, tot2, hist2, above, always_words);
   launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs, n_updates), dim3(kFinalThreads), 0, st,
          p.n_seqs, p.L, layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu,
-         tot0, tot0_words, tot1, tot2, hist2, above, always_words, header, counts, budgets_out, hits_out,
-         out_stride_update);
+         picks, tot2, hist2, above, always_words, header, counts, budgets_out, hits_out, out_stride_update);
   return hipGetLastError();
 }
 

@@ -20,10 +20,12 @@
 // Workgroup = RS x KS wavefronts: RS row slabs of 64 rows (2 MFMA tiles) x KS key tiles of 32 keys.
 // Every workgroup owns a contiguous chunk of one (sequence, KV head) and takes it through all layers of the call
 // (up to DKV_MAX_SELECT_LAYERS): the key tiles of the layers form one stream of steps, the next layer's Q and
-// normalisers arrive while the current layer's last steps run. The emit kernel computes (P-1)/2 extra keys on
-// each side of its output chunk, so pooling never needs another workgroup's sums; identical keys give
-// bit-identical sums whichever workgroup or lane computes them (fixed summation order per column), and a layer
-// gets the same bits whether it is scored alone or as part of a multi-layer call.
+// normalisers arrive while the current layer's last steps run. Pooling across the borders of the output chunks:
+// a single-layer call computes (P-1)/2 extra keys on each side of its chunk, so that it never needs another
+// workgroup's sums; a multi-layer call computes its own keys only, leaves the column sums next to the borders in the
+// workspace, and one small kernel for all layers (score_fix_borders) completes the outputs there. Identical keys
+// give bit-identical sums whichever workgroup or lane computes them (fixed summation order per column), and a
+// layer gets the same bits whether it is scored alone or as part of a multi-layer call.
 #include "dkv_internal.h"
 
 #include <type_traits>

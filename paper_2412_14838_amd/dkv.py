@@ -137,7 +137,7 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "score_borders", "score_lse", "pack", "decode", "score_merge")
+                "rebalance_final", "fill", "score_borders", "score_lse", "pack", "decode", "score_merge", "rebalance_pick")
 
 
 def dkv_profile_begin(capacity: int) -> None:
