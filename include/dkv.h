@@ -254,7 +254,8 @@ int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores
  * as above, once per update): for a caller that has scored and selected the layers of several update intervals
  * before it updates (see dkv_score_window_layers). The updates read the scores only and meet in
  * counts[q][i] <- min(counts[q][i], Z'_i), which commutes, so the result equals n_updates dkv_rebalance calls in
- * order; every kernel of the update takes the updates side by side.
+ * order; every kernel of the update takes the updates side by side, and a layer's scores are read once per scan
+ * whatever the number of updates that cover the layer.
  * n_updates          1 .. DKV_MAX_UPDATES; layers_done + (n_updates - 1) * interval <= L.
  * budgets_out, hits_out   as for dkv_rebalance, one [n_seqs][L] block per update: update u writes at
  *                    out + u * out_stride_update (ints; >= n_seqs * L when n_updates > 1). May be NULL.
