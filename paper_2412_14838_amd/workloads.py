@@ -120,9 +120,10 @@ def standard_configs() -> Dict[str, Workload]:
 
 
 def extended_configs() -> Dict[str, Workload]:
-    """Beyond the five benchmark configurations: config 3's shape at four times the context."""
+    """Beyond the five benchmark configurations: config 3's shape at four and at sixteen times the context."""
     base = standard_configs()["mistral_7b_32k"]
-    return {"mistral_7b_128k": base.with_(name="mistral_7b_128k", seqlens=(131072,), seed=1005)}
+    return {"mistral_7b_128k": base.with_(name="mistral_7b_128k", seqlens=(131072,), seed=1005),
+            "mistral_7b_512k": base.with_(name="mistral_7b_512k", seqlens=(524288,), seed=1006)}
 
 
 def all_configs() -> Dict[str, Workload]:

@@ -159,6 +159,13 @@ def test_long_context_128k(dkv):
     check_config(cfg, [0, cfg.L - 1], [2], [0], group=8)
 
 
+def test_long_context_512k(dkv):
+    """The same shape at 524288 tokens, 2 layers (one update): 1 GB of K per layer, 128 chunks of 4096 keys per
+    head, rows sixteen times longer than the selection keeps in registers."""
+    cfg = W.extended_configs()["mistral_7b_512k"].with_(L=2, interval=2)
+    check_config(cfg, [cfg.L - 1], [5], [0], group=2)
+
+
 @pytest.mark.parametrize("name", ["mistral_7b_32k", "ragged_batch8"])
 def test_full_single_sweep_scoring_from_row_lse(dkv, name):
     """At full size: the exported normalisers match the oracle's log-sum-exp on sampled heads, and the single
