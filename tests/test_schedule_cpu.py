@@ -35,7 +35,7 @@ def _record(monkeypatch):
 
 
 @pytest.mark.parametrize("L,interval,group", [(8, 2, 1), (8, 2, 8), (8, 2, 3), (8, 4, 8), (7, 2, 4), (6, 1, 8), (5, 5, 2),
-                                              (16, 2, 8)])
+                                              (16, 2, 8), (32, 4, 32), (32, 2, 32), (40, 4, 64), (28, 4, 28)])
 def test_schedules_issue_every_stage_once_and_in_a_valid_order(monkeypatch, L, interval, group):
     cfg = W.Workload("sched", L=L, Hq=4, Hkv=2, d=64, seqlens=(300, 70), dtype="f32", w=16, P=7, mean_budget=32,
                      layer_max=64, interval=interval, seed=1)
