@@ -237,6 +237,42 @@ def test_pipeline_selection_and_budgets_bit_exact(dkv, case):
         assert counts[s].tolist() == r.n
 
 
+def test_pipeline_one_group_with_more_updates_than_a_call_takes(dkv):
+    """20 layers, an update every 2, all layers in one group: one scoring, selection and compaction call, the ten
+    updates in two calls (8 + 2), the second continuing the first one's histograms. Integer results against the
+    oracle on the GPU's scores, per update; the compacted rows against the oracle's final cache."""
+    cfg = small_cfg("deep", L=20, interval=2, Hq=4, Hkv=2, seqlens=(900, 300), layer_max=96, mean_budget=24,
+                    dtype="bf16", d=128)
+    comp = Compressor(cfg, group=32)
+    snapshots = {}
+    comp.on_update = lambda l: snapshots.__setitem__(l, (comp.hits, comp.budgets))   # views of that update's rows
+    host = [W.make_layer(cfg, l) for l in range(cfg.L)]
+    for l in range(cfg.L):
+        dev = to_device(cfg, host[l])
+        comp.step(l, dev["q_win"], dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    assert sorted(snapshots) == list(range(2, 21, 2))
+    scores = comp.scores.cpu().numpy()
+    ref = _oracle_on_gpu_scores(cfg, scores)
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    cu = cfg.cu_seqlens
+    for s in range(cfg.n_seqs):
+        r = ref[s]
+        for l in range(cfg.L):
+            assert np.array_equal(idx[l, s][:, :r.idx[l].shape[1]], r.idx[l])
+        for (l, cnt, Z, Zp) in r.budgets:
+            hits, budgets = (x.cpu().numpy() for x in snapshots[l])
+            assert np.array_equal(hits[s, :l], cnt) and np.array_equal(budgets[s, :l], np.minimum(Zp, 2**31 - 1))
+        assert counts[s].tolist() == r.n
+        for l in (0, 7, cfg.L - 1):                     # the rows the updates left, then nothing; window rows first
+            n = r.n[l]
+            ref_k, ref_v = O.gather_kv(host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]],
+                                       r.idx[l][:, :n], cfg.w)
+            kb, vb = comp.kb[l, s].float().cpu().numpy(), comp.vb[l, s].float().cpu().numpy()
+            assert np.array_equal(kb[:, cfg.w:cfg.w + n], ref_k[:, :n]) and np.array_equal(kb[:, :cfg.w], ref_k[:, n:])
+            assert np.array_equal(vb[:, cfg.w:cfg.w + n], ref_v[:, :n]) and np.array_equal(vb[:, :cfg.w], ref_v[:, n:])
+
+
 def test_rebalance_skewed_and_tied_scores(dkv):
     """Synthetic score tensors that stress the global selection: all mass in one layer, bit-equal scores in
     every layer (ties resolved toward earlier layers), and a two-level mix."""
