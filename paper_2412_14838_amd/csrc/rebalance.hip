@@ -217,19 +217,34 @@ __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hk
   for (int b = threadIdx.x; b < kRadixBins * kHist0Copies; b += 256) h[b] = 0;
   __syncthreads();
   int* __restrict__ hc = h + (threadIdx.x & (kHist0Copies - 1));
+  // Scores crowd into a few top digits (a quarter of an octave each) and pooling repeats values along a row, so a
+  // thread mostly meets the digit it met last: runs of equal digits are counted in a register and cost one LDS
+  // atomic per run instead of one per element.
+  uint32_t run_digit = 0;
+  int run = 0;
+  auto count = [&](uint32_t u) {
+    const uint32_t d = u >> 21;
+    if (d != run_digit) {
+      if (run) atomicAdd(&hc[run_digit * kHist0Copies], run);
+      run_digit = d;
+      run = 0;
+    }
+    ++run;
+  };
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     if (cv.ok[j] == 0xf) {
-      atomicAdd(&hc[(cv.v[j].x >> 21) * kHist0Copies], 1);
-      atomicAdd(&hc[(cv.v[j].y >> 21) * kHist0Copies], 1);
-      atomicAdd(&hc[(cv.v[j].z >> 21) * kHist0Copies], 1);
-      atomicAdd(&hc[(cv.v[j].w >> 21) * kHist0Copies], 1);
+      count(cv.v[j].x);
+      count(cv.v[j].y);
+      count(cv.v[j].z);
+      count(cv.v[j].w);
     } else if (cv.ok[j]) {
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        if (cv.ok[j] >> q & 1) atomicAdd(&hc[(lane_of(cv.v[j], q) >> 21) * kHist0Copies], 1);
+        if (cv.ok[j] >> q & 1) count(lane_of(cv.v[j], q));
     }
   }
+  if (run) atomicAdd(&hc[run_digit * kHist0Copies], run);
   __syncthreads();
   int32_t* __restrict__ g = tot0 + slot * tot0_words + (int64_t)seq * kRadixBins;
   for (int b = threadIdx.x; b < kRadixBins; b += 256) {
