@@ -334,9 +334,14 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
                                                              int32_t* __restrict__ hist2, int32_t* __restrict__ above,
                                                              int64_t always_words) {
   constexpr int BINS = PASS == 1 ? kRadixBins : kLowBins;
-  __shared__ int h[BINS];
+  // classes taken through the chunk together: PASS 1 usually has one (the top digit of T rarely moves between the
+  // updates of a call), PASS 2 often one per update (the middle digit does), and its histograms are small
+  constexpr int ROUND = PASS == 1 ? 1 : DKV_MAX_UPDATES;
+  __shared__ int h[ROUND * BINS];
   __shared__ uint32_t key_of[DKV_MAX_UPDATES];        // the digits of the updates' thresholds found so far
-  __shared__ int n_above;
+  __shared__ int cls_update[DKV_MAX_UPDATES];         // the classes of the updates that cover this layer (first members)
+  __shared__ int n_cls;
+  __shared__ int n_above[ROUND];
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kScanChunk, w, blockIdx.x, seq, c, begin, len)) return;
   const int head = blockIdx.y, layer = blockIdx.z;
@@ -353,58 +358,87 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
     key_of[threadIdx.x] = PASS == 1 ? (uint32_t)pk[0] : (((uint32_t)pk[0] << 11) | (uint32_t)pk[2]);
   }
   __syncthreads();
+  if (threadIdx.x == 0) {
+    int k = 0;
+    for (int update = first_update; update < n_updates; ++update)
+      if (class_of(key_of, first_update, update) == update) cls_update[k++] = update;
+    n_cls = k;
+  }
+  __syncthreads();
+  const int classes = n_cls;
   // PASS 1 looks at the top digit p = u >> 21, PASS 2 at the top two p = u >> 10; an element is "above" when
   // p lies in (key, end): PASS 1 any larger top digit, PASS 2 a larger middle digit under the same top digit.
   constexpr int SH = PASS == 1 ? 21 : 10;
   auto bin_of = [](uint32_t u) { return PASS == 1 ? ((u >> 10) & (uint32_t)(kRadixBins - 1)) : (u & (uint32_t)(kLowBins - 1)); };
-  for (int update = first_update; update < n_updates; ++update) {
-    if (class_of(key_of, first_update, update) != update) continue;       // an earlier update did this class's work
-    for (int b = threadIdx.x; b < BINS; b += 256) h[b] = 0;
-    if (threadIdx.x == 0) n_above = 0;
+  for (int c0 = 0; c0 < classes; c0 += ROUND) {
+    const int in_round = classes - c0 < ROUND ? classes - c0 : ROUND;
+    for (int b = threadIdx.x; b < in_round * BINS; b += 256) h[b] = 0;
+    if (threadIdx.x < ROUND) n_above[threadIdx.x] = 0;
     __syncthreads();
-    const uint32_t key = key_of[update];
-    const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((key >> 11) + 1u) << 11);
-    const uint32_t span = end - key - 1u;   // p in (key, end)  <=>  p - key - 1 < span (unsigned)
-    int mine = 0;
+    int mine[ROUND];
+#pragma unroll
+    for (int r = 0; r < ROUND; ++r) mine[r] = 0;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       if (cv.ok[j] == 0xf) {
         const uint32_t p0 = cv.v[j].x >> SH, p1 = cv.v[j].y >> SH, p2 = cv.v[j].z >> SH, p3 = cv.v[j].w >> SH;
-        mine += (p0 - key - 1u < span) + (p1 - key - 1u < span) + (p2 - key - 1u < span) + (p3 - key - 1u < span);
-        if (p0 == key || p1 == key || p2 == key || p3 == key) {       // one branch per vector
-          if (p0 == key) atomicAdd(&h[bin_of(cv.v[j].x)], 1);
-          if (p1 == key) atomicAdd(&h[bin_of(cv.v[j].y)], 1);
-          if (p2 == key) atomicAdd(&h[bin_of(cv.v[j].z)], 1);
-          if (p3 == key) atomicAdd(&h[bin_of(cv.v[j].w)], 1);
+#pragma unroll
+        for (int r = 0; r < ROUND; ++r) {
+          if (r >= in_round) break;
+          const uint32_t key = key_of[cls_update[c0 + r]];
+          const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((key >> 11) + 1u) << 11);
+          const uint32_t span = end - key - 1u;   // p in (key, end)  <=>  p - key - 1 < span (unsigned)
+          mine[r] += (p0 - key - 1u < span) + (p1 - key - 1u < span) + (p2 - key - 1u < span) + (p3 - key - 1u < span);
+          if (p0 == key || p1 == key || p2 == key || p3 == key) {       // one branch per vector and class
+            int* __restrict__ hr = h + r * BINS;
+            if (p0 == key) atomicAdd(&hr[bin_of(cv.v[j].x)], 1);
+            if (p1 == key) atomicAdd(&hr[bin_of(cv.v[j].y)], 1);
+            if (p2 == key) atomicAdd(&hr[bin_of(cv.v[j].z)], 1);
+            if (p3 == key) atomicAdd(&hr[bin_of(cv.v[j].w)], 1);
+          }
         }
       } else if (cv.ok[j]) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           if (!(cv.ok[j] >> q & 1)) continue;
           const uint32_t u = lane_of(cv.v[j], q), pq = u >> SH;
-          mine += pq - key - 1u < span;
-          if (pq == key) atomicAdd(&h[bin_of(u)], 1);
+#pragma unroll
+          for (int r = 0; r < ROUND; ++r) {
+            if (r >= in_round) break;
+            const uint32_t key = key_of[cls_update[c0 + r]];
+            const uint32_t end = PASS == 1 ? (uint32_t)kRadixBins : (((key >> 11) + 1u) << 11);
+            mine[r] += pq - key - 1u < end - key - 1u;
+            if (pq == key) atomicAdd(&h[r * BINS + bin_of(u)], 1);
+          }
         }
       }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&n_above, mine);
+    for (int r = 0; r < ROUND; ++r) {
+      if (r >= in_round) break;
+      int m = mine[r];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m += __shfl_xor(m, o);
+      if ((threadIdx.x & 63) == 0 && m) atomicAdd(&n_above[r], m);
+    }
     __syncthreads();
-    const int64_t cls = (int64_t)update * always_words;                 // the class's block
-    if (threadIdx.x == 0 && n_above) atomicAdd(&above[cls + ((int64_t)(PASS - 1) * n_seqs + seq) * L + layer], n_above);
     const int64_t slot = (int64_t)seq * DKV_MAX_UPDATES + first_update;
-    for (int b = threadIdx.x; b < BINS; b += 256) {
-      const int v = h[b];
-      if (!v) continue;
-      if (PASS == 1) {
-        atomicAdd(&tot1[cls + slot * kRadixBins + b], v);
-      } else {
-        atomicAdd(&tot2[cls + slot * kLowBins + b], v);
-        atomicAdd(&hist2[cls + ((int64_t)seq * L + layer) * kLowBins + b], v);
+    for (int r = 0; r < in_round; ++r) {
+      const int64_t cls = (int64_t)cls_update[c0 + r] * always_words;   // the class's block
+      if (threadIdx.x == 0 && n_above[r])
+        atomicAdd(&above[cls + ((int64_t)(PASS - 1) * n_seqs + seq) * L + layer], n_above[r]);
+      for (int b = threadIdx.x; b < BINS; b += 256) {
+        const int v = h[r * BINS + b];
+        if (!v) continue;
+        if (PASS == 1) {
+          atomicAdd(&tot1[cls + slot * kRadixBins + b], v);
+        } else {
+          atomicAdd(&tot2[cls + slot * kLowBins + b], v);
+          atomicAdd(&hist2[cls + ((int64_t)seq * L + layer) * kLowBins + b], v);
+        }
       }
     }
-    __syncthreads();                                                    // h and n_above are reused by the next class
+    __syncthreads();                                                    // h and n_above are reused by the next round
   }
 }
 
