@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the DynamicKV prefill-compression hot path on one MI355X.
 
-A step = one pass of Algorithm 1's layer loop over one synthetic batch: for every layer score (two kernels),
-select, gather, and the progressive update every `interval` layers.  All inputs are resident in HBM before
+A step = one pass of Algorithm 1's layer loop over one synthetic batch: for every layer score (two sweeps over
+K), select, gather, and the progressive update every `interval` layers - issued layer by layer (`--group 1`) or,
+by default, with one call per stage for as many layers as a call takes.  All inputs are resident in HBM before
 the timed region.  Prints ONE JSON line: context tokens compressed per second, the roofline of the dominant
 kernel (timed live with HIP events attached to its launches) and the CPU oracle timed on a bounded sample.
 
