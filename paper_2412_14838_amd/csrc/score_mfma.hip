@@ -736,8 +736,12 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
       __builtin_amdgcn_sched_barrier(0);
     }
     float col = (s0 + s1) + (s2 + s3);
-    const float other = __shfl_xor(col, 32);
-    col = lane < 32 ? col + other : other + col;           // rows 0-3 mod 8 first, in both half-wavefronts
+    {
+      // the other half-wavefront holds the same keys and the other rows: v_permlane32_swap hands every lane the
+      // lower half's value ([0]) and the upper half's ([1]) without a trip through the LDS crossbar
+      const auto halves = __builtin_amdgcn_permlane32_swap(__float_as_uint(col), __float_as_uint(col), false, false);
+      col = __uint_as_float(halves[0]) + __uint_as_float(halves[1]);   // rows 0-3 mod 8 first
+    }
     if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
     store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2, issued one step ago
     if (fetch_q) store_q_part<RS, KS>(qbuf, qnext, q_part);    // every wavefront has this layer's Q in registers
