@@ -77,7 +77,7 @@ def main():
 
     import torch
     from paper_2412_14838_amd import dkv, workloads as W
-    from paper_2412_14838_amd.pipeline import Compressor, to_device
+    from paper_2412_14838_amd.pipeline import Compressor, default_group, to_device
 
     dkv.load()
     if not torch.cuda.is_available():
@@ -93,8 +93,7 @@ def main():
     torch.cuda.synchronize()
 
     # default: as many whole update intervals as one call takes (all layers, for the configurations at hand)
-    most = min(cfg.L, dkv.DKV_MAX_SELECT_LAYERS, dkv.DKV_MAX_UPDATES * cfg.interval)
-    group = args.group if args.group > 0 else max(most // cfg.interval * cfg.interval, 1)
+    group = args.group if args.group > 0 else default_group(cfg)
     comp = Compressor(cfg, group=group)
     d, T = cfg.d, cfg.total_tokens
     st, sh = d, T * d

@@ -21,6 +21,13 @@ import torch
 from . import dkv
 
 
+def default_group(cfg) -> int:
+    """Layers per call of the grouped schedule when nothing else is asked for: as many whole update intervals as
+    one call of the library takes (all layers, for the benchmark configurations)."""
+    most = min(cfg.L, dkv.DKV_MAX_SELECT_LAYERS, dkv.DKV_MAX_UPDATES * cfg.interval)
+    return max(most // cfg.interval * cfg.interval, 1)
+
+
 class Compressor:
     def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None, group=1):
         self.cfg = cfg

@@ -17,7 +17,7 @@ import torch
 
 from oracle import dkv_oracle as O
 from paper_2412_14838_amd import workloads as W
-from paper_2412_14838_amd.pipeline import Compressor, to_device
+from paper_2412_14838_amd.pipeline import Compressor, default_group as bench_group, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -133,22 +133,22 @@ def test_full_tiny_chained_end_to_end(dkv):
 
 def test_full_llama3_8b_8k(dkv):
     cfg = W.standard_configs()["llama3_8b_8k"]
-    check_config(cfg, [0, 13, cfg.L - 1], [0, 5], [0], group=16)    # two calls of four updates each
+    check_config(cfg, [0, 13, cfg.L - 1], [0, 5], [0], group=bench_group(cfg))
 
 
 def test_full_mistral_7b_32k(dkv):
     cfg = W.standard_configs()["mistral_7b_32k"]
-    check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=32)    # the schedule bench.py times: all layers, eight updates per call
+    check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=bench_group(cfg))   # all layers, eight updates per call
 
 
 def test_full_qwen2_7b_32k_extreme(dkv):
     cfg = W.standard_configs()["qwen2_7b_32k_extreme"]
-    check_config(cfg, [3, cfg.L - 1], [0, 3], [0], group=3)     # groups of 3 and 1 between the updates
+    check_config(cfg, [3, cfg.L - 1], [0, 3], [0], group=bench_group(cfg))   # 28 layers, seven updates per call
 
 
 def test_full_ragged_batch8(dkv):
     cfg = W.standard_configs()["ragged_batch8"]
-    check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7], group=4)
+    check_config(cfg, [2, cfg.L - 1], [0, 6], [0, 6, 7], group=bench_group(cfg))
 
 
 def test_long_context_128k(dkv):
