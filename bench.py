@@ -57,8 +57,9 @@ def _cpu_baseline(cfg, host_layers, target_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # the clocks of an idle GPU take some 10-20 ms of load to settle: the defaults warm up for that long
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mistral_7b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--group", type=int, default=0,
@@ -105,7 +106,8 @@ def main():
         comp.run(layers)
     torch.cuda.synchronize()
     graph = comp.capture(layers, overlap=args.overlap)
-    graph.replay()
+    for _ in range(max(args.warmup, 1)):                 # warm-up in the form that is timed
+        graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
