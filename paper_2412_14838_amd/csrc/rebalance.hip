@@ -47,8 +47,8 @@ __device__ inline int layers_already_counted(const int32_t* __restrict__ header,
   return same && layers_done > interval ? layers_done - interval : 0;
 }
 
-// always: the per-update histograms of this call (n_updates slots, contiguous); tot0: the kMaxUpdates slots T[v] of
-// the top-digit histogram, tot0_words each. With a matching history the slots the previous call used (header[7])
+// always: the per-class blocks of this call (n_updates of them, contiguous: there are at most as many classes as
+// updates); tot0: the DKV_MAX_UPDATES slots T[v] of the top-digit histogram, tot0_words each. With a matching history the slots the previous call used (header[7])
 // are folded into T[0]; without, T[0] starts from zero. The other slots are zeroed either way.
 __global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restrict__ always, size_t always_words,
                                                               uint32_t* __restrict__ tot0, size_t tot0_words,
@@ -588,8 +588,8 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, con
   int32_t* hist2 = reinterpret_cast<int32_t*>(ws + wl.hist2);
   int32_t* above = reinterpret_cast<int32_t*>(ws + wl.above);
   int32_t* picks = reinterpret_cast<int32_t*>(ws + wl.picks);
-  // tot1 .. above of an update are one contiguous block, the blocks of the updates follow each other: those of
-  // this call are cleared; the top-digit slots are folded or cleared according to the history
+  // tot1 .. above of a class of updates are one contiguous block, the blocks follow each other: as many as the call
+  // has updates are cleared; the top-digit slots are folded or cleared according to the history
   const int64_t always_words = (int64_t)(wl.update_block_bytes / 4), tot0_words = (int64_t)(wl.tot0_slot_bytes / 4);
   const size_t clear_words = (size_t)always_words * n_updates;
   size_t blocks = (clear_words + 255) / 256;
