@@ -433,6 +433,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         __builtin_amdgcn_sched_barrier(0);
+        // Half-way through the step the tile of step v + 2 goes from registers to LDS: its loads were issued a
+        // step and a half ago, and the LDS writes complete under the rest of the step instead of in front of the
+        // barrier. (This buffer held this step's tile, whose MFMAs ran before the previous barrier: it is free.)
+        if (j == 4) store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);
         mfma_slice<true>(j, kf[j], qf, b);
         exps(j);
         // the sums are pinned here: without an anchor the compiler sinks the exponentials of all eight slices past
@@ -441,9 +445,6 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    // this buffer held this step's tile, whose MFMAs ran before the previous barrier: it is free for tile v + 2,
-    // whose load was issued one step ago
-    store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);
     if (fetch_q) store_q_part<RS, KS>(qbuf, qnext, q_part);   // every wavefront has this layer's Q in registers
     lds_barrier();
     if (!last) {
@@ -726,6 +727,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
         __builtin_amdgcn_sched_barrier(0);
         const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
         const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
+        if (j == 4) store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2 (see the statistics kernel)
         mfma_slice<false>(j, kfj, qf, b);
         if (live) exps(j, lz);
         // pinned here (see the statistics kernel)
@@ -743,7 +745,6 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
       col = __uint_as_float(halves[0]) + __uint_as_float(halves[1]);   // rows 0-3 mod 8 first
     }
     if (lane < 32) part[rs * kPartStride + wave_row0 + lane] = col;
-    store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2, issued one step ago
     if (fetch_q) store_q_part<RS, KS>(qbuf, qnext, q_part);    // every wavefront has this layer's Q in registers
     if (fetch_lse) lse_s[(li + 1) & 1][tid] = lse_next;
     lds_barrier();
