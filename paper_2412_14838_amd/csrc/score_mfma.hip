@@ -727,7 +727,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
         __builtin_amdgcn_sched_barrier(0);
         const float4 lz_next = rows_of_slice(lse_cur, rs, (j + 1) & 7);
         const bf16x8 kf_ahead = read_k_frag(next_tile, (j + 1) & 7);
-        if (j == 4) store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2 (see the statistics kernel)
+        if (j == 2) store_tile<RS, KS>(tiles + kBuf * TL::kTileBytes, ld[kBuf]);   // the tile of step v + 2 (see the statistics kernel; measured best here)
         mfma_slice<false>(j, kfj, qf, b);
         if (live) exps(j, lz);
         // pinned here (see the statistics kernel)
