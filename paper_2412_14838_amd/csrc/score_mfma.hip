@@ -353,6 +353,10 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   // for two steps (one step is shorter than the memory latency under load), so there are two register sets:
   // the set of tile u is ld[u & 1].
   typename PieceVec<TL::kPieces>::type ld[2];
+  // the K pointer of the layer whose tiles are being fetched stays in scalar registers from step to step (reading it
+  // from the kernel argument in every step makes every step begin with a wait)
+  int k_layer;
+  const char* k_ptr;
   {
     const typename PieceVec<TL::kPieces>::type reg0 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, 0, len - 1);
     const typename PieceVec<QS::kPieces>::type q0 = load_q_pieces<RS, KS>(src.q[0] + q_off, p.rows);
@@ -360,6 +364,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
     int l2, t2;
     stream_tile(0, 2, n_steps, n_layers, l2, t2);
     ld[0] = load_tile<RS, KS>(src.k[l2] + k_off, stride_b, t2 * TL::kKeys, len - 1);   // stored by the first step
+    k_layer = l2;
+    k_ptr = src.k[l2] + k_off;
     store_tile<RS, KS>(tiles, reg0);
     store_q_pieces<RS, KS>(qbuf, q0);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
@@ -391,7 +397,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
     if (fetch_q) qnext = load_q_part<RS, KS>(src.q[li + 1] + q_off, p.rows, q_part);
     int la, ta;                                     // tile v + 3: issued now, stored to LDS at the end of the next step
     stream_tile(li, it + 3, n_steps, n_layers, la, ta);
-    ld[kBuf ^ 1] = load_tile<RS, KS>(src.k[la] + k_off, stride_b, ta * TL::kKeys, len - 1);
+    if (la != k_layer) {
+      k_layer = la;
+      k_ptr = src.k[la] + k_off;
+    }
+    ld[kBuf ^ 1] = load_tile<RS, KS>(k_ptr, stride_b, ta * TL::kKeys, len - 1);
     const int wave_row0 = it * TL::kKeys + ks * 32;
     if (wave_row0 + 32 > lim_all) {                        // touches the window or runs past the chunk
       const int kb = wave_row0 + 4 * (lane >> 5);          // + 8 * (j / 4) + j % 4
@@ -645,6 +655,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
   // the set of the tile of step u is ld[u & 1].
   typename PieceVec<TL::kPieces>::type ld[2];
   bf16x8 qf[2][8];
+  int k_layer;                    // layer and K pointer of the tiles being fetched (see the statistics kernel)
+  const char* k_ptr;
   {
     const typename PieceVec<TL::kPieces>::type reg0 = load_tile<RS, KS>(src.k[0] + k_off, stride_b, emit_tile(n_iter, 0) * TL::kKeys, len - 1);
     typename PieceVec<QS::kPieces>::type q0;
@@ -654,6 +666,8 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     int l2, t2;
     stream_tile(0, 2, n_steps, n_layers, l2, t2);
     ld[0] = load_tile<RS, KS>(src.k[l2] + k_off, stride_b, emit_tile(n_iter, t2) * TL::kKeys, len - 1);   // stored by the first step
+    k_layer = l2;
+    k_ptr = src.k[l2] + k_off;
     store_tile<RS, KS>(tiles, reg0);
     if (QS::kEmitViaLds) store_q_pieces<RS, KS>(qbuf, q0);
     store_tile<RS, KS>(tiles + TL::kTileBytes, reg1);
@@ -699,7 +713,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
     if (fetch_lse) lse_next = lse_row[(li + 1) * lse_rows_stride_layer];
     int la, ta;                                                // tile v + 3: issued now, stored to LDS at the end of the next step
     stream_tile(li, it + 3, n_steps, n_layers, la, ta);
-    ld[kBuf ^ 1] = load_tile<RS, KS>(src.k[la] + k_off, stride_b, emit_tile(n_iter, ta) * TL::kKeys, len - 1);
+    if (la != k_layer) {
+      k_layer = la;
+      k_ptr = src.k[la] + k_off;
+    }
+    ld[kBuf ^ 1] = load_tile<RS, KS>(k_ptr, stride_b, emit_tile(n_iter, ta) * TL::kKeys, len - 1);
     const float* __restrict__ lse_cur = lse_s[li & 1];
     const int wave_row0 = emit_tile(n_iter, it) * TL::kKeys + ks * 32;
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
