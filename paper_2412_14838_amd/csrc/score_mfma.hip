@@ -250,6 +250,32 @@ __device__ inline float4 rows_of_slice(const float* __restrict__ row_val, int rs
 // sequence; also returns the number of chunks of (length) items in the earlier sequences (first_full) and in
 // this one (n_full): the statistics kernel cuts all S keys, the emit kernel the S' prefix outputs.
 // A single sequence spans [0, total_tokens) (cu_seqlens[0] = 0, cu_seqlens[1] = total_tokens): nothing is read.
+// The host sizes the grid of the score kernels for `chunk` keys per workgroup from the token total alone (it does
+// not see the lengths, so it allows every sequence a ragged tail): grid_x = total / chunk + n_seqs. With the lengths
+// at hand a shorter chunk often fits the same grid, and the longest chunk sets the kernel's time: every kernel of a
+// score call starts by finding the shortest multiple of the tile (down to half the host's chunk) whose chunks, over
+// all sequences, still fit grid_x - the same value in every workgroup and kernel of the call.
+constexpr int kFitMaxSeqs = 32;       // beyond that the search would cost more than it saves
+__device__ inline int fitted_chunk(const int32_t* __restrict__ cu, int n_seqs, int chunk, int tile, int grid_x) {
+  if (n_seqs == 1 || n_seqs > kFitMaxSeqs) return chunk;
+  // lane t of every wavefront tries chunk - t * tile (at most chunk / (2 * tile) <= 32 candidates); fewer keys per
+  // chunk mean more chunks, so the feasible candidates are the first ones
+  const int c = chunk - (int)(threadIdx.x & 63) * tile;
+  bool ok = c >= kMfmaMinChunk && 2 * c >= chunk;
+  if (ok) {
+    int n = 0, begin = cu[0];
+    for (int s = 0; s < n_seqs; ++s) {
+      const int end = cu[s + 1];
+      n += (end - begin + c - 1) / c;
+      begin = end;
+    }
+    ok = n <= grid_x;
+  }
+  const unsigned long long feasible = __ballot(ok) | 1ull;           // the host's own chunk always fits
+  const int first_bad = ~feasible == 0ull ? 64 : __ffsll((long long)~feasible) - 1;
+  return chunk - (first_bad - 1) * tile;
+}
+
 __device__ inline bool find_chunk2(const int32_t* __restrict__ cu, int n_seqs, int total_tokens, int chunk,
                                    int window_off, int b, int& seq, int& c, int& nc, int& seq_begin, int& seq_len,
                                    int& first_full, int& n_full) {
@@ -329,6 +355,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_stats_mfma(Params p, int c
   char* qbuf = smem + 2 * TL::kTileBytes;                                      // Q staging
   float2* stat = reinterpret_cast<float2*>(smem + 2 * TL::kTileBytes + QS::kBytes);   // [KS][RS * 64]
 
+  chunk = fitted_chunk(cu, p.n_seqs, chunk, TL::kKeys, gridDim.x);
   int seq, c, nc, begin, S, first_full, n_full;
   if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, 0, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   const int head = blockIdx.y;
@@ -559,13 +586,15 @@ __device__ inline float combine_groups(const float2* __restrict__ mstage, int ro
 // sweeps. grid = (n_seqs, Hkv, n_layers), RS * KS * 64 threads. Inside the emit kernel this merge would sit on
 // the critical path of every layer (a chain of dependent loads per thread, 32 deep for 64 chunks).
 template <int RS, int KS>
-__global__ __launch_bounds__(RS * KS * 64) void score_merge_mfma(Params p, int chunk, const int32_t* __restrict__ cu,
+__global__ __launch_bounds__(RS * KS * 64) void score_merge_mfma(Params p, int chunk, int grid_x,
+                                                                 const int32_t* __restrict__ cu,
                                                                  const float* __restrict__ partials,
                                                                  int64_t partials_stride_layer,
                                                                  float* __restrict__ lse_rows) {
   constexpr int kRows = RS * 64;
   __shared__ float2 mstage[KS * kRows];
   const int seq = blockIdx.x, head = blockIdx.y, layer = blockIdx.z;
+  chunk = fitted_chunk(cu, p.n_seqs, chunk, Tile<RS, KS>::kKeys, grid_x);      // as the statistics kernel cut the keys
   int first_full = 0;
   for (int q = 0; q < seq; ++q) first_full += (cu[q + 1] - cu[q] + chunk - 1) / chunk;
   const int n_full = (cu[seq + 1] - cu[seq] + chunk - 1) / chunk;
@@ -613,6 +642,7 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
                                                                 int64_t edges_stride_layer) {
   using TL = Tile<RS, KS>;
   using QS = QStage<RS, KS>;
+  chunk = fitted_chunk(cu, p.n_seqs, chunk, TL::kKeys, gridDim.x);             // not longer than the host's: the LDS fits
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* tiles = smem;                                                          // 2 x kTileBytes
   float* part = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);           // [emit_slabs][kPartStride]
@@ -819,10 +849,11 @@ __global__ __launch_bounds__(RS * KS * 64) void score_emit_mfma(Params p, int ch
 // pooling window reaches (a maximum is exact, so the result is the one the halo variant computes).
 // grid = (chunk upper bound, Hkv, layers), 64 threads: one workgroup per border, thread t < half the output
 // half - t before it, thread half + u the output u after it.
-__global__ __launch_bounds__(64) void score_fix_borders(Params p, int chunk, const int32_t* __restrict__ cu,
+__global__ __launch_bounds__(64) void score_fix_borders(Params p, int chunk, int tile, const int32_t* __restrict__ cu,
                                                         const float* __restrict__ edges, int64_t edges_stride_layer,
                                                         float* __restrict__ scores, int64_t scores_stride_head,
                                                         int64_t scores_stride_layer) {
+  chunk = fitted_chunk(cu, p.n_seqs, chunk, tile, gridDim.x);  // as the emit kernel cut the outputs
   int seq, c, nc, begin, S, first_full, n_full;
   if (!find_chunk2(cu, p.n_seqs, p.total_tokens, chunk, p.w, blockIdx.x, seq, c, nc, begin, S, first_full, n_full)) return;
   if (c == nc - 1) return;                                     // no chunk behind the last one
@@ -850,9 +881,11 @@ __global__ __launch_bounds__(64) void score_fix_borders(Params p, int chunk, con
 
 // Natural-log row normalisers from the chunk partials of the statistics kernel (log2 domain):
 // lse_out[(seq * Hq + head * G) * w + r]. grid = (n_seqs, Hkv), 256 threads.
-__global__ __launch_bounds__(256) void score_lse_mfma(Params p, int chunk, const int32_t* __restrict__ cu,
+__global__ __launch_bounds__(256) void score_lse_mfma(Params p, int chunk, int tile, int grid_x,
+                                                      const int32_t* __restrict__ cu,
                                                       const float* __restrict__ partials, float* __restrict__ lse_out) {
   const int seq = blockIdx.x, head = blockIdx.y;
+  chunk = fitted_chunk(cu, p.n_seqs, chunk, tile, grid_x);     // as the statistics kernel cut the keys
   int first_full = 0;
   for (int q = 0; q < seq; ++q) first_full += (cu[q + 1] - cu[q] + chunk - 1) / chunk;
   const int n_full = (cu[seq + 1] - cu[seq] + chunk - 1) / chunk;
@@ -965,7 +998,7 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
         launch(DKV_KERNEL_SCORE_MERGE, score_import_lse, dim3(p.n_seqs, p.Hkv, n_layers), dim3(256), 0, st, p, in, lse_rows);
       } else {
         launch(DKV_KERNEL_SCORE_MERGE, (score_merge_mfma<RS, KS>), dim3(p.n_seqs, p.Hkv, n_layers), dim3(TL::kThreads), 0, st,
-               p, chunk, cu, static_cast<const float*>(partials), partials_stride_layer, lse_rows);
+               p, chunk, grid_x, cu, static_cast<const float*>(partials), partials_stride_layer, lse_rows);
       }
     } else if (lse_layers != nullptr) {
       lse_in = lse_layers[0];
@@ -979,12 +1012,14 @@ static hipError_t launch_mfma_t(const Params& p, int phases, int n_layers, const
            lse_rows ? static_cast<const float*>(lse_rows) + last * lse_rows_stride_layer : nullptr, -lse_rows_stride_layer,
            lse_in, scores + last * scores_stride_layer, scores_stride_head, -scores_stride_layer, edges, edges_stride_layer);
     if (edges != nullptr)
-      launch(DKV_KERNEL_SCORE_BORDERS, score_fix_borders, dim3(grid_x, p.Hkv, n_layers), dim3(64), 0, st, p, chunk, cu,
+      launch(DKV_KERNEL_SCORE_BORDERS, score_fix_borders, dim3(grid_x, p.Hkv, n_layers), dim3(64), 0, st, p, chunk,
+             (int)TL::kKeys, cu,
              static_cast<const float*>(edges), edges_stride_layer, scores + last * scores_stride_layer, scores_stride_head,
              -scores_stride_layer);
   }
   if (phases & kPhaseLse)
-    launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, cu, partials, lse_out);
+    launch(DKV_KERNEL_SCORE_LSE, score_lse_mfma, dim3(p.n_seqs, p.Hkv), dim3(256), 0, st, p, chunk, (int)TL::kKeys, grid_x, cu,
+           partials, lse_out);
   return hipGetLastError();
 }
 
