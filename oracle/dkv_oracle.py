@@ -242,6 +242,88 @@ def update_buffer_length(A_list: Sequence[np.ndarray], layer_max: int, mean_budg
 
 
 # --------------------------------------------------------------------------
+# Fixed-pattern budget schedules: the comparison methods of Section 5.1 ("Baselines") and Figure 1 (b), (c),
+# as alternative producers of the per-layer retained counts.  The paper names them in one sentence each and
+# gives no formula, so each function states the reading it implements.
+# --------------------------------------------------------------------------
+def fixed_layer_budgets(L: int, mean_budget: int) -> np.ndarray:
+    """Figure 1 (b): the same cache size in every layer, Z'_i = wt - ws.
+
+    With Eq. 1-3 as the selection this is the SnapKV-style baseline: every layer keeps the top (wt - ws)
+    prefix positions per KV head and no update ever runs.
+    """
+    return np.full(L, int(mean_budget), dtype=np.int64)
+
+
+def pyramid_layer_budgets(L: int, mean_budget: int, layer_max: int, beta: int = 4) -> np.ndarray:
+    """Figure 1 (c): retention that decreases monotonically with depth (the PyramidKV-style baseline).
+
+    Reading: a straight line from `hi` rows at layer 0 to `lo` rows at layer L - 1 whose mean is the
+    mean budget: lo = floor(mean_budget / beta), hi = 2 * mean_budget - lo, and if hi exceeds the
+    per-layer maximum B^l it is lowered to B^l and lo raised by the same amount.  Layer i gets
+    floor(((L - 1 - i) * hi + i * lo) / (L - 1)) (exact integers); L = 1 gets the mean budget.
+    The sum is at most B = (wt - ws) * L and misses it by less than L.
+    """
+    assert L >= 1 and beta >= 1
+    if L == 1:
+        return np.array([int(mean_budget)], dtype=np.int64)
+    lo = int(mean_budget) // int(beta)
+    hi = 2 * int(mean_budget) - lo
+    if hi > layer_max:
+        lo += hi - int(layer_max)
+        hi = int(layer_max)
+    return np.array([((L - 1 - i) * hi + i * lo) // (L - 1) for i in range(L)], dtype=np.int64)
+
+
+def recent_indices(prefix_len: int, budget: int, n_sink: int) -> np.ndarray:
+    """StreamingLLM-style retention of one row of `prefix_len` candidate positions: the first n_sink positions
+    (the attention sinks) and the most recent ones, budget positions in all (k = min(budget, prefix_len)).
+
+    Order: the sinks in position order, then the recent positions from the newest to the oldest, so that
+    keeping the first n entries of the list is again "sinks + the most recent" (the truncation rule of
+    Algorithm 1 applies to this list unchanged).  No scores are involved; the window itself is always kept.
+    """
+    k = min(int(budget), int(prefix_len))
+    sinks = min(int(n_sink), k)
+    recent = k - sinks
+    return np.concatenate([np.arange(sinks), prefix_len - 1 - np.arange(recent)]).astype(np.int32)
+
+
+def apply_layer_budgets(n: Sequence[int], budgets: Sequence[int]) -> List[int]:
+    """The truncation loop of Algorithm 1 with preset budgets: n_i <- min(n_i, budgets_i)."""
+    return [min(int(a), int(b)) for a, b in zip(n, budgets)]
+
+
+def compress_fixed_pattern(layers, L: int, w: int, P: int, layer_max: int, budgets: Sequence[int],
+                           scale: Optional[float] = None, row_scale: float = 1.0, keep_buffers: bool = True,
+                           scores_override: Optional[Sequence[np.ndarray]] = None,
+                           n_sink: Optional[int] = None) -> "Compressed":
+    """The layer loop of Algorithm 1 with a preset schedule instead of the progressive update: every layer is
+    scored and selected as in Eq. 1-3 (k = min(B^l, S')), then truncated to budgets[l].  With n_sink given the
+    candidates come from recent_indices (no scoring) instead of the top-k.
+    """
+    out = Compressed()
+    for l, (q_win, k, v) in enumerate(layers, start=1):
+        if n_sink is None:
+            A = (np.asarray(scores_override[l - 1], dtype=np.float32) if scores_override is not None
+                 else score_window(q_win, k, P, scale, row_scale))
+            idx = select_topk(A, layer_max)
+        else:
+            Hkv, S = k.shape[0], k.shape[1]
+            A = np.zeros((Hkv, S - w), dtype=np.float32)
+            idx = np.tile(recent_indices(S - w, layer_max, n_sink), (Hkv, 1))
+        out.A.append(A)
+        out.idx.append(idx)
+        out.n.append(idx.shape[1])
+        if keep_buffers:
+            kb, vb = gather_kv(k, v, idx, w)
+            out.kb.append(kb)
+            out.vb.append(vb)
+    out.n = apply_layer_budgets(out.n, budgets)
+    return out
+
+
+# --------------------------------------------------------------------------
 # Algorithm 1, the whole prefill loop for one sequence
 # --------------------------------------------------------------------------
 class Compressed:

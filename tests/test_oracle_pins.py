@@ -290,6 +290,109 @@ def test_scores_override_isolates_selection():
     assert r.n == r2.n and all(np.array_equal(a, b) for a, b in zip(r.idx, r2.idx))
 
 
+def _hand_case_for_the_final_cache():
+    """Two layers, two KV heads, S = 10, ws = 2 (prefix 8), B^l = 4, mean budget 3, one update after layer 2.
+    Key row (layer l, head h, position s) = [100 l + 10 h + s, -(100 l + 10 h + s)], value = key + 0.5, so every
+    cache row names where it came from.  Scores are supplied, so that everything below follows by hand."""
+    L, Hkv, S, w, d = 2, 2, 10, 2, 2
+    layers = []
+    for l in range(L):
+        base = (100 * l + 10 * np.arange(Hkv)[:, None] + np.arange(S)[None, :]).astype(np.float64)
+        k = np.stack([base, -base], axis=-1)
+        layers.append((None, k, k + 0.5))
+    A = [np.array([[.90, .10, .80, .20, .70, .30, .60, .05],      # layer 1 head 0: order 0, 2, 4, 6
+                   [.15, .95, .25, .85, .35, .75, .45, .65]],     #         head 1: order 1, 3, 5, 7
+                  dtype=np.float32),
+         np.array([[.01, .91, .02, .81, .03, .04, .05, .06],      # layer 2 head 0: order 1, 3, 7, 6
+                   [.71, .07, .61, .08, .09, .11, .12, .13]],     #         head 1: order 0, 2, 7, 6
+                  dtype=np.float32)]
+    return layers, A, dict(L=L, w=w, P=1, layer_max=4, mean_budget=3, interval=2)
+
+
+def test_final_cache_rows_of_a_hand_worked_case():
+    """Algorithm 1, last line, after the truncation lines: K^c_l = the first n_l buffer rows, then the ws window
+    rows.  By hand: kg = 3 * 2 * 2 = 12; the 12 largest of the 32 scores are .95 .91 .90 .85 .81 .80 .75 .71 .70
+    .65 .61 .60, eight of them in layer 1 and four in layer 2: cnt = [8, 4]; Z = [4 * 8 / 8, 4 * 4 / 8] = [4, 2];
+    sum Z = 6 = B, so Z' = [4, 2] and n = [4, 2]: layer 2 keeps only the first TWO of its four selected rows."""
+    layers, A, kw = _hand_case_for_the_final_cache()
+    r = O.compress(layers, scores_override=A, **kw)
+    assert r.budgets[0][1].tolist() == [8, 4] and r.budgets[0][3].tolist() == [4, 2] and r.n == [4, 2]
+    assert r.idx[1].tolist() == [[1, 3, 7, 6], [0, 2, 7, 6]]
+    kc0, vc0 = r.cache(0, kw["w"])
+    kc1, vc1 = r.cache(1, kw["w"])
+    # layer 1 (index 0): all four selected rows of each head, then the window rows 8 and 9
+    assert kc0[:, :, 0].tolist() == [[0, 2, 4, 6, 8, 9], [11, 13, 15, 17, 18, 19]]
+    # layer 2 (index 1): rows 1, 3 (head 0) and 0, 2 (head 1) survive the update, then the window rows
+    assert kc1[:, :, 0].tolist() == [[101, 103, 108, 109], [110, 112, 118, 119]]
+    for kc, vc in ((kc0, vc0), (kc1, vc1)):
+        assert np.array_equal(kc[:, :, 1], -kc[:, :, 0]) and np.array_equal(vc, kc + 0.5)
+
+
+# ---------------------------------------------------------------- fixed-pattern schedules (Section 5.1, Figure 1)
+def _schedule_rows(kind):
+    with open(os.path.join(GOLDEN, "schedule_examples.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line.startswith(kind + " "):
+                left, right = line[len(kind):].split("|")
+                yield [int(x) for x in left.split()], [int(x) for x in right.split()]
+
+
+def test_schedules_against_hand_worked_rows():
+    rows = list(_schedule_rows("pyramid"))
+    assert len(rows) >= 5
+    for (L, mean, layer_max, beta), want in rows:
+        assert O.pyramid_layer_budgets(L, mean, layer_max, beta).tolist() == want
+    for (L, mean), want in _schedule_rows("fixed"):
+        assert O.fixed_layer_budgets(L, mean).tolist() == want
+    rows = list(_schedule_rows("recent"))
+    assert len(rows) >= 5
+    for (prefix, budget, n_sink), want in rows:
+        assert O.recent_indices(prefix, budget, n_sink).tolist() == want
+
+
+def test_pyramid_schedule_invariants():
+    """Monotone non-increasing, first layer hi and last layer lo exactly, every layer within B^l, and the sum
+    within L of the global budget B = mean * L from below (the straight line has mean exactly `mean`)."""
+    for L, mean, layer_max, beta in ((32, 512, 2048, 4), (28, 64, 256, 4), (32, 128, 150, 8), (5, 7, 9, 3), (2, 1, 1, 2)):
+        z = O.pyramid_layer_budgets(L, mean, layer_max, beta)
+        lo = mean // beta
+        hi = 2 * mean - lo
+        if hi > layer_max:
+            lo, hi = lo + hi - layer_max, layer_max
+        assert (np.diff(z) <= 0).all() and z[0] == hi and z[-1] == lo and z.max() <= layer_max and z.min() >= 0
+        assert mean * L - L < z.sum() <= mean * L
+        # the exact line, in rationals
+        assert z.tolist() == [int(Fraction((L - 1 - i) * hi + i * lo, L - 1)) for i in range(L)]
+
+
+def test_fixed_pattern_loop_is_per_layer_topk_cut_to_the_schedule():
+    """With the fixed schedule the loop is Eq. 1-3 with k = the mean budget in every layer (brute-force sort);
+    with any schedule n_l = min(B^l, S', budgets_l) and the retained list is a prefix of the B^l list."""
+    cfg = W.standard_configs()["tiny"]
+    S, w = cfg.seqlens[0], cfg.w
+    fixed = O.fixed_layer_budgets(cfg.L, cfg.mean_budget)
+    r = O.compress_fixed_pattern(_layers(cfg), cfg.L, w, cfg.P, cfg.layer_max, fixed)
+    assert r.n == [cfg.mean_budget] * cfg.L and r.budgets == []
+    for l, (q, k, v) in enumerate(_layers(cfg)):
+        A = O.score_window(q, k, cfg.P)
+        for h in range(cfg.Hkv):
+            brute = sorted(range(S - w), key=lambda s: (-float(A[h, s]), s))[:cfg.mean_budget]
+            assert r.idx[l][h][:r.n[l]].tolist() == brute
+        kc, vc = r.cache(l, w)
+        assert kc.shape[1] == cfg.mean_budget + w and np.array_equal(kc[:, -w:], k[:, S - w:])
+    pyr = O.pyramid_layer_budgets(cfg.L, cfg.mean_budget, cfg.layer_max, 4)
+    r2 = O.compress_fixed_pattern(_layers(cfg), cfg.L, w, cfg.P, cfg.layer_max, pyr)
+    assert r2.n == [min(cfg.layer_max, S - w, int(b)) for b in pyr]
+    assert all(np.array_equal(a, b) for a, b in zip(r.idx, r2.idx))
+    # the recency pattern: no scores, sinks + newest prefix rows, the window rows behind them
+    r3 = O.compress_fixed_pattern(_layers(cfg), cfg.L, w, cfg.P, cfg.layer_max, fixed, n_sink=4)
+    kc, _ = r3.cache(0, w)
+    k0 = next(iter(_layers(cfg)))[1]
+    want = list(range(4)) + list(range(S - w - 1, S - w - 1 - (cfg.mean_budget - 4), -1)) + list(range(S - w, S))
+    assert np.array_equal(kc, k0[:, want])
+
+
 # ---------------------------------------------------------------- Eq. 1 with supplied row normalisers
 def test_row_lse_matches_library_logsumexp_and_closed_form():
     """lse[g, i] = log of the denominator of Eq. 1 over the keys the row may see: torch.logsumexp on the masked
@@ -433,3 +536,28 @@ def test_pins_catch_planted_mistakes(monkeypatch):
     monkeypatch.setattr(O, "budgets_from_counts", rounded)
     assert fails(test_budget_formulas_against_hand_worked_rows)
     monkeypatch.setattr(O, "budgets_from_counts", orig_b)
+
+    orig_cache = O.Compressed.cache
+
+    def window_from_the_wrong_end(self, layer, w):      # the first w buffer rows instead of the last w
+        n = self.n[layer]
+        kb, vb = self.kb[layer], self.vb[layer]
+        return np.concatenate([kb[:, :n], kb[:, :w]], axis=1), np.concatenate([vb[:, :n], vb[:, :w]], axis=1)
+
+    monkeypatch.setattr(O.Compressed, "cache", window_from_the_wrong_end)
+    assert fails(test_final_cache_rows_of_a_hand_worked_case)
+    monkeypatch.setattr(O.Compressed, "cache", lambda self, layer, w: tuple(
+        np.concatenate([b[:, :b.shape[1] - w], b[:, b.shape[1] - w:]], axis=1) for b in (self.kb[layer], self.vb[layer])))
+    assert fails(test_final_cache_rows_of_a_hand_worked_case)       # no truncation to n_l
+    monkeypatch.setattr(O.Compressed, "cache", orig_cache)
+
+    orig_pyr = O.pyramid_layer_budgets
+    monkeypatch.setattr(O, "pyramid_layer_budgets", lambda L, m, lm, beta=4: orig_pyr(L, m, lm, beta)[::-1].copy())
+    assert fails(test_schedules_against_hand_worked_rows) and fails(test_pyramid_schedule_invariants)
+    monkeypatch.setattr(O, "pyramid_layer_budgets", lambda L, m, lm, beta=4: np.minimum(orig_pyr(L, m, 10**9, beta), lm))
+    assert fails(test_schedules_against_hand_worked_rows)           # a cap without moving the excess to lo
+    monkeypatch.setattr(O, "pyramid_layer_budgets", orig_pyr)
+    orig_recent = O.recent_indices
+    monkeypatch.setattr(O, "recent_indices", lambda p, b, s: np.sort(orig_recent(p, b, s)))
+    assert fails(test_schedules_against_hand_worked_rows)           # position order instead of newest first
+    monkeypatch.setattr(O, "recent_indices", orig_recent)
