@@ -49,6 +49,7 @@ enum {
 #define DKV_MAX_ROWS 256       /* G * window: score rows per KV head         */
 #define DKV_MAX_SEQS 4096
 #define DKV_MAX_LAYERS 512
+#define DKV_MAX_KV_HEADS 1024      /* KV heads (a grid dimension of every stage) */
 #define DKV_MAX_DECODE_GROUP 16   /* query heads per KV head dkv_decode_attention handles */
 #define DKV_MAX_SELECT_LAYERS 32  /* layers one dkv_*_layers call may cover */
 #define DKV_MAX_UPDATES 8         /* progressive updates per dkv_rebalance_batch call */
@@ -87,7 +88,8 @@ enum {
   DKV_KERNEL_PACK = 10,           /* tight packing of the final cache                 */
   DKV_KERNEL_DECODE = 11,         /* decode attention over the compressed cache       */
   DKV_KERNEL_SCORE_MERGE = 12,    /* row normalisers of a multi-layer scoring call    */
-  DKV_KERNEL_REBALANCE_PICK = 13  /* digits of the updates' thresholds, between the scans */
+  DKV_KERNEL_REBALANCE_PICK = 13, /* digits of the updates' thresholds, between the scans */
+  DKV_KERNEL_SCHEDULE = 14        /* fixed-pattern schedules: preset budgets, recency candidates */
 };
 
 /* Library version (DKV_VERSION it was built with). Host only. */
@@ -98,8 +100,17 @@ const char* dkv_status_string(int status);
 
 /* Bytes of device workspace the stage calls need for this descriptor (0 if the descriptor is invalid).
  * Host only, launches nothing. The workspace must be 256-byte aligned; it needs no initialisation and carries
- * nothing from one stage call to the next, except from dkv_score_window_stats to dkv_score_window_emit. */
+ * nothing from one stage call to the next, except from dkv_score_window_stats to dkv_score_window_emit and, when
+ * the caller asks for it with a non-zero epoch, from one dkv_rebalance call of a prefill to the next. */
 size_t dkv_workspace_bytes(const dkv_desc* desc);
+
+/*
+ * Which kernels a scoring call (Eq. 1-2) with this descriptor and key token stride (elements) runs on: 1 = the bf16
+ * matrix-core kernels (bf16, head_dim 128, and a token stride short enough for their 32-bit row offsets: at most
+ * about 485 000 elements), 0 = the vector-ALU kernels (everything else the library accepts), negative = a status.
+ * Host only, launches nothing.
+ */
+int dkv_score_path(const dkv_desc* desc, int64_t k_stride_token);
 
 /*
  * Per-kernel timing (a measurement aid, not part of the method). Between dkv_profile_begin(capacity) and
@@ -239,14 +250,17 @@ int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_
  * counts       int32 [n_seqs][L], updated in place for layers < l.
  * budgets_out  int32 [n_seqs][L]: Z' for layers < l (others untouched). May be NULL.
  * hits_out     int32 [n_seqs][L]: cnt for layers < l. May be NULL.
- * A layer's scores do not change once written, so the call keeps a histogram of the layers it has scanned in the
- * workspace and the next call of the same prefill (layers_done + interval, same scores_all, same workspace)
- * extends it instead of recounting; a call with any other history, and every call with layers_done == interval,
- * recounts from scratch. Hence: do not rewrite the scores of layers < l between the calls of one prefill, and
- * do not share one workspace between prefills that are in flight together.
+ * epoch        names the prefill this call belongs to. 0: the call scans all layers [0, l) and leaves nothing behind.
+ *              Non-zero: within one prefill a layer's scores do not change once written, so the call leaves a
+ *              histogram of the layers it has scanned in the workspace, and the next call with the SAME epoch,
+ *              layers_done + interval, the same scores_all and the same workspace extends it instead of
+ *              recounting. A call whose epoch, predecessor or tensors differ, and every call with
+ *              layers_done == interval, recounts from scratch. The caller's side of the contract: give every
+ *              prefill its own epoch (a counter will do), do not rewrite the scores of layers < l between the
+ *              calls of one epoch, and do not share one workspace between prefills that are in flight together.
  */
-int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
-                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
+int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, uint32_t epoch, const float* scores_all,
+                  const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
                   size_t workspace_bytes, void* stream);
 
 /*
@@ -259,11 +273,12 @@ int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores
  * n_updates          1 .. DKV_MAX_UPDATES; layers_done + (n_updates - 1) * interval <= L.
  * budgets_out, hits_out   as for dkv_rebalance, one [n_seqs][L] block per update: update u writes at
  *                    out + u * out_stride_update (ints; >= n_seqs * L when n_updates > 1). May be NULL.
- * The history rule of dkv_rebalance applies with the last update's layers_done.
+ * The epoch rule of dkv_rebalance applies with the last update's layers_done.
  */
-int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, const float* scores_all,
-                        const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
-                        int64_t out_stride_update, void* workspace, size_t workspace_bytes, void* stream);
+int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, uint32_t epoch,
+                        const float* scores_all, const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out,
+                        int32_t* hits_out, int64_t out_stride_update, void* workspace, size_t workspace_bytes,
+                        void* stream);
 
 /*
  * Compaction of the retained K/V rows of layer index `layer` (Algorithm 1, the two cat(gather(...), window) lines).
@@ -336,6 +351,42 @@ int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_
 int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new, const void* kb, const void* vb,
                          int64_t stride_seq, int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts,
                          float* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Fixed-pattern schedules: the comparison methods of Section 5.1 ("Baselines") and Figure 1 (b), (c) as alternative
+ * producers of `counts`, through the same scoring, selection and compaction calls. The paper names the patterns
+ * and gives no formulas; the readings:
+ *   DKV_SCHEDULE_FIXED    Figure 1 (b): every layer keeps mean_budget rows per KV head (with Eq. 1-3 as the
+ *                         selection this is the SnapKV-style baseline; no update ever runs).
+ *   DKV_SCHEDULE_PYRAMID  Figure 1 (c): retention falls with depth along a straight line from hi rows (layer 0) to
+ *                         lo rows (layer L-1), lo = floor(mean_budget / beta), hi = 2 * mean_budget - lo; a hi above
+ *                         layer_max is lowered to layer_max and lo raised by the same amount. Layer i gets
+ *                         floor(((L-1-i) * hi + i * lo) / (L-1)); L = 1 gets mean_budget. The sum is at most
+ *                         mean_budget * L and misses it by less than L.
+ * dkv_layer_budgets   HOST only, launches nothing: writes the L budgets of `schedule` to h_budgets_out (host memory).
+ *                     beta >= 1 (ignored by DKV_SCHEDULE_FIXED).
+ * dkv_apply_budgets   counts[q][i] <- min(counts[q][i], budgets[i]) for i < n_layers and every sequence q: the
+ *                     truncation lines of Algorithm 1 with preset budgets. budgets: DEVICE int32 [n_layers].
+ *                     Negative budgets count as 0. One kernel.
+ * Recipe: per layer dkv_score_window, dkv_select_topk (counts = min(layer_max, S')), dkv_apply_budgets, dkv_gather_kv
+ * (or the *_layers forms); nothing else differs from the DynamicKV loop, which calls dkv_rebalance instead.
+ */
+enum { DKV_SCHEDULE_FIXED = 0, DKV_SCHEDULE_PYRAMID = 1 };
+int dkv_layer_budgets(const dkv_desc* desc, int32_t schedule, int32_t beta, int32_t* h_budgets_out /* host */);
+int dkv_apply_budgets(const dkv_desc* desc, int32_t n_layers, const int32_t* budgets, int32_t* counts, void* stream);
+
+/*
+ * Candidates of the recency pattern (the StreamingLLM-style baseline of Section 5.1: attention sinks plus the most
+ * recent tokens) for layer index `layer`, in place of dkv_score_window + dkv_select_topk: no scores are involved.
+ * For every (sequence, KV head), k = min(layer_max, S'):
+ *     idx_out[q][h][0 .. sinks)   the first sinks = min(n_sink, k) prefix positions, in position order,
+ *     idx_out[q][h][sinks .. k)   the prefix positions S'-1, S'-2, ... (newest first),
+ * so that the first n entries are again "sinks + the n - sinks most recent" and truncation (dkv_apply_budgets)
+ * works as for a score-ordered list; entries >= k are -1; counts[q][layer] = k. The window rows themselves are
+ * always kept by dkv_gather_kv. idx_out int32 [n_seqs][Hkv][layer_max]; n_sink >= 0. One kernel.
+ */
+int dkv_select_recent(const dkv_desc* desc, int32_t layer, int32_t n_sink, const int32_t* cu_seqlens, int32_t* idx_out,
+                      int32_t* counts, void* stream);
 
 #ifdef __cplusplus
 }

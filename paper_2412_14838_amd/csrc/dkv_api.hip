@@ -19,7 +19,7 @@ int validate_desc(const dkv_desc* d) {
   if (d->head_dim != 64 && d->head_dim != 128) return DKV_ERR_UNSUPPORTED;
   if (d->layer_max > DKV_MAX_LAYER_MAX || d->pool_kernel > DKV_MAX_POOL) return DKV_ERR_UNSUPPORTED;
   if ((d->n_q_heads / d->n_kv_heads) * (int64_t)d->window > DKV_MAX_ROWS) return DKV_ERR_UNSUPPORTED;
-  if (d->n_seqs > DKV_MAX_SEQS || d->n_layers > DKV_MAX_LAYERS) return DKV_ERR_UNSUPPORTED;
+  if (d->n_seqs > DKV_MAX_SEQS || d->n_layers > DKV_MAX_LAYERS || d->n_kv_heads > DKV_MAX_KV_HEADS) return DKV_ERR_UNSUPPORTED;
   // 64-bit budget arithmetic must not overflow: layer_max * (L * Hkv * S') and Z * B
   if ((int64_t)d->n_layers * d->n_kv_heads * (int64_t)d->max_seq_len > (int64_t)1 << 31) return DKV_ERR_UNSUPPORTED;
   return DKV_OK;
@@ -106,6 +106,14 @@ int dkv_profile_end(int32_t* kernel_ids_out, float* microseconds_out, int32_t ma
   delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
   g_profile = ProfileSession{};
   return status == DKV_OK ? n : status;
+}
+
+int dkv_score_path(const dkv_desc* desc, int64_t k_stride_token) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  st = check_kv_strides(*desc, k_stride_token, desc->head_dim);
+  if (st != DKV_OK) return st;
+  return score_mfma_supported(make_params(*desc), desc->dtype, k_stride_token) ? 1 : 0;
 }
 
 size_t dkv_workspace_bytes(const dkv_desc* desc) {
@@ -269,9 +277,10 @@ int dkv_select_topk_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 
-int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, const float* scores_all,
-                        const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
-                        int64_t out_stride_update, void* workspace, size_t workspace_bytes, void* stream) {
+int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_updates, uint32_t epoch,
+                        const float* scores_all, const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out,
+                        int32_t* hits_out, int64_t out_stride_update, void* workspace, size_t workspace_bytes,
+                        void* stream) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   if (!scores_all || !cu_seqlens || !counts || !aligned16(scores_all)) return DKV_ERR_INVALID_ARG;
@@ -284,17 +293,17 @@ int dkv_rebalance_batch(const dkv_desc* desc, int32_t layers_done, int32_t n_upd
   st = check_workspace(*desc, workspace, workspace_bytes, wl);
   if (st != DKV_OK) return st;
   const Params p = make_params(*desc);
-  const hipError_t e = launch_rebalance(p, layers_done, n_updates, scores_all, cu_seqlens, counts, budgets_out, hits_out,
+  const hipError_t e = launch_rebalance(p, layers_done, n_updates, epoch, scores_all, cu_seqlens, counts, budgets_out, hits_out,
                                         out_stride_update, static_cast<char*>(workspace), wl,
                                         static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 
-int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, const float* scores_all, const int32_t* cu_seqlens,
-                  int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
+int dkv_rebalance(const dkv_desc* desc, int32_t layers_done, uint32_t epoch, const float* scores_all,
+                  const int32_t* cu_seqlens, int32_t* counts, int32_t* budgets_out, int32_t* hits_out, void* workspace,
                   size_t workspace_bytes, void* stream) {
-  return dkv_rebalance_batch(desc, layers_done, 1, scores_all, cu_seqlens, counts, budgets_out, hits_out, 0, workspace,
-                             workspace_bytes, stream);
+  return dkv_rebalance_batch(desc, layers_done, 1, epoch, scores_all, cu_seqlens, counts, budgets_out, hits_out, 0,
+                             workspace, workspace_bytes, stream);
 }
 
 int dkv_gather_kv(const dkv_desc* desc, int32_t layer, const void* k, const void* v, int64_t stride_token,
@@ -392,6 +401,46 @@ int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new,
   const Params p = make_params(*desc);
   const hipError_t e = launch_decode(p, desc->dtype, layer, q_new, kb, vb, stride_seq, stride_head, cu_seqlens, counts,
                                      out, lse_out, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_layer_budgets(const dkv_desc* desc, int32_t schedule, int32_t beta, int32_t* h_budgets_out) {
+  const int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!h_budgets_out || beta < 1) return DKV_ERR_INVALID_ARG;
+  const int64_t L = desc->n_layers, mean = desc->mean_budget;
+  if (schedule == DKV_SCHEDULE_FIXED || L == 1) {
+    if (schedule != DKV_SCHEDULE_FIXED && schedule != DKV_SCHEDULE_PYRAMID) return DKV_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < L; ++i) h_budgets_out[i] = (int32_t)mean;
+    return DKV_OK;
+  }
+  if (schedule != DKV_SCHEDULE_PYRAMID) return DKV_ERR_INVALID_ARG;
+  int64_t lo = mean / beta, hi = 2 * mean - lo;
+  if (hi > desc->layer_max) {
+    lo += hi - desc->layer_max;
+    hi = desc->layer_max;
+  }
+  for (int64_t i = 0; i < L; ++i) h_budgets_out[i] = (int32_t)(((L - 1 - i) * hi + i * lo) / (L - 1));
+  return DKV_OK;
+}
+
+int dkv_apply_budgets(const dkv_desc* desc, int32_t n_layers, const int32_t* budgets, int32_t* counts, void* stream) {
+  const int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!budgets || !counts || n_layers < 1 || n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_apply_budgets(p, n_layers, budgets, counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_select_recent(const dkv_desc* desc, int32_t layer, int32_t n_sink, const int32_t* cu_seqlens, int32_t* idx_out,
+                      int32_t* counts, void* stream) {
+  const int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!cu_seqlens || !idx_out || !counts || n_sink < 0) return DKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= desc->n_layers) return DKV_ERR_INVALID_ARG;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_select_recent(p, layer, n_sink, cu_seqlens, idx_out, counts, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 

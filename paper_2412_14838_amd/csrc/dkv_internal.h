@@ -30,7 +30,7 @@ struct WorkspaceLayout {
   size_t edges;        // float [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][64] column sums next to the chunk borders of a multi-layer emit launch
   size_t edges_layer_bytes;      // one layer's share of it
   // progressive update: digit histograms summed over layers (tot0 persists from call to call, see header)
-  size_t header;       // int32 [8]                      which layers tot0 covers, and for which score tensor
+  size_t header;       // int32 [16]                     which layers tot0 covers, for which score tensor and prefill epoch
   size_t tot0;         // int32 [DKV_MAX_UPDATES][n_seqs][kRadixBins]  top digit: slot 0 kept from call to call, slot u the layers new to update u
   // per class of updates of a call (updates whose thresholds share the digits found so far see the same elements;
   // a class is named by its first update), DKV_MAX_UPDATES blocks of:
@@ -70,7 +70,7 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   off += w.edges_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
-  w.header = off;   off += align256(8 * sizeof(int32_t));
+  w.header = off;   off += align256(16 * sizeof(int32_t));
   w.tot0_slot_bytes = align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
   w.tot0 = off;     off += w.tot0_slot_bytes * DKV_MAX_UPDATES;
   const size_t block = off;                                                             // tot1 .. above: one class's block
@@ -148,13 +148,17 @@ hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, 
 hipError_t launch_decode(const Params& p, int dtype, int layer, const void* q_new, const void* kb, const void* vb,
                          int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts, float* out,
                          float* lse_out, char* ws, const WorkspaceLayout& wl, hipStream_t st);
-hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, const float* scores_all, const int32_t* cu,
-                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, int64_t out_stride_update,
-                            char* ws, const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, uint32_t epoch, const float* scores_all,
+                            const int32_t* cu, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
+                            int64_t out_stride_update, char* ws, const WorkspaceLayout& wl, hipStream_t st);
 hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers, const void* const* k_layers,
                          const void* const* v_layers, int64_t stride_token, int64_t stride_head, const int32_t* cu,
                          const int32_t* idx, int64_t idx_stride_layer, const int32_t* counts, void* k_out, void* v_out,
                          int64_t out_stride_layer, int64_t out_stride_seq, int64_t out_stride_head, hipStream_t st);
+
+hipError_t launch_apply_budgets(const Params& p, int n_layers, const int32_t* budgets, int32_t* counts, hipStream_t st);
+hipError_t launch_select_recent(const Params& p, int layer, int n_sink, const int32_t* cu, int32_t* idx_out,
+                                int32_t* counts, hipStream_t st);
 
 // ----------------------------------------------------------------------------------------------
 // Device helpers

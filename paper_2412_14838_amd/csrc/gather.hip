@@ -11,9 +11,11 @@ struct GatherSources {
 };
 
 // One workgroup copies ROWS = 256 / LANES row slots of one (layer, sequence, KV head); LANES lanes x 16 bytes = one
-// row. grid = (ceil((w + layer_max) / ROWS), Hkv, n_seqs * layers of the call).
+// row. grid = (slot_blocks * n_seqs * layers of the call, Hkv), slot_blocks = ceil((w + layer_max) / ROWS): the
+// (sequence, layer) pair rides in x, whose range is 2^31, not in z, whose range is 65535.
 template <int LANES>
 __global__ __launch_bounds__(256) void gather_kernel(int w, int layer_max, int L, int layer0, int n_seqs, int row_bytes,
+                                                     int slot_blocks,
                                                      GatherSources src_layers,
                                                      int64_t stride_token_b, int64_t stride_head_b,
                                                      const int32_t* __restrict__ cu, const int32_t* __restrict__ idx0,
@@ -22,14 +24,15 @@ __global__ __launch_bounds__(256) void gather_kernel(int w, int layer_max, int L
                                                      char* __restrict__ v_out0, int64_t out_stride_layer_b,
                                                      int64_t out_stride_seq_b, int64_t out_stride_head_b) {
   constexpr int ROWS = 256 / LANES;
-  const int seq = blockIdx.z % n_seqs, lz = blockIdx.z / n_seqs, head = blockIdx.y;
+  const int pair = blockIdx.x / slot_blocks, slot_block = blockIdx.x % slot_blocks;
+  const int seq = pair % n_seqs, lz = pair / n_seqs, head = blockIdx.y;
   const int layer = layer0 + lz;
   const char* __restrict__ k = src_layers.k[lz];
   const char* __restrict__ v = src_layers.v[lz];
   const int32_t* __restrict__ idx = idx0 + (int64_t)lz * idx_stride_layer;
   char* __restrict__ k_out = k_out0 + (int64_t)lz * out_stride_layer_b;
   char* __restrict__ v_out = v_out0 + (int64_t)lz * out_stride_layer_b;
-  const int slot = blockIdx.x * ROWS + threadIdx.x / LANES;
+  const int slot = slot_block * ROWS + threadIdx.x / LANES;
   const int lane = threadIdx.x % LANES;
   if (slot >= w + layer_max || lane * 16 >= row_bytes) return;
   const int begin = cu[seq];
@@ -70,8 +73,10 @@ hipError_t launch_gather(const Params& p, int elt_bytes, int layer, int n_layers
   }
   auto go = [&](auto kernel, int LANES) {
     const int rows = 256 / LANES;
-    dim3 grid((slots + rows - 1) / rows, p.Hkv, p.n_seqs * n_layers);
-    launch(DKV_KERNEL_GATHER, kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, layer, p.n_seqs, row_bytes, src,
+    const int slot_blocks = (slots + rows - 1) / rows;
+    dim3 grid(slot_blocks * p.n_seqs * n_layers, p.Hkv);
+    launch(DKV_KERNEL_GATHER, kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, layer, p.n_seqs, row_bytes,
+           slot_blocks, src,
            stride_token * elt_bytes, stride_head * elt_bytes, cu, idx, idx_stride_layer, counts,
            static_cast<char*>(k_out), static_cast<char*>(v_out), out_stride_layer * elt_bytes,
            out_stride_seq * elt_bytes, out_stride_head * elt_bytes);
@@ -126,13 +131,14 @@ __global__ __launch_bounds__(1024) void pack_offsets_kernel(int n_seqs, int L, i
   if (tid == 0) row_offsets[total] = carry;
 }
 
-// grid = (ceil((w + layer_max) / ROWS), Hkv, n_seqs * L), 256 threads: LANES lanes x 16 bytes = one row.
+// grid = (slot_blocks * n_seqs * L, Hkv), slot_blocks = ceil((w + layer_max) / ROWS) (the (sequence, layer) pair rides
+// in x: z ends at 65535), 256 threads: LANES lanes x 16 bytes = one row.
 // Packed block of (q, l), head h: rows [off + h * (w_q + n), + w_q + n): the n retained rows in selection order,
 // then the window rows in position order (the order of Algorithm 1's cat). Blocks that would pass `capacity_rows`
 // are not written.
 template <int LANES>
 __global__ __launch_bounds__(256) void pack_cache_kernel(int w, int layer_max, int L, int n_seqs, int row_bytes,
-                                                         const int32_t* __restrict__ cu,
+                                                         int slot_blocks, const int32_t* __restrict__ cu,
                                                          const int32_t* __restrict__ counts,
                                                          const int64_t* __restrict__ row_offsets,
                                                          const char* __restrict__ kb, const char* __restrict__ vb,
@@ -140,8 +146,9 @@ __global__ __launch_bounds__(256) void pack_cache_kernel(int w, int layer_max, i
                                                          int64_t stride_head_b, char* __restrict__ k_packed,
                                                          char* __restrict__ v_packed, int64_t capacity_rows) {
   constexpr int ROWS = 256 / LANES;
-  const int q = blockIdx.z % n_seqs, l = blockIdx.z / n_seqs, h = blockIdx.y;
-  const int slot = blockIdx.x * ROWS + threadIdx.x / LANES;      // packed slot inside the head's rows
+  const int pair = blockIdx.x / slot_blocks;
+  const int q = pair % n_seqs, l = pair / n_seqs, h = blockIdx.y;
+  const int slot = (blockIdx.x % slot_blocks) * ROWS + threadIdx.x / LANES;      // packed slot inside the head's rows
   const int lane = threadIdx.x % LANES;
   if (lane * 16 >= row_bytes) return;
   const int S = cu[q + 1] - cu[q];
@@ -171,8 +178,9 @@ hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, 
   const int slots = p.w + p.layer_max;
   auto go = [&](auto kernel, int LANES) {
     const int rows = 256 / LANES;
-    dim3 grid((slots + rows - 1) / rows, p.Hkv, p.n_seqs * p.L);
-    launch(DKV_KERNEL_PACK, kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, p.n_seqs, row_bytes, cu, counts,
+    const int slot_blocks = (slots + rows - 1) / rows;
+    dim3 grid(slot_blocks * p.n_seqs * p.L, p.Hkv);
+    launch(DKV_KERNEL_PACK, kernel, grid, dim3(256), 0, st, p.w, p.layer_max, p.L, p.n_seqs, row_bytes, slot_blocks, cu, counts,
            static_cast<const int64_t*>(row_offsets), static_cast<const char*>(kb), static_cast<const char*>(vb),
            stride_layer * elt_bytes, stride_seq * elt_bytes, stride_head * elt_bytes, static_cast<char*>(k_packed),
            static_cast<char*>(v_packed), capacity_rows);

@@ -5,9 +5,10 @@
 // pattern, scores are >= 0) finds the kg-th largest value T from digit histograms summed over all layers.
 //
 //   clear   zeroes the histograms of this call.
-//   hist0   histogram of the top digit. A layer's scores never change once written, so the histogram is kept in
-//           the workspace and a call only adds the layers that the previous call (layers_done - interval, same
-//           score tensor, recorded in a small header) had not seen; any other history means a full recount.
+//   hist0   histogram of the top digit. Within one prefill a layer's scores never change once written, so a caller
+//           that names its prefill (a non-zero epoch) lets the histogram stay in the workspace: a call then only
+//           adds the layers that the previous call of the same epoch (layers_done - interval, same score tensor,
+//           recorded in a small header) had not seen. Epoch 0, or any other history, means a full recount.
 //   pick0   digit 0 of T from the top-digit histogram (one workgroup per sequence and update).
 //   scan1   histograms the middle digit of the elements that share digit 0 and counts, per layer, the elements
 //           whose digit 0 is larger (they are above T).
@@ -37,11 +38,14 @@ constexpr int kLowBins = 1024;       // the last digit has 10 bits
 constexpr uint32_t kHeaderMagic = 0x646b7631u;
 
 // header[0] magic, [1] layers_done of the last completed call, [2..3] its score tensor, [4] interval, [5] n_seqs,
-// [6] total_tokens. Layers below the returned value already are in the top-digit histogram.
+// [6] total_tokens, [7] updates of that call, [8] its epoch. Layers below the returned value already are in the
+// top-digit histogram. Epoch 0 never matches: such a call neither uses nor leaves a history.
 __device__ inline int layers_already_counted(const int32_t* __restrict__ header, const float* scores_all,
-                                             int layers_done, int interval, int n_seqs, int total_tokens) {
+                                             int layers_done, int interval, int n_seqs, int total_tokens,
+                                             uint32_t epoch) {
   const uint64_t ptr = reinterpret_cast<uint64_t>(scores_all);
-  const bool same = (uint32_t)header[0] == kHeaderMagic && header[1] == layers_done - interval &&
+  const bool same = epoch != 0u && (uint32_t)header[8] == epoch &&
+                    (uint32_t)header[0] == kHeaderMagic && header[1] == layers_done - interval &&
                     (uint32_t)header[2] == (uint32_t)ptr && (uint32_t)header[3] == (uint32_t)(ptr >> 32) &&
                     header[4] == interval && header[5] == n_seqs && header[6] == total_tokens;
   return same && layers_done > interval ? layers_done - interval : 0;
@@ -54,10 +58,10 @@ __global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restri
                                                               uint32_t* __restrict__ tot0, size_t tot0_words,
                                                               const int32_t* __restrict__ header,
                                                               const float* scores_all, int layers_done, int interval,
-                                                              int n_seqs, int total_tokens) {
+                                                              int n_seqs, int total_tokens, uint32_t epoch) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < always_words; i += stride) always[i] = 0u;
-  const bool keep = layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens) != 0;
+  const bool keep = layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens, epoch) != 0;
   int used = keep ? header[7] : 0;
   used = used < 1 ? 1 : (used > DKV_MAX_UPDATES ? DKV_MAX_UPDATES : used);
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < tot0_words; i += stride) {
@@ -199,11 +203,11 @@ __global__ __launch_bounds__(256) void rebalance_hist0_kernel(int n_seqs, int Hk
                                                               int layers_done, int interval,
                                                               const float* __restrict__ scores_all,
                                                               const int32_t* __restrict__ cu,
-                                                              const int32_t* __restrict__ header,
+                                                              const int32_t* __restrict__ header, uint32_t epoch,
                                                               int32_t* __restrict__ tot0, int64_t tot0_words) {
   __shared__ int h[kRadixBins * kHist0Copies];
   const int head = blockIdx.y, layer = blockIdx.z;
-  if (layer < layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens)) return;
+  if (layer < layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens, epoch)) return;
   const int slot = layer < layers_done ? 0 : 1 + (layer - layers_done) / interval;
   int seq, c, begin, len;
   if (!find_chunk(cu, n_seqs, kHist0Chunk, w, blockIdx.x, seq, c, begin, len)) return;
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     int n_seqs, int L, int layers_done, int interval, int w, int Hkv, int mean_budget, int layer_max, int total_tokens,
     const float* scores_all, const int32_t* __restrict__ cu, const int32_t* __restrict__ picks,
     const int32_t* __restrict__ tot2, const int32_t* __restrict__ hist2, const int32_t* __restrict__ above,
-    int64_t always_words, int32_t* __restrict__ header, int32_t* __restrict__ counts,
+    int64_t always_words, int32_t* __restrict__ header, uint32_t epoch, int32_t* __restrict__ counts,
     int32_t* __restrict__ budgets_out, int32_t* __restrict__ hits_out, int64_t out_stride_update) {
   const int update = blockIdx.y, n_updates = gridDim.y;
   const int first_done = layers_done;                  // of the call's first update: it fixes the slots of the layers
@@ -573,14 +577,15 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
     header[0] = (int32_t)kHeaderMagic; header[1] = layers_done;
     header[2] = (int32_t)(uint32_t)ptr; header[3] = (int32_t)(uint32_t)(ptr >> 32);
     header[4] = interval; header[5] = n_seqs; header[6] = total_tokens; header[7] = n_updates;
+    header[8] = (int32_t)epoch;
   }
 }
 
 // layers_done: of the first update; update u of the n_updates covers layers [0, layers_done + u * interval).
 // budgets_out / hits_out (may be null): update u writes its block out_stride_update ints after update u - 1's.
-hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, const float* scores_all, const int32_t* cu,
-                            int32_t* counts, int32_t* budgets_out, int32_t* hits_out, int64_t out_stride_update,
-                            char* ws, const WorkspaceLayout& wl, hipStream_t st) {
+hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, uint32_t epoch, const float* scores_all,
+                            const int32_t* cu, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
+                            int64_t out_stride_update, char* ws, const WorkspaceLayout& wl, hipStream_t st) {
   int32_t* header = reinterpret_cast<int32_t*>(ws + wl.header);
   int32_t* tot0 = reinterpret_cast<int32_t*>(ws + wl.tot0);
   int32_t* tot1 = reinterpret_cast<int32_t*>(ws + wl.tot1);
@@ -596,11 +601,11 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, con
   blocks = blocks > 1024 ? 1024 : blocks;
   launch(DKV_KERNEL_FILL, rebalance_clear_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
          reinterpret_cast<uint32_t*>(tot1), clear_words, reinterpret_cast<uint32_t*>(tot0), (size_t)tot0_words, header,
-         scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens);
+         scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens, epoch);
   const int last_done = layers_done + (n_updates - 1) * p.interval;
   const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, last_done);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist0_kernel, grid0, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, layers_done, p.interval, scores_all, cu, header, tot0, tot0_words);
+         p.total_tokens, layers_done, p.interval, scores_all, cu, header, epoch, tot0, tot0_words);
   const dim3 grid_pick(p.n_seqs, n_updates);
   launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<0>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
          p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
@@ -613,7 +618,7 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, con
          p.total_tokens, layers_done, p.interval, n_updates, scores_all, cu, picks, tot1, tot2, hist2, above, always_words);
   launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs, n_updates), dim3(kFinalThreads), 0, st,
          p.n_seqs, p.L, layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu,
-         picks, tot2, hist2, above, always_words, header, counts, budgets_out, hits_out, out_stride_update);
+         picks, tot2, hist2, above, always_words, header, epoch, counts, budgets_out, hits_out, out_stride_update);
   return hipGetLastError();
 }
 

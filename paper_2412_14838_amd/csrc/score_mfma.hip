@@ -906,9 +906,14 @@ __global__ __launch_bounds__(256) void score_lse_mfma(Params p, int chunk, int t
   }
 }
 
+// load_tile() forms the byte offset of a key row inside a chunk in 32 bits (a 24-bit multiply): the largest row
+// index it can see (the chunk, the pooling halo and two tiles of slack) times the token stride must stay below
+// 2^32, and the stride itself below 2^24. Longer strides take the vector-ALU kernels.
 bool score_mfma_supported(const Params& p, int dtype, int64_t k_stride_token) {
-  return dtype == DKV_BF16 && p.d == 128 && p.rows <= 256 && 2 * p.half <= kMaxHalo &&
-         k_stride_token * 2 < (1 << 24);
+  const int64_t stride_b = k_stride_token * 2;
+  const int64_t max_row = kMaxChunk + kMaxHalo + 2 * 128;
+  return dtype == DKV_BF16 && p.d == 128 && p.rows <= 256 && 2 * p.half <= kMaxHalo && stride_b < (1 << 24) &&
+         max_row * stride_b < ((int64_t)1 << 32);
 }
 
 // Keys per workgroup. Every workgroup pays a fixed cost (locating its chunk, the first loads, the epilogue) and the

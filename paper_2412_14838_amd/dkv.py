@@ -20,7 +20,9 @@ DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAU
 
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance", "dkv_rebalance_batch",
-           "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention")
+           "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention", "dkv_layer_budgets",
+           "dkv_apply_budgets", "dkv_select_recent", "dkv_score_path")
+DKV_SCHEDULE_FIXED, DKV_SCHEDULE_PYRAMID = 0, 1
 
 
 class dkv_desc(C.Structure):
@@ -82,11 +84,19 @@ def load() -> C.CDLL:
     lib.dkv_decode_attention.restype = C.c_int
     lib.dkv_decode_attention.argtypes = [D, I32, P, P, P, I64, I64, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance.restype = C.c_int
-    lib.dkv_rebalance.argtypes = [D, I32, P, P, P, P, P, P, SZ, P]
+    lib.dkv_rebalance.argtypes = [D, I32, C.c_uint32, P, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance_batch.restype = C.c_int
-    lib.dkv_rebalance_batch.argtypes = [D, I32, I32, P, P, P, P, P, I64, P, SZ, P]
+    lib.dkv_rebalance_batch.argtypes = [D, I32, I32, C.c_uint32, P, P, P, P, P, I64, P, SZ, P]
     lib.dkv_gather_kv.restype = C.c_int
     lib.dkv_gather_kv.argtypes = [D, I32, P, P, I64, I64, P, P, P, P, P, I64, I64, P]
+    lib.dkv_layer_budgets.restype = C.c_int
+    lib.dkv_layer_budgets.argtypes = [D, I32, I32, P]
+    lib.dkv_apply_budgets.restype = C.c_int
+    lib.dkv_apply_budgets.argtypes = [D, I32, P, P, P]
+    lib.dkv_select_recent.restype = C.c_int
+    lib.dkv_select_recent.argtypes = [D, I32, I32, P, P, P, P]
+    lib.dkv_score_path.restype = C.c_int
+    lib.dkv_score_path.argtypes = [D, I64]
     _lib = lib
     return lib
 
@@ -137,7 +147,8 @@ def dkv_workspace_bytes(desc: dkv_desc) -> int:
 
 
 KERNEL_NAMES = ("score_stats", "score_emit", "select", "gather", "rebalance_hist", "rebalance_scan",
-                "rebalance_final", "fill", "score_borders", "score_lse", "pack", "decode", "score_merge", "rebalance_pick")
+                "rebalance_final", "fill", "score_borders", "score_lse", "pack", "decode", "score_merge", "rebalance_pick",
+                "schedule")
 
 
 def dkv_profile_begin(capacity: int) -> None:
@@ -159,6 +170,23 @@ def dkv_score_window(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, 
     _check(load().dkv_score_window(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head, _ptr(cu_seqlens),
                                    _ptr(scores_out), scores_stride_head, _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_score_window")
+
+
+def dkv_layer_budgets(desc, schedule, beta=4):
+    """The L budgets of a fixed-pattern schedule as a list of ints (host only)."""
+    out = (C.c_int32 * desc.n_layers)()
+    _check(load().dkv_layer_budgets(C.byref(desc), schedule, beta, out), "dkv_layer_budgets")
+    return list(out)
+
+
+def dkv_apply_budgets(desc, n_layers, budgets, counts, stream=None) -> None:
+    _check(load().dkv_apply_budgets(C.byref(desc), n_layers, _ptr(budgets), _ptr(counts), _stream(stream)),
+           "dkv_apply_budgets")
+
+
+def dkv_select_recent(desc, layer, n_sink, cu_seqlens, idx_out, counts, stream=None) -> None:
+    _check(load().dkv_select_recent(C.byref(desc), layer, n_sink, _ptr(cu_seqlens), _ptr(idx_out), _ptr(counts),
+                                    _stream(stream)), "dkv_select_recent")
 
 
 def dkv_score_window_layers(desc, layer_begin, q_layers, k_layers, k_stride_token, k_stride_head, cu_seqlens, scores_all,
@@ -241,16 +269,16 @@ def dkv_gather_kv_layers(desc, layer_begin, k_layers, v_layers, stride_token, st
            "dkv_gather_kv_layers")
 
 
-def dkv_rebalance(desc, layers_done, scores_all, cu_seqlens, counts, budgets_out, hits_out, workspace,
+def dkv_rebalance(desc, layers_done, epoch, scores_all, cu_seqlens, counts, budgets_out, hits_out, workspace,
                   stream=None) -> None:
-    _check(load().dkv_rebalance(C.byref(desc), layers_done, _ptr(scores_all), _ptr(cu_seqlens), _ptr(counts),
+    _check(load().dkv_rebalance(C.byref(desc), layers_done, epoch, _ptr(scores_all), _ptr(cu_seqlens), _ptr(counts),
                                 _ptr(budgets_out), _ptr(hits_out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_rebalance")
 
 
-def dkv_rebalance_batch(desc, layers_done, n_updates, scores_all, cu_seqlens, counts, budgets_out, hits_out,
+def dkv_rebalance_batch(desc, layers_done, n_updates, epoch, scores_all, cu_seqlens, counts, budgets_out, hits_out,
                         out_stride_update, workspace, stream=None) -> None:
-    _check(load().dkv_rebalance_batch(C.byref(desc), layers_done, n_updates, _ptr(scores_all), _ptr(cu_seqlens),
+    _check(load().dkv_rebalance_batch(C.byref(desc), layers_done, n_updates, epoch, _ptr(scores_all), _ptr(cu_seqlens),
                                       _ptr(counts), _ptr(budgets_out), _ptr(hits_out), out_stride_update,
                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream)), "dkv_rebalance_batch")

@@ -16,9 +16,13 @@ caller then holds the window queries, K and V of a group's layers until that poi
 """
 from __future__ import annotations
 
+import itertools
+
 import torch
 
 from . import dkv
+
+_epochs = itertools.count(1)   # every prefill of every Compressor gets its own non-zero epoch for dkv_rebalance
 
 
 def default_group(cfg) -> int:
@@ -28,9 +32,19 @@ def default_group(cfg) -> int:
     return max(most // cfg.interval * cfg.interval, 1)
 
 
+SCHEDULES = ("dynamic", "fixed", "pyramid", "recent")
+
+
 class Compressor:
-    def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None, group=1):
+    """schedule: "dynamic" is Algorithm 1 (progressive updates every `interval` layers); "fixed" and "pyramid" score
+    and select as Algorithm 1 does but cut every layer to a preset budget instead (no update ever runs);
+    "recent" takes sinks + the newest prefix rows as candidates (no scoring) and cuts them to the fixed budget."""
+
+    def __init__(self, cfg, device="cuda", keep_cache=True, desc_override=None, group=1, schedule="dynamic", beta=4,
+                 n_sink=4):
+        assert schedule in SCHEDULES
         self.cfg = cfg
+        self.schedule, self.n_sink = schedule, n_sink
         self.group = max(1, min(int(group), dkv.DKV_MAX_SELECT_LAYERS))
         self._pending = []
         self.on_update = None       # optional host callback(layers_done), called after each update has been issued
@@ -47,11 +61,16 @@ class Compressor:
         self.budgets_all = torch.zeros((n_updates, cfg.n_seqs, L), dtype=torch.int32, device=device)
         self.hits_all = torch.zeros((n_updates, cfg.n_seqs, L), dtype=torch.int32, device=device)
         self._last_update = 0
+        self.epoch = next(_epochs)
         self.keep_cache = keep_cache
         if keep_cache:
             self.kb = torch.zeros((L, cfg.n_seqs, Hkv, self.slots, d), dtype=self.tdtype, device=device)
             self.vb = torch.zeros_like(self.kb)
         self.ws = dkv.alloc_workspace(self.desc, device)
+        self.preset = None
+        if schedule != "dynamic":
+            kind = dkv.DKV_SCHEDULE_PYRAMID if schedule == "pyramid" else dkv.DKV_SCHEDULE_FIXED
+            self.preset = torch.tensor(dkv.dkv_layer_budgets(self.desc, kind, beta), dtype=torch.int32, device=device)
 
     @property
     def budgets(self):
@@ -128,17 +147,21 @@ class Compressor:
 
     def rebalance(self, layers_done, stream=None):
         self._last_update = self._update_slot(layers_done)
-        dkv.dkv_rebalance(self.desc, layers_done, self.scores, self.cu, self.counts, self.budgets, self.hits, self.ws,
-                          stream)
+        dkv.dkv_rebalance(self.desc, layers_done, self.epoch, self.scores, self.cu, self.counts, self.budgets,
+                          self.hits, self.ws, stream)
 
     def rebalance_batch(self, layers_done, n_updates, stream=None):
         """The updates after layers_done, layers_done + interval, ... layers in one call."""
         u0 = self._update_slot(layers_done)
         self._last_update = u0 + n_updates - 1
-        dkv.dkv_rebalance_batch(self.desc, layers_done, n_updates, self.scores, self.cu, self.counts,
+        dkv.dkv_rebalance_batch(self.desc, layers_done, n_updates, self.epoch, self.scores, self.cu, self.counts,
                                 self.budgets_all[u0], self.hits_all[u0], self.cfg.n_seqs * self.cfg.L, self.ws, stream)
 
     def step(self, layer, q_win, k, v, **strides):
+        if layer == 0:
+            self.epoch = next(_epochs)      # a new prefill: the updates must not extend the previous one's history
+        if self.schedule != "dynamic":
+            return self._step_preset(layer, q_win, k, v, **strides)
         if self.group > 1:
             return self._step_grouped(layer, q_win, k, v, **strides)
         self.score(layer, q_win, k, **strides)
@@ -147,6 +170,23 @@ class Compressor:
             self.gather(layer, k, v, **strides)
         if (layer + 1) % self.cfg.interval == 0:
             self._update(layer + 1)
+
+    def apply_budgets(self, n_layers, stream=None):
+        dkv.dkv_apply_budgets(self.desc, n_layers, self.preset, self.counts, stream)
+
+    def select_recent(self, layer, stream=None):
+        dkv.dkv_select_recent(self.desc, layer, self.n_sink, self.cu, self.idx[layer], self.counts, stream)
+
+    def _step_preset(self, layer, q_win, k, v, **strides):
+        # the comparison patterns: the layer's candidates, cut to the preset budget, then the compaction of what is left
+        if self.schedule == "recent":
+            self.select_recent(layer)
+        else:
+            self.score(layer, q_win, k, **strides)
+            self.select(layer)
+        self.apply_budgets(layer + 1)           # a minimum: applying it to the earlier layers again changes nothing
+        if self.keep_cache:
+            self.gather(layer, k, v, **strides)
 
     def _update(self, layers_done):
         self.rebalance(layers_done)

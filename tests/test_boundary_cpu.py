@@ -71,7 +71,7 @@ def test_bad_descriptors_are_rejected(lib, bad, status):
     fake = C.c_void_p(0x1000)
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 64 * 1024, fake, fake, 1024, fake, 1 << 30, None) == status
     assert lib.dkv_select_topk(C.byref(d), 0, fake, 1024, fake, fake, fake, fake, 1 << 30, None) == status
-    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 1 << 30, None) == status
+    assert lib.dkv_rebalance(C.byref(d), 2, 0, fake, fake, fake, None, None, fake, 1 << 30, None) == status
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64,
                              272 * 64, None) == status
     ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
@@ -90,7 +90,7 @@ def test_bad_call_arguments_are_rejected(lib):
     assert lib.dkv_score_window(C.byref(d), None, fake, 64, 65536, fake, fake, 1024, fake, need, None) == inv
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, None, fake, 1024, fake, need, None) == inv
     assert lib.dkv_select_topk(C.byref(d), 0, None, 1024, fake, fake, fake, fake, need, None) == inv
-    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, None, None, None, fake, need, None) == inv
+    assert lib.dkv_rebalance(C.byref(d), 2, 0, fake, fake, None, None, None, fake, need, None) == inv
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, None, 64, 65536, fake, fake, fake, fake, fake, 2 * 272 * 64, 272 * 64,
                              None) == inv
     assert lib.dkv_workspace_bytes(None) == 0
@@ -103,12 +103,12 @@ def test_bad_call_arguments_are_rejected(lib):
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, None, need, None) == wsp
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, fake, need - 1, None) == wsp
     assert lib.dkv_score_window(C.byref(d), fake, fake, 64, 65536, fake, fake, 1024, C.c_void_p(0x1010), need, None) == wsp
-    assert lib.dkv_rebalance(C.byref(d), 2, fake, fake, fake, None, None, fake, 16, None) == wsp
+    assert lib.dkv_rebalance(C.byref(d), 2, 0, fake, fake, fake, None, None, fake, 16, None) == wsp
     # layer / layers_done out of range or not a multiple of the interval
     assert lib.dkv_select_topk(C.byref(d), 4, fake, 1024, fake, fake, fake, fake, need, None) == inv
     assert lib.dkv_select_topk(C.byref(d), -1, fake, 1024, fake, fake, fake, fake, need, None) == inv
     for bad_l in (0, 1, 3, 6):
-        assert lib.dkv_rebalance(C.byref(d), bad_l, fake, fake, fake, None, None, fake, need, None) == inv
+        assert lib.dkv_rebalance(C.byref(d), bad_l, 0, fake, fake, fake, None, None, fake, need, None) == inv
     # output block too small for window + layer_max rows
     assert lib.dkv_gather_kv(C.byref(d), 0, fake, fake, 64, 65536, fake, fake, fake, fake, fake, 2 * 100 * 64, 100 * 64,
                              None) == inv
@@ -150,19 +150,19 @@ def test_batched_updates_validate_their_arguments(lib):
     inv = dkv.DKV_ERR_INVALID_ARG
     call = lib.dkv_rebalance_batch
     big = d.n_seqs * d.n_layers
-    assert call(C.byref(d), d.interval, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval, dkv.DKV_MAX_UPDATES + 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval + 1, 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv      # not a boundary
-    assert call(C.byref(d), 0, 1, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 0, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, dkv.DKV_MAX_UPDATES + 1, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval + 1, 1, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv      # not a boundary
+    assert call(C.byref(d), 0, 1, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv
     last = d.n_layers // d.interval * d.interval
-    assert call(C.byref(d), last, 2, fake, fake, fake, fake, fake, big, fake, need, None) == inv                # runs past L
-    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big - 1, fake, need, None) == inv      # outputs overlap
-    assert call(C.byref(d), d.interval, 2, None, fake, fake, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval, 2, fake, None, fake, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval, 2, fake, fake, None, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval, 2, C.c_void_p(0x1004), fake, fake, fake, fake, big, fake, need, None) == inv
-    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big, None, need, None) == dkv.DKV_ERR_WORKSPACE
-    assert call(C.byref(d), d.interval, 2, fake, fake, fake, fake, fake, big, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), last, 2, 0, fake, fake, fake, fake, fake, big, fake, need, None) == inv                # runs past L
+    assert call(C.byref(d), d.interval, 2, 0, fake, fake, fake, fake, fake, big - 1, fake, need, None) == inv      # outputs overlap
+    assert call(C.byref(d), d.interval, 2, 0, None, fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, 0, fake, None, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, 0, fake, fake, None, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, 0, C.c_void_p(0x1004), fake, fake, fake, fake, big, fake, need, None) == inv
+    assert call(C.byref(d), d.interval, 2, 0, fake, fake, fake, fake, fake, big, None, need, None) == dkv.DKV_ERR_WORKSPACE
+    assert call(C.byref(d), d.interval, 2, 0, fake, fake, fake, fake, fake, big, fake, need - 1, None) == dkv.DKV_ERR_WORKSPACE
 
 
 def test_layer_batched_scoring_rejects_bad_ranges_and_pointers(lib):
@@ -265,6 +265,52 @@ def test_decode_attention_validates_its_arguments(lib):
     assert lib.dkv_decode_attention(C.byref(d), *a) == wsp
     wide = _good(n_q_heads=34, n_kv_heads=2, window=4)        # 17 query heads per KV head
     assert lib.dkv_decode_attention(C.byref(wide), *ok[:11], dkv.dkv_workspace_bytes(wide), None) == dkv.DKV_ERR_UNSUPPORTED
+
+
+def test_fixed_pattern_schedules_match_the_oracle_and_validate(lib):
+    """dkv_layer_budgets is host-only: its budgets equal the oracle's for both schedules over a sweep of shapes
+    (including a hi that hits the per-layer maximum, beta = 1 and L = 1), and bad arguments are rejected."""
+    from oracle import dkv_oracle as O
+    for L in (1, 2, 4, 7, 28, 32):
+        for mean, layer_max in ((128, 256), (512, 2048), (64, 100), (7, 9), (1, 1)):
+            d = _good(n_layers=L, mean_budget=mean, layer_max=layer_max, interval=1)
+            assert dkv.dkv_layer_budgets(d, dkv.DKV_SCHEDULE_FIXED) == O.fixed_layer_budgets(L, mean).tolist()
+            for beta in (1, 2, 4, 9):
+                assert dkv.dkv_layer_budgets(d, dkv.DKV_SCHEDULE_PYRAMID, beta) == \
+                    O.pyramid_layer_budgets(L, mean, layer_max, beta).tolist(), (L, mean, layer_max, beta)
+    d = _good()
+    out = (C.c_int32 * 4)()
+    fake = C.c_void_p(0x1000)
+    inv = dkv.DKV_ERR_INVALID_ARG
+    assert lib.dkv_layer_budgets(C.byref(d), 2, 4, out) == inv            # unknown schedule
+    assert lib.dkv_layer_budgets(C.byref(d), dkv.DKV_SCHEDULE_PYRAMID, 0, out) == inv
+    assert lib.dkv_layer_budgets(C.byref(d), dkv.DKV_SCHEDULE_FIXED, 4, None) == inv
+    assert lib.dkv_layer_budgets(C.byref(_good(interval=0)), dkv.DKV_SCHEDULE_FIXED, 4, out) == inv
+    assert lib.dkv_apply_budgets(C.byref(d), 4, None, fake, None) == inv
+    assert lib.dkv_apply_budgets(C.byref(d), 4, fake, None, None) == inv
+    for n in (0, 5):
+        assert lib.dkv_apply_budgets(C.byref(d), n, fake, fake, None) == inv
+    assert lib.dkv_select_recent(C.byref(d), 0, 4, None, fake, fake, None) == inv
+    assert lib.dkv_select_recent(C.byref(d), 0, -1, fake, fake, fake, None) == inv
+    assert lib.dkv_select_recent(C.byref(d), 4, 4, fake, fake, fake, None) == inv
+    assert lib.dkv_select_recent(C.byref(_good(pool_kernel=2)), 0, 4, fake, fake, fake, None) == inv
+
+
+def test_score_path_and_the_token_stride_limit(lib):
+    """The matrix-core kernels form key-row offsets in 32 bits: a token stride whose product with the largest row
+    index of a chunk would pass 2^32 bytes must take the vector-ALU kernels (dkv_score_path tells which)."""
+    bf = _good(head_dim=128, dtype=dkv.DKV_BF16, n_q_heads=8, n_kv_heads=2, window=32)
+    assert lib.dkv_score_path(C.byref(bf), 128) == 1
+    assert lib.dkv_score_path(C.byref(bf), 8 * 128) == 1                   # token-major, 8 KV heads
+    limit_elems = (1 << 32) // (4096 + 64 + 256) // 2                      # bytes -> bf16 elements
+    assert lib.dkv_score_path(C.byref(bf), limit_elems // 8 * 8) == 1
+    assert lib.dkv_score_path(C.byref(bf), (limit_elems // 8 + 1) * 8) == 0
+    assert lib.dkv_score_path(C.byref(bf), 1 << 22) == 0
+    assert lib.dkv_score_path(C.byref(_good()), 64) == 0                   # fp32: vector ALU
+    assert lib.dkv_score_path(C.byref(_good(head_dim=64, dtype=dkv.DKV_BF16)), 64) == 0
+    assert lib.dkv_score_path(C.byref(bf), 100) == dkv.DKV_ERR_INVALID_ARG  # rows overlap
+    assert lib.dkv_score_path(None, 128) == dkv.DKV_ERR_INVALID_ARG
+    assert lib.dkv_score_path(C.byref(_good(n_kv_heads=2048, n_q_heads=2048)), 64) == dkv.DKV_ERR_UNSUPPORTED
 
 
 def test_binding_raises_on_error():

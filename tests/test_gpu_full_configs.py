@@ -1,7 +1,8 @@
 """GPU parity at the full size of the five benchmark configurations, in the launch shape bench.py times.
 
 Per configuration the whole layer loop runs on the GPU; then
-  A. pooled scores of sampled (layer, sequence, KV head) rows are compared with the oracle (2e-3 relative);
+  A. pooled scores are compared with the oracle (2e-3 relative): in EVERY layer of the launch one KV head of one
+     sequence (head and sequence rotate with the layer), and on a few sampled layers further heads and sequences;
   B. every integer result (ordered indices of all layers, hit counts and budgets of every update, final counts)
      is compared bit for bit with the oracle run on the GPU's own fp32 scores;
   C. gathered K/V rows of sampled layers are compared bit for bit with the oracle's gather;
@@ -25,10 +26,17 @@ SCORE_RTOL = 2e-3
 BAND_RTOL = 1e-5
 
 
+def rotating(cfg, layer):
+    """The (sequence, KV head) whose scores are checked against the oracle in `layer`: both rotate with the layer, so
+    that over the layers of a launch every head and every sequence is covered."""
+    return layer % cfg.n_seqs, (3 * layer + 1) % cfg.Hkv
+
+
 def run_config(cfg, sample_layers, group=1):
     workers = min(16, len(os.sched_getaffinity(0)))
     comp = Compressor(cfg, group=group)
-    host, snaps = {}, {}
+    host, snaps, slices = {}, {}, {}
+    cu = cfg.cu_seqlens
 
     def snapshot(layers_done):      # hit counts and budgets of every update, whenever the schedule issues it
         torch.cuda.synchronize()
@@ -41,8 +49,11 @@ def run_config(cfg, sample_layers, group=1):
             comp.step(l, dev["q_win"], dev["k"], dev["v"])
             if l in sample_layers:
                 host[l] = data
+            s, h = rotating(cfg, l)     # one head's queries and keys of every layer stay on the host (16 MB at 32K)
+            slices[l] = (data["q_win"][s][h * cfg.G:(h + 1) * cfg.G].copy(), data["k"][h:h + 1, cu[s]:cu[s + 1]].copy())
             del dev
     torch.cuda.synchronize()
+    comp.host_slices = slices
     return comp, host, snaps
 
 
@@ -72,6 +83,20 @@ def check_config(cfg, sample_layers, sample_heads, sample_seqs, chain_budgets=Fa
         assert counts[s].tolist() == r.n
         B = cfg.global_budget
         assert sum(r.n) <= B and all(n <= cfg.layer_max for n in r.n)
+
+    # ---- A'. every layer of the launch: one rotating (sequence, KV head) against the oracle
+    def one_layer(l):
+        s, h = rotating(cfg, l)
+        q_h, k_h = comp.host_slices[l]
+        pre = cfg.seqlens[s] - w
+        ref = O.score_window(q_h, k_h, cfg.P)[0]
+        got = scores[l][h, cu[s]:cu[s] + pre]
+        rel = np.abs(got - ref) / np.maximum(ref, 1e-30)
+        return l, s, h, float(rel.max()) if pre > 0 else 0.0, bool(np.isneginf(scores[l][h, cu[s] + pre:cu[s + 1]]).all())
+
+    with cf.ThreadPoolExecutor(max_workers=4) as ex:      # each task holds ~100 MB of float64 logits at 32K
+        for l, s, h, worst, guarded in ex.map(one_layer, range(cfg.L)):
+            assert worst <= SCORE_RTOL and guarded, (l, s, h, worst)
 
     G = cfg.G
     for l in sample_layers:
@@ -136,9 +161,21 @@ def test_full_llama3_8b_8k(dkv):
     check_config(cfg, [0, 13, cfg.L - 1], [0, 5], [0], group=bench_group(cfg))
 
 
+def test_full_llama3_8b_8k_layer_by_layer(dkv):
+    """The paper's order at full size: one scoring, selection and compaction call per layer, an update every m."""
+    cfg = W.standard_configs()["llama3_8b_8k"]
+    check_config(cfg, [5, cfg.L - 1], [2], [0], group=1)
+
+
 def test_full_mistral_7b_32k(dkv):
     cfg = W.standard_configs()["mistral_7b_32k"]
     check_config(cfg, [0, cfg.L - 1], [1, 7], [0], group=bench_group(cfg))   # all layers, eight updates per call
+
+
+def test_full_mistral_7b_32k_one_update_interval_per_call(dkv):
+    """Config 3 with the layers of one update interval per call (the natural integration point of a prefill)."""
+    cfg = W.standard_configs()["mistral_7b_32k"]
+    check_config(cfg, [cfg.L - 1], [4], [0], group=cfg.interval)
 
 
 def test_full_qwen2_7b_32k_extreme(dkv):

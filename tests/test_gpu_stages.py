@@ -39,6 +39,7 @@ CASES = {
     "pool15": small_cfg("pool15", P=15, seqlens=(900,)),
     "pool63": small_cfg("pool63", P=63, seqlens=(2300, 70)),                     # the widest pooling window
     "rows256": small_cfg("rows256", Hq=16, Hkv=2, seqlens=(1300, 300)),         # G * w = 256: the most score rows
+    "small_f32_d128": small_cfg("f32_d128", dtype="f32", seqlens=(900, 40, 300)),   # fp32 at head size 128 (vector ALU)
 }
 
 
@@ -88,6 +89,32 @@ def test_score_window_token_major_strides_and_determinism(dkv):
     comp.score(2, dev["q_win"], dev["k"])
     torch.cuda.synchronize()
     assert torch.equal(a, comp.scores[1]) and torch.equal(a, comp.scores[2])
+
+
+def test_long_token_stride_takes_the_vector_alu_kernels(dkv):
+    """bf16 at head size 128 with a token stride past what the matrix-core kernels' 32-bit row offsets allow: the
+    call must run the vector-ALU kernels (no wrapped offsets) and match the oracle and the contiguous layout."""
+    cfg = small_cfg("wide_stride", seqlens=(520, 300), L=2)
+    stride = 1 << 19                                       # elements: 1 MiB per token
+    assert dkv.load().dkv_score_path(dkv.desc_from_workload(cfg), stride) == 0
+    assert dkv.load().dkv_score_path(dkv.desc_from_workload(cfg), cfg.d) == 1
+    data = W.make_layer(cfg, 0, with_v=False)
+    dev = to_device(cfg, data)
+    comp = Compressor(cfg, keep_cache=False)
+    T = cfg.total_tokens
+    wide = torch.zeros((T, stride), dtype=torch.bfloat16, device="cuda")      # token-major rows of 2^19 elements
+    for h in range(cfg.Hkv):
+        wide[:, h * 4096:h * 4096 + cfg.d] = dev["k"][h]
+    comp.score(0, dev["q_win"], wide, stride_token=stride, stride_head=4096)
+    comp.score(1, dev["q_win"], dev["k"])
+    torch.cuda.synchronize()
+    got = comp.scores[0].cpu().numpy()
+    assert_scores_close(cfg, got, oracle_scores(cfg, data))
+    cu = cfg.cu_seqlens
+    for s in range(cfg.n_seqs):
+        n = cfg.seqlens[s] - cfg.w
+        a, b = got[:, cu[s]:cu[s] + n], comp.scores[1].cpu().numpy()[:, cu[s]:cu[s] + n]
+        assert (np.abs(a - b) <= 1e-5 * np.abs(b)).all()
 
 
 def test_score_scale_overrides(dkv):
@@ -419,6 +446,23 @@ def test_rebalance_history_is_only_used_when_it_matches(dkv):
     comp.scores.copy_(torch.from_numpy(A2))  # a new prefill in the same tensors
     for l in (2, 4, 6):
         check(comp, A2, l)
+    # Prefill A updates after 2 and 4 layers; then ANOTHER prefill writes its scores into the same tensors (same
+    # workspace, same addresses) and its first update comes after 6 layers, exactly where A's history would continue:
+    # under its own epoch the call must recount, and so must every call under epoch 0 (no history kept or used).
+    for epoch_a, epoch_b in ((1001, 1002), (0, 0), (1003, 0), (0, 1004)):
+        comp.scores.copy_(torch.from_numpy(A))
+        comp.epoch = epoch_a
+        check(comp, A, 2)
+        check(comp, A, 4)
+        comp.scores.copy_(torch.from_numpy(A2))
+        comp.epoch = epoch_b
+        check(comp, A2, 6)
+        check(comp, A2, 6)
+    # within one epoch the history is used: calls 2, 4 and then 6 over unchanged scores agree with a fresh recount
+    comp.scores.copy_(torch.from_numpy(A))
+    comp.epoch = 2001
+    for l in (2, 4, 6):
+        check(comp, A, l)
 
 
 BATCH_PLANS = {
@@ -615,7 +659,7 @@ def test_pack_cache_equals_the_oracles_final_cache(dkv, case):
 
 
 @pytest.mark.parametrize("case", ["tiny_norm", "small_bf16", "small_bf16_gqa7", "small_bf16_d64", "ragged_bf16",
-                                  "ragged_f32", "short_seqs"])
+                                  "ragged_f32", "short_seqs", "small_f32_d128"])
 def test_decode_attention_over_the_compressed_cache(dkv, case):
     """After a whole prefill compression, attention of one new token per sequence over every layer's compressed
     cache equals the oracle's softmax attention over the same rows (the rows the GPU's index lists and final
@@ -654,3 +698,90 @@ def test_decode_attention_over_the_compressed_cache(dkv, case):
     # without the optional output
     comp.decode_attention(0, q_dev, out, None)
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- fixed-pattern schedules (Section 5.1, Figure 1)
+@pytest.mark.parametrize("schedule", ["fixed", "pyramid", "recent"])
+@pytest.mark.parametrize("case", ["tiny_norm", "ragged_bf16", "small_bf16"])
+def test_fixed_pattern_schedules_match_the_oracle(dkv, case, schedule):
+    """The comparison patterns through the same calls: candidates (top-k of the scores, or sinks + newest rows),
+    preset budgets applied as the truncation, compaction. Index lists, counts and the packed cache equal the
+    oracle's loop with the same schedule, bit for bit (the oracle selects on the GPU's own fp32 scores)."""
+    cfg = CASES[case].with_(L=4)
+    comp = Compressor(cfg, schedule=schedule, n_sink=3)
+    host = []
+    for l in range(cfg.L):
+        data = W.make_layer(cfg, l)
+        host.append(data)
+        dev = to_device(cfg, data)
+        comp.step(l, dev["q_win"], dev["k"], dev["v"])
+    kp, vp, off = comp.pack()
+    torch.cuda.synchronize()
+    budgets = {"fixed": O.fixed_layer_budgets(cfg.L, cfg.mean_budget), "recent": O.fixed_layer_budgets(cfg.L, cfg.mean_budget),
+               "pyramid": O.pyramid_layer_budgets(cfg.L, cfg.mean_budget, cfg.layer_max, 4)}[schedule]
+    assert comp.preset.cpu().numpy().tolist() == budgets.tolist()
+    scores, idx, counts = comp.scores.cpu().numpy(), comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    kp, vp, off = kp.float().cpu().numpy(), vp.float().cpu().numpy(), off.cpu().numpy()
+    cu, w = cfg.cu_seqlens, cfg.w
+    for s in range(cfg.n_seqs):
+        S = cfg.seqlens[s]
+        if S <= w:
+            assert (counts[s] == 0).all()
+            continue
+        layers = [(host[l]["q_win"][s], host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]])
+                  for l in range(cfg.L)]
+        A = [scores[l][:, cu[s]:cu[s] + S - w] for l in range(cfg.L)]
+        r = O.compress_fixed_pattern(layers, cfg.L, w, cfg.P, cfg.layer_max, budgets, scores_override=A,
+                                     n_sink=3 if schedule == "recent" else None)
+        assert counts[s].tolist() == r.n
+        for l in range(cfg.L):
+            k = r.idx[l].shape[1]
+            assert np.array_equal(idx[l, s][:, :k], r.idx[l]) and (idx[l, s][:, k:] == -1).all()
+            kc, vc = r.cache(l, w)
+            o, rows = off[s * cfg.L + l], kc.shape[1]
+            for h in range(cfg.Hkv):
+                assert np.array_equal(kp[o + h * rows:o + (h + 1) * rows], kc[h]), (s, l, h)
+                assert np.array_equal(vp[o + h * rows:o + (h + 1) * rows], vc[h]), (s, l, h)
+
+
+def test_planted_recall_of_the_schedules(dkv):
+    """Calibrated planting (every planted key outranks the background) with a planted count that varies strongly by
+    layer: the share of planted positions that survives in the final cache, per schedule, at the same total
+    budget. The layer-adaptive update keeps at least as many as the fixed pattern, which keeps more than
+    recency (which ignores the scores); the GPU's recall equals the oracle's for every schedule."""
+    cfg = small_cfg("recall", L=8, interval=4, seqlens=(3000,), mean_budget=48, layer_max=192, plant_lo=1, plant_hi=40,
+                    plant_normalize=True, seed=123)
+    cu, w = cfg.cu_seqlens, cfg.w
+    host = [W.make_layer(cfg, l) for l in range(cfg.L)]
+    planted = [W.planted_positions(cfg, l, 0) for l in range(cfg.L)]
+    assert len({len(p) for p in planted}) > 3
+    recall = {}
+    for schedule in ("dynamic", "fixed", "pyramid", "recent"):
+        comp = Compressor(cfg, schedule=schedule, keep_cache=False)
+        for l in range(cfg.L):
+            dev = to_device(cfg, host[l])
+            comp.step(l, dev["q_win"], dev["k"], dev["v"])
+        torch.cuda.synchronize()
+        idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+        kept = total = 0
+        for l in range(cfg.L):
+            for h in range(cfg.Hkv):
+                kept += int(np.isin(planted[l], idx[l, 0][h, :counts[0, l]]).sum())
+                total += len(planted[l])
+        recall[schedule] = kept / total
+        # the oracle's own loop on the same inputs retains the same share
+        layers = [(host[l]["q_win"][0], host[l]["k"], host[l]["v"]) for l in range(cfg.L)]
+        A = [comp.scores[l].cpu().numpy()[:, :cfg.seqlens[0] - w] for l in range(cfg.L)]
+        if schedule == "dynamic":
+            r = O.compress(layers, cfg.L, w, cfg.P, cfg.layer_max, cfg.mean_budget, cfg.interval, scores_override=A,
+                           keep_buffers=False)
+        else:
+            b = (O.pyramid_layer_budgets(cfg.L, cfg.mean_budget, cfg.layer_max, 4) if schedule == "pyramid"
+                 else O.fixed_layer_budgets(cfg.L, cfg.mean_budget))
+            r = O.compress_fixed_pattern(layers, cfg.L, w, cfg.P, cfg.layer_max, b, scores_override=A,
+                                         keep_buffers=False, n_sink=4 if schedule == "recent" else None)
+        ref_kept = sum(int(np.isin(planted[l], r.idx[l][h, :r.n[l]]).sum()) for l in range(cfg.L) for h in range(cfg.Hkv))
+        assert ref_kept == kept, schedule
+        assert int(counts[0].sum()) <= cfg.global_budget
+    print("planted recall:", recall)
+    assert recall["dynamic"] > recall["fixed"] + 0.1 and recall["fixed"] > recall["recent"] + 0.1
