@@ -144,6 +144,24 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
                      int64_t scores_stride_head, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dkv_score_window for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and bit-identical
+ * output, but the row statistics that go from the first sweep to the second live in a fixed array inside the
+ * library (8 MiB of device memory per GPU the library runs on, held until the process ends) instead of a
+ * caller's workspace. The call allocates and frees nothing.
+ * Limit: the statistics of one layer, (total_tokens / 256 + n_seqs) * n_kv_heads * rows_pad * 8 bytes with
+ * rows_pad = G * ws rounded up to 64, 128 or 256, must fit dkv_static_scratch_limit() (e.g. 8 KV heads, 128 rows:
+ * about 260 000 tokens per call); a larger problem returns DKV_ERR_UNSUPPORTED and launches nothing.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or threads) race
+ * on it; calls on one stream are ordered. Nothing in it needs clearing between calls (the first sweep writes
+ * every entry the second one reads).
+ */
+int dkv_score_window_static(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                            int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                            int64_t scores_stride_head, void* stream);
+size_t dkv_static_scratch_limit(void);   /* host only: bytes of the fixed array */
+
+/*
  * dkv_score_window (Eq. 1-2) for the n_layers consecutive layers [layer_begin, layer_begin + n_layers) in one call,
  * for a caller that holds the window queries and the keys of a few layers (see dkv_select_topk_layers): a layer's
  * scores depend on that layer's Q and K only. One launch per sweep covers all the layers; a workgroup takes its

@@ -1,11 +1,36 @@
 // C ABI entry points of libdkv.so: host-side validation, then the stage launchers.
 // The operations are those of Algorithm 1 of the paper (DynamicKV in Prefill Phase); see include/dkv.h.
 #include <math.h>
+#include <mutex>
 #include "dkv_internal.h"
 
 namespace dkv {
 
 ProfileSession g_profile;
+
+// Scratch memory of dkv_score_window_static: the row statistics that go from the first sweep to the second live in
+// this array instead of a caller's workspace. Every GPU the library runs on holds its own copy at its own address
+// until the process ends; host code reaches it only through the address hipGetSymbolAddress returns for the
+// current device (the array's name is a host-side stand-in, not a device address).
+constexpr size_t kStaticScratchBytes = size_t(8) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (resolved once per device), or nullptr.
+static void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 int validate_desc(const dkv_desc* d) {
   if (d == nullptr) return DKV_ERR_INVALID_ARG;
@@ -128,7 +153,7 @@ static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, c
                                const int32_t* cu_seqlens, float* scores_out, int64_t scores_stride_head,
                                int64_t scores_stride_layer, void* workspace, size_t workspace_bytes,
                                const float* lse_in, float* lse_out, void* stream,
-                               const float* const* lse_layers = nullptr) {
+                               const float* const* lse_layers = nullptr, bool static_scratch = false) {
   int st = validate_desc(desc);
   if (st != DKV_OK) return st;
   const bool sweeps = (phases & (kPhaseStats | kPhaseEmit)) != 0;       // reads Q and K
@@ -148,7 +173,13 @@ static int score_window_phases(int phases, const dkv_desc* desc, int n_layers, c
     for (int i = 0; i < n_layers; ++i)
       if (!lse_layers[i]) return DKV_ERR_INVALID_ARG;
   const bool needs_workspace = phases != kPhaseEmit || lse_in == nullptr;   // everything but the single-layer single sweep
-  if (needs_workspace) {
+  if (static_scratch) {
+    // one layer, both sweeps: only the first layer's share of the row statistics is used
+    wl = workspace_layout(*desc);
+    if (n_layers != 1 || wl.partials + wl.partials_layer_bytes > kStaticScratchBytes) return DKV_ERR_UNSUPPORTED;
+    workspace = static_scratch_ptr();
+    if (workspace == nullptr) return DKV_ERR_LAUNCH;
+  } else if (needs_workspace) {
     st = check_workspace(*desc, workspace, workspace_bytes, wl);
     if (st != DKV_OK) return st;
   } else {
@@ -179,6 +210,15 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
   return score_window_phases(kPhaseStats | kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens,
                              scores_out, scores_stride_head, 0, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
+
+int dkv_score_window_static(const dkv_desc* desc, const void* q_win, const void* k, int64_t k_stride_token,
+                            int64_t k_stride_head, const int32_t* cu_seqlens, float* scores_out,
+                            int64_t scores_stride_head, void* stream) {
+  return score_window_phases(kPhaseStats | kPhaseEmit, desc, 1, &q_win, &k, k_stride_token, k_stride_head, cu_seqlens,
+                             scores_out, scores_stride_head, 0, nullptr, 0, nullptr, nullptr, stream, nullptr, true);
+}
+
+size_t dkv_static_scratch_limit(void) { return kStaticScratchBytes; }
 
 int dkv_score_window_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* const* h_q_layers,
                             const void* const* h_k_layers, int64_t k_stride_token, int64_t k_stride_head,

@@ -21,7 +21,7 @@ DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAU
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance", "dkv_rebalance_batch",
            "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention", "dkv_layer_budgets",
-           "dkv_apply_budgets", "dkv_select_recent", "dkv_score_path")
+           "dkv_apply_budgets", "dkv_select_recent", "dkv_score_window_static", "dkv_static_scratch_limit", "dkv_score_path")
 DKV_SCHEDULE_FIXED, DKV_SCHEDULE_PYRAMID = 0, 1
 
 
@@ -95,8 +95,12 @@ def load() -> C.CDLL:
     lib.dkv_apply_budgets.argtypes = [D, I32, P, P, P]
     lib.dkv_select_recent.restype = C.c_int
     lib.dkv_select_recent.argtypes = [D, I32, I32, P, P, P, P]
+    lib.dkv_score_window_static.restype = C.c_int
+    lib.dkv_score_window_static.argtypes = [D, P, P, I64, I64, P, P, I64, P]
     lib.dkv_score_path.restype = C.c_int
     lib.dkv_score_path.argtypes = [D, I64]
+    lib.dkv_static_scratch_limit.restype = SZ
+    lib.dkv_static_scratch_limit.argtypes = []
     _lib = lib
     return lib
 
@@ -170,6 +174,17 @@ def dkv_score_window(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, 
     _check(load().dkv_score_window(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head, _ptr(cu_seqlens),
                                    _ptr(scores_out), scores_stride_head, _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)), "dkv_score_window")
+
+
+def dkv_score_window_static(desc, q_win, k, k_stride_token, k_stride_head, cu_seqlens, scores_out, scores_stride_head,
+                            stream=None) -> None:
+    _check(load().dkv_score_window_static(C.byref(desc), _ptr(q_win), _ptr(k), k_stride_token, k_stride_head,
+                                          _ptr(cu_seqlens), _ptr(scores_out), scores_stride_head, _stream(stream)),
+           "dkv_score_window_static")
+
+
+def dkv_static_scratch_limit() -> int:
+    return int(load().dkv_static_scratch_limit())
 
 
 def dkv_layer_budgets(desc, schedule, beta=4):

@@ -313,6 +313,23 @@ def test_score_path_and_the_token_stride_limit(lib):
     assert lib.dkv_score_path(C.byref(_good(n_kv_heads=2048, n_q_heads=2048)), 64) == dkv.DKV_ERR_UNSUPPORTED
 
 
+def test_static_scratch_entry_rejects_what_does_not_fit(lib):
+    """dkv_score_window_static validates like dkv_score_window and refuses, before anything is launched, a problem
+    whose row statistics do not fit its fixed array."""
+    fake = C.c_void_p(0x1000)
+    limit = dkv.dkv_static_scratch_limit()
+    assert limit == 8 << 20
+    big = _good(head_dim=128, dtype=dkv.DKV_BF16, n_q_heads=32, n_kv_heads=8, window=32, total_tokens=1 << 19,
+                max_seq_len=1 << 19, n_layers=2)
+    need = ((1 << 19) // 256 + 1) * 8 * 128 * 8
+    assert need > limit
+    assert lib.dkv_score_window_static(C.byref(big), fake, fake, 128, 128 << 19, fake, fake, 1 << 19, None) == dkv.DKV_ERR_UNSUPPORTED
+    d = _good()
+    assert lib.dkv_score_window_static(C.byref(d), None, fake, 64, 65536, fake, fake, 1024, None) == dkv.DKV_ERR_INVALID_ARG
+    assert lib.dkv_score_window_static(C.byref(d), fake, fake, 64, 65536, fake, fake, 1000, None) == dkv.DKV_ERR_INVALID_ARG
+    assert lib.dkv_score_window_static(C.byref(_good(pool_kernel=2)), fake, fake, 64, 65536, fake, fake, 1024, None) == dkv.DKV_ERR_INVALID_ARG
+
+
 def test_binding_raises_on_error():
     d = _good(pool_kernel=2)
     with pytest.raises(dkv.DkvError):
