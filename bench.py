@@ -2,10 +2,14 @@
 """Benchmark of the DynamicKV prefill-compression hot path on one MI355X.
 
 A step = one pass of Algorithm 1's layer loop over one synthetic batch: for every layer score (two sweeps over
-K), select, gather, and the progressive update every `interval` layers - issued layer by layer (`--group 1`) or,
-by default, with one call per stage for as many layers as a call takes.  All inputs are resident in HBM before
-the timed region.  Prints ONE JSON line: context tokens compressed per second, the roofline of the dominant
-kernel (timed live with HIP events attached to its launches) and the CPU oracle timed on a bounded sample.
+K), select, gather, and the progressive update every `interval` layers.  Three schedules of the same calls are
+timed (identical results, tested): `value` is the grouped one (one call per stage for as many layers as a call
+takes: the caller holds Q_win, K and V of those layers), `value_layer_by_layer` is Algorithm 1's own order (one
+call per stage and layer) and `value_group_interval` issues the layers of one update interval together.
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line: context tokens compressed per
+second, the roofline of the score step (both sweeps and their two small kernels, K counted ONCE; timed live with
+HIP events attached to every launch) with the per-kernel figures beside it, and the CPU oracle timed on a
+bounded sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
@@ -97,32 +101,46 @@ def main():
 
     # default: as many whole update intervals as one call takes (all layers, for the configurations at hand)
     group = args.group if args.group > 0 else default_group(cfg)
-    comp = Compressor(cfg, group=group)
     d, T = cfg.d, cfg.total_tokens
-    st, sh = d, T * d
-    desc, cu, ws = comp.desc, comp.cu, comp.ws
     layers = [(x["q_win"], x["k"], x["v"]) for x in dev]
 
     # ---- throughput: the whole loop as one HIP graph, K replays between two synchronisations
-    for _ in range(max(args.warmup, 1)):
-        comp.run(layers)
-    torch.cuda.synchronize()
-    graph = comp.capture(layers, overlap=args.overlap)
-    # the GPU has idled through set-up and capture: give its clocks `--settle-ms` of load to come up (untimed,
-    # reported in the JSON line), then the warm-up passes in the form that is timed
-    t_settle = time.perf_counter() + args.settle_ms * 1e-3
-    while time.perf_counter() < t_settle:
-        graph.replay()
+    def time_schedule(g, steps, warmup):
+        c = Compressor(cfg, group=g)
+        for _ in range(max(min(warmup, 3), 1)):
+            c.run(layers)
         torch.cuda.synchronize()
-    for _ in range(max(args.warmup, 1)):
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+        graph = c.capture(layers, overlap=args.overlap)
+        # the GPU has idled through set-up and capture: give its clocks `--settle-ms` of load to come up (untimed,
+        # reported in the JSON line), then the warm-up passes in the form that is timed
+        t_settle = time.perf_counter() + args.settle_ms * 1e-3
+        while time.perf_counter() < t_settle:
+            graph.replay()
+            torch.cuda.synchronize()
+        for _ in range(max(warmup, 1)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        return c, (time.perf_counter() - t0) * 1e3 / steps
+
+    comp, ms_per_step = time_schedule(group, args.steps, args.warmup)
+    desc, cu, ws = comp.desc, comp.cu, comp.ws
+    st, sh = d, T * d
+    # the other schedules of the same calls: Algorithm 1's own order (one call per stage and layer) and one update
+    # interval per call; fewer replays (each is reported beside `value`, never as `value`)
+    other = {}
+    if not args.main_only:
+        for name, g in (("layer_by_layer", 1), ("group_interval", cfg.interval)):
+            if g == group:
+                other[name] = ms_per_step
+                continue
+            c2, ms2 = time_schedule(g, max(args.steps // 2, 5), max(args.warmup // 2, 2))
+            other[name] = ms2
+            del c2
+            torch.cuda.empty_cache()
 
     # ---- per-kernel durations: the same K steps launched eagerly inside a profiling session of the library:
     # every launch carries its own start/stop HIP event pair on the launch stream (events cannot be read back
@@ -144,37 +162,55 @@ def main():
     kernel_ms_per_step = {n: kernel_us[n] / 1e3 / args.steps for n in kernel_us}
     stage_us_per_launch = kernel_us_per_launch
 
-    # ---- roofline of the dominant kernel: algorithmic bytes per launch / its average duration
+    # ---- roofline of the score step (Eq. 1-2): all kernels of the step - statistics sweep, merge, emit sweep, border
+    # fix - against the ALGORITHMIC bytes of the step, K counted once although both sweeps read it. Units: one launch
+    # of the step covers `layers_per_launch` layers.
     elt = 2 if cfg.dtype == "bf16" else 4
-    k_bytes = cfg.Hkv * T * d * elt                 # every key row read once per sweep
+    k_bytes = cfg.Hkv * T * d * elt                 # every key row read once
     q_bytes = cfg.n_seqs * cfg.Hq * cfg.w * d * elt
     a_bytes = cfg.Hkv * T * 4                       # pooled fp32 scores written
-    # a score launch covers `group` layers (fewer at the end of an interval): bytes per launch = bytes per layer
-    # x the average number of layers per launch
-    layers_per_launch = {n: cfg.L * args.steps / kernel_n[n] for n in ("score_stats", "score_emit")}
+    step_kernels = [n for n in ("score_stats", "score_merge", "score_emit", "score_borders") if n in kernel_us]
+    layers_per_launch = cfg.L * args.steps / kernel_n["score_emit"]
+    step_us_per_launch = sum(kernel_us[n] for n in step_kernels) / kernel_n["score_emit"]
+    step_bytes_per_layer = k_bytes + q_bytes + a_bytes
+    step_bytes_per_launch = step_bytes_per_layer * layers_per_launch
+    achieved = step_bytes_per_launch / (step_us_per_launch * 1e-6) / 1e9
+    flops_per_sweep = 2.0 * cfg.Hq * cfg.w * T * d
+    mfma_tflops = 2 * flops_per_sweep * layers_per_launch / (step_us_per_launch * 1e-6) / 1e12
+    # per kernel: its own algorithmic bytes (each sweep reads K once) over its own duration
     alg_layer = {"score_stats": k_bytes + q_bytes, "score_emit": k_bytes + q_bytes + a_bytes}
-    alg = {n: alg_layer[n] * layers_per_launch[n] for n in alg_layer}
-    us_per_layer = {n: stage_us_per_launch[n] / layers_per_launch[n] for n in alg_layer}
-    dom = max(alg, key=lambda n: us_per_layer[n])
-    achieved = alg[dom] / (stage_us_per_launch[dom] * 1e-6) / 1e9
-    traffic = None
+    kernels = {}
+    traffic_file = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(cfg.name, {}).get(dom, {}).get("total_bytes")
+            traffic_file = json.load(open(tpath)).get(cfg.name, {})
         except Exception:
-            traffic = None
-    score_us = us_per_layer["score_stats"] + us_per_layer["score_emit"]
-    flops_per_sweep = 2.0 * cfg.Hq * cfg.w * T * d
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                "bytes_per_launch": alg[dom], "us_per_launch": stage_us_per_launch[dom],
-                "layers_per_launch": layers_per_launch[dom], "bytes_per_layer": alg_layer[dom],
-                # the whole score step (K counted ONCE although both sweeps read it) and its MFMA rate
-                "score_step": {"us_per_layer": score_us,
-                               "hbm_frac_k_once": (k_bytes + q_bytes + a_bytes) / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                               "mfma_tflops": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12,
-                               "mfma_frac": 2 * flops_per_sweep / (score_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+            traffic_file = {}
+    for n in ("score_stats", "score_emit"):
+        us = kernel_us[n] / kernel_n[n]
+        lpl = cfg.L * args.steps / kernel_n[n]
+        gbs = alg_layer[n] * lpl / (us * 1e-6) / 1e9
+        kernels[n] = {"us_per_launch": us, "layers_per_launch": lpl, "bytes_per_launch": alg_layer[n] * lpl,
+                      "achieved_GBs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+                      "mfma_frac": flops_per_sweep * lpl / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                      "traffic": traffic_file.get(n, {}).get("total_bytes")}
+    # counter traffic of the whole step per launch, from the committed profile (made with the grouped schedule)
+    traffic = None
+    if all(traffic_file.get(n, {}).get("total_bytes") for n in ("score_stats", "score_emit")) and group == default_group(cfg):
+        traffic = sum(traffic_file[n]["total_bytes"] for n in traffic_file if n.startswith("score_"))
+    hbm_frac, mfma_frac = achieved / HBM_PEAK_GBS, mfma_tflops / MFMA_BF16_PEAK_TFLOPS
+    roofline = {"bound": "hbm", "kernel": "score step: " + " + ".join(step_kernels) + " (K counted once)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac, "traffic": traffic,
+                "traffic_source": "profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                                  "committed; NOT measured in this run",
+                "traffic_over_algorithmic": traffic / step_bytes_per_launch if traffic else None,
+                "bytes_per_launch": step_bytes_per_launch, "us_per_launch": step_us_per_launch,
+                "us_per_layer": step_us_per_launch / layers_per_launch,
+                "layers_per_launch": layers_per_launch, "bytes_per_layer": step_bytes_per_layer,
+                "mfma_tflops": mfma_tflops, "mfma_frac": mfma_frac, "mfma_peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+                "nearer_roofline": "hbm" if hbm_frac >= mfma_frac else "mfma",
+                "kernels": kernels}
 
     if not args.main_only:
         # ---- the single-sweep variant (row normalisers supplied, as a prefill attention kernel would): reported
@@ -195,7 +231,7 @@ def main():
         rec = [us for name, us in dkv.dkv_profile_end(cfg.L * args.steps + 16) if name in ("score_emit", "score_merge")]
         single_us = sum(rec) / max(args.steps * cfg.L, 1)
         roofline["single_sweep_lse"] = {"us_per_layer": single_us, "layers_per_call": group,
-                                        "hbm_frac": (k_bytes + q_bytes + a_bytes) / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+                                        "hbm_frac": step_bytes_per_layer / (single_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
         # ---- decode attention of one new token per sequence over the final compressed cache, all layers (reported
         # beside the main figure, not part of `value`)
@@ -221,13 +257,19 @@ def main():
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": cfg.dtype, "data": "synthetic", "streams": 2 if args.overlap else 1, "layers_per_call": group, "settle_ms": args.settle_ms,
-           "config": {"workload": cfg.name, "layers": cfg.L, "q_heads": cfg.Hq, "kv_heads": cfg.Hkv, "head_dim": d,
+           "schedule": ("layer by layer (Algorithm 1's order)" if group == 1 else
+                        "grouped: one call per stage for %d layers; the caller holds Q_win, K, V of those layers "
+                        "(results identical to layer by layer)" % group),
+           "config": {"workload": cfg.name, "schedule_layers_per_call": group, "layers": cfg.L, "q_heads": cfg.Hq, "kv_heads": cfg.Hkv, "head_dim": d,
                       "context": list(cfg.seqlens), "window": cfg.w, "pool": cfg.P, "mean_budget": cfg.mean_budget,
                       "layer_max": cfg.layer_max, "interval": cfg.interval},
            "roofline": roofline,
            "kernel_us_per_launch": kernel_us_per_launch, "kernel_ms_per_step": kernel_ms_per_step,
            "kernel_ms_per_step_total": sum(kernel_ms_per_step.values())}
     out["eager_enqueue_ms_per_step"] = enqueue_ms
+    for name, ms in other.items():
+        out["ms_per_step_" + name] = ms
+        out["value_" + name] = T / (ms * 1e-3)
     if args.copy_calibration:
         x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         y = torch.empty_like(x)

@@ -148,7 +148,9 @@ int dkv_score_window(const dkv_desc* desc, const void* q_win, const void* k, int
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and bit-identical
  * output, but the row statistics that go from the first sweep to the second live in a fixed array inside the
  * library (8 MiB of device memory per GPU the library runs on, held until the process ends) instead of a
- * caller's workspace. The call allocates and frees nothing.
+ * caller's workspace. The call allocates and frees nothing; the first call on a device looks up the array's device
+ * address (the runtime loads the code object that holds the array at that point, if it has not yet), so a caller
+ * under stream capture makes one call outside the capture first.
  * Limit: the statistics of one layer, (total_tokens / 256 + n_seqs) * n_kv_heads * rows_pad * 8 bytes with
  * rows_pad = G * ws rounded up to 64, 128 or 256, must fit dkv_static_scratch_limit() (e.g. 8 KV heads, 128 rows:
  * about 260 000 tokens per call); a larger problem returns DKV_ERR_UNSUPPORTED and launches nothing.

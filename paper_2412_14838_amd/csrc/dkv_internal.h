@@ -14,6 +14,7 @@ namespace dkv {
 constexpr int kGenericKeys = 256;      // keys per workgroup in the generic (VALU) score kernels
 constexpr int kMfmaMinChunk = 256;     // smallest chunk of keys per workgroup in the MFMA score kernels
 constexpr int kRadixBins = 2048;       // 11-bit digits; 3 passes cover bits 31..21, 20..10, 9..0
+constexpr int kSelectSegment = 32768;  // row positions one selection workgroup keeps in registers
 
 // ----------------------------------------------------------------------------------------------
 // Workspace layout (byte offsets, all 256-byte aligned)
@@ -42,6 +43,10 @@ struct WorkspaceLayout {
   size_t update_block_bytes;   // tot1 .. above of one class; DKV_MAX_UPDATES such blocks follow each other
   size_t picks;        // int32 [DKV_MAX_UPDATES][n_seqs][4]  per update: digit 0 of its threshold, rank left inside it, digit 1, rank left inside that
   size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
+  // two-level selection of rows longer than one workgroup keeps in registers (absent when no row can be that long)
+  size_t select_cand_val;  // uint32 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][select_segments][layer_max]  candidates' score bits
+  size_t select_cand_pos;  // int32, same shape: their positions
+  int select_segments;     // segments of the longest row the descriptor admits (1: single-level selection)
   size_t total;
   int rows_pad;        // padded_rows(G*w)
   int chunks_max;      // upper bound on statistics chunks over all sequences
@@ -70,6 +75,14 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   off += w.edges_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.decode_partials = off;
   off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
+  {
+    const int longest = d.max_seq_len > d.window ? d.max_seq_len - d.window : 0;
+    w.select_segments = longest > kSelectSegment ? (longest + kSelectSegment - 1) / kSelectSegment : 1;
+    const size_t entries = w.select_segments > 1
+        ? size_t(DKV_MAX_SELECT_LAYERS) * d.n_seqs * d.n_kv_heads * w.select_segments * d.layer_max : 0;
+    w.select_cand_val = off; off += align256(entries * sizeof(uint32_t));
+    w.select_cand_pos = off; off += align256(entries * sizeof(int32_t));
+  }
   w.header = off;   off += align256(16 * sizeof(int32_t));
   w.tot0_slot_bytes = align256(size_t(d.n_seqs) * kRadixBins * sizeof(int32_t));
   w.tot0 = off;     off += w.tot0_slot_bytes * DKV_MAX_UPDATES;

@@ -7,6 +7,14 @@
 //      above T, and the first (k - #above) elements equal to T in position order (ties go to the lower position).
 //   3. the k winners are ordered by (score descending, position ascending) = ascending key: bucketed by the
 //      leading bits of their scores, the buckets laid out by a scan, the few keys of a bucket ranked by counting.
+//
+// Rows longer than the 32768 positions a workgroup keeps in registers are selected in two levels, each the same
+// kernel: level 1 cuts the row into segments of 32768 positions, one workgroup per segment, and leaves every
+// segment's own top-k (score and position, in POSITION order) in the workspace; level 2 selects the top-k of those
+// candidates with one workgroup per row. Every element of a row's top-k is in its segment's top-k, and both levels
+// break ties toward the lower position (the candidates lie in position order), so the result is the single-level
+// one bit for bit; a row of a million positions costs its segments' parallel passes plus one pass over 63 488
+// candidates instead of a serial walk over the whole row by one workgroup.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -16,6 +24,7 @@ constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kHistCopies = 8;
 constexpr int kSelPerThread = 32;                              // row positions a thread keeps in registers
 constexpr int kSelResident = kSelPerThread * kSelThreads;      // 32768 positions
+static_assert(kSelResident == kSelectSegment, "the workspace is sized for segments of what one workgroup holds");
 
 typedef unsigned long long u64;
 
@@ -41,8 +50,26 @@ __device__ inline int block_exclusive_scan(int v, int* scratch) {
   return base + incl - v;
 }
 
-// grid = (Hkv, n_seqs, layers of the call); blockIdx.z picks the layer: its scores, index list and key block lie
-// blockIdx.z layer strides behind the pointers passed in.
+// Candidates of the two-level selection: segment g of row r (r = (layer of the call * n_seqs + seq) * Hkv + head) owns
+// entries [r * cand_stride + g * layer_max, + its k) of cand_val (score bit patterns) and cand_pos (positions).
+struct SelectCandidates {
+  uint32_t* val;
+  int32_t* pos;
+  int64_t stride;      // entries per row: segments_max * layer_max
+  int segments_max;    // segments of the longest row the descriptor admits
+};
+
+enum { kSelDirect = 0, kSelSegments = 1, kSelMerge = 2 };
+
+// Candidates a row of n positions leaves behind level 1: layer_max per full segment, min(layer_max, rest) for the last.
+__host__ __device__ inline int candidates_of(int n, int layer_max) {
+  const int full = n / kSelResident, rest = n - full * kSelResident;
+  return full * (layer_max < kSelResident ? layer_max : kSelResident) + (rest < layer_max ? rest : layer_max);
+}
+
+// grid = (Hkv, n_seqs [x segments_max for MODE == kSelSegments], layers of the call); blockIdx.z picks the layer: its
+// scores, index list and key block lie blockIdx.z layer strides behind the pointers passed in.
+template <int MODE>
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer0,
                                                                   const float* __restrict__ scores0,
                                                                   int64_t scores_stride_head,
@@ -50,7 +77,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
                                                                   const int32_t* __restrict__ cu,
                                                                   int32_t* __restrict__ idx_out0,
                                                                   int64_t idx_stride_layer,
-                                                                  int32_t* __restrict__ counts) {
+                                                                  int32_t* __restrict__ counts, SelectCandidates cand) {
   extern __shared__ __attribute__((aligned(16))) char sel_smem[];
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
@@ -59,22 +86,49 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   __shared__ int n_greater_slots;
   __shared__ int wave_eq[kSelWaves];
 
-  const int seq = blockIdx.y, head = blockIdx.x;
+  const int seq = MODE == kSelSegments ? blockIdx.y / cand.segments_max : blockIdx.y, head = blockIdx.x;
+  const int segment = MODE == kSelSegments ? blockIdx.y % cand.segments_max : 0;
   const int layer = layer0 + blockIdx.z;
   const float* __restrict__ scores = scores0 + (int64_t)blockIdx.z * scores_stride_layer;
   int32_t* __restrict__ idx_out = idx_out0 + (int64_t)blockIdx.z * idx_stride_layer;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int begin = cu[seq];
   const int S = cu[seq + 1] - begin;
-  const int n = S > w ? S - w : 0;
-  const int k = layer_max < n ? layer_max : n;
-  int32_t* __restrict__ out = idx_out + ((int64_t)seq * Hkv + head) * layer_max;
-  if (head == 0 && tid == 0) counts[seq * L + layer] = k;
-  if (k == 0) {
-    for (int j = tid; j < layer_max; j += kSelThreads) out[j] = -1;
-    return;
+  const int n_row = S > w ? S - w : 0;                       // candidate positions of the whole row
+  const int n_seqs = MODE == kSelSegments ? gridDim.y / cand.segments_max : gridDim.y;
+  const int64_t cand_row = (((int64_t)blockIdx.z * n_seqs + seq) * Hkv + head) * cand.stride;
+  // what this workgroup selects from: the row, one segment of it, or the row's candidates
+  int n, k;
+  const uint32_t* __restrict__ row;
+  if (MODE == kSelSegments) {
+    const int seg_begin = segment * kSelResident;
+    n = n_row - seg_begin;
+    if (n <= 0) return;                                       // the row has fewer segments
+    n = n < kSelResident ? n : kSelResident;
+    k = layer_max < n ? layer_max : n;
+    row = reinterpret_cast<const uint32_t*>(scores + (int64_t)head * scores_stride_head + begin) + seg_begin;
+  } else if (MODE == kSelMerge) {
+    n = candidates_of(n_row, layer_max);
+    k = layer_max < n_row ? layer_max : n_row;
+    row = cand.val + cand_row;
+  } else {
+    n = n_row;
+    k = layer_max < n ? layer_max : n;
+    row = reinterpret_cast<const uint32_t*>(scores + (int64_t)head * scores_stride_head + begin);
   }
-  const uint32_t* __restrict__ row = reinterpret_cast<const uint32_t*>(scores + (int64_t)head * scores_stride_head + begin);
+  int32_t* __restrict__ out = idx_out + ((int64_t)seq * Hkv + head) * layer_max;
+  if (MODE != kSelSegments) {
+    if (head == 0 && tid == 0) counts[seq * L + layer] = k;
+    if (k == 0) {
+      for (int j = tid; j < layer_max; j += kSelThreads) out[j] = -1;
+      return;
+    }
+  }
+  // 64-bit key of element i with bit pattern u; ascending keys are the order the winners are written in:
+  // (score descending, position ascending) for a final list, position ascending for a segment's candidates
+  auto make_key = [](uint32_t u, int i) -> u64 {
+    return MODE == kSelSegments ? ((u64)(uint32_t)i << 32) | u : ((u64)(~u) << 32) | (uint32_t)i;
+  };
 
   // The first kSelResident positions of the row live in registers for all passes: thread t holds positions
   // j * 1024 + t (coalesced loads, issued back to back). Longer rows re-read their tail from memory.
@@ -168,7 +222,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   for (int j = 0; j < kSelPerThread; ++j) {
     const int i = j * kSelThreads + tid;
     const uint32_t u = v[j];
-    if (i < n_res && u > T) keys[slot++] = ((u64)(~u) << 32) | (uint32_t)i;
+    if (i < n_res && u > T) keys[slot++] = make_key(u, i);
   }
   __syncthreads();
   {
@@ -186,7 +240,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     const unsigned long long emask = __ballot(eq);
     if (eq) {
       const int rank = eq_base[j * kSelWaves + wv] + __popcll(emask & ((1ull << lane) - 1ull));
-      if (rank < need_eq) keys[n_gt + rank] = ((u64)(~T) << 32) | (uint32_t)i;
+      if (rank < need_eq) keys[n_gt + rank] = make_key(T, i);
     }
   }
   if (n > kSelResident) {
@@ -217,7 +271,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
           int base = 0;
           if (lane == 0) base = atomicAdd(&n_greater_slots, __popcll(gmask));
           base = __shfl(base, 0);
-          if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = ((u64)(~u) << 32) | (uint32_t)i;
+          if (gt) keys[base + __popcll(gmask & ((1ull << lane) - 1ull))] = make_key(u, i);
         }
       }
     }
@@ -231,7 +285,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       const unsigned long long emask = __ballot(eq);
       if (eq) {
         const int rank = running + __popcll(emask & ((1ull << lane) - 1ull));
-        if (rank < need_eq) keys[n_gt + rank] = ((u64)(~T) << 32) | (uint32_t)i;
+        if (rank < need_eq) keys[n_gt + rank] = make_key(T, i);
       }
       running += __popcll(emask);
     }
@@ -302,10 +356,19 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       const int first = bstart[bin[c]], n_in = bcount[bin[c]];
       int rank = first;
       for (int i = 0; i < n_in; ++i) rank += sorted[first + i] < mine[c] ? 1 : 0;
-      out[rank] = (int32_t)(uint32_t)mine[c];
+      if (MODE == kSelSegments) {            // the segment's candidates, in position order
+        const int64_t e = cand_row + (int64_t)segment * layer_max + rank;
+        cand.val[e] = (uint32_t)mine[c];
+        cand.pos[e] = segment * kSelResident + (int32_t)(mine[c] >> 32);
+      } else if (MODE == kSelMerge) {        // the key's low half is a place in the candidate list
+        out[rank] = cand.pos[cand_row + (uint32_t)mine[c]];
+      } else {
+        out[rank] = (int32_t)(uint32_t)mine[c];
+      }
     }
   }
-  for (int j = k + tid; j < layer_max; j += kSelThreads) out[j] = -1;
+  if (MODE != kSelSegments)
+    for (int j = k + tid; j < layer_max; j += kSelThreads) out[j] = -1;
 }
 
 hipError_t launch_select(const Params& p, int layer, int n_layers, const float* scores, int64_t scores_stride_head,
@@ -314,14 +377,31 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
   const size_t lds = 2048 * sizeof(u64) + (size_t)kRadixBins * kHistCopies * sizeof(int);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_topk_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    for (const void* f : {reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelSegments>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge>)}) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
-  (void)ws; (void)wl;   // the selection needs no scratch memory any more
-  launch(DKV_KERNEL_SELECT, select_topk_kernel, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st, p.Hkv, p.w,
-         p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts);
+  SelectCandidates cand{};
+  if (wl.select_segments <= 1) {      // every row fits the registers of one workgroup
+    launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelDirect>, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
+           p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
+           idx_stride_layer, counts, cand);
+    return hipGetLastError();
+  }
+  cand.val = reinterpret_cast<uint32_t*>(ws + wl.select_cand_val);
+  cand.pos = reinterpret_cast<int32_t*>(ws + wl.select_cand_pos);
+  cand.segments_max = wl.select_segments;
+  cand.stride = (int64_t)wl.select_segments * p.layer_max;
+  launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelSegments>, dim3(p.Hkv, p.n_seqs * wl.select_segments, n_layers),
+         dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer,
+         cu, idx_out, idx_stride_layer, counts, cand);
+  launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelMerge>, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
+         p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
+         idx_stride_layer, counts, cand);
   return hipGetLastError();
 }
 

@@ -80,6 +80,28 @@ def test_bad_descriptors_are_rejected(lib, bad, status):
                                     2 * 272 * 64, 2 * 272 * 64, 272 * 64, None) == status
 
 
+def test_long_contexts_size_the_two_level_selection_and_stop_at_the_index_limit(lib):
+    """A descriptor whose rows can pass 32768 candidate positions asks for the candidate lists of the two-level
+    selection (layers of a call x rows x segments x layer_max x 8 bytes); score tensors of more than 2^31 elements
+    (the index arithmetic of the update is 32-bit per layer block) are refused with DKV_ERR_UNSUPPORTED."""
+    kw = dict(head_dim=128, dtype=dkv.DKV_BF16, n_q_heads=32, n_kv_heads=8, window=32, layer_max=2048, mean_budget=512,
+              n_layers=32, interval=4)
+    short = dkv.dkv_workspace_bytes(_good(total_tokens=32768 + 32, max_seq_len=32768 + 32, **kw))
+    longer = dkv.dkv_workspace_bytes(_good(total_tokens=32768 + 33, max_seq_len=32768 + 33, **kw))
+    assert longer - short >= 32 * 8 * 2 * 2048 * 8 and longer - short < 32 * 8 * 2 * 2048 * 8 + (1 << 20)
+    million = _good(total_tokens=1 << 20, max_seq_len=1 << 20, **kw)
+    assert dkv.dkv_workspace_bytes(million) > 32 * 8 * 32 * 2048 * 8
+    fake = C.c_void_p(0x1000)
+    # 32 layers x 8 heads x 2^23 tokens = 2^31 elements: the last size that is accepted; one more layer is not
+    edge = _good(total_tokens=1 << 23, max_seq_len=1 << 23, **kw)
+    assert dkv.dkv_workspace_bytes(edge) > 0
+    over = _good(total_tokens=1 << 23, max_seq_len=1 << 23, **dict(kw, n_layers=36))
+    assert dkv.dkv_workspace_bytes(over) == 0
+    assert lib.dkv_select_topk(C.byref(over), 0, fake, 1 << 23, fake, fake, fake, fake, 1 << 40, None) == dkv.DKV_ERR_UNSUPPORTED
+    assert lib.dkv_rebalance(C.byref(over), 4, 0, fake, fake, fake, None, None, fake, 1 << 40, None) == dkv.DKV_ERR_UNSUPPORTED
+    assert lib.dkv_score_window(C.byref(over), fake, fake, 128, 128 << 23, fake, fake, 1 << 23, fake, 1 << 40, None) == dkv.DKV_ERR_UNSUPPORTED
+
+
 def test_bad_call_arguments_are_rejected(lib):
     d = _good()
     need = dkv.dkv_workspace_bytes(d)

@@ -182,6 +182,40 @@ def test_select_topk_large_k_and_long_rows(dkv):
         assert np.array_equal(idx[s][:, :ref.shape[1]], ref)
 
 
+@pytest.mark.parametrize("seqlens", [(1 << 20,), (70000, 300, 32768 + 32, 32769 + 32, 140000, 20)])
+def test_select_topk_two_levels_for_rows_past_one_workgroup(dkv, seqlens):
+    """Rows longer than the 32768 positions a workgroup holds go through segments and a merge: a row of a million
+    positions, and a ragged batch whose rows have one, exactly one, two, three and five segments (and none), with
+    heavy ties (few distinct values, plateaus that straddle the segment borders, all-equal rows), several layers per
+    call. Bit-exact against the oracle's stable sort."""
+    cfg = small_cfg("two_level", Hq=2, Hkv=2, seqlens=seqlens, layer_max=2048, mean_budget=512, L=3, interval=3)
+    comp = Compressor(cfg, keep_cache=False)
+    cu, T = cfg.cu_seqlens, cfg.total_tokens
+    rng = np.random.default_rng(11)
+    smooth = np.abs(rng.standard_normal((cfg.Hkv, T))).astype(np.float32)
+    plateaus = np.maximum.reduce([np.roll(smooth, r, axis=1) for r in range(-3, 4)])
+    few = (rng.integers(0, 5, size=(cfg.Hkv, T)) / 8).astype(np.float32)
+    few[1] = 0.25                                          # one head: all scores equal
+    A = np.stack([smooth, plateaus, few])
+    comp.scores.copy_(torch.from_numpy(A))
+    comp.idx.fill_(-7)
+    comp.select_layers(0, cfg.L)
+    torch.cuda.synchronize()
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    for l in range(cfg.L):
+        for s in range(cfg.n_seqs):
+            pre = max(cfg.seqlens[s] - cfg.w, 0)
+            ref = O.select_topk(A[l][:, cu[s]:cu[s] + pre], cfg.layer_max)
+            k = ref.shape[1]
+            assert counts[s, l] == k
+            assert np.array_equal(idx[l, s][:, :k], ref), (l, s)
+            assert (idx[l, s][:, k:] == -1).all()
+    comp.idx.fill_(-7)
+    comp.select(1)                                         # and the single-layer call
+    torch.cuda.synchronize()
+    assert np.array_equal(comp.idx[1].cpu().numpy(), idx[1])
+
+
 @pytest.mark.parametrize("case", ["tiny", "ragged_f32", "small_bf16_d64"])
 def test_gather_kv_bit_exact(dkv, case):
     cfg = CASES[case]

@@ -1,6 +1,9 @@
 """The entry point that allocates nothing (dkv_score_window_static) against dkv_score_window, through the C ABI:
-two calls in a row, the second with a smaller input, must each give bit-identical scores; no device memory is
-allocated during the calls."""
+two calls in a row, the second with a smaller input, must each give bit-identical scores. The first call on a
+device resolves the address of the library's fixed array (the runtime loads the code object that holds it then);
+from the second call on the device's free memory must not shrink during a call."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -31,11 +34,12 @@ def test_static_scratch_scoring_equals_workspace_scoring(dkv, kind):
         T, d = cfg.total_tokens, cfg.d
         comp.score(0, dev["q_win"], dev["k"])                                   # the existing entry point
         out = torch.full_like(comp.scores[1], 7.0)
+        gc.collect()                        # tensors of earlier tests must not be freed in the middle of the comparison
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        free_before = torch.cuda.mem_get_info()[0]        # hipMemGetInfo: sees every allocation, not only torch's
         dkv.dkv_score_window_static(comp.desc, dev["q_win"], dev["k"], d, T * d, comp.cu, out, T)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        assert cfg is big or torch.cuda.mem_get_info()[0] >= free_before
         assert torch.equal(out.view(torch.int32), comp.scores[0].view(torch.int32)), cfg.name
         # and against the oracle, to the bar of the scoring tests
         cu = cfg.cu_seqlens
