@@ -49,6 +49,16 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     if verbose:
         print("built", LIB)
+    # the stand-alone measurement programs under tests/probes (not part of the library)
+    probes = os.path.join(os.path.dirname(HERE), "tests", "probes")
+    for src in sorted(glob.glob(os.path.join(probes, "*.hip"))):
+        exe = src[:-4]
+        r = subprocess.run(["hipcc", "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                            "-o", exe, src], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+        if verbose:
+            print("built", exe)
     return LIB
 
 
