@@ -117,8 +117,9 @@ int dkv_score_path(const dkv_desc* desc, int64_t k_stride_token);
  * dkv_profile_end(...) every kernel the library launches (up to `capacity`) carries a start/stop HIP event pair
  * on its launch stream; dkv_profile_end waits for them, writes the kernel identifiers and durations of the
  * first min(n, max_out) launches in launch order and returns n, the number of launches recorded (or a negative
- * status). The session is process-wide state of the library: one session at a time, not during stream capture,
- * and not concurrently with stage calls from other threads.
+ * status). The session is the one piece of process-wide state in the library: one session at a time (a second begin
+ * returns DKV_ERR_INVALID_ARG), not during stream capture. Stage calls from other threads may run during a session
+ * (they take their slots atomically); outside a session a launch reads one integer and is otherwise untouched.
  */
 int dkv_profile_begin(int32_t capacity);
 int dkv_profile_end(int32_t* kernel_ids_out /* host */, float* microseconds_out /* host */, int32_t max_out);

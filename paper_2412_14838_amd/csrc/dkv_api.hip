@@ -96,27 +96,42 @@ const char* dkv_status_string(int status) {
   }
 }
 
+static std::mutex g_profile_mutex;   // begin / end exclude each other; launches take their slots atomically
+
+static void profile_release(int created) {
+  for (int j = 0; j < created; ++j) { (void)hipEventDestroy(g_profile.start[j]); (void)hipEventDestroy(g_profile.stop[j]); }
+  delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
+  g_profile.start = g_profile.stop = nullptr;
+  g_profile.kernel_id = nullptr;
+  g_profile.count.store(0);
+}
+
 int dkv_profile_begin(int32_t capacity) {
-  if (capacity < 1 || g_profile.capacity != 0) return DKV_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  if (capacity < 1 || g_profile.capacity.load() != 0) return DKV_ERR_INVALID_ARG;
   g_profile.start = new hipEvent_t[capacity];
   g_profile.stop = new hipEvent_t[capacity];
   g_profile.kernel_id = new int32_t[capacity];
   for (int i = 0; i < capacity; ++i) {
-    if (hipEventCreate(&g_profile.start[i]) != hipSuccess || hipEventCreate(&g_profile.stop[i]) != hipSuccess) {
-      for (int j = 0; j <= i; ++j) { (void)hipEventDestroy(g_profile.start[j]); if (j < i) (void)hipEventDestroy(g_profile.stop[j]); }
-      delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
-      g_profile = ProfileSession{};
+    const bool a = hipEventCreate(&g_profile.start[i]) == hipSuccess;
+    const bool b = a && hipEventCreate(&g_profile.stop[i]) == hipSuccess;
+    if (!b) {
+      if (a) (void)hipEventDestroy(g_profile.start[i]);
+      profile_release(i);
       return DKV_ERR_LAUNCH;
     }
   }
-  g_profile.count = 0;
-  g_profile.capacity = capacity;
+  g_profile.count.store(0);
+  g_profile.capacity.store(capacity, std::memory_order_release);   // from here on launches record
   return DKV_OK;
 }
 
 int dkv_profile_end(int32_t* kernel_ids_out, float* microseconds_out, int32_t max_out) {
-  if (g_profile.capacity == 0) return DKV_ERR_INVALID_ARG;
-  const int n = g_profile.count;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  const int capacity = g_profile.capacity.exchange(0);              // launches stop recording first
+  if (capacity == 0) return DKV_ERR_INVALID_ARG;
+  const int asked = g_profile.count.load();
+  const int n = asked < capacity ? asked : capacity;
   int status = DKV_OK;
   for (int i = 0; i < n; ++i) {
     float ms = 0.0f;
@@ -127,9 +142,7 @@ int dkv_profile_end(int32_t* kernel_ids_out, float* microseconds_out, int32_t ma
       microseconds_out[i] = ms * 1000.0f;
     }
   }
-  for (int i = 0; i < g_profile.capacity; ++i) { (void)hipEventDestroy(g_profile.start[i]); (void)hipEventDestroy(g_profile.stop[i]); }
-  delete[] g_profile.start; delete[] g_profile.stop; delete[] g_profile.kernel_id;
-  g_profile = ProfileSession{};
+  profile_release(capacity);
   return status == DKV_OK ? n : status;
 }
 

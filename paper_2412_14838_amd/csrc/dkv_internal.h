@@ -4,6 +4,7 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 #include "../../include/dkv.h"
 
 namespace dkv {
@@ -107,20 +108,23 @@ struct ProfileSession {
   hipEvent_t* start = nullptr;
   hipEvent_t* stop = nullptr;
   int32_t* kernel_id = nullptr;
-  int capacity = 0;
-  int count = 0;
+  std::atomic<int> capacity{0};   // 0: no session (the only thing a launch outside a session reads)
+  std::atomic<int> count{0};      // launches that asked for a slot (may pass capacity: those are not recorded)
 };
 extern ProfileSession g_profile;
 
 template <typename Kernel, typename... Args>
 inline void launch(int kernel_id, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, Args... args) {
-  if (g_profile.count < g_profile.capacity) {
-    const int i = g_profile.count++;
-    g_profile.kernel_id[i] = kernel_id;
-    hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, st, g_profile.start[i], g_profile.stop[i], 0, args...);
-  } else {
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, args...);
+  const int capacity = g_profile.capacity.load(std::memory_order_acquire);
+  if (capacity > 0) {                                  // slots are handed out atomically: stage calls from several
+    const int i = g_profile.count.fetch_add(1, std::memory_order_relaxed);   // threads may launch during a session
+    if (i < capacity) {
+      g_profile.kernel_id[i] = kernel_id;
+      hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, st, g_profile.start[i], g_profile.stop[i], 0, args...);
+      return;
+    }
   }
+  hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, args...);
 }
 
 // Host-side descriptor validation shared by every entry point. Returns DKV_OK or a negative status.

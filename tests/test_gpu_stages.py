@@ -388,6 +388,32 @@ def test_sequence_not_longer_than_window(dkv):
     assert np.array_equal(kb[2][:, 12:32], data["k"][:, cu[2]:cu[3]])
 
 
+def test_empty_sequences_inside_a_batch(dkv):
+    """A sequence of zero tokens between real ones owns no chunk, no candidates and no rows: the whole loop (both
+    schedules) treats the others exactly as if it were absent."""
+    with_empty = small_cfg("with_empty", seqlens=(700, 0, 33, 0, 1500), L=2, interval=2, layer_max=96, mean_budget=24)
+    without = with_empty.with_(name="without", seqlens=(700, 33, 1500))
+    keep = [0, 2, 4]
+    for group in (1, 2):
+        a, b = Compressor(with_empty, group=group), Compressor(without, group=group)
+        a.kb.fill_(-3.0)
+        for l in range(with_empty.L):
+            data = W.make_layer(without, l)
+            dev = to_device(without, data)          # same tokens: an empty sequence adds none
+            a.step(l, torch.cat([dev["q_win"][:1], dev["q_win"][:1], dev["q_win"][1:2], dev["q_win"][:1], dev["q_win"][2:]]),
+                   dev["k"], dev["v"])
+            b.step(l, dev["q_win"], dev["k"], dev["v"])
+        torch.cuda.synchronize()
+        assert torch.equal(a.scores, b.scores)
+        assert torch.equal(a.idx[:, keep], b.idx) and torch.equal(a.counts[keep], b.counts)
+        assert (a.counts[[1, 3]] == 0).all() and (a.idx[:, [1, 3]] == -1).all() and (a.kb[:, [1, 3]] == -3.0).all()
+        n = b.counts.cpu().numpy()
+        for l in range(with_empty.L):
+            for q, qa in enumerate(keep):
+                rows = with_empty.w + int(n[q, l])
+                assert torch.equal(a.kb[l, qa][:, :rows], b.kb[l, q][:, :rows]) and torch.equal(a.vb[l, qa][:, :rows], b.vb[l, q][:, :rows])
+
+
 def test_layer_batched_select_and_gather_equal_per_layer_calls(dkv):
     """dkv_select_topk_layers / dkv_gather_kv_layers over layers [1, 4) of a ragged batch give, bit for bit, what
     per-layer calls give (which the tests above check against the oracle); other layers' blocks stay untouched."""
