@@ -160,7 +160,6 @@ def main():
         kernel_n[name] = kernel_n.get(name, 0) + 1
     kernel_us_per_launch = {n: kernel_us[n] / kernel_n[n] for n in kernel_us}
     kernel_ms_per_step = {n: kernel_us[n] / 1e3 / args.steps for n in kernel_us}
-    stage_us_per_launch = kernel_us_per_launch
 
     # ---- roofline of the score step (Eq. 1-2): all kernels of the step - statistics sweep, merge, emit sweep, border
     # fix - against the ALGORITHMIC bytes of the step, K counted once although both sweeps read it. Units: one launch
