@@ -251,6 +251,22 @@ def main():
         dec_bytes = rows * cfg.Hkv * d * elt * 2 / cfg.L                      # K and V rows read per layer
         roofline["decode_attention"] = {"us_per_layer": dec_us, "cache_bytes_per_layer": dec_bytes,
                                         "hbm_frac": dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        # the same with the layers of a call in one launch (up to 32): the kernels without the per-layer launch latency
+        n_call = min(cfg.L, dkv.DKV_MAX_SELECT_LAYERS)
+        q_all = torch.randn((n_call, cfg.n_seqs, cfg.Hq, d), device="cuda").to(comp.tdtype)
+        out_all = torch.empty((n_call, cfg.n_seqs, cfg.Hq, d), dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            comp.decode_attention_layers(0, n_call, q_all, out_all)
+        torch.cuda.synchronize()
+        dkv.dkv_profile_begin(2 * args.steps + 16)
+        for _ in range(args.steps):
+            comp.decode_attention_layers(0, n_call, q_all, out_all)
+        torch.cuda.synchronize()
+        rec = [us for name, us in dkv.dkv_profile_end(2 * args.steps + 16) if name == "decode"]
+        call_us = sum(rec) / max(args.steps, 1)
+        roofline["decode_attention"]["layers_in_one_call"] = {
+            "layers": n_call, "us_per_call": call_us, "us_per_layer": call_us / n_call,
+            "hbm_frac": dec_bytes * n_call / (call_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
 
     out = {"metric": "context tokens compressed/s (all layers)", "value": T / (ms_per_step * 1e-3),
            "unit": "context tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

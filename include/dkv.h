@@ -374,6 +374,23 @@ int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new,
                          float* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dkv_decode_attention (Section 4.3) for the n_layers consecutive layers [layer_begin, layer_begin + n_layers) in one
+ * call, for a caller that holds the new token's queries of several layers at once (layers evaluated side by side:
+ * verification of drafted tokens against stored queries, parallel-attention blocks, a benchmark of the kernel); an
+ * ordinary decoder produces layer l+1's query from layer l's output and uses the single-layer call. One layer's
+ * cache is a few megabytes and one launch per layer is bound by launch latency; one launch over all layers streams
+ * the whole compressed cache. Results are identical to n_layers dkv_decode_attention calls.
+ * q_new_all  [n_layers][n_seqs][Hq][d] contiguous: the queries of layer layer_begin + i at index i.
+ * kb_all, vb_all  the whole cache dkv_gather_kv wrote: layer l at kb_all + l * stride_layer (elements).
+ * out_all    fp32 [n_layers][n_seqs][Hq][d]; lse_all fp32 [n_layers][n_seqs][Hq] or NULL.
+ * n_layers   1 .. DKV_MAX_SELECT_LAYERS, layer_begin + n_layers <= L.
+ */
+int dkv_decode_attention_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* q_new_all,
+                                const void* kb_all, const void* vb_all, int64_t stride_layer, int64_t stride_seq,
+                                int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts, float* out_all,
+                                float* lse_all, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Fixed-pattern schedules: the comparison methods of Section 5.1 ("Baselines") and Figure 1 (b), (c) as alternative
  * producers of `counts`, through the same scoring, selection and compaction calls. The paper names the patterns
  * and gives no formulas; the readings:

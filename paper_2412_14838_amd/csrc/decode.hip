@@ -22,10 +22,17 @@ __device__ inline float elem_to_float(float x) { return x; }
 // the first w slots, the n retained rows follow from slot w.
 __device__ inline int cache_slot(int r, int w, int wq) { return r < wq ? w - wq + r : w + (r - wq); }
 
-// grid = (slabs, Hkv, n_seqs), 256 threads. partial layout: [seq][Hq][slab][D + 2] floats: m, l, acc[D].
+// Strides (in elements) from one layer of a call to the next: queries, cache blocks, partial results, outputs.
+struct DecodeLayerStrides {
+  int64_t q, cache, partial, out, lse;
+};
+
+// grid = (slabs x layers of the call, Hkv, n_seqs), 256 threads. partial layout per layer: [seq][Hq][slab][D + 2]
+// floats: m, l, acc[D]. Layer i of the call is layer `layer` + i; its tensors lie i layer strides behind the pointers.
 template <typename T, int D>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int layer_max, int L, int layer, int Hq,
-                                                                     int G, float scale, const T* __restrict__ q_new,
+                                                                     int G, float scale, int n_slabs,
+                                                                     DecodeLayerStrides ls_, const T* __restrict__ q_new,
                                                                      const T* __restrict__ kb, const T* __restrict__ vb,
                                                                      int64_t stride_seq, int64_t stride_head,
                                                                      const int32_t* __restrict__ cu,
@@ -39,8 +46,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int 
   __shared__ float qs[kDecodeMaxGroup * D];
   __shared__ float xs[kDecodeMaxGroup * ROWS];          // logits, then exp(x - m)
   __shared__ float ms[kDecodeMaxGroup], ls[kDecodeMaxGroup];
-  const int slab = blockIdx.x, head = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
-  const int n_slabs = gridDim.x;
+  const int slab = blockIdx.x % n_slabs, lz = blockIdx.x / n_slabs, head = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
+  layer += lz;
+  q_new += lz * ls_.q;
+  kb += lz * ls_.cache;
+  vb += lz * ls_.cache;
+  partial += lz * ls_.partial;
   const int S = cu[seq + 1] - cu[seq];
   const int wq = S < w ? S : w;
   int n = counts[seq * L + layer];
@@ -111,17 +122,22 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int 
   }
 }
 
-// grid = (Hq, n_seqs), D threads: thread j merges element j of the slabs that hold rows (the first
+// grid = (Hq x layers of the call, n_seqs), D threads: thread j merges element j of the slabs that hold rows (the first
 // ceil(R / rows_per_slab) of them; the others were never written).
 template <int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(int w, int layer_max, int L, int layer, int Hq, int n_slabs,
-                                                         int rows_per_slab, const int32_t* __restrict__ cu,
+                                                         int rows_per_slab, DecodeLayerStrides ls_,
+                                                         const int32_t* __restrict__ cu,
                                                          const int32_t* __restrict__ counts,
                                                          const float* __restrict__ partial, float* __restrict__ out,
                                                          float* __restrict__ lse_out) {
   __shared__ float factor[kDecodeMaxSlabs];
   __shared__ float red[2];
-  const int g = blockIdx.x, seq = blockIdx.y, j = threadIdx.x;
+  const int g = blockIdx.x % Hq, lz = blockIdx.x / Hq, seq = blockIdx.y, j = threadIdx.x;
+  layer += lz;
+  partial += lz * ls_.partial;
+  out += lz * ls_.out;
+  if (lse_out) lse_out += lz * ls_.lse;
   const int S = cu[seq + 1] - cu[seq];
   int n = counts[seq * L + layer];
   n = n < 0 ? 0 : (n < layer_max ? n : layer_max);
@@ -155,29 +171,40 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(int w, int layer_max, i
 }
 
 template <typename T, int D>
-static hipError_t launch_decode_t(const Params& p, int layer, const void* q_new, const void* kb, const void* vb,
-                                  int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts,
-                                  float* out, float* lse_out, float* partial, hipStream_t st) {
+static hipError_t launch_decode_t(const Params& p, int layer, int n_layers, const void* q_new, const void* kb,
+                                  const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head,
+                                  const int32_t* cu, const int32_t* counts, float* out, float* lse_out, float* partial,
+                                  int64_t partial_stride_layer, hipStream_t st) {
   constexpr int kRows = decode_slab_rows(sizeof(T));
   const int n_slabs = (p.w + p.layer_max + kRows - 1) / kRows;
-  launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D>), dim3(n_slabs, p.Hkv, p.n_seqs), dim3(kDecThreads), 0, st, p.w,
-         p.layer_max, p.L, layer, p.Hq, p.G, p.scale, static_cast<const T*>(q_new), static_cast<const T*>(kb),
-         static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
-  launch(DKV_KERNEL_DECODE, (decode_merge_kernel<D>), dim3(p.Hq, p.n_seqs), dim3(D), 0, st, p.w, p.layer_max, p.L, layer,
-         p.Hq, n_slabs, kRows, cu, counts, static_cast<const float*>(partial), out, lse_out);
+  DecodeLayerStrides ls{};
+  ls.q = (int64_t)p.n_seqs * p.Hq * D;
+  ls.cache = stride_layer;
+  ls.partial = partial_stride_layer;
+  ls.out = (int64_t)p.n_seqs * p.Hq * D;
+  ls.lse = (int64_t)p.n_seqs * p.Hq;
+  launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D>), dim3(n_slabs * n_layers, p.Hkv, p.n_seqs), dim3(kDecThreads), 0,
+         st, p.w, p.layer_max, p.L, layer, p.Hq, p.G, p.scale, n_slabs, ls, static_cast<const T*>(q_new),
+         static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
+  launch(DKV_KERNEL_DECODE, (decode_merge_kernel<D>), dim3(p.Hq * n_layers, p.n_seqs), dim3(D), 0, st, p.w, p.layer_max,
+         p.L, layer, p.Hq, n_slabs, kRows, ls, cu, counts, static_cast<const float*>(partial), out, lse_out);
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const Params& p, int dtype, int layer, const void* q_new, const void* kb, const void* vb,
-                         int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts, float* out,
-                         float* lse_out, char* ws, const WorkspaceLayout& wl, hipStream_t st) {
+// n_layers consecutive layers from `layer` on: queries and outputs [n_layers][n_seqs][Hq][d] contiguous, cache blocks
+// stride_layer elements apart.
+hipError_t launch_decode(const Params& p, int dtype, int layer, int n_layers, const void* q_new, const void* kb,
+                         const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head, const int32_t* cu,
+                         const int32_t* counts, float* out, float* lse_out, char* ws, const WorkspaceLayout& wl,
+                         hipStream_t st) {
   float* partial = reinterpret_cast<float*>(ws + wl.decode_partials);
+  const int64_t psl = (int64_t)(wl.decode_partials_layer_bytes / sizeof(float));
   if (dtype == DKV_F32) {
-    if (p.d == 64) return launch_decode_t<float, 64>(p, layer, q_new, kb, vb, stride_seq, stride_head, cu, counts, out, lse_out, partial, st);
-    return launch_decode_t<float, 128>(p, layer, q_new, kb, vb, stride_seq, stride_head, cu, counts, out, lse_out, partial, st);
+    if (p.d == 64) return launch_decode_t<float, 64>(p, layer, n_layers, q_new, kb, vb, stride_layer, stride_seq, stride_head, cu, counts, out, lse_out, partial, psl, st);
+    return launch_decode_t<float, 128>(p, layer, n_layers, q_new, kb, vb, stride_layer, stride_seq, stride_head, cu, counts, out, lse_out, partial, psl, st);
   }
-  if (p.d == 64) return launch_decode_t<uint16_t, 64>(p, layer, q_new, kb, vb, stride_seq, stride_head, cu, counts, out, lse_out, partial, st);
-  return launch_decode_t<uint16_t, 128>(p, layer, q_new, kb, vb, stride_seq, stride_head, cu, counts, out, lse_out, partial, st);
+  if (p.d == 64) return launch_decode_t<uint16_t, 64>(p, layer, n_layers, q_new, kb, vb, stride_layer, stride_seq, stride_head, cu, counts, out, lse_out, partial, psl, st);
+  return launch_decode_t<uint16_t, 128>(p, layer, n_layers, q_new, kb, vb, stride_layer, stride_seq, stride_head, cu, counts, out, lse_out, partial, psl, st);
 }
 
 }  // namespace dkv

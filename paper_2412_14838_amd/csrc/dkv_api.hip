@@ -452,8 +452,37 @@ int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new,
   st = check_workspace(*desc, workspace, workspace_bytes, wl);
   if (st != DKV_OK) return st;
   const Params p = make_params(*desc);
-  const hipError_t e = launch_decode(p, desc->dtype, layer, q_new, kb, vb, stride_seq, stride_head, cu_seqlens, counts,
-                                     out, lse_out, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
+  const hipError_t e = launch_decode(p, desc->dtype, layer, 1, q_new, kb, vb, 0, stride_seq, stride_head, cu_seqlens,
+                                     counts, out, lse_out, static_cast<char*>(workspace), wl,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
+}
+
+int dkv_decode_attention_layers(const dkv_desc* desc, int32_t layer_begin, int32_t n_layers, const void* q_new_all,
+                                const void* kb_all, const void* vb_all, int64_t stride_layer, int64_t stride_seq,
+                                int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts, float* out_all,
+                                float* lse_all, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = validate_desc(desc);
+  if (st != DKV_OK) return st;
+  if (!q_new_all || !kb_all || !vb_all || !cu_seqlens || !counts || !out_all) return DKV_ERR_INVALID_ARG;
+  if (n_layers < 1 || n_layers > DKV_MAX_SELECT_LAYERS) return DKV_ERR_INVALID_ARG;
+  if (layer_begin < 0 || layer_begin + n_layers > desc->n_layers) return DKV_ERR_INVALID_ARG;
+  if (!aligned16(kb_all) || !aligned16(vb_all)) return DKV_ERR_INVALID_ARG;
+  if (desc->n_q_heads / desc->n_kv_heads > DKV_MAX_DECODE_GROUP) return DKV_ERR_UNSUPPORTED;
+  const int64_t elt = desc->dtype == DKV_BF16 ? 2 : 4;
+  const int64_t block = (int64_t)(desc->window + desc->layer_max) * desc->head_dim;
+  if (stride_head < block || stride_seq < stride_head * desc->n_kv_heads || stride_layer < stride_seq * desc->n_seqs)
+    return DKV_ERR_INVALID_ARG;
+  if ((stride_head * elt) % 16 != 0 || (stride_seq * elt) % 16 != 0 || (stride_layer * elt) % 16 != 0)
+    return DKV_ERR_INVALID_ARG;
+  WorkspaceLayout wl;
+  st = check_workspace(*desc, workspace, workspace_bytes, wl);
+  if (st != DKV_OK) return st;
+  const Params p = make_params(*desc);
+  const hipError_t e = launch_decode(
+      p, desc->dtype, layer_begin, n_layers, q_new_all, static_cast<const char*>(kb_all) + layer_begin * stride_layer * elt,
+      static_cast<const char*>(vb_all) + layer_begin * stride_layer * elt, stride_layer, stride_seq, stride_head, cu_seqlens,
+      counts, out_all, lse_all, static_cast<char*>(workspace), wl, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DKV_OK : DKV_ERR_LAUNCH;
 }
 

@@ -43,7 +43,8 @@ struct WorkspaceLayout {
   size_t tot0_slot_bytes;      // one of the DKV_MAX_UPDATES slots of the top-digit histogram
   size_t update_block_bytes;   // tot1 .. above of one class; DKV_MAX_UPDATES such blocks follow each other
   size_t picks;        // int32 [DKV_MAX_UPDATES][n_seqs][4]  per update: digit 0 of its threshold, rank left inside it, digit 1, rank left inside that
-  size_t decode_partials;  // float [n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
+  size_t decode_partials;  // float [DKV_MAX_SELECT_LAYERS][n_seqs][Hq][slabs][d + 2]    per-slab (max, sum, unnormalised output) of the decode attention
+  size_t decode_partials_layer_bytes;   // one layer's share of it
   // two-level selection of rows longer than one workgroup keeps in registers (absent when no row can be that long)
   size_t select_cand_val;  // uint32 [DKV_MAX_SELECT_LAYERS][n_seqs][Hkv][select_segments][layer_max]  candidates' score bits
   size_t select_cand_pos;  // int32, same shape: their positions
@@ -75,7 +76,9 @@ inline WorkspaceLayout workspace_layout(const dkv_desc& d) {
   w.edges_layer_bytes = align256(size_t(w.chunks_max) * d.n_kv_heads * 64 * sizeof(float));
   off += w.edges_layer_bytes * DKV_MAX_SELECT_LAYERS;
   w.decode_partials = off;
-  off += align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
+  w.decode_partials_layer_bytes =
+      align256(size_t(d.n_seqs) * d.n_q_heads * ((d.window + d.layer_max + 31) / 32) * (d.head_dim + 2) * sizeof(float));
+  off += w.decode_partials_layer_bytes * DKV_MAX_SELECT_LAYERS;
   {
     const int longest = d.max_seq_len > d.window ? d.max_seq_len - d.window : 0;
     w.select_segments = longest > kSelectSegment ? (longest + kSelectSegment - 1) / kSelectSegment : 1;
@@ -162,9 +165,10 @@ hipError_t launch_pack_cache(const Params& p, int elt_bytes, const int32_t* cu, 
                              const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head,
                              void* k_packed, void* v_packed, int64_t capacity_rows, int64_t* row_offsets,
                              hipStream_t st);
-hipError_t launch_decode(const Params& p, int dtype, int layer, const void* q_new, const void* kb, const void* vb,
-                         int64_t stride_seq, int64_t stride_head, const int32_t* cu, const int32_t* counts, float* out,
-                         float* lse_out, char* ws, const WorkspaceLayout& wl, hipStream_t st);
+hipError_t launch_decode(const Params& p, int dtype, int layer, int n_layers, const void* q_new, const void* kb,
+                         const void* vb, int64_t stride_layer, int64_t stride_seq, int64_t stride_head, const int32_t* cu,
+                         const int32_t* counts, float* out, float* lse_out, char* ws, const WorkspaceLayout& wl,
+                         hipStream_t st);
 hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, uint32_t epoch, const float* scores_all,
                             const int32_t* cu, int32_t* counts, int32_t* budgets_out, int32_t* hits_out,
                             int64_t out_stride_update, char* ws, const WorkspaceLayout& wl, hipStream_t st);

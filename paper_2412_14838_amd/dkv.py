@@ -21,7 +21,8 @@ DKV_OK, DKV_ERR_INVALID_ARG, DKV_ERR_UNSUPPORTED, DKV_ERR_WORKSPACE, DKV_ERR_LAU
 EXPORTS = ("dkv_version", "dkv_status_string", "dkv_workspace_bytes", "dkv_profile_begin", "dkv_profile_end", "dkv_score_window",
            "dkv_score_window_layers", "dkv_score_window_stats", "dkv_score_window_emit", "dkv_score_window_lse", "dkv_score_window_lse_layers", "dkv_row_lse", "dkv_select_topk", "dkv_select_topk_layers", "dkv_rebalance", "dkv_rebalance_batch",
            "dkv_gather_kv", "dkv_gather_kv_layers", "dkv_pack_cache", "dkv_decode_attention", "dkv_layer_budgets",
-           "dkv_apply_budgets", "dkv_select_recent", "dkv_score_window_static", "dkv_static_scratch_limit", "dkv_score_path")
+           "dkv_apply_budgets", "dkv_select_recent", "dkv_score_window_static", "dkv_static_scratch_limit", "dkv_score_path",
+           "dkv_decode_attention_layers")
 DKV_SCHEDULE_FIXED, DKV_SCHEDULE_PYRAMID = 0, 1
 
 
@@ -83,6 +84,8 @@ def load() -> C.CDLL:
     lib.dkv_pack_cache.argtypes = [D, P, P, P, P, I64, I64, I64, P, P, I64, P, P]
     lib.dkv_decode_attention.restype = C.c_int
     lib.dkv_decode_attention.argtypes = [D, I32, P, P, P, I64, I64, P, P, P, P, P, SZ, P]
+    lib.dkv_decode_attention_layers.restype = C.c_int
+    lib.dkv_decode_attention_layers.argtypes = [D, I32, I32, P, P, P, I64, I64, I64, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance.restype = C.c_int
     lib.dkv_rebalance.argtypes = [D, I32, C.c_uint32, P, P, P, P, P, P, SZ, P]
     lib.dkv_rebalance_batch.restype = C.c_int
@@ -319,6 +322,15 @@ def dkv_decode_attention(desc, layer, q_new, kb, vb, stride_seq, stride_head, cu
                                        _ptr(cu_seqlens), _ptr(counts), _ptr(out), _ptr(lse_out), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(), _stream(stream)),
            "dkv_decode_attention")
+
+
+def dkv_decode_attention_layers(desc, layer_begin, n_layers, q_new_all, kb_all, vb_all, stride_layer, stride_seq,
+                                stride_head, cu_seqlens, counts, out_all, lse_all, workspace, stream=None) -> None:
+    _check(load().dkv_decode_attention_layers(C.byref(desc), layer_begin, n_layers, _ptr(q_new_all), _ptr(kb_all),
+                                              _ptr(vb_all), stride_layer, stride_seq, stride_head, _ptr(cu_seqlens),
+                                              _ptr(counts), _ptr(out_all), _ptr(lse_all), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream)),
+           "dkv_decode_attention_layers")
 
 
 def alloc_workspace(desc, device="cuda"):

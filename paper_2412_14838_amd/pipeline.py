@@ -142,6 +142,13 @@ class Compressor:
         dkv.dkv_decode_attention(self.desc, layer, q_new, self.kb[layer], self.vb[layer], self.cfg.Hkv * self.slots * d,
                                  self.slots * d, self.cu, self.counts, out, lse_out, self.ws, stream)
 
+    def decode_attention_layers(self, layer_begin, n_layers, q_new_all, out_all, lse_all=None, stream=None):
+        """The same for n_layers consecutive layers in one call: q_new_all, out_all [n_layers][n_seqs][Hq][d]."""
+        d = self.cfg.d
+        dkv.dkv_decode_attention_layers(self.desc, layer_begin, n_layers, q_new_all, self.kb, self.vb,
+                                        self.cfg.n_seqs * self.cfg.Hkv * self.slots * d, self.cfg.Hkv * self.slots * d,
+                                        self.slots * d, self.cu, self.counts, out_all, lse_all, self.ws, stream)
+
     def _update_slot(self, layers_done):
         return min(max(layers_done // self.cfg.interval - 1, 0), self.budgets_all.shape[0] - 1)
 

@@ -287,6 +287,24 @@ def test_decode_attention_validates_its_arguments(lib):
     assert lib.dkv_decode_attention(C.byref(d), *a) == wsp
     wide = _good(n_q_heads=34, n_kv_heads=2, window=4)        # 17 query heads per KV head
     assert lib.dkv_decode_attention(C.byref(wide), *ok[:11], dkv.dkv_workspace_bytes(wide), None) == dkv.DKV_ERR_UNSUPPORTED
+    # the layer-batched form
+    sl = 2 * 272 * 64
+    okl = [0, 4, fake, fake, fake, sl, sq, sh, fake, fake, fake, None, fake, need, None]
+    call = lib.dkv_decode_attention_layers
+    for i in (2, 3, 4, 8, 9, 10):
+        a = list(okl)
+        a[i] = None
+        assert call(C.byref(d), *a) == inv
+    for begin, n in ((0, 0), (0, 5), (3, 2), (-1, 1), (4, 1)):
+        a = list(okl); a[0], a[1] = begin, n
+        assert call(C.byref(d), *a) == inv
+    a = list(okl); a[5] = sl - 64                # layer stride smaller than one layer's blocks
+    assert call(C.byref(d), *a) == inv
+    a = list(okl); a[12] = None
+    assert call(C.byref(d), *a) == wsp
+    a = list(okl); a[13] = need - 1
+    assert call(C.byref(d), *a) == wsp
+    assert call(C.byref(wide), *okl[:13], dkv.dkv_workspace_bytes(wide), None) == dkv.DKV_ERR_UNSUPPORTED
 
 
 def test_fixed_pattern_schedules_match_the_oracle_and_validate(lib):

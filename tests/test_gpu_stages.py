@@ -758,6 +758,25 @@ def test_decode_attention_over_the_compressed_cache(dkv, case):
     # without the optional output
     comp.decode_attention(0, q_dev, out, None)
     torch.cuda.synchronize()
+    # all layers in one call (each with its own queries): bit for bit what the per-layer calls give
+    q_all = rng.standard_normal((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        q_all = W.round_to_bf16(q_all)
+    q_all_dev = torch.from_numpy(q_all).to(device="cuda", dtype=comp.tdtype)
+    one_out = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d), dtype=torch.float32, device="cuda")
+    one_lse = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq), dtype=torch.float32, device="cuda")
+    for l in range(cfg.L):
+        comp.decode_attention(l, q_all_dev[l], one_out[l], one_lse[l])
+    all_out = torch.full_like(one_out, float("nan"))
+    all_lse = torch.full_like(one_lse, float("nan"))
+    comp.decode_attention_layers(0, cfg.L, q_all_dev, all_out, all_lse)
+    torch.cuda.synchronize()
+    assert torch.equal(all_out, one_out) and torch.equal(all_lse, one_lse)
+    if cfg.L > 2:        # a sub-range leaves the other layers' outputs alone
+        part = torch.full_like(one_out, 5.0)
+        comp.decode_attention_layers(1, cfg.L - 2, q_all_dev[1:], part[1:], None)
+        torch.cuda.synchronize()
+        assert torch.equal(part[1:cfg.L - 1], one_out[1:cfg.L - 1]) and (part[0] == 5.0).all() and (part[cfg.L - 1] == 5.0).all()
 
 
 # ---------------------------------------------------------------- fixed-pattern schedules (Section 5.1, Figure 1)
