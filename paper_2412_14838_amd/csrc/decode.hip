@@ -2,21 +2,25 @@
 // decoding is unchanged - ordinary softmax attention over the keys and values the prefill retained).
 //
 // The cache block of (sequence, KV head) holds at most ws + B^l rows (a few thousand at most), so one layer's
-// work is small and latency-bound: it is cut into slabs of 64 (bf16) or 32 (fp32) cache rows, one workgroup per (slab, KV head,
-// sequence), so that a layer fills the GPU (split along the keys, merged by a second kernel):
-//   partial kernel: K and V rows of the slab go to LDS with coalesced 16-byte loads; one thread per (row, query
-//                   head of the group) takes the dot product; per query head the slab's maximum m, the sum of
-//                   exponentials l and the unnormalised output acc[d] = sum_r exp(x_r - m) V_r are written;
+// work is small: it is cut into slabs of 128 (bf16) or 64 (fp32) cache rows, one workgroup per (slab, KV head,
+// sequence, layer of the call), so that the call fills the GPU (split along the keys, merged by a second kernel):
+//   partial kernel: no staging: the lanes of a wavefront that share a cache row each hold one 16-byte piece of its K
+//                   and of its V in registers (a wavefront-wide load covers whole rows, all loads of the slab are
+//                   in flight together); the dot products are summed over those lanes by DPP, the softmax weights
+//                   stay in registers, and each group of lanes leaves (m, l, unnormalised output) of its own rows
+//                   in LDS, where the workgroup merges them; per query head the slab's maximum m, the sum of
+//                   exponentials l and acc[d] = sum_r exp(x_r - m) V_r are written;
 //   merge kernel:   out = sum_s acc_s exp(m_s - M) / sum_s l_s exp(m_s - M), lse = M + log(sum ...).
-// All arithmetic in fp32 on the vector ALU (a single query row per head leaves nothing for the matrix cores).
+// All sums in fp32 on the vector ALU (a single query row per head leaves nothing for the matrix cores; the lanes
+// of a row hold different head-dim elements, so no tile of rows shares a contraction index). The kernel is bound by
+// that arithmetic, not by the loads: about 1100 vector instructions per wavefront of 32 rows and 4 query heads.
 #include "dkv_internal.h"
 
 namespace dkv {
 
 constexpr int kDecThreads = 256;
-
-__device__ inline float elem_to_float(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
-__device__ inline float elem_to_float(float x) { return x; }
+constexpr int kDecWaves = kDecThreads / 64;
+constexpr int kDecHeadsPerPass = 4;     // query heads of the group taken through the slab together
 
 // Valid row r (0 <= r < w_q + n) of a cache block -> slot of the block: the w_q window rows sit in the last w_q of
 // the first w slots, the n retained rows follow from slot w.
@@ -27,26 +31,81 @@ struct DecodeLayerStrides {
   int64_t q, cache, partial, out, lse;
 };
 
-// grid = (slabs x layers of the call, Hkv, n_seqs), 256 threads. partial layout per layer: [seq][Hq][slab][D + 2]
-// floats: m, l, acc[D]. Layer i of the call is layer `layer` + i; its tensors lie i layer strides behind the pointers.
-template <typename T, int D>
+// A 16-byte piece as fp32 values: 8 bf16 or 4 fp32.
+__device__ inline void unpack_piece(const uint4& r, float (&f)[8], uint16_t) {
+  f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+  f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+  f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+  f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+__device__ inline void unpack_piece(const uint4& r, float (&f)[4], float) {
+  f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+}
+
+// Dot product of the pieces a and b, added to c: bf16 pairs go through the packed dot instruction (products of
+// bf16 values are exact in fp32), fp32 elements through fused multiply-adds.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ inline float dot_piece(const uint4& a, const uint4& b, float c, uint16_t) {
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), c, false);
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), c, false);
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), c, false);
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), c, false);
+  return c;
+}
+__device__ inline float dot_piece(const uint4& a, const uint4& b, float c, float) {
+  c = fmaf(__uint_as_float(a.x), __uint_as_float(b.x), c);
+  c = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), c);
+  c = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), c);
+  c = fmaf(__uint_as_float(a.w), __uint_as_float(b.w), c);
+  return c;
+}
+
+// The value of another lane of the same row of 16 lanes (a DPP move; every lane is active where this is used).
+template <int CTRL>
+__device__ inline float dpp_lane(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LANES (8, 16 or 32) consecutive lanes that share a cache row; every one of them gets the sum.
+template <int LANES>
+__device__ inline float sum_over_row_lanes(float v) {
+  v += dpp_lane<0xB1>(v);                     // quad_perm [1,0,3,2]
+  v += dpp_lane<0x4E>(v);                     // quad_perm [2,3,0,1]
+  v += dpp_lane<0x141>(v);                    // row_half_mirror: the other quad of the 8
+  if (LANES >= 16) v += dpp_lane<0x140>(v);   // row_mirror: the other 8 of the 16
+  if (LANES >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
+// grid = (KV heads x sequences x layers of the call, slabs), 256 threads; the slab is the slow index, so that the
+// slabs past the rows a block holds (the grid is sized without knowing the counts) come last and leave at once.
+// partial layout per layer: [seq][Hq][slab][D + 2] floats: m, l, acc[D]. Layer i of the call is layer `layer` + i;
+// its tensors lie i layer strides behind the pointers.
+// ONE_PASS: the group has at most kDecHeadsPerPass query heads, so K is dead once the logits are there (fewer
+// registers, one more wavefront per SIMD).
+template <typename T, int D, bool ONE_PASS>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int layer_max, int L, int layer, int Hq,
-                                                                     int G, float scale, int n_slabs,
+                                                                     int Hkv, int n_seqs, int G, float scale,
                                                                      DecodeLayerStrides ls_, const T* __restrict__ q_new,
                                                                      const T* __restrict__ kb, const T* __restrict__ vb,
                                                                      int64_t stride_seq, int64_t stride_head,
                                                                      const int32_t* __restrict__ cu,
                                                                      const int32_t* __restrict__ counts,
                                                                      float* __restrict__ partial) {
-  constexpr int ROWS = decode_slab_rows(sizeof(T));   // 64 two-byte rows or 32 four-byte rows: 32 KB of LDS for K and V
+  constexpr int ROWS = decode_slab_rows(sizeof(T));   // rows of a slab
   constexpr int VEC = 16 / sizeof(T);                  // elements per 16-byte piece
-  constexpr int PIECES = D / VEC;                      // pieces per row
-  __shared__ __attribute__((aligned(16))) T ks[ROWS * D];
-  __shared__ __attribute__((aligned(16))) T vs[ROWS * D];
-  __shared__ float qs[kDecodeMaxGroup * D];
-  __shared__ float xs[kDecodeMaxGroup * ROWS];          // logits, then exp(x - m)
-  __shared__ float ms[kDecodeMaxGroup], ls[kDecodeMaxGroup];
-  const int slab = blockIdx.x % n_slabs, lz = blockIdx.x / n_slabs, head = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
+  constexpr int LPR = D / VEC;                         // lanes that share a row: 8, 16 or 32
+  constexpr int RPL = 64 / LPR;                        // rows a wavefront-wide load covers
+  constexpr int WROWS = ROWS / kDecWaves;              // rows per wavefront
+  constexpr int ITER = WROWS / RPL;                    // loads of K (and of V) per lane
+  constexpr int UNITS = kDecWaves * RPL;               // groups of lanes, each with rows of its own
+  constexpr int GB = kDecHeadsPerPass;
+  constexpr int USTRIDE = GB * D + 8;                  // floats per unit in LDS (padded: the units' pieces fall on different banks)
+  static_assert(ITER >= 1 && ITER * RPL * kDecWaves == ROWS, "a slab is a whole number of wavefront-wide loads");
+  __shared__ __attribute__((aligned(16))) float acc_s[UNITS * USTRIDE];
+  __shared__ float m_s[UNITS * GB], l_s[UNITS * GB];
+  const int n_slabs = gridDim.y, slab = blockIdx.y, tid = threadIdx.x;
+  const int head = blockIdx.x % Hkv, seq = (blockIdx.x / Hkv) % n_seqs, lz = blockIdx.x / (Hkv * n_seqs);
   layer += lz;
   q_new += lz * ls_.q;
   kb += lz * ls_.cache;
@@ -58,67 +117,99 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int 
   n = n < 0 ? 0 : (n < layer_max ? n : layer_max);
   const int R = wq + n;
   const int r0 = slab * ROWS;
-  const int rows = R - r0 < ROWS ? R - r0 : ROWS;       // <= 0: an empty slab
+  if (r0 >= R) return;                                  // an empty slab: the merge kernel only reads the slabs that hold rows
   float* __restrict__ part = partial + (((int64_t)seq * Hq + (int64_t)head * G) * n_slabs + slab) * (D + 2);
-  if (rows <= 0) return;                                // the merge kernel only reads the slabs that hold rows
   const T* __restrict__ kblock = kb + (int64_t)seq * stride_seq + (int64_t)head * stride_head;
   const T* __restrict__ vblock = vb + (int64_t)seq * stride_seq + (int64_t)head * stride_head;
-  for (int pc = tid; pc < rows * PIECES; pc += kDecThreads) {
-    const int r = pc / PIECES, c = pc % PIECES;
-    const int64_t off = (int64_t)cache_slot(r0 + r, w, wq) * D + c * VEC;
-    *reinterpret_cast<uint4*>(&ks[r * D + c * VEC]) = *reinterpret_cast<const uint4*>(kblock + off);
-    *reinterpret_cast<uint4*>(&vs[r * D + c * VEC]) = *reinterpret_cast<const uint4*>(vblock + off);
-  }
-  const T* __restrict__ q_head = q_new + ((int64_t)seq * Hq + (int64_t)head * G) * D;
-  for (int i = tid; i < G * D; i += kDecThreads) qs[i] = elem_to_float(q_head[i]);
-  __syncthreads();
-  // logits: one (row, query head) pair per thread, the row read as 16-byte pieces. The lanes of a wavefront read
-  // different rows of the LDS tile; each starts at a row-dependent piece, so that they fall on different banks.
-  for (int pair = tid; pair < G * ROWS; pair += kDecThreads) {
-    const int g = pair / ROWS, r = pair % ROWS;
-    float x = -INFINITY;
-    if (r < rows) {
-      float acc = 0.0f;
-#pragma unroll 4
-      for (int c = 0; c < PIECES; ++c) {
-        const int cc = (c + r) & (PIECES - 1);
-        T kv[VEC];
-        *reinterpret_cast<uint4*>(kv) = *reinterpret_cast<const uint4*>(&ks[r * D + cc * VEC]);
+  const int wave = tid >> 6, lane = tid & 63, piece = lane % LPR, lg = lane / LPR;
+  const int unit = wave * RPL + lg;
+  const float scale2 = scale * 1.4426950408889634f;
+  // this lane's pieces of K and V, all requested before the first is used; rows past the block's last read as zeros
+  uint4 kreg[ITER], vreg[ITER];
+  unsigned ok = 0u;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc = fmaf(qs[g * D + cc * VEC + e], elem_to_float(kv[e]), acc);
+  for (int it = 0; it < ITER; ++it) {
+    const int r = r0 + wave * WROWS + it * RPL + lg;
+    kreg[it] = make_uint4(0, 0, 0, 0);
+    vreg[it] = make_uint4(0, 0, 0, 0);
+    if (r < R) {
+      const int64_t off = (int64_t)cache_slot(r, w, wq) * D + piece * VEC;
+      kreg[it] = *reinterpret_cast<const uint4*>(kblock + off);
+      vreg[it] = *reinterpret_cast<const uint4*>(vblock + off);
+      ok |= 1u << it;
+    }
+  }
+  const T* __restrict__ q_head = q_new + ((int64_t)seq * Hq + (int64_t)head * G) * D + piece * VEC;
+  for (int g0 = 0; g0 < (ONE_PASS ? 1 : G); g0 += GB) {
+    uint4 qr[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      qr[g] = make_uint4(0, 0, 0, 0);
+      if (g0 + g < G) qr[g] = *reinterpret_cast<const uint4*>(q_head + (int64_t)(g0 + g) * D);
+    }
+    // logits of this unit's rows in units of log 2 (exponentials are 2^x): x[g][it], the same in all lanes of the unit
+    float x[GB][ITER];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {
+        const float a = sum_over_row_lanes<LPR>(dot_piece(qr[g], kreg[it], 0.0f, T()));
+        x[g][it] = (ok >> it & 1u) ? a * scale2 : -INFINITY;
       }
-      x = acc * scale;
     }
-    xs[pair] = x;
-  }
-  __syncthreads();
-  // per query head: maximum and sum of exponentials over the slab's rows (one wavefront per head, a lane per row)
-  {
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int g = wave; g < G; g += kDecThreads / 64) {
-      const float x = lane < ROWS ? xs[g * ROWS + lane] : -INFINITY;
-      float m = x;
+    // softmax weights relative to the unit's own maximum, and the unit's share of the output
+    float m[GB], l[GB], acc[GB][VEC];
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      const float e = lane < rows ? __expf(x - m) : 0.0f;
-      float l = e;
+    for (int g = 0; g < GB; ++g) {
+      m[g] = x[g][0];
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
-      if (lane < ROWS) xs[g * ROWS + lane] = e;
-      if (lane == 0) { ms[g] = m; ls[g] = l; }
+      for (int it = 1; it < ITER; ++it) m[g] = fmaxf(m[g], x[g][it]);
+      l[g] = 0.0f;
+      const float m_finite = fmaxf(m[g], -3.0e38f);      // a unit without rows: 2^(-inf - m_finite) = 0, not NaN
+#pragma unroll
+      for (int it = 0; it < ITER; ++it) {
+        x[g][it] = __builtin_amdgcn_exp2f(x[g][it] - m_finite);
+        l[g] += x[g][it];
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[g][e] = 0.0f;
     }
-  }
-  __syncthreads();
-  // unnormalised output: one (query head, head-dim element) per thread
-  for (int i = tid; i < G * D; i += kDecThreads) {
-    const int g = i / D, j = i % D;
-    float acc = 0.0f;
-    for (int r = 0; r < rows; ++r) acc = fmaf(xs[g * ROWS + r], elem_to_float(vs[r * D + j]), acc);
-    part[(int64_t)g * n_slabs * (D + 2) + 2 + j] = acc;
-  }
-  if (tid < G) {
-    part[(int64_t)tid * n_slabs * (D + 2)] = ms[tid];
-    part[(int64_t)tid * n_slabs * (D + 2) + 1] = ls[tid];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      float vf[VEC];
+      unpack_piece(vreg[it], vf, T());
+#pragma unroll
+      for (int g = 0; g < GB; ++g)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[g][e] = fmaf(x[g][it], vf[e], acc[g][e]);
+    }
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      float* __restrict__ dst = &acc_s[unit * USTRIDE + g * D + piece * VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; e += 4) *reinterpret_cast<float4*>(dst + e) = make_float4(acc[g][e], acc[g][e + 1], acc[g][e + 2], acc[g][e + 3]);
+      if (piece == 0) { m_s[unit * GB + g] = m[g]; l_s[unit * GB + g] = l[g]; }
+    }
+    __syncthreads();
+    // the slab's result per query head: the units merged (a unit without rows has m = -inf, l = 0, acc = 0)
+    for (int i = tid; i < GB * D; i += kDecThreads) {
+      const int g = i / D, j = i % D;
+      if (g0 + g >= G) break;
+      float M = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) M = fmaxf(M, m_s[u * GB + g]);      // finite: the slab's first row is valid
+      float a = 0.0f, lsum = 0.0f;
+#pragma unroll
+      for (int u = 0; u < UNITS; ++u) {
+        const float f = __builtin_amdgcn_exp2f(m_s[u * GB + g] - M);       // 0 for a unit without rows
+        a = fmaf(acc_s[u * USTRIDE + g * D + j], f, a);
+        lsum = fmaf(l_s[u * GB + g], f, lsum);
+      }
+      float* __restrict__ dst = part + (int64_t)(g0 + g) * n_slabs * (D + 2);
+      dst[2 + j] = a;
+      if (j == 0) { dst[0] = M * 0.6931471805599453f; dst[1] = lsum; }
+    }
+    __syncthreads();                                    // the LDS blocks are reused by the next heads of the group
   }
 }
 
@@ -183,9 +274,15 @@ static hipError_t launch_decode_t(const Params& p, int layer, int n_layers, cons
   ls.partial = partial_stride_layer;
   ls.out = (int64_t)p.n_seqs * p.Hq * D;
   ls.lse = (int64_t)p.n_seqs * p.Hq;
-  launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D>), dim3(n_slabs * n_layers, p.Hkv, p.n_seqs), dim3(kDecThreads), 0,
-         st, p.w, p.layer_max, p.L, layer, p.Hq, p.G, p.scale, n_slabs, ls, static_cast<const T*>(q_new),
-         static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
+  const dim3 grid_partial(p.Hkv * p.n_seqs * n_layers, n_slabs);
+  if (p.G <= kDecHeadsPerPass)
+    launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D, true>), grid_partial, dim3(kDecThreads), 0,
+           st, p.w, p.layer_max, p.L, layer, p.Hq, p.Hkv, p.n_seqs, p.G, p.scale, ls, static_cast<const T*>(q_new),
+           static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
+  else
+    launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D, false>), grid_partial, dim3(kDecThreads), 0,
+           st, p.w, p.layer_max, p.L, layer, p.Hq, p.Hkv, p.n_seqs, p.G, p.scale, ls, static_cast<const T*>(q_new),
+           static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
   launch(DKV_KERNEL_DECODE, (decode_merge_kernel<D>), dim3(p.Hq * n_layers, p.n_seqs), dim3(D), 0, st, p.w, p.layer_max,
          p.L, layer, p.Hq, n_slabs, kRows, ls, cu, counts, static_cast<const float*>(partial), out, lse_out);
   return hipGetLastError();

@@ -23,7 +23,7 @@ constexpr int kSelectSegment = 32768;  // row positions one selection workgroup 
 constexpr int kDecodeMaxGroup = 16;    // query heads per KV head the decode kernel handles
 constexpr int kDecodeMaxSlabs = (DKV_MAX_LAYER_MAX + DKV_MAX_ROWS + 31) / 32;   // slabs of one cache block at most
 // cache rows per workgroup of the decode kernel, by element size
-constexpr int decode_slab_rows(size_t elt_bytes) { return elt_bytes == 2 ? 64 : 32; }
+constexpr int decode_slab_rows(size_t elt_bytes) { return elt_bytes == 2 ? 128 : 64; }
 
 struct WorkspaceLayout {
   size_t partials;     // float2 [DKV_MAX_SELECT_LAYERS][chunks_max][Hkv][rows_pad] per-chunk row statistics (max, sum of exponentials)
