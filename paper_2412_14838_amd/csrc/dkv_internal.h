@@ -208,6 +208,69 @@ __device__ inline bool find_chunk(const int32_t* __restrict__ cu, int n_seqs, in
   return false;
 }
 
+// ---- wavefront and workgroup prefix sums on DPP moves (a few cycles each; a shuffle through LDS costs a round trip
+// per step). All of these must be called by every lane of the wavefront (workgroup), outside divergent branches.
+
+// v + the value of the lane CTRL names, where the rows of ROW_MASK have one; v elsewhere.
+template <int CTRL, int ROW_MASK>
+__device__ inline int dpp_add_from(int v) {
+  return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ inline int wave_prefix_sum(int v) {
+  v = dpp_add_from<0x111, 0xf>(v);   // row_shr:1
+  v = dpp_add_from<0x112, 0xf>(v);   // row_shr:2
+  v = dpp_add_from<0x114, 0xf>(v);   // row_shr:4
+  v = dpp_add_from<0x118, 0xf>(v);   // row_shr:8: every row of 16 lanes holds its own prefix sums
+  v = dpp_add_from<0x142, 0xa>(v);   // row_bcast:15: rows 1 and 3 add the total of the row before
+  v = dpp_add_from<0x143, 0xc>(v);   // row_bcast:31: rows 2 and 3 add the total of the first two
+  return v;
+}
+
+// Sum over the 16 lanes of a row; every lane of the row gets it.
+__device__ inline int row_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);    // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);    // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);   // row_half_mirror
+  v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);   // row_mirror
+  return v;
+}
+
+// Sum / maximum over the 64 lanes, the same value in every lane.
+__device__ inline int wave_sum(int v) {
+  v = row_sum(v);
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
+}
+__device__ inline int wave_max(int v) {
+#define DKV_MAX_STEP(CTRL)                                                       \
+  {                                                                              \
+    const int t = __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);       \
+    v = t > v ? t : v;                                                           \
+  }
+  DKV_MAX_STEP(0xB1) DKV_MAX_STEP(0x4E) DKV_MAX_STEP(0x141) DKV_MAX_STEP(0x140)
+#undef DKV_MAX_STEP
+  const int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+  const int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+  const int ab = a > b ? a : b, cd = c > d ? c : d;
+  return ab > cd ? ab : cd;
+}
+
+// Exclusive prefix sum of one int per thread over a workgroup of up to 16 wavefronts, and the sum over all of them.
+// scratch: one int per wavefront (LDS). Two barriers; scratch may be reused after the call.
+__device__ inline int block_prefix_sum(int v, int* scratch, int& total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, waves = (blockDim.x + 63) >> 6;
+  const int incl = wave_prefix_sum(v);
+  if (lane == 63) scratch[wv] = incl;
+  __syncthreads();
+  const int t = lane < waves ? scratch[lane] : 0;                   // lanes 0..15: the wavefronts' totals
+  const int before = __builtin_amdgcn_readfirstlane(row_sum(lane < wv ? t : 0));
+  total = __builtin_amdgcn_readfirstlane(row_sum(t));
+  __syncthreads();
+  return before + incl - v;
+}
+
 __device__ inline int chunks_of(int len, int window_off, int chunk) {
   int items = len - window_off;
   items = items > 0 ? items : 0;

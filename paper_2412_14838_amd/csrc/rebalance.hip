@@ -119,16 +119,6 @@ __device__ inline void load_chunk(const float* __restrict__ scores_all, int64_t 
 
 __device__ inline uint32_t lane_of(const uint4& v, int q) { return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w)); }
 
-__device__ inline int wave_inclusive_scan_i(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(v, o);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
-
 // A thread's share of a histogram of NB bins for a workgroup of NT threads: thread t owns the NB / NT bins just
 // below those of thread t - 1 (thread 0 the top ones).
 template <int NT, int NB>
@@ -163,17 +153,14 @@ __device__ inline Bins<NT, NB> load_bins_sum(const int32_t* __restrict__ tot, in
 template <int NT, int NB>
 __device__ inline void pick_digit(const Bins<NT, NB>& bins, int rem, int* scratch, int* sh, int& digit, int& rem_out) {
   constexpr int PER = NB / NT;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x;
   const int base = NB - PER * (tid + 1);
   int sum = 0;
 #pragma unroll
   for (int i = 0; i < PER; ++i) sum += bins.c[i];
-  const int incl = wave_inclusive_scan_i(sum);
-  if (lane == 63) scratch[wv] = incl;
   if (tid == 0) { sh[0] = 0; sh[1] = 0; }
-  __syncthreads();
-  int above = incl - sum;
-  for (int i = 0; i < wv; ++i) above += scratch[i];
+  int all;
+  const int above = block_prefix_sum(sum, scratch, all);    // two barriers: sh is cleared before the owner writes
   if (rem > 0 && above < rem && rem <= above + sum) {      // exactly one thread owns the bin
     int a = above;
 #pragma unroll
@@ -420,9 +407,7 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
 #pragma unroll
     for (int r = 0; r < ROUND; ++r) {
       if (r >= in_round) break;
-      int m = mine[r];
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) m += __shfl_xor(m, o);
+      const int m = wave_sum(mine[r]);
       if ((threadIdx.x & 63) == 0 && m) atomicAdd(&n_above[r], m);
     }
     __syncthreads();
@@ -448,19 +433,7 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
 
 // Exclusive prefix sum and total of one int per thread over the kFinalThreads threads.
 __device__ inline int block_exclusive_scan_final(int v, int* scratch, int& total) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int incl = wave_inclusive_scan_i(v);
-  if (lane == 63) scratch[wv] = incl;
-  __syncthreads();
-  int base = 0, all = 0;
-  for (int i = 0; i < kFinalThreads / 64; ++i) {
-    const int s = scratch[i];
-    if (i < wv) base += s;
-    all += s;
-  }
-  __syncthreads();
-  total = all;
-  return base + incl - v;
+  return block_prefix_sum(v, scratch, total);
 }
 
 // Last digit, per-layer hit counts and the budget arithmetic of Eq. 5-6, one workgroup per sequence.
@@ -481,7 +454,7 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
   __shared__ int sh[2];
   __shared__ int gt[DKV_MAX_LAYERS];
   __shared__ int eq[DKV_MAX_LAYERS];
-  __shared__ int wave_max[kFinalThreads / 64];
+  __shared__ int wave_max_s[kFinalThreads / 64];
   __shared__ uint32_t key1[DKV_MAX_UPDATES], key2[DKV_MAX_UPDATES];   // digit 0, digits (0, 1) of the updates' thresholds
   const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int kg = global_k(cu, seq, w, Hkv, mean_budget, layers_done);
@@ -540,8 +513,8 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
       acc += b > d2 ? v : 0;
       at += b == d2 ? v : 0;
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { acc += __shfl_xor(acc, o); at += __shfl_xor(at, o); }
+    acc = wave_sum(acc);
+    at = wave_sum(at);
     if (lane == 0) { gt[i] = acc; eq[i] = at; }
   }
   __syncthreads();
@@ -553,13 +526,11 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_final_kernel(
   int left = need_eq - eq_before;
   left = left > 0 ? left : 0;
   const int cnt = live && kg > 0 ? gt[tid] + above_mine + (my_eq < left ? my_eq : left) : 0;
-  int m = cnt;   // max over layers
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) { const int t = __shfl_xor(m, o); m = t > m ? t : m; }
-  if (lane == 0) wave_max[wv] = m;
+  const int m = wave_max(cnt);   // max over layers
+  if (lane == 0) wave_max_s[wv] = m;
   __syncthreads();
   int cmax = 0;
-  for (int i = 0; i < kFinalThreads / 64; ++i) cmax = wave_max[i] > cmax ? wave_max[i] : cmax;
+  for (int i = 0; i < kFinalThreads / 64; ++i) cmax = wave_max_s[i] > cmax ? wave_max_s[i] : cmax;
   const int z = cmax > 0 ? (int)(((long long)layer_max * cnt) / cmax) : 0;          // Eq. 5, exact floor
   int zsum_i;
   (void)block_exclusive_scan_final(z, scratch, zsum_i);                               // <= layer_max * layers: fits

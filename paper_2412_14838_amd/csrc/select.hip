@@ -28,26 +28,35 @@ static_assert(kSelResident == kSelectSegment, "the workspace is sized for segmen
 
 typedef unsigned long long u64;
 
-__device__ inline int wave_inclusive_scan(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(v, o);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
-
 // Exclusive prefix sum over the kSelThreads threads of the workgroup. `scratch` holds kSelWaves ints.
 __device__ inline int block_exclusive_scan(int v, int* scratch) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int incl = wave_inclusive_scan(v);
-  if (lane == 63) scratch[wv] = incl;
-  __syncthreads();
-  int base = 0;
-  for (int i = 0; i < wv; ++i) base += scratch[i];
-  __syncthreads();
-  return base + incl - v;
+  int total;
+  return block_prefix_sum(v, scratch, total);
+}
+
+// Minimum and maximum of one value per lane over the wavefront (DPP inside the rows of 16 lanes, then the four rows).
+template <int CTRL>
+__device__ inline uint32_t dpp_lane_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+__device__ inline void wave_min_max(uint32_t& lo, uint32_t& hi) {
+#define DKV_MINMAX_STEP(CTRL)                                  \
+  {                                                            \
+    const uint32_t l2 = dpp_lane_u32<CTRL>(lo), h2 = dpp_lane_u32<CTRL>(hi); \
+    lo = l2 < lo ? l2 : lo;                                    \
+    hi = h2 > hi ? h2 : hi;                                    \
+  }
+  DKV_MINMAX_STEP(0xB1) DKV_MINMAX_STEP(0x4E) DKV_MINMAX_STEP(0x141) DKV_MINMAX_STEP(0x140)
+#undef DKV_MINMAX_STEP
+  uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)lo, 0), h = (uint32_t)__builtin_amdgcn_readlane((int)hi, 0);
+#pragma unroll
+  for (int r = 16; r < 64; r += 16) {
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_readlane((int)lo, r), h2 = (uint32_t)__builtin_amdgcn_readlane((int)hi, r);
+    l = l2 < l ? l2 : l;
+    h = h2 > h ? h2 : h;
+  }
+  lo = l;
+  hi = h;
 }
 
 // Candidates of the two-level selection: segment g of row r (r = (layer of the call * n_seqs + seq) * Hkv + head) owns
@@ -179,9 +188,12 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     // thread t owns digits 2047 - 2t and 2046 - 2t (scanned from the top)
     const int hi = kRadixBins - 1 - 2 * tid, lo = hi - 1;
     int c_hi = 0, c_lo = 0;
-    if (pass == 0) {
-#pragma unroll
-      for (int c = 0; c < kHistCopies; ++c) { c_hi += hist[hi * kHistCopies + c]; c_lo += hist[lo * kHistCopies + c]; }
+    if (pass == 0) {   // lo and hi are adjacent: 16 consecutive words
+      static_assert(kHistCopies == 8, "four 16-byte reads cover the copies of two digits");
+      const int4* q = reinterpret_cast<const int4*>(&hist[lo * kHistCopies]);
+      const int4 a = q[0], b = q[1], c = q[2], d = q[3];
+      c_lo = a.x + a.y + a.z + a.w + b.x + b.y + b.z + b.w;
+      c_hi = c.x + c.y + c.z + c.w + d.x + d.y + d.z + d.w;
     } else {   // lo and hi are adjacent: 4 consecutive words
       const int4 q = *reinterpret_cast<const int4*>(&hist[lo * 2]);
       c_lo = q.x + q.y;
@@ -191,9 +203,8 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     if (above < rem && rem <= above + c_hi) { picked[0] = hi; picked[1] = above; }
     else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { picked[0] = lo; picked[1] = above + c_hi; }
     __syncthreads();
-    prefix |= (uint32_t)picked[0] << shift;
+    prefix |= (uint32_t)picked[0] << shift;     // picked is next written two barriers further on
     rem -= picked[1];
-    __syncthreads();
   }
   const uint32_t T = prefix;      // k-th largest value
   const int need_eq = rem;        // how many elements equal to T are taken (>= 1)
@@ -311,12 +322,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       hi = h > hi ? h : hi;
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint32_t l2 = __shfl_xor(lo, o), h2 = __shfl_xor(hi, o);
-    lo = l2 < lo ? l2 : lo;
-    hi = h2 > hi ? h2 : hi;
-  }
+  wave_min_max(lo, hi);
   __shared__ uint32_t wave_lo[kSelWaves], wave_hi[kSelWaves];
   if (lane == 0) { wave_lo[wv] = lo; wave_hi[wv] = hi; }
   for (int bI = tid; bI < kRadixBins; bI += kSelThreads) bcount[bI] = 0;
