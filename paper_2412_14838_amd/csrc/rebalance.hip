@@ -58,9 +58,12 @@ __global__ __launch_bounds__(256) void rebalance_clear_kernel(uint32_t* __restri
                                                               uint32_t* __restrict__ tot0, size_t tot0_words,
                                                               const int32_t* __restrict__ header,
                                                               const float* scores_all, int layers_done, int interval,
-                                                              int n_seqs, int total_tokens, uint32_t epoch) {
+                                                              int n_seqs, int total_tokens, uint32_t epoch,
+                                                              int32_t* __restrict__ picks, int picks_words) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < always_words; i += stride) always[i] = 0u;
+  // a sequence without prefix positions has no workgroup in the scans that could record its (empty) picks
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < (size_t)picks_words; i += stride) picks[i] = 0;
   const bool keep = layers_already_counted(header, scores_all, layers_done, interval, n_seqs, total_tokens, epoch) != 0;
   int used = keep ? header[7] : 0;
   used = used < 1 ? 1 : (used > DKV_MAX_UPDATES ? DKV_MAX_UPDATES : used);
@@ -315,12 +318,17 @@ __global__ __launch_bounds__(kFinalThreads) void rebalance_pick_kernel(int n_seq
 //   PASS 2: histogram of the last digit over elements with digits (0, 1) == (d0, d1) -> tot2 (slot of the layer) and
 //           hist2[layer]; above[1][layer] += #{digit 0 == d0, digit 1 > d1}
 // with (d0, d1) of the updates from `picks`. tot1 .. above point at class 0's block.
-template <int PASS>
+// PICKS_HERE (calls of a single update): no pick kernel ran; every workgroup finds the digit this scan needs by itself
+// from the histogram the kernel before completed (the top digit from tot0, the middle digit from tot1: 8 KB from
+// the L2, while its scores are on their way), and the sequence's first workgroup records it in `picks` for the
+// kernels behind.
+template <int PASS, bool PICKS_HERE>
 __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv, int w, int L, int total_tokens,
                                                              int layers_done, int interval, int n_updates,
+                                                             int mean_budget, const int32_t* __restrict__ tot0,
                                                              const float* __restrict__ scores_all,
                                                              const int32_t* __restrict__ cu,
-                                                             const int32_t* __restrict__ picks,
+                                                             int32_t* __restrict__ picks,
                                                              int32_t* __restrict__ tot1, int32_t* __restrict__ tot2,
                                                              int32_t* __restrict__ hist2, int32_t* __restrict__ above,
                                                              int64_t always_words) {
@@ -344,7 +352,21 @@ __global__ __launch_bounds__(256) void rebalance_scan_kernel(int n_seqs, int Hkv
   ChunkVectors<NV> cv;
   const int64_t e_lo = ((int64_t)layer * Hkv + head) * total_tokens + begin + i0;
   load_chunk<NV>(scores_all, (int64_t)L * Hkv * total_tokens, e_lo, e_lo + (i1 - i0), cv);
-  if (threadIdx.x < n_updates) {
+  if (PICKS_HERE) {                                      // n_updates == 1: update 0, class 0, slot 0
+    __shared__ int pick_scratch[256 / 64];
+    __shared__ int pick_sh[2];
+    int32_t* __restrict__ pk = picks + (int64_t)seq * 4;
+    const Bins<256, kRadixBins> bins = load_bins<256, kRadixBins>(
+        PASS == 1 ? tot0 + (int64_t)seq * kRadixBins : tot1 + (int64_t)seq * DKV_MAX_UPDATES * kRadixBins);
+    const int rem = PASS == 1 ? global_k(cu, seq, w, Hkv, mean_budget, layers_done) : pk[1];
+    const int d_top = PASS == 1 ? 0 : pk[0];
+    int digit, left;
+    pick_digit<256, kRadixBins>(bins, rem, pick_scratch, pick_sh, digit, left);
+    if (threadIdx.x == 0) {
+      key_of[0] = PASS == 1 ? (uint32_t)digit : (((uint32_t)d_top << 11) | (uint32_t)digit);
+      if (c == 0 && head == 0 && layer == 0) { pk[2 * (PASS - 1)] = digit; pk[2 * (PASS - 1) + 1] = left; }
+    }
+  } else if (threadIdx.x < n_updates) {
     const int32_t* __restrict__ pk = picks + ((int64_t)threadIdx.x * n_seqs + seq) * 4;
     key_of[threadIdx.x] = PASS == 1 ? (uint32_t)pk[0] : (((uint32_t)pk[0] << 11) | (uint32_t)pk[2]);
   }
@@ -572,21 +594,32 @@ hipError_t launch_rebalance(const Params& p, int layers_done, int n_updates, uin
   blocks = blocks > 1024 ? 1024 : blocks;
   launch(DKV_KERNEL_FILL, rebalance_clear_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
          reinterpret_cast<uint32_t*>(tot1), clear_words, reinterpret_cast<uint32_t*>(tot0), (size_t)tot0_words, header,
-         scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens, epoch);
+         scores_all, layers_done, p.interval, p.n_seqs, p.total_tokens, epoch, picks, n_updates * p.n_seqs * 4);
   const int last_done = layers_done + (n_updates - 1) * p.interval;
   const dim3 grid0(p.total_tokens / kHist0Chunk + p.n_seqs, p.Hkv, last_done);
   launch(DKV_KERNEL_REBALANCE_HIST, rebalance_hist0_kernel, grid0, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
          p.total_tokens, layers_done, p.interval, scores_all, cu, header, epoch, tot0, tot0_words);
   const dim3 grid_pick(p.n_seqs, n_updates);
-  launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<0>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
-         p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
   const dim3 grid(p.total_tokens / kScanChunk + p.n_seqs, p.Hkv, last_done);
-  launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<1>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, layers_done, p.interval, n_updates, scores_all, cu, picks, tot1, tot2, hist2, above, always_words);
-  launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<1>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
-         p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
-  launch(DKV_KERNEL_REBALANCE_SCAN, rebalance_scan_kernel<2>, grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
-         p.total_tokens, layers_done, p.interval, n_updates, scores_all, cu, picks, tot1, tot2, hist2, above, always_words);
+  if (n_updates == 1) {     // the scans pick their digits themselves: two launches less
+    launch(DKV_KERNEL_REBALANCE_SCAN, (rebalance_scan_kernel<1, true>), grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+           p.total_tokens, layers_done, p.interval, n_updates, p.mean_budget, tot0, scores_all, cu, picks, tot1, tot2, hist2,
+           above, always_words);
+    launch(DKV_KERNEL_REBALANCE_SCAN, (rebalance_scan_kernel<2, true>), grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+           p.total_tokens, layers_done, p.interval, n_updates, p.mean_budget, tot0, scores_all, cu, picks, tot1, tot2, hist2,
+           above, always_words);
+  } else {
+    launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<0>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
+           p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
+    launch(DKV_KERNEL_REBALANCE_SCAN, (rebalance_scan_kernel<1, false>), grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+           p.total_tokens, layers_done, p.interval, n_updates, p.mean_budget, tot0, scores_all, cu, picks, tot1, tot2, hist2,
+           above, always_words);
+    launch(DKV_KERNEL_REBALANCE_PICK, rebalance_pick_kernel<1>, grid_pick, dim3(kFinalThreads), 0, st, p.n_seqs, p.w, p.Hkv,
+           p.mean_budget, layers_done, p.interval, cu, tot0, tot0_words, tot1, always_words, picks);
+    launch(DKV_KERNEL_REBALANCE_SCAN, (rebalance_scan_kernel<2, false>), grid, dim3(256), 0, st, p.n_seqs, p.Hkv, p.w, p.L,
+           p.total_tokens, layers_done, p.interval, n_updates, p.mean_budget, tot0, scores_all, cu, picks, tot1, tot2, hist2,
+           above, always_words);
+  }
   launch(DKV_KERNEL_REBALANCE_FINAL, rebalance_final_kernel, dim3(p.n_seqs, n_updates), dim3(kFinalThreads), 0, st,
          p.n_seqs, p.L, layers_done, p.interval, p.w, p.Hkv, p.mean_budget, p.layer_max, p.total_tokens, scores_all, cu,
          picks, tot2, hist2, above, always_words, header, epoch, counts, budgets_out, hits_out, out_stride_update);
