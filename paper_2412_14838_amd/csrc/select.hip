@@ -7,6 +7,10 @@
 //      above T, and the first (k - #above) elements equal to T in position order (ties go to the lower position).
 //   3. the k winners are ordered by (score descending, position ascending) = ascending key: bucketed by the
 //      leading bits of their scores, the buckets laid out by a scan, the few keys of a bucket ranked by counting.
+// Short path (rows that fit the registers, final lists): after two digits the elements that can still win are the
+// ones above those 22 bits plus the few that share them; when they fit (4096), steps 1-2 stop there, all of them
+// become keys, step 3 orders them and writes the first k. The result is the same list bit for bit.
+// Prefix sums and reductions over the workgroup go through DPP moves (see dkv_internal.h).
 //
 // Rows longer than the 32768 positions a workgroup keeps in registers are selected in two levels, each the same
 // kernel: level 1 cuts the row into segments of 32768 positions, one workgroup per segment, and leaves every
@@ -25,6 +29,9 @@ constexpr int kHistCopies = 8;
 constexpr int kSelPerThread = 32;                              // row positions a thread keeps in registers
 constexpr int kSelResident = kSelPerThread * kSelThreads;      // 32768 positions
 static_assert(kSelResident == kSelectSegment, "the workspace is sized for segments of what one workgroup holds");
+
+constexpr int kShortCap = 4096;                                // candidates the short path orders (see below)
+constexpr int kOrderPerThread = kShortCap / kSelThreads;       // keys a thread takes through the ordering step
 
 typedef unsigned long long u64;
 
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
   __shared__ int scratch[kSelWaves];
-  __shared__ int picked[2];
+  __shared__ int picked[3];
   __shared__ int n_greater_slots;
   __shared__ int wave_eq[kSelWaves];
 
@@ -152,10 +159,11 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   // ---- radix select: the k-th largest bit pattern
   uint32_t prefix = 0;
   int rem = k;
-#pragma unroll
-  for (int pass = 0; pass < 3; ++pass) {
+  auto radix_pass = [&](auto pass_c) {
+    constexpr int pass = decltype(pass_c)::value;
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    const int hshift = pass == 0 ? 32 : (pass == 1 ? 21 : 10);   // bits above this digit
+    const int hshift = pass == 1 ? 21 : 10;                      // bits above this digit (passes 1 and 2)
+    auto matches = [&](uint32_t u) { return pass == 0 ? true : ((u >> hshift) == (prefix >> hshift)); };
     // pass 0 sees every element (lanes that share a digit spread over 8 copies of the histogram); the later
     // passes only the elements that share the digits found so far: 2 copies, less to clear and to add up
     const int copies = pass == 0 ? kHistCopies : 2;
@@ -164,8 +172,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
 #pragma unroll
     for (int j = 0; j < kSelPerThread; ++j) {
       const uint32_t u = v[j];
-      const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
-      if (j * kSelThreads + tid < n_res && match)
+      if (j * kSelThreads + tid < n_res && matches(u))
         atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
     }
     // the tail of a long row, eight loads in flight per thread
@@ -179,8 +186,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         const uint32_t u = u8[q];
-        const bool match = pass == 0 ? true : ((u >> hshift) == (prefix >> hshift));
-        if (i0 + q * kSelThreads < n && match)
+        if (i0 + q * kSelThreads < n && matches(u))
           atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
       }
     }
@@ -200,12 +206,43 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       c_hi = q.z + q.w;
     }
     const int above = block_exclusive_scan(c_hi + c_lo, scratch);
-    if (above < rem && rem <= above + c_hi) { picked[0] = hi; picked[1] = above; }
-    else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { picked[0] = lo; picked[1] = above + c_hi; }
+    if (above < rem && rem <= above + c_hi) { picked[0] = hi; picked[1] = above; picked[2] = c_hi; }
+    else if (above + c_hi < rem && rem <= above + c_hi + c_lo) { picked[0] = lo; picked[1] = above + c_hi; picked[2] = c_lo; }
     __syncthreads();
     prefix |= (uint32_t)picked[0] << shift;     // picked is next written two barriers further on
     rem -= picked[1];
-  }
+  };
+  radix_pass(std::integral_constant<int, 0>{});
+  radix_pass(std::integral_constant<int, 1>{});
+  // Short path. After the upper two digits (22 bits) the winners are known up to the elements that share them:
+  // `sure` elements have larger upper digits, picked[2] share them (a handful, unless many scores are equal). When
+  // all of those together fit, they go to LDS as keys in any order and the ordering step below sorts them ALL: the
+  // first k of the ascending keys are the answer, ties already broken by the position in the key - no third
+  // digit, no position-ordered pick of the elements equal to the threshold. Not for a segment's candidates (they
+  // are left in position order) nor for rows with a tail outside the registers.
+  // (One histogram over the upper 16 bits in place of the two digits was measured and is slower: 16384 single bins
+  // collide on the LDS banks more than 8 copies of a few hot 11-bit digits collide on their addresses.)
+  const int sure = k - rem;
+  const int m_short = sure + picked[2];
+  const bool short_path = MODE != kSelSegments && n <= kSelResident && m_short <= kShortCap;
+  int m_keys = k;                                     // keys the ordering step sorts
+  const u64* order_src = keys;
+  if (short_path) {
+    u64* __restrict__ cand_keys = reinterpret_cast<u64*>(hist);      // [kShortCap]: the histogram is spent
+    const uint32_t bound = prefix;                                   // every pattern whose upper two digits are not below the threshold's
+    int mine_n = 0;
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) mine_n += (j * kSelThreads + tid < n_res && v[j] >= bound) ? 1 : 0;
+    int slot = block_exclusive_scan(mine_n, scratch);               // its first barrier: all reads of the histogram are done
+#pragma unroll
+    for (int j = 0; j < kSelPerThread; ++j) {
+      const int i = j * kSelThreads + tid;
+      if (i < n_res && v[j] >= bound) cand_keys[slot++] = make_key(v[j], i);
+    }
+    m_keys = m_short;
+    order_src = cand_keys;
+  } else {
+  radix_pass(std::integral_constant<int, 2>{});
   const uint32_t T = prefix;      // k-th largest value
   const int need_eq = rem;        // how many elements equal to T are taken (>= 1)
   const int n_gt = k - need_eq;   // elements strictly greater than T
@@ -301,22 +338,26 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       running += __popcll(emask);
     }
   }
+  }   // long path
   __syncthreads();
 
-  // ---- order the k winners by (score descending, position ascending) = ascending 64-bit key, here in LDS:
-  // buckets by the leading bits of the keys' score halves (2048 linear bins between the smallest and the largest
-  // one), a scan over the buckets, and a rank inside the bucket by counting. The winners are the upper tail of the
-  // row, a few keys per bucket; k keys that all share one bucket (all scores equal) cost k^2 comparisons.
-  int* bcount = hist;                                          // [kRadixBins] keys per bucket
-  int* bstart = hist + kRadixBins;                             // [kRadixBins] first place of the bucket
-  u64* sorted = reinterpret_cast<u64*>(hist + 2 * kRadixBins); // [2048] keys in bucket order
-  u64 mine[2];
+  // ---- order the keys (the k winners, or the short path's candidates) by (score descending, position ascending) =
+  // ascending 64-bit key, here in LDS: buckets by the leading bits of the keys' score halves (2048 linear bins
+  // between the smallest and the largest one), a scan over the buckets, and a rank inside the bucket by counting.
+  // The keys are the upper tail of the row, a few per bucket; keys that all share one bucket (all scores equal)
+  // cost their number squared in comparisons. Only ranks below k are written.
+  int* bcount = reinterpret_cast<int*>(sel_smem);               // [kRadixBins] keys per bucket
+  int* bstart = bcount + kRadixBins;                            // [kRadixBins] first place of the bucket
+  u64* sorted = reinterpret_cast<u64*>(hist + 2 * kShortCap);   // [kShortCap] keys in bucket order (behind the candidates)
+  static_assert(2 * kRadixBins * sizeof(int) <= 2048 * sizeof(u64), "the bucket arrays take the place of the winners' keys");
+  static_assert(2 * kShortCap * sizeof(u64) <= (size_t)kRadixBins * kHistCopies * sizeof(int), "candidates and their sorted copy fit the histogram");
+  u64 mine[kOrderPerThread];
   uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < kOrderPerThread; ++c) {
     const int j = tid + c * kSelThreads;
-    mine[c] = j < k ? keys[j] : ~0ull;
-    if (j < k) {
+    mine[c] = j < m_keys ? order_src[j] : ~0ull;
+    if (j < m_keys) {
       const uint32_t h = (uint32_t)(mine[c] >> 32);
       lo = h < lo ? h : lo;
       hi = h > hi ? h : hi;
@@ -325,21 +366,22 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   wave_min_max(lo, hi);
   __shared__ uint32_t wave_lo[kSelWaves], wave_hi[kSelWaves];
   if (lane == 0) { wave_lo[wv] = lo; wave_hi[wv] = hi; }
+  __syncthreads();                                             // every key is in registers: its place in LDS is free
   for (int bI = tid; bI < kRadixBins; bI += kSelThreads) bcount[bI] = 0;
-  __syncthreads();
 #pragma unroll
   for (int i = 0; i < kSelWaves; ++i) {
     lo = wave_lo[i] < lo ? wave_lo[i] : lo;
     hi = wave_hi[i] > hi ? wave_hi[i] : hi;
   }
-  const uint32_t range = hi - lo;                              // k >= 1 here: lo <= hi
+  __syncthreads();
+  const uint32_t range = hi - lo;                              // m_keys >= 1 here: lo <= hi
   const int shift = range < (uint32_t)kRadixBins ? 0 : (32 - __builtin_clz(range)) - 11;   // (range >> shift) < 2048
-  int bin[2], place[2];
+  int bin[kOrderPerThread], place[kOrderPerThread];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < kOrderPerThread; ++c) {
     const int j = tid + c * kSelThreads;
-    bin[c] = (int)((((uint32_t)(mine[c] >> 32)) - lo) >> shift);
-    place[c] = j < k ? atomicAdd(&bcount[bin[c]], 1) : 0;       // order of arrival inside the bucket: any order will do
+    bin[c] = j < m_keys ? (int)((((uint32_t)(mine[c] >> 32)) - lo) >> shift) : 0;
+    place[c] = j < m_keys ? atomicAdd(&bcount[bin[c]], 1) : 0;  // order of arrival inside the bucket: any order will do
   }
   __syncthreads();
   {
@@ -350,18 +392,19 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   }
   __syncthreads();
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < kOrderPerThread; ++c) {
     const int j = tid + c * kSelThreads;
-    if (j < k) sorted[bstart[bin[c]] + place[c]] = mine[c];
+    if (j < m_keys) sorted[bstart[bin[c]] + place[c]] = mine[c];
   }
   __syncthreads();
 #pragma unroll
-  for (int c = 0; c < 2; ++c) {
+  for (int c = 0; c < kOrderPerThread; ++c) {
     const int j = tid + c * kSelThreads;
-    if (j < k) {
+    if (j < m_keys) {
       const int first = bstart[bin[c]], n_in = bcount[bin[c]];
       int rank = first;
       for (int i = 0; i < n_in; ++i) rank += sorted[first + i] < mine[c] ? 1 : 0;
+      if (rank >= k) continue;                 // a candidate of the short path that is not among the k winners
       if (MODE == kSelSegments) {            // the segment's candidates, in position order
         const int64_t e = cand_row + (int64_t)segment * layer_max + rank;
         cand.val[e] = (uint32_t)mine[c];
