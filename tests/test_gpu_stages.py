@@ -182,6 +182,46 @@ def test_select_topk_large_k_and_long_rows(dkv):
         assert np.array_equal(idx[s][:, :ref.shape[1]], ref)
 
 
+def test_select_topk_on_both_sides_of_the_short_path(dkv):
+    """Rows that fit one workgroup's registers take a short path when the elements above the threshold's upper 22 bits
+    plus those that share them number at most 4096, the full radix selection otherwise. Rows built to land on both
+    sides of that limit (1500 larger values + a plateau of 2596 / 2597 equal ones that holds the threshold), rows of
+    few distinct values, an all-equal row and a smooth one; bit-exact against the oracle's stable sort."""
+    cfg = small_cfg("short_path", Hq=2, Hkv=2, seqlens=(20000 + 32, 32768 + 32, 3000 + 32), layer_max=2048,
+                    mean_budget=512, L=4, interval=4)
+    comp = Compressor(cfg, keep_cache=False)
+    cu, T = cfg.cu_seqlens, cfg.total_tokens
+    rng = np.random.default_rng(23)
+    smooth = np.abs(rng.standard_normal((cfg.Hkv, T))).astype(np.float32)
+    few = (rng.integers(0, 5, size=(cfg.Hkv, T)) / 8).astype(np.float32)
+    few[1] = 0.25
+    limit = np.empty((cfg.Hkv, T), dtype=np.float32)
+    for h, plateau in enumerate((2596, 2597)):
+        for s in range(cfg.n_seqs):
+            pre = cfg.seqlens[s] - cfg.w
+            row = rng.uniform(0.001, 0.01, size=cfg.seqlens[s]).astype(np.float32)     # far below the plateau
+            where = rng.permutation(pre)
+            n_big = min(1500, pre // 4)
+            row[where[:n_big]] = rng.uniform(2.0, 3.0, size=n_big).astype(np.float32)
+            row[where[n_big:n_big + min(plateau, pre - n_big)]] = 1.0
+            limit[h, cu[s]:cu[s + 1]] = row
+    mixed = np.where(rng.random((cfg.Hkv, T)) < 0.5, smooth, np.float32(0.5)).astype(np.float32)
+    A = np.stack([smooth, few, limit, mixed])
+    comp.scores.copy_(torch.from_numpy(A))
+    comp.idx.fill_(-7)
+    comp.select_layers(0, cfg.L)
+    torch.cuda.synchronize()
+    idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
+    for l in range(cfg.L):
+        for s in range(cfg.n_seqs):
+            pre = cfg.seqlens[s] - cfg.w
+            ref = O.select_topk(A[l][:, cu[s]:cu[s] + pre], cfg.layer_max)
+            k = ref.shape[1]
+            assert counts[s, l] == k
+            assert np.array_equal(idx[l, s][:, :k], ref), (l, s)
+            assert (idx[l, s][:, k:] == -1).all()
+
+
 @pytest.mark.parametrize("seqlens", [(1 << 20,), (70000, 300, 32768 + 32, 32769 + 32, 140000, 20)])
 def test_select_topk_two_levels_for_rows_past_one_workgroup(dkv, seqlens):
     """Rows longer than the 32768 positions a workgroup holds go through segments and a merge: a row of a million
