@@ -1,0 +1,136 @@
+"""A seeded sweep over odd shapes: the whole loop on the GPU against the oracle, every stage, both schedules.
+
+The fixed cases of test_gpu_stages.py sit on the kernels' natural sizes; here window, group size, pooling width,
+head size, storage type, layer count, update interval, budgets and a ragged batch of sequence lengths (some not
+longer than the window, some a few tokens past a tile border) are drawn from a seeded generator. Scores within the
+stated tolerance; selection, hit counts, budgets, counts and the rows of the cache bit for bit (the oracle repeats
+the integer stages on the GPU's own fp32 scores); the grouped schedule identical to the layer-by-layer one; the
+attention of a new token over every layer's cache (all layers in one call) against the oracle's.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dkv_oracle as O
+from paper_2412_14838_amd import workloads as W
+from paper_2412_14838_amd.pipeline import Compressor, to_device
+
+pytestmark = pytest.mark.gpu
+
+SCORE_RTOL = 2e-3
+N_CASES = 24
+
+
+def draw_case(i):
+    rng = np.random.default_rng(1000 + i)
+    w = int(rng.choice([4, 8, 16, 24, 32, 64]))
+    g_max = max(1, 256 // w)
+    G = int(rng.integers(1, min(g_max, 8) + 1))
+    Hkv = int(rng.integers(1, 4))
+    d = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    P = int(rng.choice([1, 3, 5, 7, 9, 15, 31, 63]))
+    interval = int(rng.integers(1, 4))
+    L = interval * int(rng.integers(1, 4)) + int(rng.integers(0, 2))       # the last layers may see no update
+    n_seqs = int(rng.integers(1, 6))
+    lens = []
+    for _ in range(n_seqs):
+        kind = rng.integers(0, 5)
+        if kind == 0:
+            lens.append(int(rng.integers(1, w + 2)))                          # at most one prefix position
+        elif kind == 1:
+            lens.append(int(rng.choice([128, 256, 512, 1024]) + w + rng.integers(-2, 3)))   # next to a tile border
+        else:
+            lens.append(int(rng.integers(w + 2, 1800)))
+    layer_max = int(rng.integers(8, 400))
+    mean_budget = int(rng.integers(1, layer_max + 1))
+    return W.Workload(name="rand%d" % i, L=L, Hq=G * Hkv, Hkv=Hkv, d=d, seqlens=tuple(lens), dtype=dtype, w=w, P=P,
+                      mean_budget=mean_budget, layer_max=layer_max, interval=interval, seed=500 + i,
+                      plant="loguniform", plant_lo=2, plant_hi=30, gain=float(rng.choice([1.0, 3.0])),
+                      plant_normalize=True)
+
+
+def oracle_on_scores(cfg, scores):
+    cu = cfg.cu_seqlens
+    out = []
+    for s in range(cfg.n_seqs):
+        pre = max(cfg.seqlens[s] - cfg.w, 0)
+        A = [scores[l][:, cu[s]:cu[s] + pre] for l in range(cfg.L)]
+        out.append(O.compress([(None, None, None)] * cfg.L, cfg.L, cfg.w, cfg.P, cfg.layer_max, cfg.mean_budget,
+                              cfg.interval, scores_override=A, keep_buffers=False))
+    return out
+
+
+@pytest.mark.parametrize("i", range(N_CASES))
+def test_random_shape_against_the_oracle(dkv, i):
+    cfg = draw_case(i)
+    print("case", i, cfg, flush=True)
+    host = [W.make_layer(cfg, l) for l in range(cfg.L)]
+    dev = [to_device(cfg, h) for h in host]
+    cu = cfg.cu_seqlens
+    runs = {}
+    rng = np.random.default_rng(3000 + i)
+    q_new = rng.standard_normal((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        q_new = W.round_to_bf16(q_new)
+    for group in (1, 32):
+        comp = Compressor(cfg, group=group)
+        for l in range(cfg.L):
+            comp.step(l, dev[l]["q_win"], dev[l]["k"], dev[l]["v"])
+        torch.cuda.synchronize()
+        if group == 1:              # the new token's attention over every layer's cache, all layers in one call
+            q_dev = torch.from_numpy(q_new).to(device="cuda", dtype=comp.tdtype)
+            dec_out = torch.full((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d), float("nan"), dtype=torch.float32, device="cuda")
+            dec_lse = torch.full((cfg.L, cfg.n_seqs, cfg.Hq), float("nan"), dtype=torch.float32, device="cuda")
+            comp.decode_attention_layers(0, cfg.L, q_dev, dec_out, dec_lse)
+            torch.cuda.synchronize()
+            dec_out, dec_lse = dec_out.cpu().numpy(), dec_lse.cpu().numpy()
+        runs[group] = (comp.scores.cpu().numpy(), comp.idx.cpu().numpy(), comp.counts.cpu().numpy(),
+                       comp.kb.float().cpu().numpy(), comp.vb.float().cpu().numpy())
+    scores, idx, counts, kb, vb = runs[1]
+    # the two schedules: same bits (rows of the cache: the valid ones)
+    s32, i32, c32, kb32, vb32 = runs[32]
+    assert np.array_equal(counts, c32)
+    for s in range(cfg.n_seqs):                     # (a sequence without prefix positions has no scores)
+        n = max(cfg.seqlens[s] - cfg.w, 0)
+        assert np.array_equal(scores[:, :, cu[s]:cu[s] + n], s32[:, :, cu[s]:cu[s] + n])
+    # scores against the oracle
+    for l in range(cfg.L):
+        for s in range(cfg.n_seqs):
+            n = cfg.seqlens[s] - cfg.w
+            if n <= 0:
+                continue
+            ref = O.score_window(host[l]["q_win"][s], host[l]["k"][:, cu[s]:cu[s + 1]], cfg.P)
+            got = scores[l][:, cu[s]:cu[s] + n]
+            assert np.isfinite(got).all()
+            rel = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)
+            assert rel.max() <= SCORE_RTOL, (l, s, rel.max())
+    # integer stages and cache rows against the oracle on the GPU's scores
+    ref = oracle_on_scores(cfg, scores)
+    for s in range(cfg.n_seqs):
+        r = ref[s]
+        wq = min(cfg.seqlens[s], cfg.w)
+        assert counts[s].tolist() == r.n
+        for l in range(cfg.L):
+            k = r.idx[l].shape[1]
+            assert np.array_equal(idx[l, s][:, :k], r.idx[l]), (l, s)
+            assert np.array_equal(i32[l, s][:, :k], r.idx[l]), (l, s)
+            n = r.n[l]
+            k_seq, v_seq = host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]]
+            if cfg.seqlens[s] >= cfg.w:
+                ref_k, ref_v = O.gather_kv(k_seq, v_seq, r.idx[l][:, :n], cfg.w)
+            else:                                  # shorter than the window: no candidates, the rows it has
+                assert n == 0
+                ref_k, ref_v = k_seq, v_seq
+            for got_k, got_v in ((kb[l, s], vb[l, s]), (kb32[l, s], vb32[l, s])):
+                assert np.array_equal(got_k[:, cfg.w:cfg.w + n], ref_k[:, :n]), (l, s)
+                assert np.array_equal(got_v[:, cfg.w:cfg.w + n], ref_v[:, :n]), (l, s)
+                assert np.array_equal(got_k[:, cfg.w - wq:cfg.w], ref_k[:, n:]), (l, s)
+                assert np.array_equal(got_v[:, cfg.w - wq:cfg.w], ref_v[:, n:]), (l, s)
+            # decode attention over these rows (any row order gives the same result)
+            S = cfg.seqlens[s]
+            kc = np.stack([np.concatenate([k_seq[h][r.idx[l][h, :n]], k_seq[h][S - wq:]]) for h in range(cfg.Hkv)])
+            vc = np.stack([np.concatenate([v_seq[h][r.idx[l][h, :n]], v_seq[h][S - wq:]]) for h in range(cfg.Hkv)])
+            want, want_lse = O.decode_attention(q_new[l, s], kc, vc)
+            assert np.abs(dec_out[l, s] - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (l, s)
+            assert np.abs(dec_lse[l, s] - want_lse).max() <= 2e-5 * max(1.0, np.abs(want_lse).max()), (l, s)
