@@ -4,16 +4,16 @@
 // The cache block of (sequence, KV head) holds at most ws + B^l rows (a few thousand at most), so one layer's
 // work is small: it is cut into slabs of 128 (bf16) or 64 (fp32) cache rows, one workgroup per (slab, KV head,
 // sequence, layer of the call), so that the call fills the GPU (split along the keys, merged by a second kernel):
-//   partial kernel: no staging: the lanes of a wavefront that share a cache row each hold one 16-byte piece of its K
-//                   and of its V in registers (a wavefront-wide load covers whole rows, all loads of the slab are
-//                   in flight together); the dot products are summed over those lanes by DPP, the softmax weights
-//                   stay in registers, and each group of lanes leaves (m, l, unnormalised output) of its own rows
-//                   in LDS, where the workgroup merges them; per query head the slab's maximum m, the sum of
-//                   exponentials l and acc[d] = sum_r exp(x_r - m) V_r are written;
+//   partial kernel: per query head the slab's maximum m, the sum of exponentials l and the unnormalised output
+//                   acc[d] = sum_r exp(x_r - m) V_r.
+//                   bf16 caches: on the matrix cores, see decode_partial_mfma_kernel below.
+//                   fp32 caches: on the vector ALU, nothing staged: the lanes of a wavefront that share a cache row
+//                   each hold one 16-byte piece of its K and of its V in registers (a wavefront-wide load covers
+//                   whole rows, all loads of the slab are in flight together); the dot products are summed over
+//                   those lanes by DPP, the softmax weights stay in registers, and each group of lanes leaves
+//                   (m, l, acc) of its own rows in LDS, where the workgroup merges them;
 //   merge kernel:   out = sum_s acc_s exp(m_s - M) / sum_s l_s exp(m_s - M), lse = M + log(sum ...).
-// All sums in fp32 on the vector ALU (a single query row per head leaves nothing for the matrix cores; the lanes
-// of a row hold different head-dim elements, so no tile of rows shares a contraction index). The kernel is bound by
-// that arithmetic, not by the loads: about 1100 vector instructions per wavefront of 32 rows and 4 query heads.
+// All sums in fp32.
 #include "dkv_internal.h"
 
 namespace dkv {
@@ -31,27 +31,12 @@ struct DecodeLayerStrides {
   int64_t q, cache, partial, out, lse;
 };
 
-// A 16-byte piece as fp32 values: 8 bf16 or 4 fp32.
-__device__ inline void unpack_piece(const uint4& r, float (&f)[8], uint16_t) {
-  f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
-  f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
-  f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
-  f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
-}
+// A 16-byte piece as fp32 values.
 __device__ inline void unpack_piece(const uint4& r, float (&f)[4], float) {
   f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
 }
 
-// Dot product of the pieces a and b, added to c: bf16 pairs go through the packed dot instruction (products of
-// bf16 values are exact in fp32), fp32 elements through fused multiply-adds.
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-__device__ inline float dot_piece(const uint4& a, const uint4& b, float c, uint16_t) {
-  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), c, false);
-  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), c, false);
-  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), c, false);
-  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), c, false);
-  return c;
-}
+// Dot product of the pieces a and b, added to c.
 __device__ inline float dot_piece(const uint4& a, const uint4& b, float c, float) {
   c = fmaf(__uint_as_float(a.x), __uint_as_float(b.x), c);
   c = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), c);
@@ -213,6 +198,200 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(int w, int 
   }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// The same partial results for bf16 caches on the matrix cores (v_mfma_f32_32x32x16_bf16). A wavefront owns 32 rows
+// of the slab; all G <= 16 query heads of the group go through together as the N side of the tiles.
+//   logits   S[row][head] = sum_d K[row][d] Q[head][d]: A = K with a lane per row (lane % 32) holding 8 consecutive
+//            head-dim elements per 16-wide step (16-byte loads straight from the cache block: the two lanes of a row
+//            fetch adjacent pieces, the eight steps complete the row's cache lines), B = Q likewise (heads past G are
+//            zero). The result tile has a lane per head and, in its 16 registers, the rows
+//            8 (i / 4) + 4 (lane / 32) + i % 4: the softmax over rows is in-lane plus one exchange between the halves.
+//   output   O[head][d] = sum_row P[head][row] V[row][d]: A = P, which each lane already holds for its head - the
+//            contraction index may visit the rows in any order, and the order (step s, half h, e) -> row
+//            8 (2 s + e / 4) + 4 h + e % 4 is the one the registers are in. P goes in as two bf16 terms, hi + lo
+//            (the residue is below 2^-17 of P), V exactly. B = V needs a lane per head-dim column with 8 rows in its
+//            registers, i.e. V transposed: every wavefront stages its 32 rows of V in LDS (coalesced 16-byte loads,
+//            rows padded by 16 bytes) and reads columns as 2-byte words.
+// The per-wavefront results (max, sum, unnormalised output per head) meet in LDS as in the vector-ALU kernel.
+// ------------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ inline uint32_t pack_bf16_pair(float a, float b) {
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+template <int D>
+__global__ __launch_bounds__(kDecThreads) void decode_partial_mfma_kernel(int w, int layer_max, int L, int layer, int Hq,
+                                                                          int Hkv, int n_seqs, int G, float scale,
+                                                                          DecodeLayerStrides ls_,
+                                                                          const uint16_t* __restrict__ q_new,
+                                                                          const uint16_t* __restrict__ kb,
+                                                                          const uint16_t* __restrict__ vb,
+                                                                          int64_t stride_seq, int64_t stride_head,
+                                                                          const int32_t* __restrict__ cu,
+                                                                          const int32_t* __restrict__ counts,
+                                                                          float* __restrict__ partial) {
+  constexpr int ROWS = decode_slab_rows(2);            // 128 rows per slab
+  constexpr int WROWS = ROWS / kDecWaves;              // 32 rows per wavefront: one tile
+  constexpr int DS = D / 16;                           // 16-wide steps over the head dimension
+  constexpr int DT = D / 32;                           // 32-wide tiles of the output's head dimension
+  constexpr int PIECES = D / 8;                        // 16-byte pieces per row
+  constexpr int RPL = 64 / PIECES;                     // rows a wavefront-wide coalesced load covers
+  constexpr int ITER = WROWS / RPL;                    // such loads per wavefront for its rows of V
+  constexpr int VSTRIDE = D * 2 + 16;                  // bytes per staged row of V (the halves of a wavefront read rows 4 apart: other banks)
+  constexpr int GMAX = kDecodeMaxGroup;
+  static_assert(WROWS == 32 && GMAX <= 32, "one 32x32 tile of rows x heads per wavefront");
+  static_assert(GMAX * D * 4 <= WROWS * VSTRIDE, "a wavefront's unnormalised outputs reuse its staging area");
+  __shared__ __attribute__((aligned(16))) char stage[kDecWaves][WROWS * VSTRIDE];
+  __shared__ float m_s[kDecWaves][GMAX], l_s[kDecWaves][GMAX];
+  const int n_slabs = gridDim.y, slab = blockIdx.y, tid = threadIdx.x;
+  const int head = blockIdx.x % Hkv, seq = (blockIdx.x / Hkv) % n_seqs, lz = blockIdx.x / (Hkv * n_seqs);
+  layer += lz;
+  q_new += lz * ls_.q;
+  kb += lz * ls_.cache;
+  vb += lz * ls_.cache;
+  partial += lz * ls_.partial;
+  const int S = cu[seq + 1] - cu[seq];
+  const int wq = S < w ? S : w;
+  int n = counts[seq * L + layer];
+  n = n < 0 ? 0 : (n < layer_max ? n : layer_max);
+  const int R = wq + n;
+  const int r0 = slab * ROWS;
+  if (r0 >= R) return;                                  // an empty slab
+  float* __restrict__ part = partial + (((int64_t)seq * Hq + (int64_t)head * G) * n_slabs + slab) * (D + 2);
+  const uint16_t* __restrict__ kblock = kb + (int64_t)seq * stride_seq + (int64_t)head * stride_head;
+  const uint16_t* __restrict__ vblock = vb + (int64_t)seq * stride_seq + (int64_t)head * stride_head;
+  const int wave = tid >> 6, lane = tid & 63, col = lane & 31, half = lane >> 5;
+  const int wr0 = r0 + wave * WROWS;                    // first row of this wavefront
+  const int rows_left = R - wr0;                        // rows of the wavefront that exist (may be <= 0)
+  char* __restrict__ my_stage = stage[wave];
+
+  // ---- loads: K in operand layout (lane = row), Q likewise (lane = head), V coalesced for the staging
+  uint4 ka[DS], qb[DS], vreg[ITER];
+  {
+    const bool ok = col < rows_left;
+    const int64_t off = ok ? (int64_t)cache_slot(wr0 + col, w, wq) * D + half * 8 : 0;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) {
+      ka[ds] = make_uint4(0, 0, 0, 0);
+      if (ok) ka[ds] = *reinterpret_cast<const uint4*>(kblock + off + ds * 16);
+    }
+    const uint16_t* __restrict__ q_head = q_new + ((int64_t)seq * Hq + (int64_t)head * G) * D;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) {
+      qb[ds] = make_uint4(0, 0, 0, 0);
+      if (col < G) qb[ds] = *reinterpret_cast<const uint4*>(q_head + (int64_t)col * D + ds * 16 + half * 8);
+    }
+    const int piece = lane % PIECES, lg = lane / PIECES;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int r = it * RPL + lg;
+      vreg[it] = make_uint4(0, 0, 0, 0);                // rows past the block's last: zeros (their weights are zero too)
+      if (r < rows_left) vreg[it] = *reinterpret_cast<const uint4*>(vblock + (int64_t)cache_slot(wr0 + r, w, wq) * D + piece * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it)
+      *reinterpret_cast<uint4*>(my_stage + (it * RPL + lg) * VSTRIDE + piece * 16) = vreg[it];
+  }
+
+  // ---- logits: rows x heads
+  floatx16 sc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sc[i] = 0.0f;
+#pragma unroll
+  for (int ds = 0; ds < DS; ++ds)
+    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[ds]), __builtin_bit_cast(bf16x8, qb[ds]), sc, 0, 0, 0);
+  // this lane: head `col`, rows 8 (i / 4) + 4 half + i % 4 of the wavefront; in units of log 2
+  const float scale2 = scale * 1.4426950408889634f;
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int row = 8 * (i >> 2) + 4 * half + (i & 3);
+    sc[i] = row < rows_left ? sc[i] * scale2 : -INFINITY;
+    mx = fmaxf(mx, sc[i]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_finite = fmaxf(mx, -3.0e38f);           // a wavefront without rows: 2^(-inf - m_finite) = 0, not NaN
+  float lsum = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    sc[i] = __builtin_amdgcn_exp2f(sc[i] - m_finite);
+    lsum += sc[i];
+  }
+  lsum += __shfl_xor(lsum, 32);
+  if (half == 0 && col < GMAX) { m_s[wave][col] = mx; l_s[wave][col] = lsum; }
+
+  // ---- P as two bf16 operands per step of 16 rows
+  uint4 p_hi[2], p_lo[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float a = sc[8 * s + 2 * e], b = sc[8 * s + 2 * e + 1];
+      hi[e] = pack_bf16_pair(a, b);
+      lo[e] = pack_bf16_pair(a - __uint_as_float(hi[e] << 16), b - __uint_as_float(hi[e] & 0xffff0000u));
+    }
+    p_hi[s] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    p_lo[s] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+  }
+
+  // ---- output: heads x head-dim columns; B = V read column-wise from the staged rows (this wavefront's own stores)
+  floatx16 oc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oc[dt][i] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      uint32_t vv[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {                     // rows of the contraction slots 2 e and 2 e + 1 of step s
+        const int row_a = 8 * (2 * s + (2 * e) / 4) + 4 * half + (2 * e) % 4;
+        const uint32_t a = *reinterpret_cast<const uint16_t*>(my_stage + row_a * VSTRIDE + (dt * 32 + col) * 2);
+        const uint32_t b = *reinterpret_cast<const uint16_t*>(my_stage + (row_a + 1) * VSTRIDE + (dt * 32 + col) * 2);
+        vv[e] = a | (b << 16);
+      }
+      const bf16x8 vop = __builtin_bit_cast(bf16x8, make_uint4(vv[0], vv[1], vv[2], vv[3]));
+      oc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p_hi[s]), vop, oc[dt], 0, 0, 0);
+      oc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, p_lo[s]), vop, oc[dt], 0, 0, 0);
+    }
+  }
+  // this lane: column dt * 32 + col, heads 8 (i / 4) + 4 half + i % 4. The staged V is spent (the wavefront's LDS
+  // accesses complete in order): its place takes the wavefront's outputs [head][D]
+  float* __restrict__ my_out = reinterpret_cast<float*>(my_stage);
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int hd = 8 * (i >> 2) + 4 * half + (i & 3);
+      if (hd < GMAX) my_out[hd * D + dt * 32 + col] = oc[dt][i];
+    }
+  __syncthreads();
+  // ---- the slab's result per query head: the wavefronts merged
+  for (int i = tid; i < G * D; i += kDecThreads) {
+    const int g = i / D, j = i % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kDecWaves; ++u) M = fmaxf(M, m_s[u][g]);          // finite: the slab's first row is valid
+    float a = 0.0f, lt = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kDecWaves; ++u) {
+      const float f = __builtin_amdgcn_exp2f(m_s[u][g] - M);              // 0 for a wavefront without rows
+      a = fmaf(reinterpret_cast<const float*>(stage[u])[g * D + j], f, a);
+      lt = fmaf(l_s[u][g], f, lt);
+    }
+    float* __restrict__ dst = part + (int64_t)g * n_slabs * (D + 2);
+    dst[2 + j] = a;
+    if (j == 0) { dst[0] = M * 0.6931471805599453f; dst[1] = lt; }
+  }
+}
+
 // grid = (Hq x layers of the call, n_seqs), D threads: thread j merges element j of the slabs that hold rows (the first
 // ceil(R / rows_per_slab) of them; the others were never written).
 template <int D>
@@ -275,14 +454,19 @@ static hipError_t launch_decode_t(const Params& p, int layer, int n_layers, cons
   ls.out = (int64_t)p.n_seqs * p.Hq * D;
   ls.lse = (int64_t)p.n_seqs * p.Hq;
   const dim3 grid_partial(p.Hkv * p.n_seqs * n_layers, n_slabs);
-  if (p.G <= kDecHeadsPerPass)
+  if constexpr (sizeof(T) == 2) {
+    launch(DKV_KERNEL_DECODE, (decode_partial_mfma_kernel<D>), grid_partial, dim3(kDecThreads), 0,
+           st, p.w, p.layer_max, p.L, layer, p.Hq, p.Hkv, p.n_seqs, p.G, p.scale, ls, static_cast<const uint16_t*>(q_new),
+           static_cast<const uint16_t*>(kb), static_cast<const uint16_t*>(vb), stride_seq, stride_head, cu, counts, partial);
+  } else if (p.G <= kDecHeadsPerPass) {
     launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D, true>), grid_partial, dim3(kDecThreads), 0,
            st, p.w, p.layer_max, p.L, layer, p.Hq, p.Hkv, p.n_seqs, p.G, p.scale, ls, static_cast<const T*>(q_new),
            static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
-  else
+  } else {
     launch(DKV_KERNEL_DECODE, (decode_partial_kernel<T, D, false>), grid_partial, dim3(kDecThreads), 0,
            st, p.w, p.layer_max, p.L, layer, p.Hq, p.Hkv, p.n_seqs, p.G, p.scale, ls, static_cast<const T*>(q_new),
            static_cast<const T*>(kb), static_cast<const T*>(vb), stride_seq, stride_head, cu, counts, partial);
+  }
   launch(DKV_KERNEL_DECODE, (decode_merge_kernel<D>), dim3(p.Hq * n_layers, p.n_seqs), dim3(D), 0, st, p.w, p.layer_max,
          p.L, layer, p.Hq, n_slabs, kRows, ls, cu, counts, static_cast<const float*>(partial), out, lse_out);
   return hipGetLastError();
