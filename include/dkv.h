@@ -366,8 +366,10 @@ int dkv_pack_cache(const dkv_desc* desc, const int32_t* cu_seqlens, const int32_
  *          kb[q * stride_seq + h * stride_head + slot * d + j] (elements).
  * out      fp32 [n_seqs][Hq][d]; lse_out fp32 [n_seqs][Hq] (natural log of the softmax denominator) or NULL.
  *          A sequence without any cached row gets zeros and lse = -inf.
- * Hq / Hkv must not exceed DKV_MAX_DECODE_GROUP. fp32 arithmetic. Two kernels (the cache rows are split over
- * workgroups, then merged); the split results live in the workspace.
+ * Hq / Hkv must not exceed DKV_MAX_DECODE_GROUP. All sums in fp32 (for bf16 caches the products run on the matrix
+ * cores: bf16 x bf16 is exact there, and the softmax weights enter as two bf16 terms, hi + lo, whose residue is
+ * below 2^-17 of the weight). Two kernels (the cache rows are split over workgroups, then merged); the split
+ * results live in the workspace.
  */
 int dkv_decode_attention(const dkv_desc* desc, int32_t layer, const void* q_new, const void* kb, const void* vb,
                          int64_t stride_seq, int64_t stride_head, const int32_t* cu_seqlens, const int32_t* counts,
