@@ -229,27 +229,35 @@ def test_full_single_sweep_scoring_from_row_lse(dkv, name):
         assert np.abs(lse_h[s, h * G:(h + 1) * G] - ref).max() <= 1e-4
 
 
-def test_full_decode_attention_over_final_cache(dkv):
-    """Config 2 at full size: after the whole compression, decode attention over sampled layers of the final cache
-    against the oracle's attention over the rows the GPU's lists and final counts name."""
-    cfg = W.standard_configs()["llama3_8b_8k"].with_(L=8)
-    comp, host, snaps = run_config(cfg, list(range(cfg.L)), group=4)
+@pytest.mark.parametrize("name, L, interval, group", [("llama3_8b_8k", 8, 4, 4), ("qwen2_7b_32k_extreme", 4, 2, 4),
+                                                       ("ragged_batch8", 4, 2, 1)])
+def test_full_decode_attention_over_final_cache(dkv, name, L, interval, group):
+    """Full-width configurations (group sizes 4 and 7, one and eight sequences), a few layers deep: after the whole
+    compression, decode attention over the final cache - layer by layer and all layers in one call - against the
+    oracle's attention over the rows the GPU's lists and final counts name."""
+    cfg = W.standard_configs()[name].with_(L=L, interval=interval)
+    comp, host, snaps = run_config(cfg, list(range(cfg.L)), group=group)
     idx, counts = comp.idx.cpu().numpy(), comp.counts.cpu().numpy()
-    q_new = W.round_to_bf16(np.random.default_rng(3).standard_normal((cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32))
+    q_new = W.round_to_bf16(np.random.default_rng(3).standard_normal((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d)).astype(np.float32))
     q_dev = torch.from_numpy(q_new).to(device="cuda", dtype=comp.tdtype)
     out = torch.empty((cfg.n_seqs, cfg.Hq, cfg.d), dtype=torch.float32, device="cuda")
     lse = torch.empty((cfg.n_seqs, cfg.Hq), dtype=torch.float32, device="cuda")
-    S, w = cfg.seqlens[0], cfg.w
-    for l in (0, 3, 7):
-        comp.decode_attention(l, q_dev, out, lse)
+    all_out = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq, cfg.d), dtype=torch.float32, device="cuda")
+    all_lse = torch.empty((cfg.L, cfg.n_seqs, cfg.Hq), dtype=torch.float32, device="cuda")
+    comp.decode_attention_layers(0, cfg.L, q_dev, all_out, all_lse)
+    cu, w = cfg.cu_seqlens, cfg.w
+    for l in sorted({0, cfg.L // 2, cfg.L - 1}):
+        comp.decode_attention(l, q_dev[l], out, lse)
         torch.cuda.synchronize()
-        n = int(counts[0, l])
-        k_s, v_s = host[l]["k"], host[l]["v"]
-        kc = np.stack([np.concatenate([k_s[h][idx[l, 0][h, :n]], k_s[h][S - w:]]) for h in range(cfg.Hkv)])
-        vc = np.stack([np.concatenate([v_s[h][idx[l, 0][h, :n]], v_s[h][S - w:]]) for h in range(cfg.Hkv)])
-        ref, ref_lse = O.decode_attention(q_new[0], kc, vc)
-        assert np.abs(out[0].cpu().numpy() - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), l
-        assert np.abs(lse[0].cpu().numpy() - ref_lse).max() <= 2e-5 * np.abs(ref_lse).max(), l
+        assert torch.equal(out, all_out[l]) and torch.equal(lse, all_lse[l])
+        for s in sorted({0, cfg.n_seqs - 1}):
+            S, n = cfg.seqlens[s], int(counts[s, l])
+            k_s, v_s = host[l]["k"][:, cu[s]:cu[s + 1]], host[l]["v"][:, cu[s]:cu[s + 1]]
+            kc = np.stack([np.concatenate([k_s[h][idx[l, s][h, :n]], k_s[h][S - w:]]) for h in range(cfg.Hkv)])
+            vc = np.stack([np.concatenate([v_s[h][idx[l, s][h, :n]], v_s[h][S - w:]]) for h in range(cfg.Hkv)])
+            ref, ref_lse = O.decode_attention(q_new[l, s], kc, vc)
+            assert np.abs(out[s].cpu().numpy() - ref).max() <= 2e-5 * max(1.0, np.abs(ref).max()), (l, s)
+            assert np.abs(lse[s].cpu().numpy() - ref_lse).max() <= 2e-5 * max(1.0, np.abs(ref_lse).max()), (l, s)
 
 
 def test_calibrated_planting_gives_layer_varying_budgets(dkv):
