@@ -85,7 +85,9 @@ __host__ __device__ inline int candidates_of(int n, int layer_max) {
 
 // grid = (Hkv, n_seqs [x segments_max for MODE == kSelSegments], layers of the call); blockIdx.z picks the layer: its
 // scores, index list and key block lie blockIdx.z layer strides behind the pointers passed in.
-template <int MODE>
+// PER: row positions a thread keeps in registers: 32 (rows and segments of up to 32768 positions), or 16 / 8 when no
+// row of the call is longer than 16384 / 8192 (the passes over the registers are that much shorter).
+template <int MODE, int PER>
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w, int layer_max, int L, int layer0,
                                                                   const float* __restrict__ scores0,
                                                                   int64_t scores_stride_head,
@@ -94,6 +96,8 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
                                                                   int32_t* __restrict__ idx_out0,
                                                                   int64_t idx_stride_layer,
                                                                   int32_t* __restrict__ counts, SelectCandidates cand) {
+  constexpr int RES = PER * kSelThreads;                    // positions held in registers
+  static_assert(MODE != kSelSegments || RES == kSelectSegment, "a segment is what one workgroup holds");
   extern __shared__ __attribute__((aligned(16))) char sel_smem[];
   u64* keys = reinterpret_cast<u64*>(sel_smem);                               // [2048] candidates / exchange
   int* hist = reinterpret_cast<int*>(sel_smem + 2048 * sizeof(u64));          // [kRadixBins][kHistCopies]
@@ -117,10 +121,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   int n, k;
   const uint32_t* __restrict__ row;
   if (MODE == kSelSegments) {
-    const int seg_begin = segment * kSelResident;
+    const int seg_begin = segment * RES;
     n = n_row - seg_begin;
     if (n <= 0) return;                                       // the row has fewer segments
-    n = n < kSelResident ? n : kSelResident;
+    n = n < RES ? n : RES;
     k = layer_max < n ? layer_max : n;
     row = reinterpret_cast<const uint32_t*>(scores + (int64_t)head * scores_stride_head + begin) + seg_begin;
   } else if (MODE == kSelMerge) {
@@ -146,15 +150,15 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     return MODE == kSelSegments ? ((u64)(uint32_t)i << 32) | u : ((u64)(~u) << 32) | (uint32_t)i;
   };
 
-  // The first kSelResident positions of the row live in registers for all passes: thread t holds positions
+  // The first RES positions of the row live in registers for all passes: thread t holds positions
   // j * 1024 + t (coalesced loads, issued back to back). Longer rows re-read their tail from memory.
-  uint32_t v[kSelPerThread];
+  uint32_t v[PER];
 #pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
+  for (int j = 0; j < PER; ++j) {
     const int i = j * kSelThreads + tid;
     v[j] = i < n ? row[i] : 0u;
   }
-  const int n_res = n < kSelResident ? n : kSelResident;   // positions held in registers
+  const int n_res = n < RES ? n : RES;   // positions held in registers
 
   // ---- radix select: the k-th largest bit pattern
   uint32_t prefix = 0;
@@ -170,13 +174,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     for (int b = tid; b < kRadixBins * copies; b += kSelThreads) hist[b] = 0;
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < kSelPerThread; ++j) {
+    for (int j = 0; j < PER; ++j) {
       const uint32_t u = v[j];
       if (j * kSelThreads + tid < n_res && matches(u))
         atomicAdd(&hist[((u >> shift) & (kRadixBins - 1)) * copies + (lane & (copies - 1))], 1);
     }
     // the tail of a long row, eight loads in flight per thread
-    for (int i0 = kSelResident + tid; i0 < n; i0 += 8 * kSelThreads) {
+    for (int i0 = RES + tid; i0 < n; i0 += 8 * kSelThreads) {
       uint32_t u8[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   // collide on the LDS banks more than 8 copies of a few hot 11-bit digits collide on their addresses.)
   const int sure = k - rem;
   const int m_short = sure + picked[2];
-  const bool short_path = MODE != kSelSegments && n <= kSelResident && m_short <= kShortCap;
+  const bool short_path = MODE != kSelSegments && n <= RES && m_short <= kShortCap;
   int m_keys = k;                                     // keys the ordering step sorts
   const u64* order_src = keys;
   if (short_path) {
@@ -232,10 +236,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
     const uint32_t bound = prefix;                                   // every pattern whose upper two digits are not below the threshold's
     int mine_n = 0;
 #pragma unroll
-    for (int j = 0; j < kSelPerThread; ++j) mine_n += (j * kSelThreads + tid < n_res && v[j] >= bound) ? 1 : 0;
+    for (int j = 0; j < PER; ++j) mine_n += (j * kSelThreads + tid < n_res && v[j] >= bound) ? 1 : 0;
     int slot = block_exclusive_scan(mine_n, scratch);               // its first barrier: all reads of the histogram are done
 #pragma unroll
-    for (int j = 0; j < kSelPerThread; ++j) {
+    for (int j = 0; j < PER; ++j) {
       const int i = j * kSelThreads + tid;
       if (i < n_res && v[j] >= bound) cand_keys[slot++] = make_key(v[j], i);
     }
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
 
   // ---- compaction: everything above T (any order: the sort fixes it), and the first need_eq elements equal
   // to T in position order. Position order of the resident part is (j, wavefront, lane).
-  int* eq_base = hist;            // [kSelPerThread][kSelWaves] counts, then exclusive prefix sums (reuses hist)
+  int* eq_base = hist;            // [PER][kSelWaves] counts, then exclusive prefix sums (reuses hist)
   if (tid == 0) n_greater_slots = 0;
   for (int j = k + tid; j < 2048; j += kSelThreads) keys[j] = ~0ull;      // pads sort to the end
   __syncthreads();
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   // slots (any order will do); elements equal to T: counted per (j, wavefront) for the position-ordered pick below
   int my_gt = 0;
 #pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
+  for (int j = 0; j < PER; ++j) {
     const int i = j * kSelThreads + tid;
     const uint32_t u = v[j];
     my_gt += i < n_res && u > T ? 1 : 0;
@@ -267,22 +271,22 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
   int slot = block_exclusive_scan(my_gt, scratch);
   if (tid == kSelThreads - 1) n_greater_slots = slot + my_gt;     // the tail of a long row continues from here
 #pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
+  for (int j = 0; j < PER; ++j) {
     const int i = j * kSelThreads + tid;
     const uint32_t u = v[j];
     if (i < n_res && u > T) keys[slot++] = make_key(u, i);
   }
   __syncthreads();
   {
-    static_assert(kSelPerThread * kSelWaves <= kSelThreads, "one count per thread");
-    const int c = tid < kSelPerThread * kSelWaves ? eq_base[tid] : 0;
+    static_assert(PER * kSelWaves <= kSelThreads, "one count per thread");
+    const int c = tid < PER * kSelWaves ? eq_base[tid] : 0;
     const int ex = block_exclusive_scan(c, scratch);
-    if (tid < kSelPerThread * kSelWaves) eq_base[tid] = ex;
-    if (tid == kSelPerThread * kSelWaves - 1) picked[0] = ex + c;   // equal elements in the resident part
+    if (tid < PER * kSelWaves) eq_base[tid] = ex;
+    if (tid == PER * kSelWaves - 1) picked[0] = ex + c;   // equal elements in the resident part
     __syncthreads();
   }
 #pragma unroll
-  for (int j = 0; j < kSelPerThread; ++j) {
+  for (int j = 0; j < PER; ++j) {
     const int i = j * kSelThreads + tid;
     const bool eq = i < n_res && v[j] == T;
     const unsigned long long emask = __ballot(eq);
@@ -291,13 +295,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       if (rank < need_eq) keys[n_gt + rank] = make_key(T, i);
     }
   }
-  if (n > kSelResident) {
+  if (n > RES) {
     // tail of a long row: contiguous segments per wavefront, walked in 64-wide coalesced steps
     const int eq_resident = picked[0];
-    const int tail = n - kSelResident;
+    const int tail = n - RES;
     int seg = (tail + kSelWaves - 1) / kSelWaves;
     seg = (seg + 63) / 64 * 64;
-    const int seg_begin = kSelResident + wv * seg;
+    const int seg_begin = RES + wv * seg;
     const int seg_end = seg_begin + seg < n ? seg_begin + seg : n;
     int eq_count = 0;
     for (int i00 = seg_begin; i00 < seg_end; i00 += 4 * 64) {   // four loads in flight per lane
@@ -408,7 +412,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(int Hkv, int w
       if (MODE == kSelSegments) {            // the segment's candidates, in position order
         const int64_t e = cand_row + (int64_t)segment * layer_max + rank;
         cand.val[e] = (uint32_t)mine[c];
-        cand.pos[e] = segment * kSelResident + (int32_t)(mine[c] >> 32);
+        cand.pos[e] = segment * RES + (int32_t)(mine[c] >> 32);
       } else if (MODE == kSelMerge) {        // the key's low half is a place in the candidate list
         out[rank] = cand.pos[cand_row + (uint32_t)mine[c]];
       } else {
@@ -426,9 +430,11 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
   const size_t lds = 2048 * sizeof(u64) + (size_t)kRadixBins * kHistCopies * sizeof(int);
   static bool attr_set = false;
   if (!attr_set) {
-    for (const void* f : {reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect>),
-                          reinterpret_cast<const void*>(&select_topk_kernel<kSelSegments>),
-                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge>)}) {
+    for (const void* f : {reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect, 32>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect, 16>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect, 8>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelSegments, 32>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge, 32>)}) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
     }
@@ -436,19 +442,30 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
   }
   SelectCandidates cand{};
   if (wl.select_segments <= 1) {      // every row fits the registers of one workgroup
-    launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelDirect>, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
-           p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
-           idx_stride_layer, counts, cand);
+    // the fewest registers per thread that hold the longest row the descriptor admits
+    const int longest = p.max_seq_len - p.w;
+    if (longest <= 8 * kSelThreads)
+      launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelDirect, 8>), dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds,
+             st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
+             idx_stride_layer, counts, cand);
+    else if (longest <= 16 * kSelThreads)
+      launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelDirect, 16>), dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds,
+             st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
+             idx_stride_layer, counts, cand);
+    else
+      launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelDirect, 32>), dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds,
+             st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
+             idx_stride_layer, counts, cand);
     return hipGetLastError();
   }
   cand.val = reinterpret_cast<uint32_t*>(ws + wl.select_cand_val);
   cand.pos = reinterpret_cast<int32_t*>(ws + wl.select_cand_pos);
   cand.segments_max = wl.select_segments;
   cand.stride = (int64_t)wl.select_segments * p.layer_max;
-  launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelSegments>, dim3(p.Hkv, p.n_seqs * wl.select_segments, n_layers),
+  launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelSegments, 32>), dim3(p.Hkv, p.n_seqs * wl.select_segments, n_layers),
          dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer,
          cu, idx_out, idx_stride_layer, counts, cand);
-  launch(DKV_KERNEL_SELECT, select_topk_kernel<kSelMerge>, dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
+  launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelMerge, 32>), dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
          p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
          idx_stride_layer, counts, cand);
   return hipGetLastError();

@@ -182,12 +182,14 @@ def test_select_topk_large_k_and_long_rows(dkv):
         assert np.array_equal(idx[s][:, :ref.shape[1]], ref)
 
 
-def test_select_topk_on_both_sides_of_the_short_path(dkv):
-    """Rows that fit one workgroup's registers take a short path when the elements above the threshold's upper 22 bits
+@pytest.mark.parametrize("longest", [32768, 16384, 8192])
+def test_select_topk_on_both_sides_of_the_short_path(dkv, longest):
+    """(Three kernel variants by the longest row the descriptor admits: 32, 16 or 8 positions per thread.)
+    Rows that fit one workgroup's registers take a short path when the elements above the threshold's upper 22 bits
     plus those that share them number at most 4096, the full radix selection otherwise. Rows built to land on both
     sides of that limit (1500 larger values + a plateau of 2596 / 2597 equal ones that holds the threshold), rows of
     few distinct values, an all-equal row and a smooth one; bit-exact against the oracle's stable sort."""
-    cfg = small_cfg("short_path", Hq=2, Hkv=2, seqlens=(20000 + 32, 32768 + 32, 3000 + 32), layer_max=2048,
+    cfg = small_cfg("short_path", Hq=2, Hkv=2, seqlens=(longest * 5 // 8 + 32, longest + 32, 3000 + 32), layer_max=2048,
                     mean_budget=512, L=4, interval=4)
     comp = Compressor(cfg, keep_cache=False)
     cu, T = cfg.cu_seqlens, cfg.total_tokens
