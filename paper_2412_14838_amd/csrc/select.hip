@@ -434,7 +434,9 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
                           reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect, 16>),
                           reinterpret_cast<const void*>(&select_topk_kernel<kSelDirect, 8>),
                           reinterpret_cast<const void*>(&select_topk_kernel<kSelSegments, 32>),
-                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge, 32>)}) {
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge, 32>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge, 16>),
+                          reinterpret_cast<const void*>(&select_topk_kernel<kSelMerge, 8>)}) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
     }
@@ -465,9 +467,18 @@ hipError_t launch_select(const Params& p, int layer, int n_layers, const float* 
   launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelSegments, 32>), dim3(p.Hkv, p.n_seqs * wl.select_segments, n_layers),
          dim3(kSelThreads), lds, st, p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer,
          cu, idx_out, idx_stride_layer, counts, cand);
-  launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelMerge, 32>), dim3(p.Hkv, p.n_seqs, n_layers), dim3(kSelThreads), lds, st,
-         p.Hkv, p.w, p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out,
-         idx_stride_layer, counts, cand);
+  // level 2: the fewest registers per thread that hold a row's candidates (a longer list keeps its tail in memory)
+  const int64_t most = (int64_t)wl.select_segments * p.layer_max;
+  const dim3 grid_merge(p.Hkv, p.n_seqs, n_layers);
+  if (most <= 8 * kSelThreads)
+    launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelMerge, 8>), grid_merge, dim3(kSelThreads), lds, st, p.Hkv, p.w,
+           p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts, cand);
+  else if (most <= 16 * kSelThreads)
+    launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelMerge, 16>), grid_merge, dim3(kSelThreads), lds, st, p.Hkv, p.w,
+           p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts, cand);
+  else
+    launch(DKV_KERNEL_SELECT, (select_topk_kernel<kSelMerge, 32>), grid_merge, dim3(kSelThreads), lds, st, p.Hkv, p.w,
+           p.layer_max, p.L, layer, scores, scores_stride_head, scores_stride_layer, cu, idx_out, idx_stride_layer, counts, cand);
   return hipGetLastError();
 }
 
