@@ -5,7 +5,7 @@ head size, storage type, layer count, update interval, budgets and a ragged batc
 longer than the window, some a few tokens past a tile border) are drawn from a seeded generator. Scores within the
 stated tolerance; selection, hit counts, budgets, counts and the rows of the cache bit for bit (the oracle repeats
 the integer stages on the GPU's own fp32 scores); the grouped schedule identical to the layer-by-layer one; the
-attention of a new token over every layer's cache (all layers in one call) against the oracle's.
+attention of a new token over every layer's cache (all layers in one call) against the oracle's; the packed copy\nof the final cache row by row.
 """
 import numpy as np
 import pytest
@@ -85,6 +85,9 @@ def test_random_shape_against_the_oracle(dkv, i):
             comp.decode_attention_layers(0, cfg.L, q_dev, dec_out, dec_lse)
             torch.cuda.synchronize()
             dec_out, dec_lse = dec_out.cpu().numpy(), dec_lse.cpu().numpy()
+            kp, vp, off = comp.pack()               # the tight copy of the final cache
+            torch.cuda.synchronize()
+            kp, vp, off = kp.float().cpu().numpy(), vp.float().cpu().numpy(), off.cpu().numpy()
         runs[group] = (comp.scores.cpu().numpy(), comp.idx.cpu().numpy(), comp.counts.cpu().numpy(),
                        comp.kb.float().cpu().numpy(), comp.vb.float().cpu().numpy())
     scores, idx, counts, kb, vb = runs[1]
@@ -134,3 +137,10 @@ def test_random_shape_against_the_oracle(dkv, i):
             want, want_lse = O.decode_attention(q_new[l, s], kc, vc)
             assert np.abs(dec_out[l, s] - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (l, s)
             assert np.abs(dec_lse[l, s] - want_lse).max() <= 2e-5 * max(1.0, np.abs(want_lse).max()), (l, s)
+
+            # the packed cache: block (s, l) at off[s * L + l], head h at + h * (n + wq): retained rows, then window rows
+            o = int(off[s * cfg.L + l])
+            assert int(off[s * cfg.L + l + 1]) - o == cfg.Hkv * (n + wq), (l, s)
+            for h in range(cfg.Hkv):
+                blk = slice(o + h * (n + wq), o + (h + 1) * (n + wq))
+                assert np.array_equal(kp[blk], ref_k[h]) and np.array_equal(vp[blk], ref_v[h]), (l, s, h)
