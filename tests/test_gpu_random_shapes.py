@@ -5,7 +5,7 @@ head size, storage type, layer count, update interval, budgets and a ragged batc
 longer than the window, some a few tokens past a tile border) are drawn from a seeded generator. Scores within the
 stated tolerance; selection, hit counts, budgets, counts and the rows of the cache bit for bit (the oracle repeats
 the integer stages on the GPU's own fp32 scores); the grouped schedule identical to the layer-by-layer one; the
-attention of a new token over every layer's cache (all layers in one call) against the oracle's; the packed copy\nof the final cache row by row.
+attention of a new token over every layer's cache (all layers in one call) against the oracle's; the packed copy\nof the final cache row by row; the exported row normalisers and the single-sweep scores of the last layer.
 """
 import numpy as np
 import pytest
@@ -85,6 +85,17 @@ def test_random_shape_against_the_oracle(dkv, i):
             comp.decode_attention_layers(0, cfg.L, q_dev, dec_out, dec_lse)
             torch.cuda.synchronize()
             dec_out, dec_lse = dec_out.cpu().numpy(), dec_lse.cpu().numpy()
+            # single-sweep scoring of the last layer from the row normalisers the library exports for it
+            last = cfg.L - 1
+            comp.score(last, dev[last]["q_win"], dev[last]["k"])
+            lse_dev = torch.full((cfg.n_seqs, cfg.Hq, cfg.w), float("nan"), dtype=torch.float32, device="cuda")
+            comp.row_lse(lse_dev)
+            two_sweep = comp.scores[last].clone()
+            comp.scores[last].fill_(7.0)
+            comp.score_from_lse(last, dev[last]["q_win"], dev[last]["k"], lse_dev)
+            torch.cuda.synchronize()
+            one_sweep, two_sweep, lse_gpu = comp.scores[last].cpu().numpy(), two_sweep.cpu().numpy(), lse_dev.cpu().numpy()
+            comp.scores[last].copy_(torch.from_numpy(two_sweep))
             kp, vp, off = comp.pack()               # the tight copy of the final cache
             torch.cuda.synchronize()
             kp, vp, off = kp.float().cpu().numpy(), vp.float().cpu().numpy(), off.cpu().numpy()
@@ -108,6 +119,15 @@ def test_random_shape_against_the_oracle(dkv, i):
             assert np.isfinite(got).all()
             rel = np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)
             assert rel.max() <= SCORE_RTOL, (l, s, rel.max())
+    for s in range(cfg.n_seqs):                     # the exported normalisers and the single sweep (last layer)
+        n = cfg.seqlens[s] - cfg.w
+        if n < 0:
+            continue                                # shorter than the window: the method does not define its rows
+        ref_lse = O.row_lse(host[last]["q_win"][s], host[last]["k"][:, cu[s]:cu[s + 1]])
+        assert np.abs(lse_gpu[s] - ref_lse).max() <= 1e-4, s
+        if n > 0:
+            a, b = one_sweep[:, cu[s]:cu[s] + n], two_sweep[:, cu[s]:cu[s] + n]
+            assert (np.abs(a - b) <= 1e-4 * np.abs(b)).all(), s
     # integer stages and cache rows against the oracle on the GPU's scores
     ref = oracle_on_scores(cfg, scores)
     for s in range(cfg.n_seqs):
