@@ -18,7 +18,7 @@ from paper_2412_14838_amd.pipeline import Compressor, to_device
 pytestmark = pytest.mark.gpu
 
 SCORE_RTOL = 2e-3
-N_CASES = 24
+N_CASES = 40
 
 
 def draw_case(i):
